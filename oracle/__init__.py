@@ -1,0 +1,170 @@
+"""ctypes front end of the C oracle (oracle/aurora_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: importable from tests/, __graft_entry__.smoke() and the
+cpu_baseline leg of bench.py; never from the product package.  Marshals NumPy
+host arrays to the C entry points and back; no arithmetic happens here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import dataclasses
+from typing import Optional
+
+import numpy as np
+
+from . import build as _build
+
+F32, BF16 = 0, 1
+_DT = {"f32": F32, "bf16": BF16, F32: F32, BF16: BF16}
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(_build.build(force=False))
+        for name in ("oracle_attn", "oracle_logits", "oracle_accept_logits", "oracle_accept",
+                     "oracle_num_threads"):
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _chk(a: Optional[np.ndarray], dtype, shape=None):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    assert a.dtype == dtype, (a.dtype, dtype)
+    if shape is not None:
+        assert tuple(a.shape) == tuple(shape), (a.shape, shape)
+    return a
+
+
+def _elem_dtype(dt):
+    return np.float32 if _DT[dt] == F32 else np.uint16
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def attn(*, q, k_pages, v_pages, block_table, seq_lens, parents=None, dtype, sm_scale=0.0) -> np.ndarray:
+    """Chunk attention; returns float64 [B, Nq, Hq, D]."""
+    ed = _elem_dtype(dtype)
+    q = _chk(q, ed)
+    B, Nq, Hq, D = q.shape
+    k_pages = _chk(k_pages, ed)
+    P, Hkv, page, D2 = k_pages.shape
+    assert D2 == D
+    v_pages = _chk(v_pages, ed, k_pages.shape)
+    block_table = _chk(block_table, np.int32)
+    assert block_table.shape[0] == B
+    seq_lens = _chk(seq_lens, np.int32, (B,))
+    parents = _chk(parents, np.int32, (B, Nq))
+    out = np.empty((B, Nq, Hq, D), dtype=np.float64)
+    st = lib().oracle_attn(C.c_int(B), C.c_int(Nq), C.c_int(Hq), C.c_int(Hkv), C.c_int(D),
+                           C.c_int(page), C.c_int(block_table.shape[1]), C.c_int64(P),
+                           C.c_int(_DT[dtype]), C.c_double(sm_scale), _p(q), _p(k_pages), _p(v_pages),
+                           _p(block_table), _p(seq_lens), _p(parents), _p(out))
+    if st != 0:
+        raise ValueError(f"oracle_attn status {st}")
+    return out
+
+
+def logits(*, hidden, lm_head, dtype) -> np.ndarray:
+    """LM-head projection; hidden [..., H], lm_head [V, H] -> float64 [..., V]."""
+    ed = _elem_dtype(dtype)
+    hidden = _chk(hidden, ed)
+    lm_head = _chk(lm_head, ed)
+    H = hidden.shape[-1]
+    V = lm_head.shape[0]
+    assert lm_head.shape[1] == H
+    rows = int(np.prod(hidden.shape[:-1]))
+    out = np.empty((rows, V), dtype=np.float64)
+    st = lib().oracle_logits(C.c_int64(rows), C.c_int(H), C.c_int(V), C.c_int(_DT[dtype]),
+                             _p(hidden), _p(lm_head), _p(out))
+    if st != 0:
+        raise ValueError(f"oracle_logits status {st}")
+    return out.reshape(hidden.shape[:-1] + (V,))
+
+
+@dataclasses.dataclass
+class AcceptResult:
+    accept_len: np.ndarray      # [B] int32
+    next_token: np.ndarray      # [B] int32
+    accept_mask: np.ndarray     # [B, Nq] uint8
+    p_at_draft: np.ndarray      # [B, Nq] float64
+    row_lse: np.ndarray         # [B, Nq] float64
+    test_margin: np.ndarray     # [B, Nq] float64 (NaN where no test was evaluated)
+    top_gap: np.ndarray         # [B, Nq] float64
+    stop_node: np.ndarray       # [B] int32
+    final_cdf: Optional[np.ndarray]  # [B, V] float64 or None
+    logits: Optional[np.ndarray]     # [B, Nq, V] float64 or None
+
+
+def _alloc_results(B, Nq, V, want_cdf):
+    return dict(
+        accept_len=np.empty(B, np.int32), next_token=np.empty(B, np.int32),
+        accept_mask=np.empty((B, Nq), np.uint8), p_at_draft=np.empty((B, Nq), np.float64),
+        row_lse=np.empty((B, Nq), np.float64), test_margin=np.empty((B, Nq), np.float64),
+        top_gap=np.empty((B, Nq), np.float64), stop_node=np.empty(B, np.int32),
+        final_cdf=np.empty((B, V), np.float64) if want_cdf else None)
+
+
+def accept_from_logits(*, logits, draft_tokens, draft_probs=None, uniforms=None, parents=None,
+                       temperature, want_cdf=False) -> AcceptResult:
+    lg = _chk(logits, np.float64)
+    B, Nq, V = lg.shape
+    draft_tokens = _chk(draft_tokens, np.int32, (B, Nq))
+    draft_probs = _chk(draft_probs, np.float32, (B, Nq, V))
+    uniforms = _chk(uniforms, np.float32, (B, Nq, 2))
+    parents = _chk(parents, np.int32, (B, Nq))
+    r = _alloc_results(B, Nq, V, want_cdf and temperature > 0)
+    st = lib().oracle_accept_logits(
+        C.c_int(B), C.c_int(Nq), C.c_int(V), C.c_double(float(np.float32(temperature))), _p(lg),
+        _p(draft_tokens), _p(draft_probs), _p(uniforms), _p(parents), _p(r["accept_len"]),
+        _p(r["next_token"]), _p(r["accept_mask"]), _p(r["p_at_draft"]), _p(r["row_lse"]),
+        _p(r["test_margin"]), _p(r["top_gap"]), _p(r["stop_node"]), _p(r["final_cdf"]))
+    if st != 0:
+        raise ValueError(f"oracle_accept_logits status {st}")
+    return AcceptResult(logits=None, **r)
+
+
+def accept(*, hidden, lm_head, draft_tokens, draft_probs=None, uniforms=None, parents=None, dtype,
+           temperature, want_cdf=False, want_logits=False) -> AcceptResult:
+    """LM head + acceptance.  hidden [B, Nq, H], lm_head [V, H].  The temperature is first
+    rounded to float32 (the type it has at the library boundary), then widened."""
+    ed = _elem_dtype(dtype)
+    hidden = _chk(hidden, ed)
+    B, Nq, H = hidden.shape
+    lm_head = _chk(lm_head, ed)
+    V = lm_head.shape[0]
+    assert lm_head.shape[1] == H
+    draft_tokens = _chk(draft_tokens, np.int32, (B, Nq))
+    draft_probs = _chk(draft_probs, np.float32, (B, Nq, V))
+    uniforms = _chk(uniforms, np.float32, (B, Nq, 2))
+    parents = _chk(parents, np.int32, (B, Nq))
+    r = _alloc_results(B, Nq, V, want_cdf and temperature > 0)
+    lg = np.empty((B, Nq, V), np.float64) if want_logits else None
+    st = lib().oracle_accept(
+        C.c_int(B), C.c_int(Nq), C.c_int(H), C.c_int(V), C.c_int(_DT[dtype]),
+        C.c_double(float(np.float32(temperature))), _p(hidden), _p(lm_head), _p(draft_tokens),
+        _p(draft_probs), _p(uniforms), _p(parents), _p(r["accept_len"]), _p(r["next_token"]),
+        _p(r["accept_mask"]), _p(r["p_at_draft"]), _p(r["row_lse"]), _p(r["test_margin"]),
+        _p(r["top_gap"]), _p(r["stop_node"]), _p(r["final_cdf"]), _p(lg))
+    if st != 0:
+        raise ValueError(f"oracle_accept status {st}")
+    return AcceptResult(logits=lg, **r)
+
+
+def verify(w, want_cdf=False, want_logits=False):
+    """Both halves on a gen.Workload; returns (attention float64, AcceptResult)."""
+    o = attn(q=w.q, k_pages=w.k_pages, v_pages=w.v_pages, block_table=w.host_block_table(),
+             seq_lens=w.seq_lens, parents=w.parents, dtype=w.dtype)
+    a = accept(hidden=w.hidden, lm_head=w.lm_head, draft_tokens=w.draft_tokens,
+               draft_probs=w.draft_probs, uniforms=w.uniforms, parents=w.parents, dtype=w.dtype,
+               temperature=w.temperature, want_cdf=want_cdf, want_logits=want_logits)
+    return o, a

@@ -1,0 +1,314 @@
+"""Pins for the oracle's acceptance step (CPU only): the invariants the method fixes, a
+hand-worked fixture, closed forms (eq. 1 of the paper) and Monte-Carlo exactness."""
+import os
+
+import numpy as np
+import pytest
+
+import gen
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "accept_hand_worked.txt")
+
+
+def _softmax64(l, T=1.0):
+    z = l / T
+    z = z - z.max(-1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(-1, keepdims=True)
+
+
+def _rand_dist(rng, shape, conc=1.0):
+    return _softmax64(rng.standard_normal(shape) * conc)
+
+
+def _draw(rng, p, n):
+    """n categorical draws from the single distribution p by inverse CDF (test-side input synthesis)."""
+    cdf = np.cumsum(p)
+    return np.minimum(np.searchsorted(cdf, rng.random(n) * cdf[-1], side="right"), len(p) - 1).astype(np.int32)
+
+
+# ------------------------------------------------------------------ hand-worked fixture
+def _parse_golden():
+    cases = []
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        lhs, rhs = line.split("->")
+        name, T, prow, qrow, toks, ua, us = lhs.split()
+        vec = lambda s: np.array([[float(x) for x in r.split(",")] for r in s.split(";")])
+        cases.append(dict(name=name, T=float(T), p=vec(prow), q=vec(qrow),
+                          toks=[int(x) for x in toks.split(",")], ua=[float(x) for x in ua.split(",")],
+                          us=float(us), want=tuple(int(x) for x in rhs.split())))
+    return cases
+
+
+@pytest.mark.parametrize("case", _parse_golden(), ids=lambda c: c["name"])
+@pytest.mark.parametrize("as_tree", [False, True])
+def test_hand_worked_cases(case, as_tree):
+    p, q = case["p"], case["q"]
+    Nq = p.shape[0]
+    k = Nq - 1
+    assert len(case["toks"]) == k
+    logits = (case["T"] * np.log(p))[None]
+    toks = np.array([[0] + case["toks"]], np.int32)
+    un = np.zeros((1, Nq, 2), np.float32)
+    un[0, 1:, 0] = case["ua"]
+    un[0, :, 1] = case["us"]
+    r = oracle.accept_from_logits(logits=logits, draft_tokens=toks, draft_probs=q[None].astype(np.float32),
+                                  uniforms=un, temperature=case["T"],
+                                  parents=gen.chain_parents(1, Nq) if as_tree else None)
+    assert (int(r.accept_len[0]), int(r.next_token[0])) == case["want"]
+    assert r.accept_mask[0].tolist() == [1] * (1 + case["want"][0]) + [0] * (k - case["want"][0])
+
+
+# ------------------------------------------------------------------ P1 greedy
+@pytest.mark.parametrize("as_tree", [False, True])
+def test_greedy_is_longest_argmax_prefix(as_tree):
+    rng = np.random.default_rng(5)
+    B, Nq, V = 200, 6, 50
+    logits = rng.standard_normal((B, Nq, V))
+    top = logits.argmax(-1)
+    toks = np.zeros((B, Nq), np.int32)
+    for i in range(1, Nq):
+        hit = rng.random(B) < 0.7
+        toks[:, i] = np.where(hit, top[:, i - 1], rng.integers(0, V, B))
+    r = oracle.accept_from_logits(logits=logits, draft_tokens=toks, temperature=0.0,
+                                  parents=gen.chain_parents(B, Nq) if as_tree else None)
+    for b in range(B):
+        n = 0
+        while n < Nq - 1 and toks[b, n + 1] == top[b, n]:
+            n += 1
+        assert r.accept_len[b] == n
+        assert r.next_token[b] == top[b, n]
+        assert r.accept_mask[b].tolist() == [1] * (n + 1) + [0] * (Nq - 1 - n)
+        assert r.stop_node[b] == n
+    assert 0 < r.accept_len.mean() < Nq - 1
+
+
+def test_greedy_lowest_index_on_exact_tie():
+    logits = np.zeros((1, 2, 7))
+    logits[0, 0, [2, 5]] = 1.0
+    logits[0, 1, [6, 3]] = 2.0
+    r = oracle.accept_from_logits(logits=logits, draft_tokens=np.array([[0, 2]], np.int32), temperature=0.0)
+    assert r.accept_len[0] == 1 and r.next_token[0] == 3
+    r = oracle.accept_from_logits(logits=logits, draft_tokens=np.array([[0, 5]], np.int32), temperature=0.0)
+    assert r.accept_len[0] == 0 and r.next_token[0] == 2
+
+
+# ------------------------------------------------------------------ P2 q == p
+@pytest.mark.parametrize("T", [1.0, 0.7])
+def test_q_equal_p_accepts_everything(T):
+    rng = np.random.default_rng(6)
+    B, Nq, V = 300, 5, 40
+    logits = rng.standard_normal((B, Nq, V)) * 2
+    p = _softmax64(logits, float(np.float32(T)))
+    toks = rng.integers(0, V, (B, Nq)).astype(np.int32)
+    un = rng.random((B, Nq, 2)).astype(np.float32)
+    un[un >= 1.0] = 0.5
+    un[:7, :, 0] = np.float32(1.0 - 2.0 ** -24)  # the largest uniform the generator can emit
+    r = oracle.accept_from_logits(logits=logits, draft_tokens=toks, draft_probs=p.astype(np.float32),
+                                  uniforms=un, temperature=T)
+    assert (r.accept_len == Nq - 1).all() and (r.accept_mask == 1).all()
+    # p_at_draft and row_lse against the library softmax
+    par = np.arange(-1, Nq - 1)
+    want = p[np.arange(B)[:, None], par[None, 1:], toks[:, 1:]]
+    np.testing.assert_allclose(r.p_at_draft[:, 1:], want, rtol=1e-12)
+    from scipy.special import logsumexp
+    np.testing.assert_allclose(r.row_lse, logsumexp(logits / float(np.float32(T)), axis=-1), rtol=1e-13)
+
+
+# ------------------------------------------------------------------ P9 special cases
+def test_k0_is_plain_sampling_and_matches_inverse_cdf():
+    rng = np.random.default_rng(8)
+    B, V = 5000, 16
+    p = _rand_dist(rng, (V,), 1.5)
+    logits = np.broadcast_to(np.log(p), (B, 1, V)).copy()
+    un = rng.random((B, 1, 2)).astype(np.float32)
+    r = oracle.accept_from_logits(logits=logits, draft_tokens=np.zeros((B, 1), np.int32),
+                                  draft_probs=np.full((B, 1, V), 1 / V, np.float32), uniforms=un,
+                                  temperature=1.0, want_cdf=True)
+    assert (r.accept_len == 0).all()
+    cdf = np.cumsum(_softmax64(np.log(p)))
+    want = np.searchsorted(cdf, un[:, 0, 1].astype(np.float64), side="right")
+    # identical except possibly when u sits within rounding of a CDF knot
+    safe = np.abs(cdf[None, :] - un[:, 0, 1:2].astype(np.float64)).min(-1) > 1e-9
+    assert (r.next_token[safe] == want[safe]).all() and safe.mean() > 0.99
+    np.testing.assert_allclose(r.final_cdf[0], cdf, rtol=1e-12)
+
+
+@pytest.mark.parametrize("as_tree", [False, True])
+def test_zero_target_probability_always_rejects_and_resamples_from_p(as_tree):
+    rng = np.random.default_rng(9)
+    B, V = 20000, 8
+    p = _rand_dist(rng, (V,))
+    p[3] = 0.0
+    p /= p.sum()
+    with np.errstate(divide="ignore"):
+        logits = np.broadcast_to(np.log(p), (B, 2, V)).copy()
+    q = np.zeros((B, 2, V), np.float32)
+    q[:, :, 3] = 1.0
+    un = rng.random((B, 2, 2)).astype(np.float32)
+    un[: B // 2, 1, 0] = 0.0  # u = 0 must still reject because p(d) = 0
+    toks = np.full((B, 2), 3, np.int32)
+    r = oracle.accept_from_logits(logits=logits, draft_tokens=toks, draft_probs=q, uniforms=un, temperature=1.0,
+                                  parents=gen.chain_parents(B, 2) if as_tree else None)
+    assert (r.accept_len == 0).all()
+    f = np.bincount(r.next_token, minlength=V) / B
+    assert f[3] == 0
+    assert np.all(np.abs(f - p) <= 4 * np.sqrt(p * (1 - p) / B) + 1e-12)
+
+
+def test_u_zero_accepts_iff_p_positive():
+    p = np.array([[[0.25, 0.75, 0.0], [0.2, 0.3, 0.5]]])
+    with np.errstate(divide="ignore"):
+        logits = np.log(p)
+    q = np.array([[[0.1, 0.1, 0.8], [1 / 3, 1 / 3, 1 / 3]]], np.float32)
+    un = np.zeros((1, 2, 2), np.float32)
+    r = oracle.accept_from_logits(logits=logits, draft_tokens=np.array([[0, 1]], np.int32), draft_probs=q,
+                                  uniforms=un, temperature=1.0)
+    assert r.accept_len[0] == 1
+    r = oracle.accept_from_logits(logits=logits, draft_tokens=np.array([[0, 2]], np.int32), draft_probs=q,
+                                  uniforms=un, temperature=1.0)
+    assert r.accept_len[0] == 0
+
+
+def test_degenerate_residual_falls_back_to_p():
+    """p == q exactly and a forced rejection is impossible; but p <= q everywhere with the
+    draft token's p(d) = 0 < q(d) leaves residual max(0, p - q) == 0 only if p == q elsewhere.
+    Build p = (0.5, 0.5, 0), q = (0.5, 0.5, 0) with d = 2 (q(d) = 0 = p(d)): u*0 < 0 is false =>
+    rejected with Z = 0 => next token drawn from p itself."""
+    p = np.array([[[0.5, 0.5, 0.0], [0.2, 0.3, 0.5]]])
+    with np.errstate(divide="ignore"):
+        logits = np.log(p)
+    q = np.array([[[0.5, 0.5, 0.0], [1 / 3, 1 / 3, 1 / 3]]], np.float32)
+    for us, want in [(0.25, 0), (0.75, 1)]:
+        un = np.zeros((1, 2, 2), np.float32)
+        un[0, 0, 1] = us
+        r = oracle.accept_from_logits(logits=logits, draft_tokens=np.array([[0, 2]], np.int32),
+                                      draft_probs=q, uniforms=un, temperature=1.0)
+        assert r.accept_len[0] == 0 and r.next_token[0] == want
+
+
+def test_chain_routine_equals_tree_walk_on_chain_parents():
+    w = gen.llama_chain(21, batch=64, num_q=6, num_q_heads=2, num_kv_heads=1, head_dim=8, page_size=4,
+                        hidden_size=32, vocab=300, len_lo=8, len_hi=12, draft_noise=1.5)
+    args = dict(hidden=w.hidden, lm_head=w.lm_head, draft_tokens=w.draft_tokens, draft_probs=w.draft_probs,
+                uniforms=w.uniforms, dtype=w.dtype, temperature=1.0, want_cdf=True)
+    a = oracle.accept(**args)
+    b = oracle.accept(parents=gen.chain_parents(w.batch, w.num_q), **args)
+    for f in ("accept_len", "next_token", "accept_mask", "stop_node"):
+        assert np.array_equal(getattr(a, f), getattr(b, f)), f
+    np.testing.assert_allclose(a.final_cdf, b.final_cdf, rtol=1e-12, atol=1e-15)
+    np.testing.assert_array_equal(np.isnan(a.test_margin), np.isnan(b.test_margin))
+    assert 0 < a.accept_len.mean() < w.num_q - 1
+
+
+# ------------------------------------------------------------------ P3 / P5 / P6 Monte-Carlo, chain
+def _within(freq, p, n, sig=4.0):
+    return np.all(np.abs(freq - p) <= sig * np.sqrt(np.maximum(p * (1 - p), 1e-12) / n) + 1e-9)
+
+
+@pytest.mark.parametrize("seed,T", [(1, 1.0), (2, 0.8)])
+def test_monte_carlo_chain_emits_target_distribution(seed, T):
+    rng = np.random.default_rng(seed)
+    B, k, V = 250_000, 4, 16
+    Nq = k + 1
+    Tf = float(np.float32(T))
+    lrow = rng.standard_normal((Nq, V)) * 1.5
+    p = _softmax64(lrow, Tf)
+    q = _softmax64(lrow / Tf + rng.standard_normal((Nq, V)) * 0.8).astype(np.float32)
+    toks = np.zeros((B, Nq), np.int32)
+    for i in range(1, Nq):
+        toks[:, i] = _draw(rng, q[i - 1].astype(np.float64), B)
+    un = gen.workloads._uniform24(rng, (B, Nq, 2))
+    r = oracle.accept_from_logits(logits=np.broadcast_to(lrow, (B, Nq, V)).copy(), draft_tokens=toks,
+                                  draft_probs=np.broadcast_to(q, (B, Nq, V)).copy(), uniforms=un,
+                                  temperature=T)
+    L = r.accept_len
+    alpha = np.minimum(p, q.astype(np.float64)).sum(-1)  # acceptance probability of row j
+    reach = 1.0
+    expect_len = 0.0
+    for i in range(Nq):
+        sel = L >= i  # trials that reached row i
+        n = int(sel.sum())
+        assert abs(n / B - reach) <= 4 * np.sqrt(reach * (1 - reach) / B) + 1e-9
+        # token emitted after i accepted drafts: d_{i+1} if accepted too, else the corrected/bonus token
+        if i < k:
+            emitted = np.where(L[sel] >= i + 1, toks[sel, i + 1], r.next_token[sel])
+        else:
+            emitted = r.next_token[sel]
+        f = np.bincount(emitted, minlength=V) / n
+        assert _within(f, p[i], n), (i, f, p[i])
+        if i < k:
+            # P6: rejection probability at row i equals the residual mass 1 - alpha_i
+            rej = (L[sel] == i).mean()
+            assert abs(rej - (1 - alpha[i])) <= 4 * np.sqrt(alpha[i] * (1 - alpha[i]) / n) + 1e-9
+            expect_len += reach * alpha[i]
+            reach *= alpha[i]
+    # P5: E[accept_len + 1] = sum_i prod_{j<i} alpha_j  (eq. 1 when all alpha_j are equal)
+    assert abs(L.mean() - expect_len) <= 4 * L.std() / np.sqrt(B)
+
+
+def test_expected_length_reduces_to_eq1_for_constant_alpha():
+    """Same (p, q) at every row => alpha constant => E[L] = (1 - alpha^(k+1)) / (1 - alpha)."""
+    rng = np.random.default_rng(3)
+    B, k, V = 200_000, 5, 16
+    Nq = k + 1
+    l0 = rng.standard_normal(V)
+    p = _softmax64(l0)
+    q = _softmax64(l0 + rng.standard_normal(V)).astype(np.float32)
+    alpha = np.minimum(p, q.astype(np.float64)).sum()
+    toks = np.zeros((B, Nq), np.int32)
+    for i in range(1, Nq):
+        toks[:, i] = _draw(rng, q.astype(np.float64), B)
+    un = gen.workloads._uniform24(rng, (B, Nq, 2))
+    r = oracle.accept_from_logits(logits=np.broadcast_to(l0, (B, Nq, V)).copy(), draft_tokens=toks,
+                                  draft_probs=np.broadcast_to(q, (B, Nq, V)).copy(), uniforms=un,
+                                  temperature=1.0)
+    emitted = r.accept_len + 1.0
+    want = (1 - alpha ** (k + 1)) / (1 - alpha)
+    assert abs(emitted.mean() - want) <= 4 * emitted.std() / np.sqrt(B)
+
+
+# ------------------------------------------------------------------ P3 Monte-Carlo, tree
+def test_monte_carlo_tree_emits_target_distribution():
+    rng = np.random.default_rng(4)
+    B, V = 250_000, 16
+    #            0   1  2  3  4  5  6  7  8
+    par = np.array([-1, 0, 0, 0, 1, 1, 2, 4, 3], np.int32)
+    Nq = len(par)
+    lrow = rng.standard_normal((Nq, V)) * 1.5
+    p = _softmax64(lrow)
+    q = _softmax64(lrow + rng.standard_normal((Nq, V)) * 1.2).astype(np.float32)
+    toks = np.zeros((B, Nq), np.int32)
+    for n in range(1, Nq):
+        toks[:, n] = _draw(rng, q[par[n]].astype(np.float64), B)
+    un = gen.workloads._uniform24(rng, (B, Nq, 2))
+    r = oracle.accept_from_logits(logits=np.broadcast_to(lrow, (B, Nq, V)).copy(), draft_tokens=toks,
+                                  draft_probs=np.broadcast_to(q, (B, Nq, V)).copy(), uniforms=un,
+                                  parents=np.broadcast_to(par, (B, Nq)).copy(), temperature=1.0)
+    depth = np.zeros(Nq, int)
+    for n in range(1, Nq):
+        depth[n] = depth[par[n]] + 1
+    mask = r.accept_mask.astype(bool)
+    assert mask[:, 0].all()
+    assert np.array_equal(mask.sum(1) - 1, r.accept_len)
+    assert np.array_equal(depth[r.stop_node], r.accept_len)
+    # the token emitted right after node c was reached: the accepted child's token, or next_token
+    for c in range(Nq):
+        sel = mask[:, c]
+        n = int(sel.sum())
+        if n < 2000:
+            continue
+        kids = [m for m in range(Nq) if par[m] == c]
+        emitted = r.next_token[sel].copy()
+        for m in kids:
+            took = mask[sel, m]
+            emitted[took] = toks[sel, m][took]
+        f = np.bincount(emitted, minlength=V) / n
+        assert _within(f, p[c], n), (c, n)
+    # more candidates per node => strictly more acceptance than the first-child-only chain
+    first_only = 1 - np.minimum(p[0], q[0].astype(np.float64)).sum()
+    assert (r.accept_len == 0).mean() < first_only
