@@ -1,0 +1,155 @@
+/*
+ * aurora_verify.h - C ABI of the MI355X (gfx950) implementation of the target-model
+ * verification step of speculative decoding, the step of the Aurora serving loop that
+ * checks the drafted tokens and emits the accept / reject outcome the speculator is
+ * trained on (paper sections 2.1, 3.1, 3.3; tree form: section 3.2 and figure 2;
+ * logits l in R^{T x V}: appendix A.1, eq. 4).
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is CALLER-OWNED DEVICE memory on the current HIP device.
+ *     Descriptors are host structs, read during the call and not retained.
+ *   - The library allocates nothing and keeps no state.  All scratch lives in the
+ *     caller's `workspace` (device memory, 256-byte aligned, at least
+ *     aurora_verify_workspace_bytes() bytes).  No pointer is retained after the
+ *     enqueued work completes.  Calls with distinct workspaces may overlap.
+ *   - Calls are asynchronous: they enqueue kernels on `hip_stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream) and return.  Outputs are valid
+ *     once the caller has synchronised that stream.
+ *   - Return value: AURORA_OK or a negative AURORA_ERR_* code.  Validation is done on
+ *     the host from the descriptors and pointers only (null pointers, head-count
+ *     divisibility, supported head_dim / dtype / num_q, workspace size); when it fails
+ *     nothing is enqueued.  Device-side contents (page ids in range, seq_lens >= num_q,
+ *     parents[n] < n, token ids in range) are NOT checked.
+ *   - Deterministic: the same inputs give bit-identical outputs from run to run.
+ *   - There is no CPU fallback: without a HIP device every compute entry point
+ *     returns AURORA_ERR_HIP.
+ */
+#ifndef AURORA_VERIFY_H
+#define AURORA_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  AURORA_OK = 0,
+  AURORA_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, Hq % Hkv != 0, ...      */
+  AURORA_ERR_UNSUPPORTED = -2, /* well-formed but outside what the kernels cover           */
+  AURORA_ERR_WORKSPACE = -3,   /* workspace null, misaligned or too small                  */
+  AURORA_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed               */
+};
+
+enum { AURORA_F32 = 0, AURORA_BF16 = 1 };
+
+/* Attention half.  Nq query positions per request (k+1 for a chain of k drafts, or the
+ * number of nodes of a draft tree, root included) attend to a paged GQA KV cache. */
+typedef struct {
+  int32_t batch;             /* B >= 0 (0: nothing is enqueued)                              */
+  int32_t num_q;             /* Nq, 1..64                                                    */
+  int32_t num_q_heads;       /* Hq                                                           */
+  int32_t num_kv_heads;      /* Hkv, Hq % Hkv == 0                                           */
+  int32_t head_dim;          /* D: 64 or 128                                                 */
+  int32_t page_size;         /* tokens per KV page (any value >= 1; 16 is the tuned case)    */
+  int32_t max_pages_per_seq; /* row stride of block_table                                    */
+  int64_t num_pages;         /* P, pages in each of the K and V pools                        */
+  int32_t dtype;             /* AURORA_F32 / AURORA_BF16: type of q, k_pages, v_pages, out   */
+  float sm_scale;            /* softmax scale; 0 => 1/sqrt(head_dim)                         */
+} aurora_attn_desc;
+
+/* Acceptance half: LM head, softmax statistics, acceptance walk, residual / bonus draw. */
+typedef struct {
+  int32_t batch;     /* B                                                                    */
+  int32_t num_q;     /* Nq, 1..64                                                            */
+  int32_t hidden;    /* H (bf16: multiple of 8)                                              */
+  int32_t vocab;     /* V                                                                    */
+  int32_t dtype;     /* type of hidden and lm_head                                           */
+  float temperature; /* 0 => greedy (arg-max prefix); > 0 => speculative rejection sampling  */
+} aurora_accept_desc;
+
+/* Bytes of workspace needed by aurora_verify / _attn / _accept for these descriptors.
+ * Either descriptor may be NULL (that half then needs nothing).  Host only. */
+int aurora_verify_workspace_bytes(const aurora_attn_desc* attn, const aurora_accept_desc* accept,
+                                  size_t* out_bytes);
+
+/*
+ * Chunk attention of the draft positions over the cached context (sections 3.1, 3.2).
+ *
+ *   out[b, n, hq, :] = sum_j softmax_j( sm_scale * <q[b, n, hq, :], K_j> ) V_j
+ *
+ * over the KV positions j of request b that node n may see: the whole prefix
+ * j < L_b - Nq, plus the chunk slots L_b - Nq + a of a in {n and its ancestors}.  For a
+ * chain (parents == NULL, parent[i] = i-1) that is plain causal masking.  Query head hq
+ * reads KV head hq / (Hq / Hkv).  KV position j of request b is stored in page
+ * block_table[b][j / page_size] at in-page offset j % page_size.
+ * Numerics: fp32 path - everything in fp32.  bf16 path - scores and softmax in fp32, the
+ * probabilities rounded to bf16 for the P.V product, fp32 accumulation, output rounded to bf16.
+ */
+int aurora_verify_attn(const aurora_attn_desc* desc,
+                       const void* q,              /* [B, Nq, Hq, D]                          */
+                       const void* k_pages,        /* [P, Hkv, page_size, D]                  */
+                       const void* v_pages,        /* [P, Hkv, page_size, D]                  */
+                       const int32_t* block_table, /* [B, max_pages_per_seq]; unused = -1     */
+                       const int32_t* seq_lens,    /* [B] KV length INCLUDING the Nq chunk tokens */
+                       const int32_t* parents,     /* [B, Nq], parents[b,0] = -1, parents[b,n] < n; or NULL */
+                       void* out,                  /* [B, Nq, Hq, D], same dtype as q         */
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * LM head + softmax + acceptance (sections 2.1, 3.1, 3.3; appendix A.1).
+ *
+ *   logits[m, v] = sum_h hidden[m, h] * lm_head[v, h]          (fp32 results, kept in workspace)
+ *   T > 0 : p_n(v) = softmax_v(logits[b, n, :] / T).  Walk from the root: the children c of the
+ *           current node, in ascending node index, are tested with
+ *                 uniforms[b, c, 0] * q_cur(tok_c) < p(tok_c)        (q_cur = draft_probs[b, cur, :])
+ *           an accepted child becomes the current node (p = p_c); after a rejected child
+ *           p <- max(0, p - q_cur) renormalised (left unchanged if that is identically 0).
+ *           When no child is left, next_token is drawn from p by inverse CDF in ascending
+ *           token order with uniforms[b, cur, 1]: the first v whose running sum exceeds u * sum.
+ *           A chain is the one-child case: the first rejection ends the walk.
+ *   T == 0: a child is accepted iff its token equals the arg-max (lowest index on ties) of the
+ *           current row; next_token is the arg-max of the row the walk stops at.
+ */
+int aurora_verify_accept(const aurora_accept_desc* desc,
+                         const void* hidden,          /* [B, Nq, H]                           */
+                         const void* lm_head,         /* [V, H] row-major                     */
+                         const int32_t* draft_tokens, /* [B, Nq]; entry 0 (root) ignored      */
+                         const float* draft_probs,    /* [B, Nq, V] fp32, row n = distribution of n's
+                                                         children; NULL allowed iff T == 0    */
+                         const float* uniforms,       /* [B, Nq, 2] in [0,1); NULL allowed iff T == 0 */
+                         const int32_t* parents,      /* [B, Nq] or NULL => chain             */
+                         int32_t* accept_len,         /* [B] accepted draft tokens = depth of the stop node */
+                         int32_t* next_token,         /* [B] corrected token, or bonus token if all accepted */
+                         uint8_t* accept_mask,        /* [B, Nq] 1 on the accepted path (root always 1) */
+                         float* p_at_draft,           /* [B, Nq] optional (NULL ok): p_parent(n)(tok_n) of the
+                                                         unmodified target distribution; root 0; T == 0: 1/0 */
+                         float* row_lse,              /* [B, Nq] optional: logsumexp(logits / T); T == 0: T = 1 */
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Both halves on the same stream: attention, then acceptance.  The halves share no data
+ * (the hidden states entering the LM head are an independent input). */
+int aurora_verify(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,
+                  const void* q, const void* k_pages, const void* v_pages,
+                  const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents,
+                  void* attn_out,
+                  const void* hidden, const void* lm_head, const int32_t* draft_tokens,
+                  const float* draft_probs, const float* uniforms,
+                  int32_t* accept_len, int32_t* next_token, uint8_t* accept_mask,
+                  float* p_at_draft, float* row_lse,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* After aurora_verify_accept / aurora_verify has been enqueued with `workspace`, the fp32
+ * logits [B*Nq, V] it computed live at this device address until the workspace is reused
+ * (the target-logit payload of appendix A.1).  Host only; returns NULL on invalid descriptors. */
+const float* aurora_verify_logits_ptr(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,
+                                      const void* workspace);
+
+/* Human-readable name of a status code; never NULL. */
+const char* aurora_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AURORA_VERIFY_H */

@@ -1,0 +1,152 @@
+"""ctypes binding of libaurora_verify.so: the same names as the C ABI, argument marshalling only.
+
+PyTorch supplies device memory and streams; every step of the verify path runs in the HIP
+kernels behind the C entry points.  There is no fallback: if the library is not built, or no
+GPU is present, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+AURORA_OK = 0
+AURORA_ERR_INVALID_ARG = -1
+AURORA_ERR_UNSUPPORTED = -2
+AURORA_ERR_WORKSPACE = -3
+AURORA_ERR_HIP = -4
+AURORA_F32 = 0
+AURORA_BF16 = 1
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_verify.so")
+
+EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
+           "aurora_verify_logits_ptr", "aurora_status_string")
+
+
+class aurora_attn_desc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("num_q_heads", C.c_int32),
+                ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("page_size", C.c_int32),
+                ("max_pages_per_seq", C.c_int32), ("num_pages", C.c_int64), ("dtype", C.c_int32),
+                ("sm_scale", C.c_float)]
+
+
+class aurora_accept_desc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("hidden", C.c_int32), ("vocab", C.c_int32),
+                ("dtype", C.c_int32), ("temperature", C.c_float)]
+
+
+class AuroraError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load():
+    """Load the built library (raises if it is missing) and declare the prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2602_06932_amd.build` "
+                          "(or __graft_entry__.build()) first")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32p, f32p, u8p = C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p
+    ad, cd = C.POINTER(aurora_attn_desc), C.POINTER(aurora_accept_desc)
+    lib.aurora_verify_workspace_bytes.argtypes = [ad, cd, C.POINTER(C.c_size_t)]
+    lib.aurora_verify_workspace_bytes.restype = C.c_int
+    lib.aurora_verify_attn.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, vp, C.c_size_t, vp]
+    lib.aurora_verify_attn.restype = C.c_int
+    lib.aurora_verify_accept.argtypes = [cd, vp, vp, i32p, f32p, f32p, i32p, i32p, i32p, u8p, f32p, f32p, vp,
+                                         C.c_size_t, vp]
+    lib.aurora_verify_accept.restype = C.c_int
+    lib.aurora_verify.argtypes = [ad, cd, vp, vp, vp, i32p, i32p, i32p, vp, vp, vp, i32p, f32p, f32p, i32p, i32p,
+                                  u8p, f32p, f32p, vp, C.c_size_t, vp]
+    lib.aurora_verify.restype = C.c_int
+    lib.aurora_verify_logits_ptr.argtypes = [ad, cd, vp]
+    lib.aurora_verify_logits_ptr.restype = C.c_void_p
+    lib.aurora_status_string.argtypes = [C.c_int]
+    lib.aurora_status_string.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().aurora_status_string(int(status)).decode()
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (or a raw integer address, or None)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to the library must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _ref(d):
+    return None if d is None else C.byref(d)
+
+
+def aurora_verify_workspace_bytes(attn: Optional[aurora_attn_desc], accept: Optional[aurora_accept_desc]) -> int:
+    out = C.c_size_t(0)
+    st = load().aurora_verify_workspace_bytes(_ref(attn), _ref(accept), C.byref(out))
+    if st != AURORA_OK:
+        raise AuroraError(st, "aurora_verify_workspace_bytes")
+    return int(out.value)
+
+
+def aurora_verify_attn(desc, q, k_pages, v_pages, block_table, seq_lens, parents, out, workspace, stream=None,
+                       workspace_bytes=None, check=True) -> int:
+    wb = workspace_bytes if workspace_bytes is not None else (workspace.numel() * workspace.element_size())
+    st = load().aurora_verify_attn(_ref(desc), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                   _ptr(seq_lens), _ptr(parents), _ptr(out), _ptr(workspace), wb, _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_verify_attn")
+    return st
+
+
+def aurora_verify_accept(desc, hidden, lm_head, draft_tokens, draft_probs, uniforms, parents, accept_len,
+                         next_token, accept_mask, p_at_draft, row_lse, workspace, stream=None,
+                         workspace_bytes=None, check=True) -> int:
+    wb = workspace_bytes if workspace_bytes is not None else (workspace.numel() * workspace.element_size())
+    st = load().aurora_verify_accept(_ref(desc), _ptr(hidden), _ptr(lm_head), _ptr(draft_tokens),
+                                     _ptr(draft_probs), _ptr(uniforms), _ptr(parents), _ptr(accept_len),
+                                     _ptr(next_token), _ptr(accept_mask), _ptr(p_at_draft), _ptr(row_lse),
+                                     _ptr(workspace), wb, _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_verify_accept")
+    return st
+
+
+def aurora_verify(attn_desc, accept_desc, q, k_pages, v_pages, block_table, seq_lens, parents, attn_out, hidden,
+                  lm_head, draft_tokens, draft_probs, uniforms, accept_len, next_token, accept_mask, p_at_draft,
+                  row_lse, workspace, stream=None, workspace_bytes=None, check=True) -> int:
+    wb = workspace_bytes if workspace_bytes is not None else (workspace.numel() * workspace.element_size())
+    st = load().aurora_verify(_ref(attn_desc), _ref(accept_desc), _ptr(q), _ptr(k_pages), _ptr(v_pages),
+                              _ptr(block_table), _ptr(seq_lens), _ptr(parents), _ptr(attn_out), _ptr(hidden),
+                              _ptr(lm_head), _ptr(draft_tokens), _ptr(draft_probs), _ptr(uniforms),
+                              _ptr(accept_len), _ptr(next_token), _ptr(accept_mask), _ptr(p_at_draft),
+                              _ptr(row_lse), _ptr(workspace), wb, _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_verify")
+    return st
+
+
+def aurora_verify_logits_ptr(attn_desc, accept_desc, workspace) -> int:
+    p = load().aurora_verify_logits_ptr(_ref(attn_desc), _ref(accept_desc), _ptr(workspace))
+    return int(p or 0)

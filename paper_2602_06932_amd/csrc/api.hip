@@ -1,0 +1,234 @@
+// C-ABI layer: host-side validation, workspace planning and kernel dispatch.
+#include "../../include/aurora_verify.h"
+#include "common.hpp"
+#include "launch.hpp"
+
+using namespace aurora;
+
+namespace {
+
+int check_attn_desc(const aurora_attn_desc* d) {
+  if (!d) return AURORA_ERR_INVALID_ARG;
+  if (d->batch < 0 || d->num_q < 1 || d->num_q_heads < 1 || d->num_kv_heads < 1 || d->head_dim < 1 ||
+      d->page_size < 1 || d->max_pages_per_seq < 1 || d->num_pages < 1)
+    return AURORA_ERR_INVALID_ARG;
+  if (d->num_q_heads % d->num_kv_heads) return AURORA_ERR_INVALID_ARG;
+  if (d->dtype != AURORA_F32 && d->dtype != AURORA_BF16) return AURORA_ERR_INVALID_ARG;
+  if (!(d->sm_scale >= 0.f)) return AURORA_ERR_INVALID_ARG;
+  if (d->num_q > kMaxNq) return AURORA_ERR_UNSUPPORTED;
+  if (d->head_dim != 64 && d->head_dim != 128) return AURORA_ERR_UNSUPPORTED;
+  if ((int64_t)d->batch * d->num_q > 65535 || d->num_q_heads > 65535) return AURORA_ERR_UNSUPPORTED;
+  if ((int64_t)d->max_pages_per_seq * d->page_size > (int64_t)1 << 30) return AURORA_ERR_UNSUPPORTED;
+  return AURORA_OK;
+}
+
+int check_accept_desc(const aurora_accept_desc* d) {
+  if (!d) return AURORA_ERR_INVALID_ARG;
+  if (d->batch < 0 || d->num_q < 1 || d->hidden < 1 || d->vocab < 1) return AURORA_ERR_INVALID_ARG;
+  if (d->dtype != AURORA_F32 && d->dtype != AURORA_BF16) return AURORA_ERR_INVALID_ARG;
+  if (!(d->temperature >= 0.f)) return AURORA_ERR_INVALID_ARG;
+  if (d->num_q > kMaxNq) return AURORA_ERR_UNSUPPORTED;
+  if ((int64_t)d->batch * d->num_q > 65535) return AURORA_ERR_UNSUPPORTED;
+  if (d->dtype == AURORA_BF16 && d->hidden % 8) return AURORA_ERR_UNSUPPORTED;
+  return AURORA_OK;
+}
+
+AttnLaunch attn_launch_from(const aurora_attn_desc* d) {
+  AttnLaunch a = {};
+  a.B = d->batch; a.Nq = d->num_q; a.Hq = d->num_q_heads; a.Hkv = d->num_kv_heads; a.D = d->head_dim;
+  a.page = d->page_size; a.max_pages = d->max_pages_per_seq; a.bf16 = d->dtype == AURORA_BF16;
+  a.scale = d->sm_scale > 0.f ? d->sm_scale : 1.0f / sqrtf((float)d->head_dim);
+  return a;
+}
+
+// KV tokens per split: large enough that a split amortises its prologue, small enough that the
+// longest request is cut into many workgroups; the number of splits is bounded so that the
+// partial buffers stay modest.
+AttnPlan plan_attn(const aurora_attn_desc* d) {
+  AttnPlan p = {};
+  p.rows_per_group = d->num_q_heads / d->num_kv_heads * d->num_q;
+  const int64_t max_len = (int64_t)d->max_pages_per_seq * d->page_size;
+  int split = 512;
+  while ((max_len + split - 1) / split > 64 && split < 4096) split *= 2;
+  p.split_len = split;
+  int64_t ms = (max_len + split - 1) / split;
+  p.max_splits = (int)(ms < 1 ? 1 : ms);
+  const size_t nrows = (size_t)d->batch * d->num_q * d->num_q_heads * p.max_splits;
+  p.part_o_off = 0;
+  p.part_ml_off = align_up(nrows * d->head_dim * sizeof(float));
+  p.bytes = p.part_ml_off + align_up(nrows * 2 * sizeof(float));
+  return p;
+}
+
+AcceptLaunch accept_launch_from(const aurora_accept_desc* d) {
+  AcceptLaunch a = {};
+  a.B = d->batch; a.Nq = d->num_q; a.H = d->hidden; a.V = d->vocab; a.bf16 = d->dtype == AURORA_BF16;
+  a.temperature = d->temperature;
+  return a;
+}
+
+AcceptPlan plan_accept(const aurora_accept_desc* d) {
+  AcceptPlan p = {};
+  p.rows = (int64_t)d->batch * d->num_q;
+  AcceptLaunch probe = accept_launch_from(d);
+  p.stat_tile = lmhead_mfma_supported(probe) ? lmhead_mfma_stat_tile() : 1024;
+  p.n_tiles = (d->vocab + p.stat_tile - 1) / p.stat_tile;
+  const size_t rows = (size_t)p.rows;
+  p.logits_off = 0;
+  p.pmax_off = align_up(rows * d->vocab * sizeof(float));
+  p.psum_off = p.pmax_off + align_up(rows * p.n_tiles * sizeof(float));
+  p.parg_off = p.psum_off + align_up(rows * p.n_tiles * sizeof(float));
+  p.bytes = p.parg_off + align_up(rows * p.n_tiles * sizeof(int32_t));
+  return p;
+}
+
+bool misaligned(const void* p) { return ((uintptr_t)p & 255u) != 0; }
+
+int run_attn(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+             const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents, void* out,
+             void* workspace, size_t workspace_bytes, hipStream_t st) {
+  int rc = check_attn_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (desc->batch == 0) return AURORA_OK;
+  if (!q || !k_pages || !v_pages || !block_table || !seq_lens || !out) return AURORA_ERR_INVALID_ARG;
+  AttnPlan plan = plan_attn(desc);
+  if (!workspace || misaligned(workspace) || workspace_bytes < plan.bytes) return AURORA_ERR_WORKSPACE;
+  AttnLaunch a = attn_launch_from(desc);
+  a.q = q; a.k = k_pages; a.v = v_pages; a.block_table = block_table; a.seq_lens = seq_lens; a.parents = parents;
+  a.out = out;
+  a.part_o = (float*)((char*)workspace + plan.part_o_off);
+  a.part_ml = (float*)((char*)workspace + plan.part_ml_off);
+  a.plan = plan;
+  hipError_t e = attn_mfma_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(a, st);
+  return e == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
+}
+
+int run_accept(const aurora_accept_desc* desc, const void* hidden, const void* lm_head, const int32_t* draft_tokens,
+               const float* draft_probs, const float* uniforms, const int32_t* parents, int32_t* accept_len,
+               int32_t* next_token, uint8_t* accept_mask, float* p_at_draft, float* row_lse, void* workspace,
+               size_t workspace_bytes, hipStream_t st) {
+  int rc = check_accept_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (desc->batch == 0) return AURORA_OK;
+  if (!hidden || !lm_head || !draft_tokens || !accept_len || !next_token || !accept_mask)
+    return AURORA_ERR_INVALID_ARG;
+  if (desc->temperature > 0.f && (!draft_probs || !uniforms)) return AURORA_ERR_INVALID_ARG;
+  AcceptPlan plan = plan_accept(desc);
+  if (!workspace || misaligned(workspace) || workspace_bytes < plan.bytes) return AURORA_ERR_WORKSPACE;
+  AcceptLaunch a = accept_launch_from(desc);
+  a.hidden = hidden; a.lm_head = lm_head; a.draft_tokens = draft_tokens; a.draft_probs = draft_probs;
+  a.uniforms = uniforms; a.parents = parents; a.accept_len = accept_len; a.next_token = next_token;
+  a.accept_mask = accept_mask; a.p_at_draft = p_at_draft; a.row_lse = row_lse;
+  char* ws = (char*)workspace;
+  a.logits = (float*)(ws + plan.logits_off);
+  a.pmax = (float*)(ws + plan.pmax_off);
+  a.psum = (float*)(ws + plan.psum_off);
+  a.parg = (int32_t*)(ws + plan.parg_off);
+  a.plan = plan;
+  hipError_t e = lmhead_mfma_supported(a) ? launch_lmhead_mfma(a, st) : launch_lmhead_generic(a, st);
+  if (e != hipSuccess) return AURORA_ERR_HIP;
+  e = launch_accept(a, st);
+  return e == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
+}
+
+bool have_device() {
+  int n = 0;
+  return hipGetDeviceCount(&n) == hipSuccess && n > 0;
+}
+
+}  // namespace
+
+extern "C" {
+
+int aurora_verify_workspace_bytes(const aurora_attn_desc* attn, const aurora_accept_desc* accept, size_t* out_bytes) {
+  if (!out_bytes || (!attn && !accept)) return AURORA_ERR_INVALID_ARG;
+  size_t total = 0;
+  if (attn) {
+    int rc = check_attn_desc(attn);
+    if (rc != AURORA_OK) return rc;
+    total += plan_attn(attn).bytes;
+  }
+  if (accept) {
+    int rc = check_accept_desc(accept);
+    if (rc != AURORA_OK) return rc;
+    total += plan_accept(accept).bytes;
+  }
+  *out_bytes = total < 256 ? 256 : total;
+  return AURORA_OK;
+}
+
+int aurora_verify_attn(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                       const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents, void* out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_attn_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (!have_device()) return AURORA_ERR_HIP;
+  return run_attn(desc, q, k_pages, v_pages, block_table, seq_lens, parents, out, workspace, workspace_bytes,
+                  (hipStream_t)hip_stream);
+}
+
+int aurora_verify_accept(const aurora_accept_desc* desc, const void* hidden, const void* lm_head,
+                         const int32_t* draft_tokens, const float* draft_probs, const float* uniforms,
+                         const int32_t* parents, int32_t* accept_len, int32_t* next_token, uint8_t* accept_mask,
+                         float* p_at_draft, float* row_lse, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  int rc = check_accept_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (!have_device()) return AURORA_ERR_HIP;
+  return run_accept(desc, hidden, lm_head, draft_tokens, draft_probs, uniforms, parents, accept_len, next_token,
+                    accept_mask, p_at_draft, row_lse, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+int aurora_verify(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc, const void* q,
+                  const void* k_pages, const void* v_pages, const int32_t* block_table, const int32_t* seq_lens,
+                  const int32_t* parents, void* attn_out, const void* hidden, const void* lm_head,
+                  const int32_t* draft_tokens, const float* draft_probs, const float* uniforms, int32_t* accept_len,
+                  int32_t* next_token, uint8_t* accept_mask, float* p_at_draft, float* row_lse, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+  int rc = check_attn_desc(attn_desc);
+  if (rc != AURORA_OK) return rc;
+  rc = check_accept_desc(accept_desc);
+  if (rc != AURORA_OK) return rc;
+  if (attn_desc->batch != accept_desc->batch || attn_desc->num_q != accept_desc->num_q)
+    return AURORA_ERR_INVALID_ARG;
+  if (!have_device()) return AURORA_ERR_HIP;
+  const size_t attn_bytes = plan_attn(attn_desc).bytes;
+  const size_t acc_bytes = plan_accept(accept_desc).bytes;
+  if (!workspace || misaligned(workspace) || workspace_bytes < attn_bytes + acc_bytes) return AURORA_ERR_WORKSPACE;
+  // validate the second half's pointers before anything is enqueued
+  if (accept_desc->batch > 0) {
+    if (!hidden || !lm_head || !draft_tokens || !accept_len || !next_token || !accept_mask)
+      return AURORA_ERR_INVALID_ARG;
+    if (accept_desc->temperature > 0.f && (!draft_probs || !uniforms)) return AURORA_ERR_INVALID_ARG;
+  }
+  rc = run_attn(attn_desc, q, k_pages, v_pages, block_table, seq_lens, parents, attn_out, workspace, attn_bytes,
+                (hipStream_t)hip_stream);
+  if (rc != AURORA_OK) return rc;
+  return run_accept(accept_desc, hidden, lm_head, draft_tokens, draft_probs, uniforms, parents, accept_len,
+                    next_token, accept_mask, p_at_draft, row_lse, (char*)workspace + attn_bytes, acc_bytes,
+                    (hipStream_t)hip_stream);
+}
+
+const float* aurora_verify_logits_ptr(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,
+                                      const void* workspace) {
+  if (!workspace || check_accept_desc(accept_desc) != AURORA_OK) return nullptr;
+  size_t off = 0;
+  if (attn_desc) {
+    if (check_attn_desc(attn_desc) != AURORA_OK) return nullptr;
+    off = plan_attn(attn_desc).bytes;
+  }
+  return (const float*)((const char*)workspace + off + plan_accept(accept_desc).logits_off);
+}
+
+const char* aurora_status_string(int status) {
+  switch (status) {
+    case AURORA_OK: return "ok";
+    case AURORA_ERR_INVALID_ARG: return "invalid argument";
+    case AURORA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case AURORA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case AURORA_ERR_HIP: return "HIP runtime error or no device";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,70 @@
+// Shared device/host helpers of the verify-step library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace aurora {
+
+constexpr int kWave = 64;
+constexpr int kMaxNq = 64;
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round to nearest, ties to even (finite inputs; NaN stays NaN)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+// butterfly reductions over the 64 lanes of a wavefront; every lane gets the result
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ __forceinline__ int wave_max(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+// --- launch plans shared by the API layer and the launchers (host) ----------------------
+struct AttnPlan {
+  int rows_per_group;  // G * Nq query rows that share one KV head
+  int split_len;       // KV tokens per split (multiple of 128)
+  int max_splits;      // ceil(max_len / split_len)
+  size_t part_o_off, part_ml_off, bytes;  // fp32 partial O [B*Nq*Hq*max_splits, D]; (m,l) pairs
+};
+
+struct AcceptPlan {
+  int64_t rows;     // M = B * Nq
+  int stat_tile;    // vocab columns per softmax-statistics partial
+  int n_tiles;      // ceil(V / stat_tile)
+  size_t logits_off, pmax_off, psum_off, parg_off, bytes;
+};
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+}  // namespace aurora

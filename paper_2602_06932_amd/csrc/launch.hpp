@@ -1,0 +1,48 @@
+// Host-side launcher interfaces between the C-ABI layer and the kernel translation units.
+#pragma once
+#include "common.hpp"
+
+namespace aurora {
+
+struct AttnLaunch {
+  int B, Nq, Hq, Hkv, D, page, max_pages;
+  bool bf16;
+  float scale;
+  const void *q, *k, *v;
+  const int32_t *block_table, *seq_lens, *parents;
+  void* out;
+  float *part_o, *part_ml;
+  AttnPlan plan;
+};
+
+struct AcceptLaunch {
+  int B, Nq, H, V;
+  bool bf16;
+  float temperature;
+  const void *hidden, *lm_head;
+  const int32_t *draft_tokens, *parents;
+  const float *draft_probs, *uniforms;
+  int32_t *accept_len, *next_token;
+  uint8_t* accept_mask;
+  float *p_at_draft, *row_lse;
+  float *logits, *pmax, *psum;
+  int32_t* parg;
+  AcceptPlan plan;
+};
+
+// attention
+bool attn_mfma_supported(const AttnLaunch& a);
+hipError_t launch_attn_mfma(const AttnLaunch& a, hipStream_t st);
+hipError_t launch_attn_generic(const AttnLaunch& a, hipStream_t st);
+hipError_t launch_attn_combine(const AttnLaunch& a, hipStream_t st);
+
+// LM head + softmax statistics
+bool lmhead_mfma_supported(const AcceptLaunch& a);
+int lmhead_mfma_stat_tile();
+hipError_t launch_lmhead_mfma(const AcceptLaunch& a, hipStream_t st);
+hipError_t launch_lmhead_generic(const AcceptLaunch& a, hipStream_t st);
+
+// acceptance walk + residual / bonus draw
+hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st);
+
+}  // namespace aurora

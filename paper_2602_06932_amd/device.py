@@ -1,0 +1,109 @@
+"""Device-memory plumbing around the binding: upload a host workload (any object with the
+attribute names of the generator's Workload), allocate outputs and workspace, call the C ABI.
+Nothing here computes; torch is used for allocation, copies and streams only."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _to_dev(a, dtype_tag):
+    """Host array -> device tensor; uint16 arrays holding bf16 bits become torch.bfloat16."""
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if a.dtype == np.uint16:
+        t = t.view(torch.int16).cuda().view(torch.bfloat16)
+    else:
+        t = t.cuda()
+    return t
+
+
+class DeviceVerify:
+    """A workload resident in HBM plus the buffers one verify call needs."""
+
+    def __init__(self, w, pool_pages_on_device=None):
+        self.w = w
+        bf16 = w.dtype == "bf16"
+        self.dt = B.AURORA_BF16 if bf16 else B.AURORA_F32
+        self.q = _to_dev(w.q, w.dtype)
+        page_ids = getattr(w, "page_ids", None)
+        if page_ids is None:
+            self.k_pages = _to_dev(w.k_pages, w.dtype)
+            self.v_pages = _to_dev(w.v_pages, w.dtype)
+        else:
+            # sparse pool: allocate the whole pool, fill only the referenced pages
+            shape = (int(w.num_pages),) + tuple(w.k_pages.shape[1:])
+            tdt = torch.bfloat16 if bf16 else torch.float32
+            self.k_pages = torch.empty(shape, dtype=tdt, device="cuda")
+            self.v_pages = torch.empty(shape, dtype=tdt, device="cuda")
+            idx = torch.from_numpy(np.asarray(page_ids, dtype=np.int64)).cuda()
+            step = 8192
+            for s in range(0, len(page_ids), step):
+                self.k_pages[idx[s:s + step]] = _to_dev(w.k_pages[s:s + step], w.dtype)
+                self.v_pages[idx[s:s + step]] = _to_dev(w.v_pages[s:s + step], w.dtype)
+        self.block_table = _to_dev(w.block_table, None)
+        self.seq_lens = _to_dev(w.seq_lens, None)
+        self.parents = _to_dev(w.parents, None)
+        self.hidden = _to_dev(w.hidden, w.dtype)
+        self.lm_head = _to_dev(w.lm_head, w.dtype)
+        self.draft_tokens = _to_dev(w.draft_tokens, None)
+        self.draft_probs = _to_dev(w.draft_probs, None)
+        self.uniforms = _to_dev(w.uniforms, None)
+
+        self.attn_desc = B.aurora_attn_desc(
+            batch=w.batch, num_q=w.num_q, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
+            head_dim=w.head_dim, page_size=w.page_size, max_pages_per_seq=int(w.block_table.shape[1]),
+            num_pages=int(w.num_pages), dtype=self.dt, sm_scale=0.0)
+        self.accept_desc = B.aurora_accept_desc(batch=w.batch, num_q=w.num_q, hidden=w.hidden_size,
+                                                vocab=w.vocab, dtype=self.dt, temperature=w.temperature)
+        self.ws_bytes = B.aurora_verify_workspace_bytes(self.attn_desc, self.accept_desc)
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
+        assert self.workspace.data_ptr() % 256 == 0
+
+        Bn, Nq = w.batch, w.num_q
+        self.attn_out = torch.empty_like(self.q)
+        self.accept_len = torch.full((Bn,), -7, dtype=torch.int32, device="cuda")
+        self.next_token = torch.full((Bn,), -7, dtype=torch.int32, device="cuda")
+        self.accept_mask = torch.full((Bn, Nq), 9, dtype=torch.uint8, device="cuda")
+        self.p_at_draft = torch.full((Bn, Nq), float("nan"), dtype=torch.float32, device="cuda")
+        self.row_lse = torch.full((Bn, Nq), float("nan"), dtype=torch.float32, device="cuda")
+
+    # -- calls through the C ABI ---------------------------------------------------------------
+    def attn(self, stream=None):
+        return B.aurora_verify_attn(self.attn_desc, self.q, self.k_pages, self.v_pages, self.block_table,
+                                    self.seq_lens, self.parents, self.attn_out, self.workspace, stream)
+
+    def accept(self, stream=None):
+        return B.aurora_verify_accept(self.accept_desc, self.hidden, self.lm_head, self.draft_tokens,
+                                      self.draft_probs, self.uniforms, self.parents, self.accept_len,
+                                      self.next_token, self.accept_mask, self.p_at_draft, self.row_lse,
+                                      self.workspace, stream)
+
+    def verify(self, stream=None):
+        return B.aurora_verify(self.attn_desc, self.accept_desc, self.q, self.k_pages, self.v_pages,
+                               self.block_table, self.seq_lens, self.parents, self.attn_out, self.hidden,
+                               self.lm_head, self.draft_tokens, self.draft_probs, self.uniforms, self.accept_len,
+                               self.next_token, self.accept_mask, self.p_at_draft, self.row_lse, self.workspace,
+                               stream)
+
+    # -- results back on the host --------------------------------------------------------------
+    def attn_out_host(self) -> np.ndarray:
+        return self.attn_out.float().cpu().numpy()
+
+    def logits_host(self, after="verify") -> np.ndarray:
+        """fp32 logits [B, Nq, V] left in the workspace by the last accept / verify call."""
+        ad = self.attn_desc if after == "verify" else None
+        ptr = B.aurora_verify_logits_ptr(ad, self.accept_desc, self.workspace)
+        off = ptr - self.workspace.data_ptr()
+        n = self.w.batch * self.w.num_q * self.w.vocab
+        flat = self.workspace[off:off + 4 * n].view(torch.float32)
+        return flat.cpu().numpy().reshape(self.w.batch, self.w.num_q, self.w.vocab)
+
+    def results_host(self):
+        torch.cuda.synchronize()
+        return dict(accept_len=self.accept_len.cpu().numpy(), next_token=self.next_token.cpu().numpy(),
+                    accept_mask=self.accept_mask.cpu().numpy(), p_at_draft=self.p_at_draft.cpu().numpy(),
+                    row_lse=self.row_lse.cpu().numpy())

@@ -1,0 +1,59 @@
+"""The C-ABI library builds, loads without a GPU and exports every symbol the header declares;
+host-side validation works without a device."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "aurora_verify.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(aurora_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2602_06932_amd as av
+    if not os.path.exists(av.LIB_PATH):
+        from paper_2602_06932_amd import build
+        build.build()
+    lib = av.load()
+    names = _declared()
+    assert {"aurora_verify", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify_workspace_bytes",
+            "aurora_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(av.EXPORTS) == set(names)
+
+
+def test_host_validation_without_device():
+    import paper_2602_06932_amd as av
+    ad = av.aurora_attn_desc(batch=2, num_q=5, num_q_heads=8, num_kv_heads=2, head_dim=64, page_size=16,
+                             max_pages_per_seq=4, num_pages=8, dtype=av.AURORA_F32, sm_scale=0.0)
+    cd = av.aurora_accept_desc(batch=2, num_q=5, hidden=64, vocab=100, dtype=av.AURORA_F32, temperature=1.0)
+    n = av.aurora_verify_workspace_bytes(ad, cd)
+    assert n >= 2 * 5 * 100 * 4 and n % 256 == 0
+    assert av.aurora_verify_workspace_bytes(ad, None) + av.aurora_verify_workspace_bytes(None, cd) == n
+    bad = av.aurora_attn_desc.from_buffer_copy(ad)
+    bad.num_kv_heads = 3
+    with pytest.raises(av.AuroraError) as e:
+        av.aurora_verify_workspace_bytes(bad, cd)
+    assert e.value.status == av.AURORA_ERR_INVALID_ARG
+    bad = av.aurora_accept_desc.from_buffer_copy(cd)
+    bad.temperature = -1.0
+    with pytest.raises(av.AuroraError):
+        av.aurora_verify_workspace_bytes(None, bad)
+    assert av.status_string(av.AURORA_ERR_UNSUPPORTED) == "unsupported configuration"
+    assert av.status_string(12345) == "unknown status"
+
+
+def test_product_package_does_not_touch_the_oracle():
+    """The product path must not import, read or call anything under oracle/."""
+    pkg = os.path.join(ROOT, "paper_2602_06932_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)

@@ -1,0 +1,176 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+import oracle
+from parity_util import check_accept, check_attention, check_logits
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(av, w, which="verify"):
+    from paper_2602_06932_amd.device import DeviceVerify
+    dv = DeviceVerify(w)
+    getattr(dv, which)()
+    torch.cuda.synchronize()
+    return dv
+
+
+def _full_check(av, w, sample=None):
+    """Run the whole path on the GPU for all requests; compare the requests in `sample` (default all)."""
+    print(f"[case] {w.name} seed={w.seed} B={w.batch} Nq={w.num_q} V={w.vocab} H={w.hidden_size} "
+          f"L={int(w.seq_lens.min())}..{int(w.seq_lens.max())} T={w.temperature}", flush=True)
+    dv = _run(av, w)
+    idx = np.arange(w.batch) if sample is None else np.asarray(sample)
+    ws = w.take_requests(idx)
+    ref_o, ref_a = oracle.verify(ws, want_cdf=True, want_logits=True)
+    check_attention(dv.attn_out_host()[idx], ref_o, w.dtype)
+    check_logits(dv.logits_host()[idx], ref_a.logits, w.dtype)
+    res = {k: v[idx] for k, v in dv.results_host().items()}
+    exempt = check_accept(res, ref_a, ws)
+    if exempt:
+        print(f"[exempt] {exempt}", flush=True)
+    return dv, ref_a
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_tiny_chain_fp32(gpu_lib, seed):
+    _full_check(gpu_lib, gen.tiny_chain(seed))
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_llama_chain_bf16_reduced(gpu_lib, seed):
+    # several KV splits, several vocab tiles, ragged tails everywhere
+    w = gen.llama_chain(seed, batch=7, len_lo=37, len_hi=1500, vocab=5003, hidden_size=520)
+    _, a = _full_check(gpu_lib, w)
+    assert 0 < a.accept_len.mean() < 4
+
+
+def test_llama_chain_temperature(gpu_lib):
+    w = gen.llama_chain(4, batch=6, len_lo=20, len_hi=300, vocab=3000, hidden_size=256, temperature=0.7,
+                        draft_noise=0.5)
+    _full_check(gpu_lib, w)
+
+
+def test_greedy_chain_bf16_reduced(gpu_lib):
+    w = gen.qwen_greedy_chain(1, batch=9, len_lo=50, len_hi=900, vocab=7001, hidden_size=512)
+    _, a = _full_check(gpu_lib, w)
+    assert a.accept_len.max() > 0
+
+
+def test_tree_bf16_reduced(gpu_lib):
+    w = gen.llama_tree(1, batch=5, context=333, vocab=4099, hidden_size=512)
+    _, a = _full_check(gpu_lib, w)
+    assert a.accept_len.max() > 0
+
+
+def test_tree_fp32_small_heads(gpu_lib):
+    w = gen.llama_tree(2, batch=3, num_q=11, num_q_heads=4, num_kv_heads=4, head_dim=64, context=77,
+                       vocab=777, hidden_size=64, dtype=gen.F32)
+    _full_check(gpu_lib, w)
+
+
+def test_greedy_tree(gpu_lib):
+    w = gen.make_workload(name="greedy_tree", seed=3, dtype=gen.BF16, batch=6, num_q=16, num_q_heads=8,
+                          num_kv_heads=2, head_dim=128, page_size=16, hidden_size=256, vocab=2000,
+                          temperature=0.0, seq_lens=np.full(6, 120, np.int32), draft="greedy_mix", tree=True,
+                          distinct_siblings=True)
+    _full_check(gpu_lib, w)
+
+
+# ---------------------------------------------------------------- degenerate and edge cases
+def test_single_position_k0(gpu_lib):
+    w = gen.llama_chain(5, batch=4, num_q=1, len_lo=1, len_hi=90, vocab=1000, hidden_size=128)
+    _, a = _full_check(gpu_lib, w)
+    assert (a.accept_len == 0).all()
+
+
+def test_no_prefix_context_equals_chunk(gpu_lib):
+    w = gen.llama_chain(6, batch=3, len_lo=5, len_hi=5, vocab=600, hidden_size=64)
+    _full_check(gpu_lib, w)
+
+
+def test_mha_and_head_dim_64(gpu_lib):
+    w = gen.llama_chain(7, batch=3, num_q_heads=4, num_kv_heads=4, head_dim=64, len_lo=30, len_hi=200,
+                        vocab=900, hidden_size=64)
+    _full_check(gpu_lib, w)
+
+
+def test_wide_group_and_long_chain(gpu_lib):
+    w = gen.llama_chain(8, batch=2, num_q=9, num_q_heads=16, num_kv_heads=2, len_lo=100, len_hi=400,
+                        vocab=1200, hidden_size=128)
+    _full_check(gpu_lib, w)
+
+
+def test_q_equals_p_accepts_all_on_gpu(gpu_lib):
+    w = gen.llama_chain(9, batch=5, len_lo=20, len_hi=60, vocab=2048, hidden_size=128)
+    lg = oracle.logits(hidden=w.hidden, lm_head=w.lm_head, dtype=w.dtype)
+    from scipy.special import softmax
+    w.draft_probs = softmax(lg, axis=-1).astype(np.float32)
+    dv, a = _full_check(gpu_lib, w)
+    assert (a.accept_len == 4).all() and (dv.accept_len.cpu().numpy() == 4).all()
+
+
+def test_empty_batch_and_error_codes(gpu_lib):
+    av = gpu_lib
+    from paper_2602_06932_amd.device import DeviceVerify
+    w = gen.tiny_chain(1)
+    dv = DeviceVerify(w)
+    ad, cd = dv.attn_desc, dv.accept_desc
+    # empty batch: OK, nothing written
+    ad0 = av.aurora_attn_desc.from_buffer_copy(ad); ad0.batch = 0
+    assert av.aurora_verify_attn(ad0, None, None, None, None, None, None, None, dv.workspace, check=False) == av.AURORA_OK
+    # workspace too small / misaligned / null
+    assert av.aurora_verify_attn(ad, dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.seq_lens, None, dv.attn_out,
+                                 dv.workspace, workspace_bytes=16, check=False) == av.AURORA_ERR_WORKSPACE
+    assert av.aurora_verify_attn(ad, dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.seq_lens, None, dv.attn_out,
+                                 dv.workspace.data_ptr() + 4, workspace_bytes=dv.ws_bytes - 4,
+                                 check=False) == av.AURORA_ERR_WORKSPACE
+    # null data pointer
+    assert av.aurora_verify_attn(ad, None, dv.k_pages, dv.v_pages, dv.block_table, dv.seq_lens, None, dv.attn_out,
+                                 dv.workspace, check=False) == av.AURORA_ERR_INVALID_ARG
+    # heads not divisible, unsupported head_dim, too many positions
+    bad = av.aurora_attn_desc.from_buffer_copy(ad); bad.num_kv_heads = 3
+    assert av.aurora_verify_attn(bad, dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.seq_lens, None, dv.attn_out,
+                                 dv.workspace, check=False) == av.AURORA_ERR_INVALID_ARG
+    bad = av.aurora_attn_desc.from_buffer_copy(ad); bad.head_dim = 96
+    assert av.aurora_verify_attn(bad, dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.seq_lens, None, dv.attn_out,
+                                 dv.workspace, check=False) == av.AURORA_ERR_UNSUPPORTED
+    badc = av.aurora_accept_desc.from_buffer_copy(cd); badc.num_q = 65
+    assert av.aurora_verify_accept(badc, dv.hidden, dv.lm_head, dv.draft_tokens, dv.draft_probs, dv.uniforms, None,
+                                   dv.accept_len, dv.next_token, dv.accept_mask, None, None, dv.workspace,
+                                   check=False) == av.AURORA_ERR_UNSUPPORTED
+    # sampling without draft_probs is an argument error; greedy without them is fine
+    assert av.aurora_verify_accept(cd, dv.hidden, dv.lm_head, dv.draft_tokens, None, dv.uniforms, None,
+                                   dv.accept_len, dv.next_token, dv.accept_mask, None, None, dv.workspace,
+                                   check=False) == av.AURORA_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert (dv.accept_len.cpu().numpy() == -7).all()  # nothing was enqueued by the failing calls
+
+
+def test_halves_equal_whole_and_runs_are_deterministic(gpu_lib):
+    from paper_2602_06932_amd.device import DeviceVerify
+    w = gen.llama_chain(10, batch=6, len_lo=40, len_hi=700, vocab=4000, hidden_size=256)
+    a = DeviceVerify(w); a.verify(); ra = a.results_host(); oa = a.attn_out_host()
+    b = DeviceVerify(w); b.attn(); b.accept(); rb = b.results_host(); ob = b.attn_out_host()
+    a.verify(); ra2 = a.results_host(); oa2 = a.attn_out_host()
+    assert np.array_equal(oa, ob) and np.array_equal(oa, oa2)
+    for k in ra:
+        assert np.array_equal(ra[k], rb[k], equal_nan=True), k
+        assert np.array_equal(ra[k], ra2[k], equal_nan=True), k
+
+
+def test_optional_outputs_may_be_null(gpu_lib):
+    from paper_2602_06932_amd.device import DeviceVerify
+    import paper_2602_06932_amd as av
+    w = gen.tiny_chain(2)
+    dv = DeviceVerify(w)
+    av.aurora_verify_accept(dv.accept_desc, dv.hidden, dv.lm_head, dv.draft_tokens, dv.draft_probs, dv.uniforms,
+                            None, dv.accept_len, dv.next_token, dv.accept_mask, None, None, dv.workspace)
+    r = dv.results_host()
+    ref = oracle.accept(hidden=w.hidden, lm_head=w.lm_head, draft_tokens=w.draft_tokens, draft_probs=w.draft_probs,
+                        uniforms=w.uniforms, dtype=w.dtype, temperature=1.0)
+    assert np.array_equal(r["accept_len"], ref.accept_len) and np.array_equal(r["next_token"], ref.next_token)
+    assert np.isnan(r["row_lse"]).all()
