@@ -128,6 +128,18 @@ int aurora_verify_accept(const aurora_accept_desc* desc,
                          float* row_lse,              /* [B, Nq] optional: logsumexp(logits / T); T == 0: T = 1 */
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * First stage of aurora_verify_accept on its own: the LM-head projection (appendix A.1, eq. 4:
+ * logits l in R^{T x V}) fused with the per-vocab-tile softmax statistics.  Leaves the fp32
+ * logits [B*Nq, V] and the statistics in `workspace` (sized as for aurora_verify_accept); the
+ * logits are found with aurora_verify_logits_ptr(NULL, desc, workspace).  Used to time and to
+ * inspect the vocabulary sweep separately from the acceptance walk.
+ */
+int aurora_verify_lmhead(const aurora_accept_desc* desc,
+                         const void* hidden,  /* [B, Nq, H]       */
+                         const void* lm_head, /* [V, H] row-major */
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Both halves on the same stream: attention, then acceptance.  The halves share no data
  * (the hidden states entering the LM head are an independent input). */
 int aurora_verify(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,

@@ -21,6 +21,7 @@ AURORA_BF16 = 1
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_verify.so")
 
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
+           "aurora_verify_lmhead",
            "aurora_verify_logits_ptr", "aurora_status_string")
 
 
@@ -63,6 +64,8 @@ def load():
     lib.aurora_verify_accept.argtypes = [cd, vp, vp, i32p, f32p, f32p, i32p, i32p, i32p, u8p, f32p, f32p, vp,
                                          C.c_size_t, vp]
     lib.aurora_verify_accept.restype = C.c_int
+    lib.aurora_verify_lmhead.argtypes = [cd, vp, vp, vp, C.c_size_t, vp]
+    lib.aurora_verify_lmhead.restype = C.c_int
     lib.aurora_verify.argtypes = [ad, cd, vp, vp, vp, i32p, i32p, i32p, vp, vp, vp, i32p, f32p, f32p, i32p, i32p,
                                   u8p, f32p, f32p, vp, C.c_size_t, vp]
     lib.aurora_verify.restype = C.c_int
@@ -130,6 +133,14 @@ def aurora_verify_accept(desc, hidden, lm_head, draft_tokens, draft_probs, unifo
                                      _ptr(workspace), wb, _stream(stream))
     if check and st != AURORA_OK:
         raise AuroraError(st, "aurora_verify_accept")
+    return st
+
+
+def aurora_verify_lmhead(desc, hidden, lm_head, workspace, stream=None, workspace_bytes=None, check=True) -> int:
+    wb = workspace_bytes if workspace_bytes is not None else (workspace.numel() * workspace.element_size())
+    st = load().aurora_verify_lmhead(_ref(desc), _ptr(hidden), _ptr(lm_head), _ptr(workspace), wb, _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_verify_lmhead")
     return st
 
 

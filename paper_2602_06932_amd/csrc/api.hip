@@ -131,6 +131,26 @@ int run_accept(const aurora_accept_desc* desc, const void* hidden, const void* l
   return e == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
 }
 
+int run_lmhead(const aurora_accept_desc* desc, const void* hidden, const void* lm_head, void* workspace,
+               size_t workspace_bytes, hipStream_t st) {
+  int rc = check_accept_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (desc->batch == 0) return AURORA_OK;
+  if (!hidden || !lm_head) return AURORA_ERR_INVALID_ARG;
+  AcceptPlan plan = plan_accept(desc);
+  if (!workspace || misaligned(workspace) || workspace_bytes < plan.bytes) return AURORA_ERR_WORKSPACE;
+  AcceptLaunch a = accept_launch_from(desc);
+  a.hidden = hidden; a.lm_head = lm_head;
+  char* ws = (char*)workspace;
+  a.logits = (float*)(ws + plan.logits_off);
+  a.pmax = (float*)(ws + plan.pmax_off);
+  a.psum = (float*)(ws + plan.psum_off);
+  a.parg = (int32_t*)(ws + plan.parg_off);
+  a.plan = plan;
+  hipError_t e = lmhead_mfma_supported(a) ? launch_lmhead_mfma(a, st) : launch_lmhead_generic(a, st);
+  return e == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
+}
+
 bool have_device() {
   int n = 0;
   return hipGetDeviceCount(&n) == hipSuccess && n > 0;
@@ -177,6 +197,14 @@ int aurora_verify_accept(const aurora_accept_desc* desc, const void* hidden, con
   if (!have_device()) return AURORA_ERR_HIP;
   return run_accept(desc, hidden, lm_head, draft_tokens, draft_probs, uniforms, parents, accept_len, next_token,
                     accept_mask, p_at_draft, row_lse, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+int aurora_verify_lmhead(const aurora_accept_desc* desc, const void* hidden, const void* lm_head, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  int rc = check_accept_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (!have_device()) return AURORA_ERR_HIP;
+  return run_lmhead(desc, hidden, lm_head, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
 int aurora_verify(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc, const void* q,

@@ -1,8 +1,227 @@
-// bf16 MFMA LM head (placeholder until the kernel lands).
+// bf16 LM-head projection on the matrix cores, fused with per-tile softmax statistics
+// (appendix A.1, eq. 4 of the paper: target logits l in R^{T x V}; the acceptance step needs
+// their row-wise softmax).
+//
+//   logits[m, v] = sum_h hidden[m, h] * W[v, h]      hidden [M, H] bf16, W [V, H] bf16, fp32 out
+//
+// The weight matrix is streamed from HBM exactly once; it is the dominant traffic of the whole
+// verify step.  One workgroup (4 wavefronts) owns 256 vocabulary rows and up to 160 token rows
+// and walks the hidden dimension in steps of 64.  Each step's operands are brought in with
+// direct global->LDS loads (16 B per lane, fully coalesced 128-B rows) into a 3-deep ring of
+// LDS stages, so two steps are always in flight while one is being multiplied.  The 16-byte
+// chunks of every row are XOR-swizzled by (row mod 8) on the way in - the global address a lane
+// reads is permuted, the LDS slot is fixed by the lane id - which makes the 128-bit operand
+// reads of v_mfma_f32_32x32x16_bf16 bank-conflict free.
+// Vocabulary rows are the MFMA "A" rows and tokens its "B" columns: a lane then holds 16 vocab
+// entries of ONE token per accumulator tile, so row statistics (max, arg-max, sum exp) reduce
+// inside a lane and need a single cross-lane step.
 #include "common.hpp"
 #include "launch.hpp"
+
 namespace aurora {
-bool lmhead_mfma_supported(const AcceptLaunch&) { return false; }
-int lmhead_mfma_stat_tile() { return 256; }
-hipError_t launch_lmhead_mfma(const AcceptLaunch&, hipStream_t) { return hipErrorNotSupported; }
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+constexpr int kLmThreads = 256;
+constexpr int kLmBK = 64;                      // hidden elements per stage
+constexpr int kLmRowBytes = kLmBK * 2;         // 128
+constexpr int kLmVTile = 256;                  // vocab rows per workgroup
+constexpr int kLmWaveV = 64;                   // vocab rows per wavefront (= statistics tile)
+constexpr int kLmStages = 3;
+constexpr int kLmWBytes = kLmVTile * kLmRowBytes;  // 32 KB
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14])
+#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+
+template <int NT>
+__global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
+    const bf16_t* __restrict__ hidden, const bf16_t* __restrict__ w, float* __restrict__ logits,
+    float* __restrict__ pmax, float* __restrict__ psum, int32_t* __restrict__ parg, int M, int H, int V, int n_tiles,
+    float exp_scale /* log2(e) / T */) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  constexpr int kStageBytes = kLmWBytes + NT * 32 * kLmRowBytes;
+  constexpr int kLoadsPerStage = 8 + NT;  // global->LDS instructions per wavefront per stage
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int vbase = blockIdx.x * kLmVTile;
+  const int m0 = blockIdx.y * (NT * 32);
+  const int nk = H / kLmBK;
+
+  // ---- per-lane source pointers (rows clamped into range; out-of-range rows are masked later) ----
+  const int sub = lane >> 3;                 // row within an 8-row load instruction
+  const int chunk = (lane & 7) ^ sub;        // swizzled 16-byte chunk this lane fetches
+  const bf16_t* wsrc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    int row = vbase + wv * kLmWaveV + 8 * j + sub;
+    row = row < V ? row : V - 1;
+    wsrc[j] = w + (size_t)row * H + chunk * 8;
+  }
+  const bf16_t* hsrc[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    int row = m0 + 8 * (wv * NT + j) + sub;
+    row = row < M ? row : M - 1;
+    hsrc[j] = hidden + (size_t)row * H + chunk * 8;
+  }
+
+  auto issue = [&](int ks, int buf) {
+    char* base = lds + buf * kStageBytes;
+    const int koff = ks * kLmBK;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      __builtin_amdgcn_global_load_lds(GLB_PTR(wsrc[j] + koff), LDS_PTR(base + (wv * kLmWaveV + 8 * j) * kLmRowBytes),
+                                       16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+      __builtin_amdgcn_global_load_lds(GLB_PTR(hsrc[j] + koff),
+                                       LDS_PTR(base + kLmWBytes + 8 * (wv * NT + j) * kLmRowBytes), 16, 0, 0);
+  };
+
+  f32x16_t acc[2][NT];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
+
+  const int li = lane & 31, lh = lane >> 5;
+  // byte offsets of this lane's operand rows inside a stage (the chunk term is added per step)
+  const int wrow_off = (wv * kLmWaveV + li) * kLmRowBytes;
+  const int hrow_off = kLmWBytes + li * kLmRowBytes;
+  const int sw = li & 7;
+
+  issue(0, 0);
+  if (nk > 1) issue(1, 1);
+
+  for (int ks = 0; ks < nk; ++ks) {
+    // stage ks has landed once at most one younger stage's loads are still outstanding
+    if (ks + 1 < nk) WAIT_VMCNT(kLoadsPerStage); else WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    if (ks + 2 < nk) issue(ks + 2, (ks + 2) % kLmStages);
+    const char* base = lds + (ks % kLmStages) * kStageBytes;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int coff = ((2 * s + lh) ^ sw) * 16;
+      bf16x8_t wa[2], hb[NT];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) wa[a] = *(const bf16x8_t*)(base + wrow_off + a * 32 * kLmRowBytes + coff);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) hb[t] = *(const bf16x8_t*)(base + hrow_off + t * 32 * kLmRowBytes + coff);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[t], acc[a][t], 0, 0, 0);
+    }
+  }
+
+  // ---- epilogue: logits out, and (max, arg-max, sum exp) of this wavefront's 64 vocab rows ----------
+  // accumulator register r of tile a holds vocab row  vrow0 + 32a + 8(r/4) + 4*lh + r%4  of token m0 + 32t + li
+  const int vrow0 = vbase + wv * kLmWaveV;
+  const int stat_tile = blockIdx.x * (kLmVTile / kLmWaveV) + wv;
+  const bool vec_ok = (V & 3) == 0;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int m = m0 + 32 * t + li;
+    const bool m_ok = m < M;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int v = vrow0 + 32 * a + 8 * (r >> 2) + 4 * lh + (r & 3);
+        if (v >= V) acc[a][t][r] = -INFINITY;
+        mx = fmaxf(mx, acc[a][t][r]);
+      }
+    int arg = 0x7fffffff;
+#pragma unroll
+    for (int a = 1; a >= 0; --a)
+#pragma unroll
+      for (int r = 15; r >= 0; --r) {
+        const int v = vrow0 + 32 * a + 8 * (r >> 2) + 4 * lh + (r & 3);
+        arg = (acc[a][t][r] == mx) ? v : arg;
+      }
+    // merge the two lane halves (they hold interleaved groups of 4 rows of the same token)
+    const float omx = __shfl_xor(mx, 32, kWave);
+    const int oarg = __shfl_xor(arg, 32, kWave);
+    if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
+    float sum = 0.f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f((acc[a][t][r] - mx) * exp_scale);
+    sum += __shfl_xor(sum, 32, kWave);
+    if (m_ok) {
+      if (lh == 0 && stat_tile < n_tiles) {
+        pmax[(size_t)m * n_tiles + stat_tile] = mx;
+        psum[(size_t)m * n_tiles + stat_tile] = sum;
+        parg[(size_t)m * n_tiles + stat_tile] = arg;
+      }
+      float* lrow = logits + (size_t)m * V;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int v = vrow0 + 32 * a + 8 * g + 4 * lh;
+          if (vec_ok && v + 3 < V) {
+            f32x4_t o = {acc[a][t][4 * g], acc[a][t][4 * g + 1], acc[a][t][4 * g + 2], acc[a][t][4 * g + 3]};
+            *(f32x4_t*)(lrow + v) = o;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (v + e < V) lrow[v + e] = acc[a][t][4 * g + e];
+          }
+        }
+    }
+  }
+}
+
+bool lmhead_mfma_supported(const AcceptLaunch& a) {
+  return a.bf16 && a.H % kLmBK == 0 && a.H >= kLmBK && a.V >= 1 &&
+         (((uintptr_t)a.hidden | (uintptr_t)a.lm_head) & 15) == 0;
+}
+
+int lmhead_mfma_stat_tile() { return kLmWaveV; }
+
+template <int NT>
+static hipError_t launch_nt(const AcceptLaunch& a, hipStream_t st, int m_tiles) {
+  constexpr int lds_bytes = kLmStages * (kLmWBytes + NT * 32 * kLmRowBytes);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)lmhead_mfma_kernel<NT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const float exp_scale = 1.4426950408889634f / (a.temperature > 0.f ? a.temperature : 1.f);
+  dim3 grid((a.V + kLmVTile - 1) / kLmVTile, m_tiles);
+  hipLaunchKernelGGL(lmhead_mfma_kernel<NT>, grid, dim3(kLmThreads), lds_bytes, st, (const bf16_t*)a.hidden,
+                     (const bf16_t*)a.lm_head, a.logits, a.pmax, a.psum, a.parg, (int)a.plan.rows, a.H, a.V,
+                     a.plan.n_tiles, exp_scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_lmhead_mfma(const AcceptLaunch& a, hipStream_t st) {
+  const int M = (int)a.plan.rows;
+  // token rows per workgroup: the fewest 160-row passes over W, each as narrow as the rows allow
+  const int passes = (M + 159) / 160;
+  const int per = (M + passes - 1) / passes;
+  const int nt = (per + 31) / 32;
+  const int m_tiles = (M + nt * 32 - 1) / (nt * 32);
+  switch (nt) {
+    case 1: return launch_nt<1>(a, st, m_tiles);
+    case 2: return launch_nt<2>(a, st, m_tiles);
+    case 3: return launch_nt<3>(a, st, m_tiles);
+    case 4: return launch_nt<4>(a, st, m_tiles);
+    default: return launch_nt<5>(a, st, m_tiles);
+  }
+}
+
 }  // namespace aurora

@@ -82,6 +82,9 @@ class DeviceVerify:
                                       self.next_token, self.accept_mask, self.p_at_draft, self.row_lse,
                                       self.workspace, stream)
 
+    def lmhead(self, stream=None):
+        return B.aurora_verify_lmhead(self.accept_desc, self.hidden, self.lm_head, self.workspace, stream)
+
     def verify(self, stream=None):
         return B.aurora_verify(self.attn_desc, self.accept_desc, self.q, self.k_pages, self.v_pages,
                                self.block_table, self.seq_lens, self.parents, self.attn_out, self.hidden,
