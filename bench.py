@@ -51,7 +51,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama", choices=["llama", "tiny", "qwen_greedy", "tree"])
     ap.add_argument("--seed", type=int, default=1)
-    ap.add_argument("--cpu-sample", type=int, default=8, help="requests given to the CPU oracle (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding of the "
