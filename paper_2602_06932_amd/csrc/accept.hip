@@ -2,16 +2,22 @@
 // 3.3: the target keeps a prefix of the drafted chain - or a root-to-node path of the drafted
 // tree - and emits one more token; accepted and rejected positions are both reported).
 //
-// One workgroup of 1024 threads per request.  Inputs are the fp32 logits written by the LM-head
-// kernel and the per-(row, vocab tile) softmax statistics (max, sum exp, arg-max).
-//   1. merge the tile statistics of each of the request's Nq rows into (max, logsumexp, arg-max);
-//   2. walk: children of the current node in ascending index; the test u * q(tok) < p(tok) is
-//      evaluated by thread 0 in fp64; after a rejection the whole workgroup sweeps the row pair
-//      (logits, q) once to get the residual mass Z of max(0, p - q) and its sums over groups of
-//      consecutive tokens;
-//   3. inverse-CDF draw: exclusive scan of the group sums, pick the group the threshold u * total
-//      falls in, rescan that group with a wavefront prefix sum to find the token.
-// All sums are fp64 with a fixed reduction order, so results are reproducible bit for bit.
+// Inputs are the fp32 logits written by the LM-head kernel and the per-(row, vocab tile) softmax
+// statistics (max, sum exp, arg-max) of its epilogue.
+//
+// Chains at T > 0 (the serving default) take three small kernels so that the one vocabulary sweep
+// a request needs is spread over the whole chip instead of one compute unit:
+//   accept_chain_walk   one workgroup per request: merge the tile statistics of the request's rows,
+//                       evaluate the k accept tests u * q(d) < p(d) in parallel (fp64), find the
+//                       first failure, write accept_len / accept_mask / p_at_draft / row_lse;
+//   accept_chain_sweep  S workgroups per request: sums of the draw weights - max(0, p - q) after a
+//                       rejection, p itself when every draft was kept - over groups of 256 tokens;
+//   accept_chain_pick   one workgroup per request: scan the group sums, find the group holding
+//                       u * total, rescan that group with wavefront prefix sums for the token.
+// Trees at T > 0 may need one sweep per rejected sibling, each depending on the previous one; they
+// run in one workgroup per request (accept_tree_kernel), which also serves every greedy (T = 0)
+// call, where no sweep exists.
+// All sums are fp64 in a fixed order: results are reproducible bit for bit.
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -19,14 +25,27 @@ namespace aurora {
 
 constexpr int kAccThreads = 1024;
 constexpr int kAccWaves = kAccThreads / kWave;
-constexpr int kMaxGroups = 4096;  // group sums kept in LDS (32 KB of doubles)
+constexpr int kMaxGroups = 4096;  // group sums kept in LDS by the tree kernel (32 KB of doubles)
+constexpr int kSmallThreads = 256;
 
-// Probability mass of token v at the current node after `nres` residual steps.
-// p0 = exp(l / T - lse);  p_{s+1} = max(0, p_s - q) / Z_s.  skip_last leaves the last step
-// unnormalised (the weights whose sum is Z_{nres-1}).
-__device__ __forceinline__ double node_weight(float l, float qv, double lse, double T, int nres, const double* Zs,
-                                              bool skip_last) {
+// Probability of token v at the current node after `nres` residual steps, in fp64 throughout (used
+// for the accept tests).  p0 = exp(l / T - lse);  p_{s+1} = max(0, p_s - q) / Z_s.
+__device__ __forceinline__ double node_weight(float l, float qv, double lse, double T, int nres, const double* Zs) {
   double x = exp((double)l / T - lse);
+  for (int s = 0; s < nres; ++s) x = fmax(0.0, x - (double)qv) / Zs[s];
+  return x;
+}
+
+// The same quantity for the vocabulary sweeps.  The exponent is formed in fp64 (so the row's
+// logsumexp enters unrounded), rounded once to fp32 and exponentiated by the hardware exp2, the
+// function the LM-head epilogue used for the statistics lse was merged from - a bias of that
+// function cancels between the two.  The fp32 rounding is an independent ~1e-7 relative
+// perturbation per token and averages out of the running sums.  skip_last leaves the last residual
+// step unnormalised (weights whose sum is Z_{nres-1}).
+__device__ __forceinline__ double sweep_weight(float l, float qv, double lse, double inv_t, int nres, const double* Zs,
+                                               bool skip_last) {
+  const double a = ((double)l * inv_t - lse) * 1.4426950408889634;
+  double x = (double)__builtin_amdgcn_exp2f((float)a);
   for (int s = 0; s < nres; ++s) {
     x = fmax(0.0, x - (double)qv);
     if (!(skip_last && s == nres - 1)) x /= Zs[s];
@@ -43,19 +62,8 @@ __device__ __forceinline__ double wave_incl_scan(double x, int lane) {
   return x;
 }
 
-// Sum over the workgroup in a fixed order; result returned to every thread.  `buf` holds kAccWaves doubles.
-__device__ __forceinline__ double block_sum(double x, double* buf, int lane, int wv) {
-  x = wave_sum(x);
-  __syncthreads();
-  if (lane == 0) buf[wv] = x;
-  __syncthreads();
-  double t = 0.0;
-  for (int i = 0; i < kAccWaves; ++i) t += buf[i];
-  return t;
-}
-
 struct AcceptParams {
-  int Nq, V, n_tiles;
+  int Nq, V, n_tiles, slices, gmul, ngroups;
   float temperature;
   const float* logits;
   const float* pmax;
@@ -70,53 +78,265 @@ struct AcceptParams {
   uint8_t* accept_mask;
   float* p_at_draft;
   float* row_lse;
+  // scratch of the chain path
+  double* st_lse;     // [B] logsumexp of the row the draw happens on
+  int32_t* st_row;    // [B] that row (= accept_len)
+  int32_t* st_rej;    // [B] 1: draw from max(0, p - q); 0: draw from p
+  double* gsum;       // [B, ngroups]
+  int32_t* lastpos;   // [B, slices] largest token with positive weight per slice, or -1
 };
 
-__global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptParams P) {
+// (max, logsumexp(l / T), arg-max) of row `n` of request-row base `row0`, merged from the tile
+// statistics by one wavefront; result valid in every lane.
+__device__ __forceinline__ void merge_row_stats(const AcceptParams& P, size_t row, double T, int lane, float* out_max,
+                                                double* out_lse, int* out_arg) {
+  const int nt = P.n_tiles;
+  const float* pm = P.pmax + row * nt;
+  const float* ps = P.psum + row * nt;
+  float mx = -INFINITY;
+  int mt = 0x7fffffff;
+  for (int t = lane; t < nt; t += kWave) {
+    const float x = pm[t];
+    if (x > mx) { mx = x; mt = t; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float om = __shfl_xor(mx, o, kWave);
+    const int ot = __shfl_xor(mt, o, kWave);
+    if (om > mx || (om == mx && ot < mt)) { mx = om; mt = ot; }
+  }
+  double s = 0.0;
+  for (int t = lane; t < nt; t += kWave) s += (double)ps[t] * exp(((double)pm[t] - (double)mx) / T);
+  s = wave_sum(s);
+  *out_max = mx;
+  *out_lse = (double)mx / T + log(s);
+  *out_arg = P.parg[row * nt + mt];
+}
+
+// ============================================================================================
+// Chain path, kernel 1: statistics merge, parallel accept tests, per-node outputs.
+// ============================================================================================
+__global__ __launch_bounds__(kSmallThreads) void accept_chain_walk(AcceptParams P) {
   __shared__ double s_lse[kMaxNq];
-  __shared__ float s_max[kMaxNq];
+  __shared__ int s_ok[kMaxNq];
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
+  const int Nq = P.Nq, V = P.V;
+  const double T = (double)P.temperature;
+  const size_t row0 = (size_t)b * Nq;
+  for (int n = wv; n < Nq; n += kSmallThreads / kWave) {
+    float mx; double lse; int arg;
+    merge_row_stats(P, row0 + n, T, lane, &mx, &lse, &arg);
+    if (lane == 0) s_lse[n] = lse;
+  }
+  __syncthreads();
+  if (tid < Nq) {
+    const int n = tid;
+    float pv = 0.f;
+    int ok = 1;
+    if (n > 0) {
+      const int tk = P.tok[row0 + n];
+      const float l = P.logits[(row0 + n - 1) * V + tk];
+      const float qv = P.q[(row0 + n - 1) * V + tk];
+      const double p = exp((double)l / T - s_lse[n - 1]);
+      const double u = (double)P.un[(row0 + n) * 2 + 0];
+      ok = (u * (double)qv < p) ? 1 : 0;
+      pv = (float)p;
+    }
+    s_ok[n] = ok;
+    if (P.p_at_draft) P.p_at_draft[row0 + n] = pv;
+    if (P.row_lse) P.row_lse[row0 + n] = (float)s_lse[n];
+  }
+  __syncthreads();
+  if (tid < Nq) {
+    int first_fail = Nq;
+    for (int n = 1; n < Nq; ++n)
+      if (!s_ok[n]) { first_fail = n; break; }
+    const int j = first_fail - 1;  // accepted drafts = index of the row the draw happens on
+    P.accept_mask[row0 + tid] = tid <= j ? 1 : 0;
+    if (tid == 0) {
+      P.accept_len[b] = j;
+      P.st_row[b] = j;
+      P.st_rej[b] = first_fail < Nq ? 1 : 0;
+      P.st_lse[b] = s_lse[j];
+    }
+  }
+}
+
+// ============================================================================================
+// Chain path, kernel 2: group sums of the draw weights over one slice of the vocabulary.
+// Group g covers tokens [g * 64 * gmul, (g+1) * 64 * gmul); lane i of the owning wavefront adds
+// tokens g*64*gmul + it*64 + i.
+// ============================================================================================
+__global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams P) {
+  __shared__ int s_last[kSmallThreads / kWave];
+  const int slice = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
+  const int V = P.V, gmul = P.gmul, GE = kWave * gmul;
+  const int row = P.st_row[b];
+  const int nres = P.st_rej[b];
+  const double lse = P.st_lse[b];
+  const double inv_t = 1.0 / (double)P.temperature;
+  const float* lrow = P.logits + ((size_t)b * P.Nq + row) * V;
+  const float* qrow = P.q + ((size_t)b * P.Nq + row) * V;
+  const int per = (P.ngroups + P.slices - 1) / P.slices;
+  const int g0 = slice * per, g1 = min(P.ngroups, g0 + per);
+  int lastpos = -1;
+  for (int g = g0 + wv; g < g1; g += kSmallThreads / kWave) {
+    double acc = 0.0;
+    for (int it = 0; it < gmul; ++it) {
+      const int v = g * GE + it * kWave + lane;
+      if (v < V) {
+        const double x = sweep_weight(lrow[v], qrow[v], lse, inv_t, nres, nullptr, true);
+        acc += x;
+        if (x > 0.0) lastpos = v;
+      }
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) P.gsum[(size_t)b * P.ngroups + g] = acc;
+  }
+  lastpos = wave_max(lastpos);
+  if (lane == 0) s_last[wv] = lastpos;
+  __syncthreads();
+  if (tid == 0) {
+    int m = -1;
+    for (int i = 0; i < kSmallThreads / kWave; ++i) m = max(m, s_last[i]);
+    P.lastpos[(size_t)b * P.slices + slice] = m;
+  }
+}
+
+// ============================================================================================
+// Chain path, kernel 3: inverse-CDF draw from the group sums.
+// A residual that vanished (sum 0) falls back to the row's p: rare enough for one workgroup.
+// ============================================================================================
+__global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams P) {
+  __shared__ double s_wtot[kSmallThreads / kWave];
+  __shared__ int s_pick;
+  __shared__ double s_prefix;
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
+  const int V = P.V, gmul = P.gmul, GE = kWave * gmul, ng = P.ngroups;
+  const int row = P.st_row[b];
+  int nres = P.st_rej[b];
+  const double lse = P.st_lse[b];
+  const double inv_t = 1.0 / (double)P.temperature;
+  const float* lrow = P.logits + ((size_t)b * P.Nq + row) * V;
+  const float* qrow = P.q + ((size_t)b * P.Nq + row) * V;
+  double* gs = P.gsum + (size_t)b * ng;
+  const int per = (ng + kSmallThreads - 1) / kSmallThreads;
+  const int ga = min(ng, tid * per), gb = min(ng, ga + per);
+
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    double loc = 0.0;
+    for (int g = ga; g < gb; ++g) loc += gs[g];
+    const double incl = wave_incl_scan(loc, lane);
+    if (lane == kWave - 1) s_wtot[wv] = incl;
+    if (tid == 0) s_pick = 0x7fffffff;
+    __syncthreads();
+    double wbase = 0.0, total = 0.0;
+    for (int i = 0; i < kSmallThreads / kWave; ++i) {
+      if (i < wv) wbase += s_wtot[i];
+      total += s_wtot[i];
+    }
+    if (total > 0.0 || nres == 0) {
+      const double thr = (double)P.un[((size_t)b * P.Nq + row) * 2 + 1] * total;
+      double run = wbase + incl - loc;
+      int found = 0x7fffffff;
+      double before = 0.0;
+      for (int g = ga; g < gb; ++g) {
+        const double nxt = run + gs[g];
+        if (found == 0x7fffffff && nxt > thr) { found = g; before = run; }
+        run = nxt;
+      }
+      if (found != 0x7fffffff) atomicMin(&s_pick, found);
+      __syncthreads();
+      const int pick = s_pick;
+      if (pick == found && found != 0x7fffffff) s_prefix = before;
+      __syncthreads();
+      if (wv == 0) {
+        int token = -1;
+        if (pick != 0x7fffffff) {
+          double run2 = s_prefix;
+          int last_in_group = -1;
+          bool done = false;
+          for (int it = 0; it < gmul && !done; ++it) {
+            const int v = pick * GE + it * kWave + lane;
+            const double x = v < V ? sweep_weight(lrow[v], qrow[v], lse, inv_t, nres, nullptr, true) : 0.0;
+            const double inc = wave_incl_scan(x, lane) + run2;
+            const unsigned long long hit = __ballot(v < V && inc > thr);
+            const unsigned long long pos = __ballot(x > 0.0);
+            if (hit) {
+              token = pick * GE + it * kWave + (__ffsll((long long)hit) - 1);
+              done = true;
+            } else {
+              if (pos) last_in_group = pick * GE + it * kWave + (63 - __clzll((long long)pos));
+              run2 = __shfl(inc, kWave - 1, kWave);
+            }
+          }
+          if (!done) token = last_in_group;
+        }
+        if (token < 0) {  // rounding left no crossing: the largest token with positive weight
+          int m = -1;
+          for (int i = lane; i < P.slices; i += kWave) m = max(m, P.lastpos[(size_t)b * P.slices + i]);
+          token = wave_max(m);
+        }
+        if (lane == 0) P.next_token[b] = token;
+      }
+      return;
+    }
+    // residual identically zero: recompute the group sums of p itself with this workgroup, then draw
+    __syncthreads();
+    nres = 0;
+    int lastpos = -1;
+    for (int g = wv; g < ng; g += kSmallThreads / kWave) {
+      double acc = 0.0;
+      for (int it = 0; it < gmul; ++it) {
+        const int v = g * GE + it * kWave + lane;
+        if (v < V) {
+          const double x = sweep_weight(lrow[v], qrow[v], lse, inv_t, 0, nullptr, true);
+          acc += x;
+          if (x > 0.0) lastpos = v;
+        }
+      }
+      acc = wave_sum(acc);
+      if (lane == 0) gs[g] = acc;
+    }
+    lastpos = wave_max(lastpos);
+    if (lane == 0) atomicMax(&P.lastpos[(size_t)b * P.slices], lastpos);
+    __threadfence_block();
+    __syncthreads();
+  }
+}
+
+// ============================================================================================
+// One workgroup per request: trees at T > 0, and every greedy call.
+// ============================================================================================
+__global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P) {
+  __shared__ double s_lse[kMaxNq];
   __shared__ int s_arg[kMaxNq];
   __shared__ double s_Z[kMaxNq];
   __shared__ double s_gsum[kMaxGroups];
   __shared__ double s_wtot[kAccWaves];
-  __shared__ double s_red[kAccWaves];
-  __shared__ int s_cur, s_depth, s_nres, s_last_child, s_state, s_have_gsum, s_exact_node, s_pick, s_lastpos;
-  __shared__ double s_lse_cur, s_pick_prefix;
+  __shared__ int s_cur, s_depth, s_nres, s_last_child, s_state, s_have_gsum, s_pick, s_lastpos;
+  __shared__ double s_pick_prefix;
 
   const int b = blockIdx.x;
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
-  const int Nq = P.Nq, V = P.V, nt = P.n_tiles;
+  const int Nq = P.Nq, V = P.V;
   const bool greedy = !(P.temperature > 0.f);
   const double T = greedy ? 1.0 : (double)P.temperature;
+  const double inv_t = 1.0 / T;
   const size_t row0 = (size_t)b * Nq;
 
-  // ---- 1. per-row (max, logsumexp, arg-max) from the tile statistics -----------------------
+  // ---- 1. per-row (logsumexp, arg-max) from the tile statistics ---------------------------------
   for (int n = wv; n < Nq; n += kAccWaves) {
-    const float* pm = P.pmax + (row0 + n) * nt;
-    const float* ps = P.psum + (row0 + n) * nt;
-    float mx = -INFINITY;
-    int mt = 0x7fffffff;
-    for (int t = lane; t < nt; t += kWave) {
-      const float x = pm[t];
-      if (x > mx) { mx = x; mt = t; }
-    }
-    for (int o = 32; o > 0; o >>= 1) {
-      const float om = __shfl_xor(mx, o, kWave);
-      const int ot = __shfl_xor(mt, o, kWave);
-      if (om > mx || (om == mx && ot < mt)) { mx = om; mt = ot; }
-    }
-    double s = 0.0;
-    for (int t = lane; t < nt; t += kWave) s += (double)ps[t] * exp(((double)pm[t] - (double)mx) / T);
-    s = wave_sum(s);
-    if (lane == 0) {
-      s_max[n] = mx;
-      s_arg[n] = P.parg[(row0 + n) * nt + mt];
-      s_lse[n] = (double)mx / T + log(s);
-    }
+    float mx; double lse; int arg;
+    merge_row_stats(P, row0 + n, T, lane, &mx, &lse, &arg);
+    if (lane == 0) { s_lse[n] = lse; s_arg[n] = arg; }
   }
   __syncthreads();
 
-  // ---- optional per-node outputs ---------------------------------------------------------------
+  // ---- per-node outputs ------------------------------------------------------------------------
   if (tid < Nq) {
     const int n = tid;
     if (P.row_lse) P.row_lse[row0 + n] = (float)s_lse[n];
@@ -159,11 +379,10 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptParams P) {
 
   // ---- 2b. sampling walk ------------------------------------------------------------------------
   const int gmul = (V + kWave * kMaxGroups - 1) / (kWave * kMaxGroups);
-  const int GE = kWave * gmul;               // tokens per group
-  const int ngroups = (V + GE - 1) / GE;     // <= kMaxGroups
+  const int GE = kWave * gmul;            // tokens per group
+  const int ngroups = (V + GE - 1) / GE;  // <= kMaxGroups
   if (tid == 0) {
-    s_cur = 0; s_depth = 0; s_nres = 0; s_last_child = 0; s_have_gsum = 0; s_exact_node = -1;
-    s_lse_cur = s_lse[0];
+    s_cur = 0; s_depth = 0; s_nres = 0; s_last_child = 0; s_have_gsum = 0;
   }
   enum { ST_DONE = 0, ST_ACCEPTED = 1, ST_REJECTED = 2 };
   for (;;) {
@@ -181,7 +400,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptParams P) {
         const int tk = P.tok[row0 + c];
         const float l = P.logits[(row0 + cur) * V + tk];
         const float qv = P.q[(row0 + cur) * V + tk];
-        const double p = node_weight(l, qv, s_lse_cur, T, s_nres, s_Z, false);
+        const double p = node_weight(l, qv, s_lse[cur], T, s_nres, s_Z);
         const double u = (double)P.un[(row0 + c) * 2 + 0];
         s_last_child = c;
         if (u * (double)qv < p) {
@@ -189,8 +408,6 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptParams P) {
           s_depth = s_depth + 1;
           s_nres = 0;
           s_have_gsum = 0;
-          s_lse_cur = s_lse[c];
-          s_exact_node = -1;
           P.accept_mask[row0 + c] = 1;
           s_state = ST_ACCEPTED;
         } else {
@@ -205,35 +422,20 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptParams P) {
     const int cur = s_cur;
     const float* lrow = P.logits + (row0 + cur) * V;
     const float* qrow = P.q + (row0 + cur) * V;
-    const bool need_sweep = state == ST_REJECTED || !s_have_gsum;
+    const double lse = s_lse[cur];
 
-    if (need_sweep && s_exact_node != cur) {
-      // logsumexp of this row again, now in fp64 straight from the fp32 logits, so that the
-      // row's probabilities sum to one to fp64 accuracy before differences with q are taken
-      const double mx = (double)s_max[cur];
-      double acc = 0.0;
-      for (int v = tid; v < V; v += kAccThreads) acc += exp(((double)lrow[v] - mx) / T);
-      const double tot = block_sum(acc, s_red, lane, wv);
-      if (tid == 0) {
-        s_lse_cur = mx / T + log(tot);
-        s_exact_node = cur;
-      }
-      __syncthreads();
-    }
-
-    if (need_sweep) {
+    if (state == ST_REJECTED || !s_have_gsum) {
       // group sums of the weights: after a rejection the unnormalised next residual level,
       // otherwise (nothing rejected at this node, or its residual vanished) the current level
       const int nres = state == ST_REJECTED ? s_nres + 1 : s_nres;
       const bool skip_last = state == ST_REJECTED;
-      const double lse = s_lse_cur;
       int lastpos = -1;
       for (int g = wv; g < ngroups; g += kAccWaves) {
         double acc = 0.0;
         for (int it = 0; it < gmul; ++it) {
           const int v = g * GE + it * kWave + lane;
           if (v < V) {
-            const double x = node_weight(lrow[v], qrow[v], lse, T, nres, s_Z, skip_last);
+            const double x = sweep_weight(lrow[v], qrow[v], lse, inv_t, nres, s_Z, skip_last);
             acc += x;
             if (x > 0.0) lastpos = v;
           }
@@ -310,13 +512,12 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptParams P) {
       if (pick != 0x7fffffff) {
         const bool have = s_have_gsum;
         const int nres = s_nres;
-        const double lse = s_lse_cur;
         double run = s_pick_prefix;
         int last_in_group = -1;
         bool done = false;
         for (int it = 0; it < gmul && !done; ++it) {
           const int v = pick * GE + it * kWave + lane;
-          const double x = v < V ? node_weight(lrow[v], qrow[v], lse, T, nres, s_Z, have) : 0.0;
+          const double x = v < V ? sweep_weight(lrow[v], qrow[v], lse, inv_t, nres, s_Z, have) : 0.0;
           const double inc = wave_incl_scan(x, lane) + run;
           const unsigned long long hit = __ballot(v < V && inc > thr);
           const unsigned long long pos = __ballot(x > 0.0);
@@ -339,14 +540,40 @@ __global__ __launch_bounds__(kAccThreads) void accept_kernel(AcceptParams P) {
   }
 }
 
+void accept_chain_geometry(int batch, int vocab, int* slices, int* gmul, int* ngroups) {
+  int gm = 4;
+  while ((vocab + kWave * gm - 1) / (kWave * gm) > 16384) gm *= 2;
+  const int ng = (vocab + kWave * gm - 1) / (kWave * gm);
+  int s = (1024 + batch - 1) / (batch > 0 ? batch : 1);
+  if (s > (ng + 3) / 4) s = (ng + 3) / 4;
+  if (s < 1) s = 1;
+  if (s > 64) s = 64;
+  *slices = s;
+  *gmul = gm;
+  *ngroups = ng;
+}
+
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st) {
-  AcceptParams P;
+  AcceptParams P = {};
   P.Nq = a.Nq; P.V = a.V; P.n_tiles = a.plan.n_tiles; P.temperature = a.temperature;
   P.logits = a.logits; P.pmax = a.pmax; P.psum = a.psum; P.parg = a.parg;
   P.tok = a.draft_tokens; P.q = a.draft_probs; P.un = a.uniforms; P.parents = a.parents;
   P.accept_len = a.accept_len; P.next_token = a.next_token; P.accept_mask = a.accept_mask;
   P.p_at_draft = a.p_at_draft; P.row_lse = a.row_lse;
-  hipLaunchKernelGGL(accept_kernel, dim3(a.B), dim3(kAccThreads), 0, st, P);
+  P.slices = a.plan.slices; P.gmul = a.plan.gmul; P.ngroups = a.plan.ngroups;
+  P.st_lse = a.st_lse; P.st_row = a.st_row; P.st_rej = a.st_rej; P.gsum = a.gsum; P.lastpos = a.lastpos;
+  const bool chain_sampling = a.temperature > 0.f && a.parents == nullptr;
+  if (!chain_sampling) {
+    hipLaunchKernelGGL(accept_tree_kernel, dim3(a.B), dim3(kAccThreads), 0, st, P);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(accept_chain_walk, dim3(a.B), dim3(kSmallThreads), 0, st, P);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(accept_chain_sweep, dim3(P.slices, a.B), dim3(kSmallThreads), 0, st, P);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(accept_chain_pick, dim3(a.B), dim3(kSmallThreads), 0, st, P);
   return hipGetLastError();
 }
 

@@ -78,7 +78,14 @@ AcceptPlan plan_accept(const aurora_accept_desc* d) {
   p.pmax_off = align_up(rows * d->vocab * sizeof(float));
   p.psum_off = p.pmax_off + align_up(rows * p.n_tiles * sizeof(float));
   p.parg_off = p.psum_off + align_up(rows * p.n_tiles * sizeof(float));
-  p.bytes = p.parg_off + align_up(rows * p.n_tiles * sizeof(int32_t));
+  accept_chain_geometry(d->batch, d->vocab, &p.slices, &p.gmul, &p.ngroups);
+  const size_t B = (size_t)d->batch;
+  p.st_lse_off = p.parg_off + align_up(rows * p.n_tiles * sizeof(int32_t));
+  p.st_row_off = p.st_lse_off + align_up(B * sizeof(double));
+  p.st_rej_off = p.st_row_off + align_up(B * sizeof(int32_t));
+  p.gsum_off = p.st_rej_off + align_up(B * sizeof(int32_t));
+  p.lastpos_off = p.gsum_off + align_up(B * p.ngroups * sizeof(double));
+  p.bytes = p.lastpos_off + align_up(B * p.slices * sizeof(int32_t));
   return p;
 }
 
@@ -124,6 +131,11 @@ int run_accept(const aurora_accept_desc* desc, const void* hidden, const void* l
   a.pmax = (float*)(ws + plan.pmax_off);
   a.psum = (float*)(ws + plan.psum_off);
   a.parg = (int32_t*)(ws + plan.parg_off);
+  a.st_lse = (double*)(ws + plan.st_lse_off);
+  a.st_row = (int32_t*)(ws + plan.st_row_off);
+  a.st_rej = (int32_t*)(ws + plan.st_rej_off);
+  a.gsum = (double*)(ws + plan.gsum_off);
+  a.lastpos = (int32_t*)(ws + plan.lastpos_off);
   a.plan = plan;
   hipError_t e = lmhead_mfma_supported(a) ? launch_lmhead_mfma(a, st) : launch_lmhead_generic(a, st);
   if (e != hipSuccess) return AURORA_ERR_HIP;

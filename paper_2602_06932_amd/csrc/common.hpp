@@ -62,7 +62,10 @@ struct AcceptPlan {
   int64_t rows;     // M = B * Nq
   int stat_tile;    // vocab columns per softmax-statistics partial
   int n_tiles;      // ceil(V / stat_tile)
-  size_t logits_off, pmax_off, psum_off, parg_off, bytes;
+  int slices;       // chain draw: workgroups per request in the vocabulary sweep
+  int gmul;         // chain draw: a group is 64 * gmul consecutive tokens
+  int ngroups;      // chain draw: ceil(V / (64 * gmul))
+  size_t logits_off, pmax_off, psum_off, parg_off, st_lse_off, st_row_off, st_rej_off, gsum_off, lastpos_off, bytes;
 };
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }

@@ -27,6 +27,8 @@ struct AcceptLaunch {
   float *p_at_draft, *row_lse;
   float *logits, *pmax, *psum;
   int32_t* parg;
+  double *st_lse, *gsum;
+  int32_t *st_row, *st_rej, *lastpos;
   AcceptPlan plan;
 };
 
@@ -43,6 +45,7 @@ hipError_t launch_lmhead_mfma(const AcceptLaunch& a, hipStream_t st);
 hipError_t launch_lmhead_generic(const AcceptLaunch& a, hipStream_t st);
 
 // acceptance walk + residual / bonus draw
+void accept_chain_geometry(int batch, int vocab, int* slices, int* gmul, int* ngroups);
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st);
 
 }  // namespace aurora

@@ -174,3 +174,24 @@ def test_optional_outputs_may_be_null(gpu_lib):
                         uniforms=w.uniforms, dtype=w.dtype, temperature=1.0)
     assert np.array_equal(r["accept_len"], ref.accept_len) and np.array_equal(r["next_token"], ref.next_token)
     assert np.isnan(r["row_lse"]).all()
+
+
+def test_vanishing_residual_falls_back_to_p(gpu_lib):
+    """q >= p everywhere (q = 1 for every token): every first test fails unless u is tiny, the residual
+    max(0, p - q) is identically zero, and the corrected token must be drawn from p itself."""
+    w = gen.llama_chain(11, batch=6, len_lo=20, len_hi=60, vocab=3000, hidden_size=128)
+    w.draft_probs = np.ones_like(w.draft_probs)
+    _, a = _full_check(gpu_lib, w)
+    assert (a.accept_len == 0).all()
+    wt = gen.llama_tree(12, batch=4, num_q=9, context=40, vocab=3000, hidden_size=128)
+    wt.draft_probs = np.ones_like(wt.draft_probs)
+    _, a = _full_check(gpu_lib, wt)
+    assert (a.accept_len == 0).all()
+
+
+# ---------------------------------------------------------------- full-size configurations
+def test_full_size_llama_chain(gpu_lib):
+    """The benchmark workload exactly as bench.py launches it; every request checked."""
+    w = gen.llama_chain(1)
+    _, a = _full_check(gpu_lib, w)
+    assert 0.8 < a.accept_len.mean() < 2.2  # E[accepted drafts] = 1.38 for this recipe
