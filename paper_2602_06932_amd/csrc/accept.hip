@@ -86,30 +86,54 @@ struct AcceptParams {
   int32_t* lastpos;   // [B, slices] largest token with positive weight per slice, or -1
 };
 
-// (max, logsumexp(l / T), arg-max) of row `n` of request-row base `row0`, merged from the tile
-// statistics by one wavefront; result valid in every lane.
+// (max, logsumexp(l / T), arg-max) of one logits row, merged from its tile statistics by one
+// wavefront; result valid in every lane.  Each lane folds its tiles into a running (max, scaled
+// sum) pair - the loads of eight tiles are issued together - then the lanes are folded by
+// butterfly exchanges.  Scale factors go through the hardware exp2 of an fp64-formed exponent.
 __device__ __forceinline__ void merge_row_stats(const AcceptParams& P, size_t row, double T, int lane, float* out_max,
                                                 double* out_lse, int* out_arg) {
   const int nt = P.n_tiles;
   const float* pm = P.pmax + row * nt;
   const float* ps = P.psum + row * nt;
-  float mx = -INFINITY;
+  const double c = 1.4426950408889634 / T;
+  float m = -INFINITY;
+  double s = 0.0;
   int mt = 0x7fffffff;
-  for (int t = lane; t < nt; t += kWave) {
-    const float x = pm[t];
-    if (x > mx) { mx = x; mt = t; }
+  for (int t0 = 0; t0 < nt; t0 += kWave * 8) {
+    float xm[8], xs[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int t = t0 + u * kWave + lane;
+      xm[u] = t < nt ? pm[t] : -INFINITY;
+      xs[u] = t < nt ? ps[t] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (xm[u] > m) {
+        s = s * (double)__builtin_amdgcn_exp2f((float)(((double)m - (double)xm[u]) * c)) + (double)xs[u];
+        m = xm[u];
+        mt = t0 + u * kWave + lane;
+      } else if (xm[u] > -INFINITY) {
+        s += (double)xs[u] * (double)__builtin_amdgcn_exp2f((float)(((double)xm[u] - (double)m) * c));
+      }
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
-    const float om = __shfl_xor(mx, o, kWave);
+    const float om = __shfl_xor(m, o, kWave);
+    const double os = __shfl_xor(s, o, kWave);
     const int ot = __shfl_xor(mt, o, kWave);
-    if (om > mx || (om == mx && ot < mt)) { mx = om; mt = ot; }
+    const float nm = fmaxf(m, om);
+    if (nm > -INFINITY) {
+      const double fa = m > -INFINITY ? (double)__builtin_amdgcn_exp2f((float)(((double)m - (double)nm) * c)) : 0.0;
+      const double fb = om > -INFINITY ? (double)__builtin_amdgcn_exp2f((float)(((double)om - (double)nm) * c)) : 0.0;
+      s = s * fa + os * fb;
+    }
+    if (om > m || (om == m && ot < mt)) mt = ot;
+    m = nm;
   }
-  double s = 0.0;
-  for (int t = lane; t < nt; t += kWave) s += (double)ps[t] * exp(((double)pm[t] - (double)mx) / T);
-  s = wave_sum(s);
-  *out_max = mx;
-  *out_lse = (double)mx / T + log(s);
+  *out_max = m;
+  *out_lse = (double)m / T + log(s);
   *out_arg = P.parg[row * nt + mt];
 }
 

@@ -96,27 +96,24 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
   const int ntile = (end - start + kAtTile - 1) / kAtTile;
   const int32_t* bt = block_table + (size_t)b * max_pages;
 
-  // ---- tile loads: 8 instructions of 4 token rows each, zero fill past the end of the sequence ----
+  // ---- tile loads: always exactly 8 instructions of 4 token rows each (the s_waitcnt bookkeeping
+  // below counts them).  Rows past the end of the sequence re-read the last valid token; their
+  // scores are masked to -inf, so their (finite) values are multiplied by exact zeros.
   const int lrow = lane >> 4;    // token row within a 4-row instruction
   const int lpos = lane & 15;    // 16-byte slot within the row
+  const int page_mask = (1 << page_shift) - 1;
   auto issue_tile = [&](const bf16_t* pool, char* buf, int tt) {
     const int j0 = start + tt * kAtTile;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const int tok0 = j0 + 4 * j;           // wave-uniform
-      const int tok = tok0 + lrow;
-      int pid = 0;
-      if (tok0 < L) pid = bt[tok0 >> page_shift];
+      const int tok0 = min(j0 + 4 * j, L - 1);  // wave-uniform
+      const int tok = min(tok0 + lrow, L - 1);  // same page as tok0
+      const int pid = bt[tok0 >> page_shift];
       const int r = 4 * j + lrow;
       const int chunk = lpos ^ (r & 7);
-      if (tok < L) {
-        const bf16_t* src =
-            pool + ((((size_t)pid * Hkv + hk) << page_shift) + (tok & ((1 << page_shift) - 1))) * kAtD + chunk * 8;
-        __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(buf + j * 1024), 16, 0, 0);
-      } else {
-        u32x4_t z = {0u, 0u, 0u, 0u};
-        *(u32x4_t*)(buf + j * 1024 + lane * 16) = z;
-      }
+      const bf16_t* src =
+          pool + ((((size_t)pid * Hkv + hk) << page_shift) + (tok & page_mask)) * kAtD + chunk * 8;
+      __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(buf + j * 1024), 16, 0, 0);
     }
   };
 

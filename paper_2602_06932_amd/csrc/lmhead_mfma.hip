@@ -70,9 +70,15 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     hsrc[j] = hidden + (size_t)row * H + chunk * 8;
   }
 
+  // Workgroups start their walk over the hidden dimension at different offsets (and wrap around):
+  // rows are a multiple of the memory-channel interleave apart, so workgroups marching through k
+  // in lockstep would all hit the same few HBM channels at any moment.
+  const int ks0 = (int)((blockIdx.x * 13u + blockIdx.y * 7u) % (unsigned)nk);
   auto issue = [&](int ks, int buf) {
     char* base = lds + buf * kStageBytes;
-    const int koff = ks * kLmBK;
+    int kk = ks + ks0;
+    kk = kk >= nk ? kk - nk : kk;
+    const int koff = kk * kLmBK;
 #pragma unroll
     for (int j = 0; j < 8; ++j)
       __builtin_amdgcn_global_load_lds(GLB_PTR(wsrc[j] + koff), LDS_PTR(base + (wv * kLmWaveV + 8 * j) * kLmRowBytes),
@@ -122,10 +128,15 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     }
   }
 
-  // ---- epilogue: logits out, and (max, arg-max, sum exp) of this wavefront's 64 vocab rows ----------
-  // accumulator register r of tile a holds vocab row  vrow0 + 32a + 8(r/4) + 4*lh + r%4  of token m0 + 32t + li
+  // ---- epilogue: logits out, and (max, arg-max, sum exp) of the workgroup's 256 vocab rows ---------
+  // accumulator register r of tile a holds vocab row  vrow0 + 32a + 8(r/4) + 4*lh + r%4  of token m0 + 32t + li.
+  // Each wavefront reduces its 64 rows per token in registers and parks the triple in an LDS stage
+  // that the main loop no longer touches; after one barrier the first 32*NT threads merge the four
+  // wavefronts (ascending vocab order, so ties keep the lowest index).
+  float* st_max = (float*)(lds + (nk % kLmStages) * kStageBytes);
+  float* st_sum = st_max + 4 * NT * 32;
+  int* st_arg = (int*)(st_sum + 4 * NT * 32);
   const int vrow0 = vbase + wv * kLmWaveV;
-  const int stat_tile = blockIdx.x * (kLmVTile / kLmWaveV) + wv;
   const bool vec_ok = (V & 3) == 0;
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
@@ -152,18 +163,19 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     const float omx = __shfl_xor(mx, 32, kWave);
     const int oarg = __shfl_xor(arg, 32, kWave);
     if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
+    const float mx_safe = mx == -INFINITY ? 0.f : mx;
     float sum = 0.f;
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f((acc[a][t][r] - mx) * exp_scale);
+      for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f((acc[a][t][r] - mx_safe) * exp_scale);
     sum += __shfl_xor(sum, 32, kWave);
+    if (lh == 0) {
+      st_max[wv * NT * 32 + t * 32 + li] = mx;
+      st_sum[wv * NT * 32 + t * 32 + li] = sum;
+      st_arg[wv * NT * 32 + t * 32 + li] = arg;
+    }
     if (m_ok) {
-      if (lh == 0 && stat_tile < n_tiles) {
-        pmax[(size_t)m * n_tiles + stat_tile] = mx;
-        psum[(size_t)m * n_tiles + stat_tile] = sum;
-        parg[(size_t)m * n_tiles + stat_tile] = arg;
-      }
       float* lrow = logits + (size_t)m * V;
 #pragma unroll
       for (int a = 0; a < 2; ++a)
@@ -181,6 +193,29 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
         }
     }
   }
+  __syncthreads();
+  if (tid < NT * 32) {
+    const int m = m0 + tid;
+    if (m < M) {
+      float mx = -INFINITY;
+      int arg = 0x7fffffff;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float x = st_max[w * NT * 32 + tid];
+        if (x > mx) { mx = x; arg = st_arg[w * NT * 32 + tid]; }
+      }
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float x = st_max[w * NT * 32 + tid];
+        if (x > -INFINITY) sum += st_sum[w * NT * 32 + tid] * __builtin_amdgcn_exp2f((x - mx) * exp_scale);
+      }
+      const size_t o = (size_t)m * n_tiles + blockIdx.x;
+      pmax[o] = mx;
+      psum[o] = sum;
+      parg[o] = arg;
+    }
+  }
 }
 
 bool lmhead_mfma_supported(const AcceptLaunch& a) {
@@ -188,7 +223,7 @@ bool lmhead_mfma_supported(const AcceptLaunch& a) {
          (((uintptr_t)a.hidden | (uintptr_t)a.lm_head) & 15) == 0;
 }
 
-int lmhead_mfma_stat_tile() { return kLmWaveV; }
+int lmhead_mfma_stat_tile() { return kLmVTile; }
 
 template <int NT>
 static hipError_t launch_nt(const AcceptLaunch& a, hipStream_t st, int m_tiles) {
