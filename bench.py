@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--workload", default="llama", choices=["llama", "tiny", "qwen_greedy", "tree"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
+    ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "copy"],
+                    help="profiling aid: launch only this stage --steps times (after --warmup) and exit; "
+                         "'copy' runs a plain device-to-device copy of 1 GiB for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding of the "
@@ -70,6 +73,20 @@ def main():
     gen_s = time.time() - t0
     dv = DeviceVerify(w)
     torch.cuda.synchronize()
+
+    if args.stage:
+        if args.stage == "copy":
+            src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            dst = torch.empty_like(src)
+            fn = lambda: dst.copy_(src)
+        else:
+            fn = getattr(dv, args.stage)
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        ms = event_time_ms(fn, args.steps, torch)
+        print(json.dumps({"stage": args.stage, "steps": args.steps, "avg_ms": ms, "workload": w.name}))
+        return
 
     # ---- timed region: K whole verify steps -------------------------------------------------------
     for _ in range(args.warmup):

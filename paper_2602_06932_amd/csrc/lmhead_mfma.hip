@@ -24,13 +24,16 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-constexpr int kLmThreads = 256;
+constexpr int kLmThreads = 512;                // 4 consumer + 4 producer wavefronts
 constexpr int kLmBK = 64;                      // hidden elements per stage
 constexpr int kLmRowBytes = kLmBK * 2;         // 128
 constexpr int kLmVTile = 256;                  // vocab rows per workgroup
 constexpr int kLmWaveV = 64;                   // vocab rows per wavefront (= statistics tile)
 constexpr int kLmStages = 3;
 constexpr int kLmWBytes = kLmVTile * kLmRowBytes;  // 32 KB
+// cache-policy operand of the LDS-direct load: "non-temporal".  W is read exactly once, so it should
+// not displace the hidden-state rows that every workgroup re-reads from L2.
+constexpr int kCpolNT = 2;
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
@@ -45,50 +48,70 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     float exp_scale /* log2(e) / T */) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   constexpr int kStageBytes = kLmWBytes + NT * 32 * kLmRowBytes;
-  constexpr int kLoadsPerStage = 8 + NT;  // global->LDS instructions per wavefront per stage
+  constexpr int kLoadsPerStage = 8 + NT;  // global->LDS instructions per producer wavefront per stage
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool producer = wave >= 4;
+  const int wv = wave & 3;  // vocab slice: consumer wv multiplies the rows producer wv + 4 brings in
   const int vbase = blockIdx.x * kLmVTile;
   const int m0 = blockIdx.y * (NT * 32);
   const int nk = H / kLmBK;
-
-  // ---- per-lane source pointers (rows clamped into range; out-of-range rows are masked later) ----
-  const int sub = lane >> 3;                 // row within an 8-row load instruction
-  const int chunk = (lane & 7) ^ sub;        // swizzled 16-byte chunk this lane fetches
-  const bf16_t* wsrc[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    int row = vbase + wv * kLmWaveV + 8 * j + sub;
-    row = row < V ? row : V - 1;
-    wsrc[j] = w + (size_t)row * H + chunk * 8;
-  }
-  const bf16_t* hsrc[NT];
-#pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    int row = m0 + 8 * (wv * NT + j) + sub;
-    row = row < M ? row : M - 1;
-    hsrc[j] = hidden + (size_t)row * H + chunk * 8;
-  }
-
   // Workgroups start their walk over the hidden dimension at different offsets (and wrap around):
   // rows are a multiple of the memory-channel interleave apart, so workgroups marching through k
   // in lockstep would all hit the same few HBM channels at any moment.
   const int ks0 = (int)((blockIdx.x * 13u + blockIdx.y * 7u) % (unsigned)nk);
-  auto issue = [&](int ks, int buf) {
-    char* base = lds + buf * kStageBytes;
-    int kk = ks + ks0;
-    kk = kk >= nk ? kk - nk : kk;
-    const int koff = kk * kLmBK;
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-      __builtin_amdgcn_global_load_lds(GLB_PTR(wsrc[j] + koff), LDS_PTR(base + (wv * kLmWaveV + 8 * j) * kLmRowBytes),
-                                       16, 0, 0);
-#pragma unroll
-    for (int j = 0; j < NT; ++j)
-      __builtin_amdgcn_global_load_lds(GLB_PTR(hsrc[j] + koff),
-                                       LDS_PTR(base + kLmWBytes + 8 * (wv * NT + j) * kLmRowBytes), 16, 0, 0);
-  };
 
+  if (producer) {
+    // ---- producer wavefronts: nothing but address arithmetic, LDS-direct loads and barriers ----------
+    // rows are clamped into range; out-of-range rows are masked in the epilogue
+    const int sub = lane >> 3;  // row within an 8-row load instruction
+    // 16-byte chunk c of row r lives in LDS slot c ^ ((r >> 1) & 7): sixteen consecutive rows then
+    // put one chunk index into sixteen different 16-byte bank groups of the 64-bank LDS
+    const int chunk_even = (lane & 7) ^ (sub >> 1);        // instructions whose first row is 0 mod 16
+    const int chunk_odd = (lane & 7) ^ (4 + (sub >> 1));   // ... 8 mod 16
+    const bf16_t* wsrc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      int row = vbase + wv * kLmWaveV + 8 * j + sub;
+      row = row < V ? row : V - 1;
+      wsrc[j] = w + (size_t)row * H + ((j & 1) ? chunk_odd : chunk_even) * 8;
+    }
+    const bf16_t* hsrc[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int q8 = wv * NT + j;  // 8-row group of the hidden tile
+      int row = m0 + 8 * q8 + sub;
+      row = row < M ? row : M - 1;
+      hsrc[j] = hidden + (size_t)row * H + ((q8 & 1) ? chunk_odd : chunk_even) * 8;
+    }
+    auto issue = [&](int ks, int buf) {
+      char* base = lds + buf * kStageBytes;
+      int kk = ks + ks0;
+      kk = kk >= nk ? kk - nk : kk;
+      const int koff = kk * kLmBK;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        __builtin_amdgcn_global_load_lds(GLB_PTR(wsrc[j] + koff),
+                                         LDS_PTR(base + (wv * kLmWaveV + 8 * j) * kLmRowBytes), 16, 0, kCpolNT);
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        __builtin_amdgcn_global_load_lds(GLB_PTR(hsrc[j] + koff),
+                                         LDS_PTR(base + kLmWBytes + 8 * (wv * NT + j) * kLmRowBytes), 16, 0, 0);
+    };
+    issue(0, 0);
+    if (nk > 1) issue(1, 1);
+    for (int ks = 0; ks < nk; ++ks) {
+      // stage ks has landed once at most one younger stage's loads are still outstanding
+      if (ks + 1 < nk) WAIT_VMCNT(kLoadsPerStage); else WAIT_VMCNT(0);
+      __builtin_amdgcn_s_barrier();  // stage ks visible to the consumers; stage ks-1's buffer is free
+      if (ks + 2 < nk) issue(ks + 2, (ks + 2) % kLmStages);
+    }
+    __builtin_amdgcn_s_barrier();  // pairs with the consumers' statistics exchange below
+    return;
+  }
+
+  // ---- consumer wavefronts ------------------------------------------------------------------------
   f32x16_t acc[2][NT];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
@@ -101,16 +124,11 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
   // byte offsets of this lane's operand rows inside a stage (the chunk term is added per step)
   const int wrow_off = (wv * kLmWaveV + li) * kLmRowBytes;
   const int hrow_off = kLmWBytes + li * kLmRowBytes;
-  const int sw = li & 7;
-
-  issue(0, 0);
-  if (nk > 1) issue(1, 1);
+  const int sw = (li >> 1) & 7;
 
   for (int ks = 0; ks < nk; ++ks) {
-    // stage ks has landed once at most one younger stage's loads are still outstanding
-    if (ks + 1 < nk) WAIT_VMCNT(kLoadsPerStage); else WAIT_VMCNT(0);
     __builtin_amdgcn_s_barrier();
-    if (ks + 2 < nk) issue(ks + 2, (ks + 2) % kLmStages);
+    asm volatile("" ::: "memory");
     const char* base = lds + (ks % kLmStages) * kStageBytes;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -126,6 +144,7 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
         for (int t = 0; t < NT; ++t)
           acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[t], acc[a][t], 0, 0, 0);
     }
+    asm volatile("" ::: "memory");
   }
 
   // ---- epilogue: logits out, and (max, arg-max, sum exp) of the workgroup's 256 vocab rows ---------
@@ -193,7 +212,7 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
         }
     }
   }
-  __syncthreads();
+  __syncthreads();  // the producers' last barrier pairs with this one
   if (tid < NT * 32) {
     const int m = m0 + tid;
     if (m < M) {
