@@ -195,3 +195,36 @@ def test_full_size_llama_chain(gpu_lib):
     w = gen.llama_chain(1)
     _, a = _full_check(gpu_lib, w)
     assert 0.8 < a.accept_len.mean() < 2.2  # E[accepted drafts] = 1.38 for this recipe
+
+
+def _spread_sample(w, n):
+    """n requests spanning the length distribution (shortest, longest, evenly between)."""
+    order = np.argsort(w.seq_lens, kind="stable")
+    pick = np.unique(np.round(np.linspace(0, w.batch - 1, n)).astype(int))
+    return np.sort(order[pick])
+
+
+def test_full_size_qwen_greedy(gpu_lib):
+    """Config 3: greedy chain, Qwen3-8B vocabulary, B 64, k 6, contexts 512..8192.  The whole batch runs
+    on the GPU; the oracle checks a sample of requests that spans the length range."""
+    w = gen.qwen_greedy_chain(1)
+    _, a = _full_check(gpu_lib, w, sample=_spread_sample(w, 8))
+    assert a.accept_len.max() >= 2
+
+
+def test_full_size_tree(gpu_lib):
+    """Config 4: 32-node draft trees, B 16, context 4096."""
+    w = gen.llama_tree(1)
+    _, a = _full_check(gpu_lib, w, sample=[0, 7, 15])
+    assert a.accept_len.max() >= 1
+
+
+@pytest.mark.timeout(900)
+def test_full_size_stress_sparse_pool(gpu_lib):
+    """Config 5: B 256, contexts log-uniform in 256..32768, 48/8/128 heads, H 6144, V 200064, T 0.7, KV pages
+    scattered over a pool that fills 40 % of HBM (only referenced pages are initialised)."""
+    pool_bytes = int(0.40 * torch.cuda.get_device_properties(0).total_memory)
+    page_bytes = 2 * 8 * 16 * 128 * 2  # K and V, all KV heads, bf16
+    w = gen.stress_chain(1, pool_pages=pool_bytes // page_bytes)
+    assert w.seq_lens.max() > 20000 and w.seq_lens.min() < 400
+    _, a = _full_check(gpu_lib, w, sample=_spread_sample(w, 4))
