@@ -18,6 +18,14 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --stage <stage>` for the
+# default workload (seed 1), scaled by what the same counters read for `--stage copy` (FETCH_SIZE x 2.0,
+# WRITE_SIZE x 1.0); the summaries are in profiles/.  None for workloads that were not profiled.
+MEASURED_TRAFFIC = {
+    ("llama", 1, "lmhead"): {"read_bytes": 523400 * 1024 * 2, "write_bytes": 87820 * 1024},
+    ("llama", 1, "attn"): {"read_bytes": 154900 * 1024 * 2, "write_bytes": 13690 * 1024},
+}
+
 
 def make_workload(name, seed):
     import gen
@@ -29,6 +37,10 @@ def make_workload(name, seed):
         return gen.qwen_greedy_chain(seed)
     if name == "tree":
         return gen.llama_tree(seed)
+    if name == "stress":
+        import torch
+        pool_bytes = int(0.40 * torch.cuda.get_device_properties(0).total_memory)
+        return gen.stress_chain(seed, pool_pages=pool_bytes // (2 * 8 * 16 * 128 * 2))
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -49,7 +61,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="llama", choices=["llama", "tiny", "qwen_greedy", "tree"])
+    ap.add_argument("--workload", default="llama", choices=["llama", "tiny", "qwen_greedy", "tree", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
     ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "copy"],
@@ -116,8 +128,11 @@ def main():
     kv_gbs = kv_bytes / (ms_attn * 1e-3) / 1e9
     lm_flops = 2.0 * w.batch * w.num_q * w.hidden_size * w.vocab
 
+    tr_lm = MEASURED_TRAFFIC.get((args.workload, args.seed, "lmhead"))
+    tr_at = MEASURED_TRAFFIC.get((args.workload, args.seed, "attn"))
     out = {
-        "metric": "verified draft tokens/sec on 1 GPU (Llama-3-8B shape, k=4)",
+        "metric": "verified draft tokens/sec on 1 GPU (Llama-3-8B shape, k=4)" if args.workload == "llama"
+                  else f"verified draft tokens/sec on 1 GPU ({w.name})",
         "value": draft_tokens / (ms_step * 1e-3),
         "unit": "draft tokens/s",
         "n_gpus": 1,
@@ -139,11 +154,13 @@ def main():
                      "verify_by_events": ms_verify_ev},
         "roofline": {"kernel": "lmhead (LM-head GEMM + softmax statistics)", "bound": "hbm",
                      "achieved": lm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": lm_gbs / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes": w_bytes,
+                     "traffic": (tr_lm["read_bytes"] + tr_lm["write_bytes"]) if tr_lm else None,
+                     "traffic_detail": tr_lm, "algorithmic_bytes": w_bytes,
                      "mfma_tflops": lm_flops / (ms_lmhead * 1e-3) / 1e12},
         "roofline_attn": {"kernel": "chunk attention (KV sweep)", "bound": "hbm", "achieved": kv_gbs,
                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kv_gbs / HBM_PEAK_GBS,
-                          "algorithmic_bytes": kv_bytes},
+                          "traffic": (tr_at["read_bytes"] + tr_at["write_bytes"]) if tr_at else None,
+                          "traffic_detail": tr_at, "algorithmic_bytes": kv_bytes},
         "host_generation_s": gen_s,
     }
 
