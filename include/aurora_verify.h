@@ -8,6 +8,8 @@
  * Conventions for every entry point
  *   - Every data pointer is CALLER-OWNED DEVICE memory on the current HIP device.
  *     Descriptors are host structs, read during the call and not retained.
+ *     q, k_pages, v_pages, out, hidden and lm_head must be 16-byte aligned
+ *     (AURORA_ERR_INVALID_ARG otherwise).
  *   - The library allocates nothing and keeps no state.  All scratch lives in the
  *     caller's `workspace` (device memory, 256-byte aligned, at least
  *     aurora_verify_workspace_bytes() bytes).  No pointer is retained after the

@@ -47,16 +47,28 @@ AttnLaunch attn_launch_from(const aurora_attn_desc* d) {
 AttnPlan plan_attn(const aurora_attn_desc* d) {
   AttnPlan p = {};
   p.rows_per_group = d->num_q_heads / d->num_kv_heads * d->num_q;
-  const int64_t max_len = (int64_t)d->max_pages_per_seq * d->page_size;
-  int split = 512;
-  while ((max_len + split - 1) / split > 64 && split < 4096) split *= 2;
-  p.split_len = split;
-  int64_t ms = (max_len + split - 1) / split;
-  p.max_splits = (int)(ms < 1 ? 1 : ms);
-  const size_t nrows = (size_t)d->batch * d->num_q * d->num_q_heads * p.max_splits;
-  p.part_o_off = 0;
-  p.part_ml_off = align_up(nrows * d->head_dim * sizeof(float));
-  p.bytes = p.part_ml_off + align_up(nrows * 2 * sizeof(float));
+  AttnLaunch probe = attn_launch_from(d);
+  p.mfma = attn_mfma_supported(probe);
+  p.pb_off = 0;
+  const size_t pb_bytes = align_up(((size_t)d->batch + 1) * sizeof(int32_t));
+  p.part_o_off = pb_bytes;
+  if (p.mfma) {
+    p.row_tiles = (p.rows_per_group + 31) / 32;
+    p.slots = kAttnWorkgroups + d->batch * d->num_kv_heads;
+    const size_t nrows = (size_t)p.slots * p.row_tiles * 32;
+    p.part_ml_off = p.part_o_off + align_up(nrows * d->head_dim * sizeof(float));
+    p.bytes = p.part_ml_off + align_up(nrows * 2 * sizeof(float));
+  } else {
+    const int64_t max_len = (int64_t)d->max_pages_per_seq * d->page_size;
+    int split = 512;
+    while ((max_len + split - 1) / split > 64 && split < 4096) split *= 2;
+    p.split_len = split;
+    int64_t ms = (max_len + split - 1) / split;
+    p.max_splits = (int)(ms < 1 ? 1 : ms);
+    const size_t nrows = (size_t)d->batch * d->num_q * d->num_q_heads * p.max_splits;
+    p.part_ml_off = p.part_o_off + align_up(nrows * d->head_dim * sizeof(float));
+    p.bytes = p.part_ml_off + align_up(nrows * 2 * sizeof(float));
+  }
   return p;
 }
 
@@ -98,15 +110,17 @@ int run_attn(const aurora_attn_desc* desc, const void* q, const void* k_pages, c
   if (rc != AURORA_OK) return rc;
   if (desc->batch == 0) return AURORA_OK;
   if (!q || !k_pages || !v_pages || !block_table || !seq_lens || !out) return AURORA_ERR_INVALID_ARG;
+  if (((uintptr_t)q | (uintptr_t)k_pages | (uintptr_t)v_pages | (uintptr_t)out) & 15) return AURORA_ERR_INVALID_ARG;
   AttnPlan plan = plan_attn(desc);
   if (!workspace || misaligned(workspace) || workspace_bytes < plan.bytes) return AURORA_ERR_WORKSPACE;
   AttnLaunch a = attn_launch_from(desc);
   a.q = q; a.k = k_pages; a.v = v_pages; a.block_table = block_table; a.seq_lens = seq_lens; a.parents = parents;
   a.out = out;
+  a.plan_pb = (int32_t*)((char*)workspace + plan.pb_off);
   a.part_o = (float*)((char*)workspace + plan.part_o_off);
   a.part_ml = (float*)((char*)workspace + plan.part_ml_off);
   a.plan = plan;
-  hipError_t e = attn_mfma_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(a, st);
+  hipError_t e = plan.mfma ? launch_attn_mfma(a, st) : launch_attn_generic(a, st);
   return e == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
 }
 
@@ -120,6 +134,7 @@ int run_accept(const aurora_accept_desc* desc, const void* hidden, const void* l
   if (!hidden || !lm_head || !draft_tokens || !accept_len || !next_token || !accept_mask)
     return AURORA_ERR_INVALID_ARG;
   if (desc->temperature > 0.f && (!draft_probs || !uniforms)) return AURORA_ERR_INVALID_ARG;
+  if (((uintptr_t)hidden | (uintptr_t)lm_head) & 15) return AURORA_ERR_INVALID_ARG;
   AcceptPlan plan = plan_accept(desc);
   if (!workspace || misaligned(workspace) || workspace_bytes < plan.bytes) return AURORA_ERR_WORKSPACE;
   AcceptLaunch a = accept_launch_from(desc);
@@ -149,6 +164,7 @@ int run_lmhead(const aurora_accept_desc* desc, const void* hidden, const void* l
   if (rc != AURORA_OK) return rc;
   if (desc->batch == 0) return AURORA_OK;
   if (!hidden || !lm_head) return AURORA_ERR_INVALID_ARG;
+  if (((uintptr_t)hidden | (uintptr_t)lm_head) & 15) return AURORA_ERR_INVALID_ARG;
   AcceptPlan plan = plan_accept(desc);
   if (!workspace || misaligned(workspace) || workspace_bytes < plan.bytes) return AURORA_ERR_WORKSPACE;
   AcceptLaunch a = accept_launch_from(desc);

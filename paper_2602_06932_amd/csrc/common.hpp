@@ -51,11 +51,18 @@ __device__ __forceinline__ int wave_max(int v) {
 }
 
 // --- launch plans shared by the API layer and the launchers (host) ----------------------
+constexpr int kAttnWorkgroups = 512;  // resident workgroups of the MFMA attention kernel (2 per compute unit)
+
 struct AttnPlan {
   int rows_per_group;  // G * Nq query rows that share one KV head
+  bool mfma;           // the bf16 MFMA kernel takes this shape
+  // generic kernel: fixed-length KV splits
   int split_len;       // KV tokens per split (multiple of 128)
   int max_splits;      // ceil(max_len / split_len)
-  size_t part_o_off, part_ml_off, bytes;  // fp32 partial O [B*Nq*Hq*max_splits, D]; (m,l) pairs
+  // MFMA kernel: one partial per (workgroup, pair) segment
+  int slots;           // kAttnWorkgroups + B * Hkv
+  int row_tiles;       // ceil(G * Nq / 32)
+  size_t pb_off, part_o_off, part_ml_off, bytes;
 };
 
 struct AcceptPlan {

@@ -12,6 +12,7 @@ struct AttnLaunch {
   const int32_t *block_table, *seq_lens, *parents;
   void* out;
   float *part_o, *part_ml;
+  int32_t* plan_pb;
   AttnPlan plan;
 };
 

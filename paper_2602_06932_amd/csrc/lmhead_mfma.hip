@@ -238,8 +238,7 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
 }
 
 bool lmhead_mfma_supported(const AcceptLaunch& a) {
-  return a.bf16 && a.H % kLmBK == 0 && a.H >= kLmBK && a.V >= 1 &&
-         (((uintptr_t)a.hidden | (uintptr_t)a.lm_head) & 15) == 0;
+  return a.bf16 && a.H % kLmBK == 0 && a.H >= kLmBK && a.V >= 1;
 }
 
 int lmhead_mfma_stat_tile() { return kLmVTile; }
