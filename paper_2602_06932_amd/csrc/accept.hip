@@ -5,15 +5,16 @@
 // Inputs are the fp32 logits written by the LM-head kernel and the per-(row, vocab tile) softmax
 // statistics (max, sum exp, arg-max) of its epilogue.
 //
-// Chains at T > 0 (the serving default) take three small kernels so that the one vocabulary sweep
-// a request needs is spread over the whole chip instead of one compute unit:
-//   accept_chain_walk   one workgroup per request: merge the tile statistics of the request's rows,
-//                       evaluate the k accept tests u * q(d) < p(d) in parallel (fp64), find the
-//                       first failure, write accept_len / accept_mask / p_at_draft / row_lse;
-//   accept_chain_sweep  S workgroups per request: sums of the draw weights - max(0, p - q) after a
-//                       rejection, p itself when every draft was kept - over groups of 256 tokens;
+// Chains at T > 0 (the serving default) take two small kernels so that the one vocabulary sweep a
+// request needs is spread over the whole chip instead of one compute unit:
+//   accept_chain_sweep  S workgroups per request.  Each repeats the cheap part - merge the tile
+//                       statistics of the request's rows, evaluate the k accept tests
+//                       u * q(d) < p(d) in parallel (fp64), find the first failure - and then sums
+//                       the draw weights - max(0, p - q) after a rejection, p itself when every
+//                       draft was kept - over groups of 256 tokens of its slice; slice 0 writes
+//                       accept_len / accept_mask / p_at_draft / row_lse;
 //   accept_chain_pick   one workgroup per request: scan the group sums, find the group holding
-//                       u * total, rescan that group with wavefront prefix sums for the token.
+//                       u * total, rescan that group with a wavefront prefix sum for the token.
 // Trees at T > 0 may need one sweep per rejected sibling, each depending on the previous one; they
 // run in one workgroup per request (accept_tree_kernel), which also serves every greedy (T = 0)
 // call, where no sweep exists.
@@ -27,6 +28,7 @@ constexpr int kAccThreads = 1024;
 constexpr int kAccWaves = kAccThreads / kWave;
 constexpr int kMaxGroups = 4096;  // group sums kept in LDS by the tree kernel (32 KB of doubles)
 constexpr int kSmallThreads = 256;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 // Probability of token v at the current node after `nres` residual steps, in fp64 throughout (used
 // for the accept tests).  p0 = exp(l / T - lse);  p_{s+1} = max(0, p_s - q) / Z_s.
@@ -138,12 +140,40 @@ __device__ __forceinline__ void merge_row_stats(const AcceptParams& P, size_t ro
 }
 
 // ============================================================================================
-// Chain path, kernel 1: statistics merge, parallel accept tests, per-node outputs.
+// Chain path.  A group is 256 consecutive tokens: lane i of the wavefront that owns it holds tokens
+// 4i .. 4i+3 (one 16-byte load per row when the row is 16-byte aligned).
 // ============================================================================================
-__global__ __launch_bounds__(kSmallThreads) void accept_chain_walk(AcceptParams P) {
+constexpr int kGroup = 256;
+
+// weights of the four tokens v0 .. v0+3 a lane owns (0 past the end of the vocabulary)
+__device__ __forceinline__ void lane_weights(const float* __restrict__ lrow, const float* __restrict__ qrow, int v0,
+                                             int V, bool vec_ok, double lse, double inv_t, int nres, double x[4]) {
+  float l[4], q[4];
+  if (vec_ok && v0 + 3 < V) {
+    const f32x4_t lv = *(const f32x4_t*)(lrow + v0);
+    const f32x4_t qv = *(const f32x4_t*)(qrow + v0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { l[e] = lv[e]; q[e] = qv[e]; }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      l[e] = v0 + e < V ? lrow[v0 + e] : -INFINITY;
+      q[e] = v0 + e < V ? qrow[v0 + e] : 0.f;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) x[e] = v0 + e < V ? sweep_weight(l[e], q[e], lse, inv_t, nres, nullptr, true) : 0.0;
+}
+
+// Kernel 1: S workgroups per request.  Every workgroup repeats the (cheap) walk - merge the tile
+// statistics of the request's rows, evaluate the k accept tests in parallel in fp64, find the first
+// failure - then sums the draw weights over its slice of the vocabulary.  Slice 0 writes the
+// per-request outputs and the state the draw kernel needs.
+__global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams P) {
   __shared__ double s_lse[kMaxNq];
   __shared__ int s_ok[kMaxNq];
-  const int b = blockIdx.x;
+  __shared__ int s_last[kSmallThreads / kWave];
+  const int slice = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
   const int Nq = P.Nq, V = P.V;
   const double T = (double)P.temperature;
@@ -168,56 +198,53 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_walk(AcceptParams 
       pv = (float)p;
     }
     s_ok[n] = ok;
-    if (P.p_at_draft) P.p_at_draft[row0 + n] = pv;
-    if (P.row_lse) P.row_lse[row0 + n] = (float)s_lse[n];
-  }
-  __syncthreads();
-  if (tid < Nq) {
-    int first_fail = Nq;
-    for (int n = 1; n < Nq; ++n)
-      if (!s_ok[n]) { first_fail = n; break; }
-    const int j = first_fail - 1;  // accepted drafts = index of the row the draw happens on
-    P.accept_mask[row0 + tid] = tid <= j ? 1 : 0;
-    if (tid == 0) {
-      P.accept_len[b] = j;
-      P.st_row[b] = j;
-      P.st_rej[b] = first_fail < Nq ? 1 : 0;
-      P.st_lse[b] = s_lse[j];
+    if (slice == 0) {
+      if (P.p_at_draft) P.p_at_draft[row0 + n] = pv;
+      if (P.row_lse) P.row_lse[row0 + n] = (float)s_lse[n];
     }
   }
-}
+  __syncthreads();
+  int first_fail = Nq;
+  for (int n = 1; n < Nq; ++n)
+    if (!s_ok[n]) { first_fail = n; break; }
+  const int row = first_fail - 1;          // accepted drafts = index of the row the draw happens on
+  const int nres = first_fail < Nq ? 1 : 0;  // 1: draw from max(0, p - q); 0: all kept, draw from p
+  const double lse = s_lse[row];
+  if (slice == 0) {
+    if (tid < Nq) P.accept_mask[row0 + tid] = tid <= row ? 1 : 0;
+    if (tid == 0) {
+      P.accept_len[b] = row;
+      P.st_row[b] = row;
+      P.st_rej[b] = nres;
+      P.st_lse[b] = lse;
+    }
+  }
 
-// ============================================================================================
-// Chain path, kernel 2: group sums of the draw weights over one slice of the vocabulary.
-// Group g covers tokens [g * 64 * gmul, (g+1) * 64 * gmul); lane i of the owning wavefront adds
-// tokens g*64*gmul + it*64 + i.
-// ============================================================================================
-__global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams P) {
-  __shared__ int s_last[kSmallThreads / kWave];
-  const int slice = blockIdx.x, b = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
-  const int V = P.V, gmul = P.gmul, GE = kWave * gmul;
-  const int row = P.st_row[b];
-  const int nres = P.st_rej[b];
-  const double lse = P.st_lse[b];
-  const double inv_t = 1.0 / (double)P.temperature;
-  const float* lrow = P.logits + ((size_t)b * P.Nq + row) * V;
-  const float* qrow = P.q + ((size_t)b * P.Nq + row) * V;
+  const double inv_t = 1.0 / T;
+  const float* lrow = P.logits + (row0 + row) * V;
+  const float* qrow = P.q + (row0 + row) * V;
+  const bool vec_ok = (V & 3) == 0 && (((uintptr_t)P.q | (uintptr_t)P.logits) & 15) == 0;
   const int per = (P.ngroups + P.slices - 1) / P.slices;
   const int g0 = slice * per, g1 = min(P.ngroups, g0 + per);
   int lastpos = -1;
-  for (int g = g0 + wv; g < g1; g += kSmallThreads / kWave) {
-    double acc = 0.0;
-    for (int it = 0; it < gmul; ++it) {
-      const int v = g * GE + it * kWave + lane;
-      if (v < V) {
-        const double x = sweep_weight(lrow[v], qrow[v], lse, inv_t, nres, nullptr, true);
-        acc += x;
-        if (x > 0.0) lastpos = v;
-      }
+  for (int g = g0 + wv; g < g1; g += 2 * (kSmallThreads / kWave)) {
+    // two groups per trip so that their loads are in flight together
+    const int gb = g + kSmallThreads / kWave;
+    double xa[4], xb[4] = {0.0, 0.0, 0.0, 0.0};
+    const int va = g * kGroup + lane * 4, vb = gb * kGroup + lane * 4;
+    lane_weights(lrow, qrow, va, V, vec_ok, lse, inv_t, nres, xa);
+    if (gb < g1) lane_weights(lrow, qrow, vb, V, vec_ok, lse, inv_t, nres, xb);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (xa[e] > 0.0) lastpos = max(lastpos, va + e);
+      if (xb[e] > 0.0) lastpos = max(lastpos, vb + e);
     }
-    acc = wave_sum(acc);
-    if (lane == 0) P.gsum[(size_t)b * P.ngroups + g] = acc;
+    const double sa = wave_sum((xa[0] + xa[1]) + (xa[2] + xa[3]));
+    const double sb = wave_sum((xb[0] + xb[1]) + (xb[2] + xb[3]));
+    if (lane == 0) {
+      P.gsum[(size_t)b * P.ngroups + g] = sa;
+      if (gb < g1) P.gsum[(size_t)b * P.ngroups + gb] = sb;
+    }
   }
   lastpos = wave_max(lastpos);
   if (lane == 0) s_last[wv] = lastpos;
@@ -229,23 +256,22 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams
   }
 }
 
-// ============================================================================================
-// Chain path, kernel 3: inverse-CDF draw from the group sums.
+// Kernel 2: inverse-CDF draw from the group sums, one workgroup per request.
 // A residual that vanished (sum 0) falls back to the row's p: rare enough for one workgroup.
-// ============================================================================================
 __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams P) {
   __shared__ double s_wtot[kSmallThreads / kWave];
   __shared__ int s_pick;
   __shared__ double s_prefix;
   const int b = blockIdx.x;
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
-  const int V = P.V, gmul = P.gmul, GE = kWave * gmul, ng = P.ngroups;
+  const int V = P.V, ng = P.ngroups;
   const int row = P.st_row[b];
   int nres = P.st_rej[b];
   const double lse = P.st_lse[b];
   const double inv_t = 1.0 / (double)P.temperature;
   const float* lrow = P.logits + ((size_t)b * P.Nq + row) * V;
   const float* qrow = P.q + ((size_t)b * P.Nq + row) * V;
+  const bool vec_ok = (V & 3) == 0 && (((uintptr_t)P.q | (uintptr_t)P.logits) & 15) == 0;
   double* gs = P.gsum + (size_t)b * ng;
   const int per = (ng + kSmallThreads - 1) / kSmallThreads;
   const int ga = min(ng, tid * per), gb = min(ng, ga + per);
@@ -280,26 +306,34 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams 
       if (wv == 0) {
         int token = -1;
         if (pick != 0x7fffffff) {
-          double run2 = s_prefix;
-          int last_in_group = -1;
-          bool done = false;
-          for (int it = 0; it < gmul && !done; ++it) {
-            const int v = pick * GE + it * kWave + lane;
-            const double x = v < V ? sweep_weight(lrow[v], qrow[v], lse, inv_t, nres, nullptr, true) : 0.0;
-            const double inc = wave_incl_scan(x, lane) + run2;
-            const unsigned long long hit = __ballot(v < V && inc > thr);
-            const unsigned long long pos = __ballot(x > 0.0);
-            if (hit) {
-              token = pick * GE + it * kWave + (__ffsll((long long)hit) - 1);
-              done = true;
-            } else {
-              if (pos) last_in_group = pick * GE + it * kWave + (63 - __clzll((long long)pos));
-              run2 = __shfl(inc, kWave - 1, kWave);
-            }
+          const int v0 = pick * kGroup + lane * 4;
+          double x[4];
+          lane_weights(lrow, qrow, v0, V, vec_ok, lse, inv_t, nres, x);
+          const double lane_tot = (x[0] + x[1]) + (x[2] + x[3]);
+          const double lane_incl = wave_incl_scan(lane_tot, lane) + s_prefix;
+          const unsigned long long hit = __ballot(lane_incl > thr);
+          const unsigned long long pos = __ballot(lane_tot > 0.0);
+          if (hit) {
+            const int hl = __ffsll((long long)hit) - 1;  // first lane whose running sum crosses
+            double r0 = __shfl(lane_incl - lane_tot, hl, kWave);
+            int e_hit = 3;
+            const double y0 = __shfl(x[0], hl, kWave), y1 = __shfl(x[1], hl, kWave), y2 = __shfl(x[2], hl, kWave);
+            if (r0 + y0 > thr) e_hit = 0;
+            else if (r0 + y0 + y1 > thr) e_hit = 1;
+            else if (r0 + y0 + y1 + y2 > thr) e_hit = 2;
+            token = pick * kGroup + hl * 4 + e_hit;
+            if (token >= V) token = -1;
+          } else if (pos) {
+            // rounding left no crossing inside the group: its last token with positive weight
+            const int pl = 63 - __clzll((long long)pos);
+            int e_last = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (__shfl(x[e], pl, kWave) > 0.0) e_last = e;
+            token = pick * kGroup + pl * 4 + e_last;
           }
-          if (!done) token = last_in_group;
         }
-        if (token < 0) {  // rounding left no crossing: the largest token with positive weight
+        if (token < 0) {  // no crossing at all: the largest token with positive weight
           int m = -1;
           for (int i = lane; i < P.slices; i += kWave) m = max(m, P.lastpos[(size_t)b * P.slices + i]);
           token = wave_max(m);
@@ -313,16 +347,13 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams 
     nres = 0;
     int lastpos = -1;
     for (int g = wv; g < ng; g += kSmallThreads / kWave) {
-      double acc = 0.0;
-      for (int it = 0; it < gmul; ++it) {
-        const int v = g * GE + it * kWave + lane;
-        if (v < V) {
-          const double x = sweep_weight(lrow[v], qrow[v], lse, inv_t, 0, nullptr, true);
-          acc += x;
-          if (x > 0.0) lastpos = v;
-        }
-      }
-      acc = wave_sum(acc);
+      const int v0 = g * kGroup + lane * 4;
+      double x[4];
+      lane_weights(lrow, qrow, v0, V, vec_ok, lse, inv_t, 0, x);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (x[e] > 0.0) lastpos = max(lastpos, v0 + e);
+      const double acc = wave_sum((x[0] + x[1]) + (x[2] + x[3]));
       if (lane == 0) gs[g] = acc;
     }
     lastpos = wave_max(lastpos);
@@ -565,15 +596,13 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
 }
 
 void accept_chain_geometry(int batch, int vocab, int* slices, int* gmul, int* ngroups) {
-  int gm = 4;
-  while ((vocab + kWave * gm - 1) / (kWave * gm) > 16384) gm *= 2;
-  const int ng = (vocab + kWave * gm - 1) / (kWave * gm);
-  int s = (1024 + batch - 1) / (batch > 0 ? batch : 1);
-  if (s > (ng + 3) / 4) s = (ng + 3) / 4;
+  const int ng = (vocab + kGroup - 1) / kGroup;
+  int s = (256 + batch - 1) / (batch > 0 ? batch : 1);  // about one workgroup per compute unit in total
+  if (s > (ng + 7) / 8) s = (ng + 7) / 8;
   if (s < 1) s = 1;
-  if (s > 64) s = 64;
+  if (s > 32) s = 32;
   *slices = s;
-  *gmul = gm;
+  *gmul = kGroup / kWave;
   *ngroups = ng;
 }
 
@@ -591,11 +620,8 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st) {
     hipLaunchKernelGGL(accept_tree_kernel, dim3(a.B), dim3(kAccThreads), 0, st, P);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(accept_chain_walk, dim3(a.B), dim3(kSmallThreads), 0, st, P);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(accept_chain_sweep, dim3(P.slices, a.B), dim3(kSmallThreads), 0, st, P);
-  e = hipGetLastError();
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(accept_chain_pick, dim3(a.B), dim3(kSmallThreads), 0, st, P);
   return hipGetLastError();

@@ -126,7 +126,6 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
   const int mrow = rt * 32 + li;
   const bool row_ok = mrow < R;
   const int node = row_ok ? mrow / G : 0;
-  const int gq = row_ok ? mrow % G : 0;
   // the query row this thread stages into LDS at the start of a segment (8 threads per row, 32 B each)
   const int qs_row = tid >> 3;
   const int qs_m = rt * 32 + qs_row;
