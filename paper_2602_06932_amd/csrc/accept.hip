@@ -145,24 +145,30 @@ __device__ __forceinline__ void merge_row_stats(const AcceptParams& P, size_t ro
 // ============================================================================================
 constexpr int kGroup = 256;
 
-// weights of the four tokens v0 .. v0+3 a lane owns (0 past the end of the vocabulary)
-__device__ __forceinline__ void lane_weights(const float* __restrict__ lrow, const float* __restrict__ qrow, int v0,
-                                             int V, bool vec_ok, double lse, double inv_t, int nres, double x[4]) {
-  float l[4], q[4];
+// the logits and draft probabilities of the four tokens v0 .. v0+3 a lane owns
+struct Lane4 { float l[4], q[4]; };
+__device__ __forceinline__ Lane4 lane_load(const float* __restrict__ lrow, const float* __restrict__ qrow, int v0, int V,
+                                           bool vec_ok) {
+  Lane4 r;
   if (vec_ok && v0 + 3 < V) {
     const f32x4_t lv = *(const f32x4_t*)(lrow + v0);
     const f32x4_t qv = *(const f32x4_t*)(qrow + v0);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { l[e] = lv[e]; q[e] = qv[e]; }
+    for (int e = 0; e < 4; ++e) { r.l[e] = lv[e]; r.q[e] = qv[e]; }
   } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      l[e] = v0 + e < V ? lrow[v0 + e] : -INFINITY;
-      q[e] = v0 + e < V ? qrow[v0 + e] : 0.f;
+      r.l[e] = v0 + e < V ? lrow[v0 + e] : -INFINITY;
+      r.q[e] = v0 + e < V ? qrow[v0 + e] : 0.f;
     }
   }
+  return r;
+}
+// their draw weights (0 past the end of the vocabulary)
+__device__ __forceinline__ void lane_weights(const Lane4& r, int v0, int V, double lse, double inv_t, int nres,
+                                             double x[4]) {
 #pragma unroll
-  for (int e = 0; e < 4; ++e) x[e] = v0 + e < V ? sweep_weight(l[e], q[e], lse, inv_t, nres, nullptr, true) : 0.0;
+  for (int e = 0; e < 4; ++e) x[e] = v0 + e < V ? sweep_weight(r.l[e], r.q[e], lse, inv_t, nres, nullptr, true) : 0.0;
 }
 
 // Kernel 1: S workgroups per request.  Every workgroup repeats the (cheap) walk - merge the tile
@@ -227,23 +233,28 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams
   const int per = (P.ngroups + P.slices - 1) / P.slices;
   const int g0 = slice * per, g1 = min(P.ngroups, g0 + per);
   int lastpos = -1;
-  for (int g = g0 + wv; g < g1; g += 2 * (kSmallThreads / kWave)) {
-    // two groups per trip so that their loads are in flight together
-    const int gb = g + kSmallThreads / kWave;
-    double xa[4], xb[4] = {0.0, 0.0, 0.0, 0.0};
-    const int va = g * kGroup + lane * 4, vb = gb * kGroup + lane * 4;
-    lane_weights(lrow, qrow, va, V, vec_ok, lse, inv_t, nres, xa);
-    if (gb < g1) lane_weights(lrow, qrow, vb, V, vec_ok, lse, inv_t, nres, xb);
+  constexpr int kBatch = 4;  // groups whose loads a wavefront keeps in flight together
+  constexpr int kStep = kSmallThreads / kWave;
+  for (int g = g0 + wv; g < g1; g += kBatch * kStep) {
+    Lane4 r[kBatch];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      if (xa[e] > 0.0) lastpos = max(lastpos, va + e);
-      if (xb[e] > 0.0) lastpos = max(lastpos, vb + e);
+    for (int i = 0; i < kBatch; ++i) {
+      const int gi = g + i * kStep;
+      if (gi < g1) r[i] = lane_load(lrow, qrow, gi * kGroup + lane * 4, V, vec_ok);
     }
-    const double sa = wave_sum((xa[0] + xa[1]) + (xa[2] + xa[3]));
-    const double sb = wave_sum((xb[0] + xb[1]) + (xb[2] + xb[3]));
-    if (lane == 0) {
-      P.gsum[(size_t)b * P.ngroups + g] = sa;
-      if (gb < g1) P.gsum[(size_t)b * P.ngroups + gb] = sb;
+#pragma unroll
+    for (int i = 0; i < kBatch; ++i) {
+      const int gi = g + i * kStep;
+      if (gi < g1) {  // wave-uniform
+        const int v0 = gi * kGroup + lane * 4;
+        double x[4];
+        lane_weights(r[i], v0, V, lse, inv_t, nres, x);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (x[e] > 0.0) lastpos = max(lastpos, v0 + e);
+        const double sg = wave_sum((x[0] + x[1]) + (x[2] + x[3]));
+        if (lane == 0) P.gsum[(size_t)b * P.ngroups + gi] = sg;
+      }
     }
   }
   lastpos = wave_max(lastpos);
@@ -308,7 +319,7 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams 
         if (pick != 0x7fffffff) {
           const int v0 = pick * kGroup + lane * 4;
           double x[4];
-          lane_weights(lrow, qrow, v0, V, vec_ok, lse, inv_t, nres, x);
+          lane_weights(lane_load(lrow, qrow, v0, V, vec_ok), v0, V, lse, inv_t, nres, x);
           const double lane_tot = (x[0] + x[1]) + (x[2] + x[3]);
           const double lane_incl = wave_incl_scan(lane_tot, lane) + s_prefix;
           const unsigned long long hit = __ballot(lane_incl > thr);
@@ -349,7 +360,7 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams 
     for (int g = wv; g < ng; g += kSmallThreads / kWave) {
       const int v0 = g * kGroup + lane * 4;
       double x[4];
-      lane_weights(lrow, qrow, v0, V, vec_ok, lse, inv_t, 0, x);
+      lane_weights(lane_load(lrow, qrow, v0, V, vec_ok), v0, V, lse, inv_t, 0, x);
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         if (x[e] > 0.0) lastpos = max(lastpos, v0 + e);
@@ -597,10 +608,13 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
 
 void accept_chain_geometry(int batch, int vocab, int* slices, int* gmul, int* ngroups) {
   const int ng = (vocab + kGroup - 1) / kGroup;
-  int s = (256 + batch - 1) / (batch > 0 ? batch : 1);  // about one workgroup per compute unit in total
-  if (s > (ng + 7) / 8) s = (ng + 7) / 8;
+  // enough slices that a wavefront sweeps its share in two batches of four groups, within about two
+  // workgroups per compute unit over the whole batch
+  int s = (ng + 31) / 32;
+  const int cap = (512 + batch - 1) / (batch > 0 ? batch : 1);
+  if (s > cap) s = cap;
   if (s < 1) s = 1;
-  if (s > 32) s = 32;
+  if (s > 64) s = 64;
   *slices = s;
   *gmul = kGroup / kWave;
   *ngroups = ng;
