@@ -66,7 +66,7 @@ typedef struct {
   int32_t batch;     /* B                                                                    */
   int32_t num_q;     /* Nq, 1..64                                                            */
   int32_t hidden;    /* H (bf16: multiple of 8)                                              */
-  int32_t vocab;     /* V                                                                    */
+  int32_t vocab;     /* V (tree sampling, i.e. parents != NULL with T > 0: V <= 2^20)           */
   int32_t dtype;     /* type of hidden and lm_head                                           */
   float temperature; /* 0 => greedy (arg-max prefix); > 0 => speculative rejection sampling  */
 } aurora_accept_desc;

@@ -26,7 +26,7 @@ namespace aurora {
 
 constexpr int kAccThreads = 1024;
 constexpr int kAccWaves = kAccThreads / kWave;
-constexpr int kMaxGroups = 4096;  // group sums kept in LDS by the tree kernel (32 KB of doubles)
+constexpr int kMaxGroups = 4096;  // group sums kept in LDS by the tree kernel (32 KB of doubles): V <= 2^20
 constexpr int kSmallThreads = 256;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
@@ -166,9 +166,10 @@ __device__ __forceinline__ Lane4 lane_load(const float* __restrict__ lrow, const
 }
 // their draw weights (0 past the end of the vocabulary)
 __device__ __forceinline__ void lane_weights(const Lane4& r, int v0, int V, double lse, double inv_t, int nres,
-                                             double x[4]) {
+                                             double x[4], const double* Zs = nullptr, bool skip_last = true) {
 #pragma unroll
-  for (int e = 0; e < 4; ++e) x[e] = v0 + e < V ? sweep_weight(r.l[e], r.q[e], lse, inv_t, nres, nullptr, true) : 0.0;
+  for (int e = 0; e < 4; ++e)
+    x[e] = v0 + e < V ? sweep_weight(r.l[e], r.q[e], lse, inv_t, nres, Zs, skip_last) : 0.0;
 }
 
 // Kernel 1: S workgroups per request.  Every workgroup repeats the (cheap) walk - merge the tile
@@ -444,9 +445,8 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   }
 
   // ---- 2b. sampling walk ------------------------------------------------------------------------
-  const int gmul = (V + kWave * kMaxGroups - 1) / (kWave * kMaxGroups);
-  const int GE = kWave * gmul;            // tokens per group
-  const int ngroups = (V + GE - 1) / GE;  // <= kMaxGroups
+  const int ngroups = (V + kGroup - 1) / kGroup;  // <= kMaxGroups (checked by the launcher)
+  const bool vec_ok = (V & 3) == 0 && (((uintptr_t)P.q | (uintptr_t)P.logits) & 15) == 0;
   if (tid == 0) {
     s_cur = 0; s_depth = 0; s_nres = 0; s_last_child = 0; s_have_gsum = 0;
   }
@@ -496,18 +496,28 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       const int nres = state == ST_REJECTED ? s_nres + 1 : s_nres;
       const bool skip_last = state == ST_REJECTED;
       int lastpos = -1;
-      for (int g = wv; g < ngroups; g += kAccWaves) {
-        double acc = 0.0;
-        for (int it = 0; it < gmul; ++it) {
-          const int v = g * GE + it * kWave + lane;
-          if (v < V) {
-            const double x = sweep_weight(lrow[v], qrow[v], lse, inv_t, nres, s_Z, skip_last);
-            acc += x;
-            if (x > 0.0) lastpos = v;
+      constexpr int kBatch = 4;  // groups whose loads a wavefront keeps in flight together
+      for (int g = wv; g < ngroups; g += kBatch * kAccWaves) {
+        Lane4 r[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+          const int gi = g + i * kAccWaves;
+          if (gi < ngroups) r[i] = lane_load(lrow, qrow, gi * kGroup + lane * 4, V, vec_ok);
+        }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+          const int gi = g + i * kAccWaves;
+          if (gi < ngroups) {  // wave-uniform
+            const int v0 = gi * kGroup + lane * 4;
+            double x[4];
+            lane_weights(r[i], v0, V, lse, inv_t, nres, x, s_Z, skip_last);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (x[e] > 0.0) lastpos = max(lastpos, v0 + e);
+            const double sg = wave_sum((x[0] + x[1]) + (x[2] + x[3]));
+            if (lane == 0) s_gsum[gi] = sg;
           }
         }
-        acc = wave_sum(acc);
-        if (lane == 0) s_gsum[g] = acc;
       }
       lastpos = wave_max(lastpos);
       if (tid == 0) s_lastpos = -1;
@@ -578,24 +588,31 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       if (pick != 0x7fffffff) {
         const bool have = s_have_gsum;
         const int nres = s_nres;
-        double run = s_pick_prefix;
-        int last_in_group = -1;
-        bool done = false;
-        for (int it = 0; it < gmul && !done; ++it) {
-          const int v = pick * GE + it * kWave + lane;
-          const double x = v < V ? sweep_weight(lrow[v], qrow[v], lse, inv_t, nres, s_Z, have) : 0.0;
-          const double inc = wave_incl_scan(x, lane) + run;
-          const unsigned long long hit = __ballot(v < V && inc > thr);
-          const unsigned long long pos = __ballot(x > 0.0);
-          if (hit) {
-            token = pick * GE + it * kWave + (__ffsll((long long)hit) - 1);
-            done = true;
-          } else {
-            if (pos) last_in_group = pick * GE + it * kWave + (63 - __clzll((long long)pos));
-            run = __shfl(inc, kWave - 1, kWave);
-          }
+        const int v0 = pick * kGroup + lane * 4;
+        double x[4];
+        lane_weights(lane_load(lrow, qrow, v0, V, vec_ok), v0, V, lse, inv_t, nres, x, s_Z, have);
+        const double lane_tot = (x[0] + x[1]) + (x[2] + x[3]);
+        const double lane_incl = wave_incl_scan(lane_tot, lane) + s_pick_prefix;
+        const unsigned long long hit = __ballot(lane_incl > thr);
+        const unsigned long long pos = __ballot(lane_tot > 0.0);
+        if (hit) {
+          const int hl = __ffsll((long long)hit) - 1;  // first lane whose running sum crosses
+          const double r0 = __shfl(lane_incl - lane_tot, hl, kWave);
+          const double y0 = __shfl(x[0], hl, kWave), y1 = __shfl(x[1], hl, kWave), y2 = __shfl(x[2], hl, kWave);
+          int e_hit = 3;
+          if (r0 + y0 > thr) e_hit = 0;
+          else if (r0 + y0 + y1 > thr) e_hit = 1;
+          else if (r0 + y0 + y1 + y2 > thr) e_hit = 2;
+          const int cand = pick * kGroup + hl * 4 + e_hit;
+          if (cand < V) token = cand;
+        } else if (pos) {
+          const int pl = 63 - __clzll((long long)pos);
+          int e_last = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (__shfl(x[e], pl, kWave) > 0.0) e_last = e;
+          token = pick * kGroup + pl * 4 + e_last;
         }
-        if (!done && last_in_group >= 0) token = last_in_group;
       }
       if (lane == 0) {
         P.next_token[b] = token;
@@ -631,6 +648,7 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st) {
   P.st_lse = a.st_lse; P.st_row = a.st_row; P.st_rej = a.st_rej; P.gsum = a.gsum; P.lastpos = a.lastpos;
   const bool chain_sampling = a.temperature > 0.f && a.parents == nullptr;
   if (!chain_sampling) {
+    if (a.temperature > 0.f && (a.V + kGroup - 1) / kGroup > kMaxGroups) return hipErrorInvalidValue;
     hipLaunchKernelGGL(accept_tree_kernel, dim3(a.B), dim3(kAccThreads), 0, st, P);
     return hipGetLastError();
   }

@@ -135,6 +135,8 @@ int run_accept(const aurora_accept_desc* desc, const void* hidden, const void* l
     return AURORA_ERR_INVALID_ARG;
   if (desc->temperature > 0.f && (!draft_probs || !uniforms)) return AURORA_ERR_INVALID_ARG;
   if (((uintptr_t)hidden | (uintptr_t)lm_head) & 15) return AURORA_ERR_INVALID_ARG;
+  // the one-workgroup tree walk keeps one partial sum per 256 tokens in LDS
+  if (desc->temperature > 0.f && parents && desc->vocab > (1 << 20)) return AURORA_ERR_UNSUPPORTED;
   AcceptPlan plan = plan_accept(desc);
   if (!workspace || misaligned(workspace) || workspace_bytes < plan.bytes) return AURORA_ERR_WORKSPACE;
   AcceptLaunch a = accept_launch_from(desc);
