@@ -90,10 +90,13 @@ __device__ __forceinline__ int units_per_wg(int U, int wgs) {
   return (c + 3) & ~3;  // a multiple of four tiles: the four wavefronts of a workgroup stay balanced
 }
 
+constexpr int kLocalPlanMax = 1024;  // up to this many requests every workgroup builds the prefix itself
+
+template <bool kLocalPlan>
 __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens,
-    const int32_t* __restrict__ parents, const int32_t* __restrict__ PB, float* __restrict__ part_o,
+    const int32_t* __restrict__ parents, int32_t* __restrict__ PB, float* __restrict__ part_o,
     float* __restrict__ part_ml, int B, int Nq, int Hq, int Hkv, int page_shift, int max_pages, float scale_log2) {
   // K and V tiles live in separate LDS objects: the compiler tracks pending LDS-direct loads per object,
   // so a read of a K tile does not wait for the V tile still in flight (and vice versa)
@@ -103,8 +106,42 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
   __shared__ float s_m[4][32];
   __shared__ float s_l[4][32];
 
+  __shared__ int s_pb[kLocalPlan ? kLocalPlanMax + 1 : 1];
+  __shared__ int s_wsum[4];
+  if (kLocalPlan) {
+    // prefix of tiles per request (see attn_plan_kernel), built by every workgroup: thread t owns
+    // requests 4t .. 4t+3; workgroup (0,0) also publishes it for the merge kernel
+    const int t4 = threadIdx.x * 4;
+    int un[4], loc = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      un[i] = t4 + i < B ? ((seq_lens[t4 + i] + kAtTile - 1) / kAtTile) * Hkv : 0;
+      loc += un[i];
+    }
+    int incl = loc;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int y = __shfl_up(incl, o, kWave);
+      if ((int)(threadIdx.x & 63) >= o) incl += y;
+    }
+    if ((threadIdx.x & 63) == 63) s_wsum[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    int run = incl - loc;
+    for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) run += s_wsum[w];
+    if (threadIdx.x == 0) s_pb[0] = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      run += un[i];
+      if (t4 + i < B) s_pb[t4 + i + 1] = run;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && blockIdx.y == 0)
+      for (int i = threadIdx.x; i <= B; i += kAtThreads) PB[i] = s_pb[i];
+  }
+  auto pbv = [&](int i) -> int { return kLocalPlan ? s_pb[i] : PB[i]; };
+
   const int rt = blockIdx.y, row_tiles = gridDim.y;
-  const int U = PB[B];
+  const int U = pbv(B);
   const int c = units_per_wg(U, gridDim.x);
   int u = blockIdx.x * c;
   const int u_end = min(U, u + c);
@@ -139,17 +176,17 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
     int lo = 0, hi = B - 1;
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
-      if (PB[mid] <= u) lo = mid; else hi = mid - 1;
+      if (pbv(mid) <= u) lo = mid; else hi = mid - 1;
     }
     b = lo;
   }
 
   // ---- one segment per (request, KV head) pair this workgroup's unit range touches --------------------
   while (u < u_end) {
-    while (PB[b + 1] <= u) ++b;
+    while (pbv(b + 1) <= u) ++b;
     const int L = seq_lens[b];
     const int n_b = (L + kAtTile - 1) / kAtTile;
-    const int rel = u - PB[b];
+    const int rel = u - pbv(b);
     const int hk = __builtin_amdgcn_readfirstlane(rel / n_b);
     const int t0 = rel - hk * n_b;
     const int t1 = min(n_b, t0 + (u_end - u));
@@ -184,10 +221,14 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
     // counts them).  Rows past the end of the sequence re-read the last valid token; their scores are
     // masked to -inf, so their (finite) values are multiplied by exact zeros.  A 32-token tile touches
     // at most two pages, whose ids are fetched with scalar loads.
-    auto issue_tile = [&](const bf16_t* pool, char* buf, int tt) {
+    auto tile_pages = [&](int tt, int& pid_a, int& pid_b) {
       const int j0 = start + tt * kAtTile;
-      const int pa = j0 >> page_shift, pb = min(j0 + 16, L - 1) >> page_shift;
-      const int pid_a = bt[pa], pid_b = bt[pb];
+      pid_a = bt[j0 >> page_shift];
+      pid_b = bt[min(j0 + 16, L - 1) >> page_shift];
+    };
+    auto issue_tile = [&](const bf16_t* pool, char* buf, int tt, int pid_a, int pid_b) {
+      const int j0 = start + tt * kAtTile;
+      const int pa = j0 >> page_shift;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int tok = min(j0 + 4 * j + lrow, L - 1);
@@ -211,11 +252,16 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
     __syncthreads();  // query rows staged (nothing is in flight yet, so the fence costs nothing)
     int tt = wv;
     if (tt < ntile) {
-      issue_tile(kp, kbuf, tt);
-      issue_tile(vp, vbuf, tt);
+      int pa0, pb0;
+      tile_pages(tt, pa0, pb0);
+      issue_tile(kp, kbuf, tt, pa0, pb0);
+      issue_tile(vp, vbuf, tt, pa0, pb0);
     }
     for (; tt < ntile; tt += 4) {
       const bool more = tt + 4 < ntile;
+      // page ids of the next tile: scalar loads issued a whole tile ahead of their use
+      int npa = 0, npb = 0;
+      if (more) tile_pages(tt + 4, npa, npb);
       // ---- S^T = K Q^T ----------------------------------------------------------------------------
       WAIT_VMCNT(8);  // K(t) landed (V(t) may still be in flight)
       f32x16_t s_acc;
@@ -231,7 +277,7 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
       // the K buffer is free once the products above have their operands; the memory clobber keeps
       // the compiler from moving the LDS reads below the overwrite
       asm volatile("" ::: "memory");
-      if (more) issue_tile(kp, kbuf, tt + 4);
+      if (more) issue_tile(kp, kbuf, tt + 4, npa, npb);
 
       // ---- online softmax (register r holds token j0 + 8(r/4) + 4*lh + r%4 of this lane's row) --
       const int j0 = start + tt * kAtTile;
@@ -286,7 +332,7 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
         }
       }
       asm volatile("" ::: "memory");
-      if (more) issue_tile(vp, vbuf, tt + 4);
+      if (more) issue_tile(vp, vbuf, tt + 4, npa, npb);
     }
 
     // ---- merge the four wavefronts and write this segment's partial (m, l, O) -------------------------
@@ -360,16 +406,29 @@ __global__ __launch_bounds__(kAtD) void attn_mfma_combine(const float* __restric
   const int u0 = PB[b] + hk * n_b, u1 = u0 + n_b;
   const int w0 = u0 / c, w1 = (u1 - 1) / c;
   const int pair = b * Hkv + hk;
-  float M = -INFINITY;
-  for (int w = w0; w <= w1; ++w) M = fmaxf(M, part_ml[(((size_t)(w + pair) * row_tiles + rt) * 32 + li) * 2]);
   const int d = threadIdx.x;
-  float num = 0.f, den = 0.f;
-  for (int w = w0; w <= w1; ++w) {
-    const size_t prow = ((size_t)(w + pair) * row_tiles + rt) * 32 + li;
-    const float ms = part_ml[prow * 2];
-    const float f = ms == -INFINITY ? 0.f : __expf(ms - M);
-    num = fmaf(f, part_o[prow * kAtD + d], num);
-    den = fmaf(f, part_ml[prow * 2 + 1], den);
+  // online merge, four segments' loads in flight at a time
+  float M = -INFINITY, num = 0.f, den = 0.f;
+  for (int w = w0; w <= w1; w += 4) {
+    float ms[4], ls[4], os[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bool ok = w + i <= w1;
+      const size_t prow = ((size_t)(ok ? w + i + pair : w + pair) * row_tiles + rt) * 32 + li;
+      ms[i] = ok ? part_ml[prow * 2] : -INFINITY;
+      ls[i] = ok ? part_ml[prow * 2 + 1] : 0.f;
+      os[i] = ok ? part_o[prow * kAtD + d] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (ms[i] == -INFINITY) continue;
+      const float nm = fmaxf(M, ms[i]);
+      const float fo = M == -INFINITY ? 0.f : __expf(M - nm);
+      const float fn = __expf(ms[i] - nm);
+      num = num * fo + fn * os[i];
+      den = den * fo + fn * ls[i];
+      M = nm;
+    }
   }
   out[row * kAtD + d] = f32_to_bf16(den > 0.f ? num / den : 0.f);
 }
@@ -381,12 +440,21 @@ bool attn_mfma_supported(const AttnLaunch& a) {
 hipError_t launch_attn_mfma(const AttnLaunch& a, hipStream_t st) {
   const int R = a.Hq / a.Hkv * a.Nq;
   const int row_tiles = (R + 31) / 32;
-  hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, st, a.seq_lens, a.B, a.Hkv, a.plan_pb);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_mfma_kernel, dim3(kAttnWorkgroups, row_tiles), dim3(kAtThreads), 0, st, (const bf16_t*)a.q,
-                     (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, a.plan_pb, a.part_o,
-                     a.part_ml, a.B, a.Nq, a.Hq, a.Hkv, __builtin_ctz(a.page), a.max_pages, a.scale * kLog2e);
+  hipError_t e;
+  if (a.B <= kLocalPlanMax) {
+    hipLaunchKernelGGL(attn_mfma_kernel<true>, dim3(kAttnWorkgroups, row_tiles), dim3(kAtThreads), 0, st,
+                       (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
+                       a.plan_pb, a.part_o, a.part_ml, a.B, a.Nq, a.Hq, a.Hkv, __builtin_ctz(a.page), a.max_pages,
+                       a.scale * kLog2e);
+  } else {
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, st, a.seq_lens, a.B, a.Hkv, a.plan_pb);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(attn_mfma_kernel<false>, dim3(kAttnWorkgroups, row_tiles), dim3(kAtThreads), 0, st,
+                       (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
+                       a.plan_pb, a.part_o, a.part_ml, a.B, a.Nq, a.Hq, a.Hkv, __builtin_ctz(a.page), a.max_pages,
+                       a.scale * kLog2e);
+  }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const unsigned rows = (unsigned)((size_t)a.B * a.Nq * a.Hq);

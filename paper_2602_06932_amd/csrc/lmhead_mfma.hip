@@ -152,15 +152,13 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
   // Each wavefront reduces its 64 rows per token in registers and parks the triple in an LDS stage
   // that the main loop no longer touches; after one barrier the first 32*NT threads merge the four
   // wavefronts (ascending vocab order, so ties keep the lowest index).
-  float* st_max = (float*)(lds + (nk % kLmStages) * kStageBytes);
+  float* st_max = (float*)(lds + (nk % kLmStages) * kStageBytes + kLmWBytes);  // hidden part of an idle stage
   float* st_sum = st_max + 4 * NT * 32;
   int* st_arg = (int*)(st_sum + 4 * NT * 32);
   const int vrow0 = vbase + wv * kLmWaveV;
   const bool vec_ok = (V & 3) == 0;
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
-    const int m = m0 + 32 * t + li;
-    const bool m_ok = m < M;
     float mx = -INFINITY;
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -194,22 +192,40 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
       st_sum[wv * NT * 32 + t * 32 + li] = sum;
       st_arg[wv * NT * 32 + t * 32 + li] = arg;
     }
-    if (m_ok) {
-      float* lrow = logits + (size_t)m * V;
+    // Logits out.  In the accumulator layout a lane holds 4 consecutive vocab entries of ONE token, so a
+    // direct store would touch 64 different rows per instruction.  The 64 x 32 tile is turned through
+    // this wavefront's private 8 KB of LDS (its W rows of stage 0, idle now) so that every store
+    // instruction writes four token rows of 256 contiguous bytes.  16-byte slots are XOR-swizzled by
+    // the token row on both sides: no bank conflicts.  LDS operations of one wavefront execute in
+    // order, so the next tile's writes cannot overtake this tile's reads.
+    {
+      char* tb = lds + wv * (kLmWaveV * kLmRowBytes);
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const int v = vrow0 + 32 * a + 8 * g + 4 * lh;
+          const int slot = 8 * a + 2 * g + lh;  // 16-byte slot of vocab 32a + 8g + 4lh within the 64-wide row
+          f32x4_t o = {acc[a][t][4 * g], acc[a][t][4 * g + 1], acc[a][t][4 * g + 2], acc[a][t][4 * g + 3]};
+          *(f32x4_t*)(tb + li * 256 + ((slot ^ (li & 15)) * 16)) = o;
+        }
+      const int srow = lane >> 4, sslot = lane & 15;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int n = 4 * j + srow;  // token row of the tile
+        const f32x4_t o = *(const f32x4_t*)(tb + n * 256 + ((sslot ^ (n & 15)) * 16));
+        const int mm = m0 + 32 * t + n;
+        const int v = vrow0 + 4 * sslot;
+        if (mm < M) {
+          float* dst = logits + (size_t)mm * V + v;
           if (vec_ok && v + 3 < V) {
-            f32x4_t o = {acc[a][t][4 * g], acc[a][t][4 * g + 1], acc[a][t][4 * g + 2], acc[a][t][4 * g + 3]};
-            *(f32x4_t*)(lrow + v) = o;
+            *(f32x4_t*)dst = o;
           } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-              if (v + e < V) lrow[v + e] = acc[a][t][4 * g + e];
+              if (v + e < V) dst[e] = o[e];
           }
         }
+      }
     }
   }
   __syncthreads();  // the producers' last barrier pairs with this one

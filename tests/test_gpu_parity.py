@@ -228,3 +228,11 @@ def test_full_size_stress_sparse_pool(gpu_lib):
     w = gen.stress_chain(1, pool_pages=pool_bytes // page_bytes)
     assert w.seq_lens.max() > 20000 and w.seq_lens.min() < 400
     _, a = _full_check(gpu_lib, w, sample=_spread_sample(w, 4))
+
+
+def test_many_short_requests(gpu_lib):
+    """More requests than the attention kernel plans for in shared memory (separate planning kernel),
+    many (request, head) pairs per workgroup, every sequence shorter than one tile run."""
+    w = gen.llama_chain(13, batch=1030, num_q=3, num_q_heads=4, num_kv_heads=2, len_lo=3, len_hi=70, vocab=512,
+                        hidden_size=64)
+    _full_check(gpu_lib, w, sample=np.arange(0, 1030, 41))
