@@ -45,7 +45,7 @@ template <int NT>
 __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     const bf16_t* __restrict__ hidden, const bf16_t* __restrict__ w, float* __restrict__ logits,
     float* __restrict__ pmax, float* __restrict__ psum, int32_t* __restrict__ parg, int M, int H, int V, int n_tiles,
-    float exp_scale /* log2(e) / T */) {
+    int m_tiles, float exp_scale /* log2(e) / T */) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   constexpr int kStageBytes = kLmWBytes + NT * 32 * kLmRowBytes;
   constexpr int kLoadsPerStage = 8 + NT;  // global->LDS instructions per producer wavefront per stage
@@ -54,13 +54,20 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool producer = wave >= 4;
   const int wv = wave & 3;  // vocab slice: consumer wv multiplies the rows producer wv + 4 brings in
-  const int vbase = blockIdx.x * kLmVTile;
-  const int m0 = blockIdx.y * (NT * 32);
+  // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  The m_tiles token passes
+  // over one vocab tile get ids 8 apart: same XCD, launched together, walking k in the same order - so
+  // the W tile comes from HBM once and from L2 for the other passes.
+  const int wg = blockIdx.x;
+  const int vt = (wg / (8 * m_tiles)) * 8 + (wg & 7);
+  const int mt = (wg >> 3) % m_tiles;
+  if (vt >= n_tiles) return;
+  const int vbase = vt * kLmVTile;
+  const int m0 = mt * (NT * 32);
   const int nk = H / kLmBK;
   // Workgroups start their walk over the hidden dimension at different offsets (and wrap around):
   // rows are a multiple of the memory-channel interleave apart, so workgroups marching through k
   // in lockstep would all hit the same few HBM channels at any moment.
-  const int ks0 = (int)((blockIdx.x * 13u + blockIdx.y * 7u) % (unsigned)nk);
+  const int ks0 = (int)((vt * 13u) % (unsigned)nk);
 
   if (producer) {
     // ---- producer wavefronts: nothing but address arithmetic, LDS-direct loads and barriers ----------
@@ -245,7 +252,7 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
         const float x = st_max[w * NT * 32 + tid];
         if (x > -INFINITY) sum += st_sum[w * NT * 32 + tid] * __builtin_amdgcn_exp2f((x - mx) * exp_scale);
       }
-      const size_t o = (size_t)m * n_tiles + blockIdx.x;
+      const size_t o = (size_t)m * n_tiles + vt;
       pmax[o] = mx;
       psum[o] = sum;
       parg[o] = arg;
@@ -270,10 +277,11 @@ static hipError_t launch_nt(const AcceptLaunch& a, hipStream_t st, int m_tiles) 
     attr_set = true;
   }
   const float exp_scale = 1.4426950408889634f / (a.temperature > 0.f ? a.temperature : 1.f);
-  dim3 grid((a.V + kLmVTile - 1) / kLmVTile, m_tiles);
+  const int v_tiles = (a.V + kLmVTile - 1) / kLmVTile;
+  dim3 grid((v_tiles + 7) / 8 * 8 * m_tiles);
   hipLaunchKernelGGL(lmhead_mfma_kernel<NT>, grid, dim3(kLmThreads), lds_bytes, st, (const bf16_t*)a.hidden,
                      (const bf16_t*)a.lm_head, a.logits, a.pmax, a.psum, a.parg, (int)a.plan.rows, a.H, a.V,
-                     a.plan.n_tiles, exp_scale);
+                     a.plan.n_tiles, m_tiles, exp_scale);
   return hipGetLastError();
 }
 
