@@ -236,3 +236,31 @@ def test_many_short_requests(gpu_lib):
     w = gen.llama_chain(13, batch=1030, num_q=3, num_q_heads=4, num_kv_heads=2, len_lo=3, len_hi=70, vocab=512,
                         hidden_size=64)
     _full_check(gpu_lib, w, sample=np.arange(0, 1030, 41))
+
+
+@pytest.mark.parametrize("page", [32, 64, 256])
+def test_larger_pages(gpu_lib, page):
+    w = gen.llama_chain(14, batch=5, page_size=page, len_lo=10, len_hi=900, vocab=1500, hidden_size=128)
+    _full_check(gpu_lib, w)
+
+
+def test_page_size_not_power_of_two_uses_generic_kernel(gpu_lib):
+    w = gen.llama_chain(15, batch=3, page_size=24, len_lo=10, len_hi=300, vocab=900, hidden_size=64)
+    _full_check(gpu_lib, w)
+
+
+def test_max_positions_and_deep_chain(gpu_lib):
+    """Nq = 64 query positions (the maximum): two row tiles even with a single head per group."""
+    w = gen.llama_chain(16, batch=2, num_q=64, num_q_heads=2, num_kv_heads=2, len_lo=64, len_hi=400, vocab=700,
+                        hidden_size=64, draft_noise=0.3)
+    _full_check(gpu_lib, w)
+
+
+def test_lmhead_stage_alone_matches_oracle_logits(gpu_lib):
+    from paper_2602_06932_amd.device import DeviceVerify
+    w = gen.llama_chain(17, batch=6, len_lo=20, len_hi=50, vocab=3001, hidden_size=192)
+    dv = DeviceVerify(w)
+    dv.lmhead()
+    torch.cuda.synchronize()
+    ref = oracle.logits(hidden=w.hidden, lm_head=w.lm_head, dtype=w.dtype)
+    check_logits(dv.logits_host(after="accept"), ref, w.dtype)
