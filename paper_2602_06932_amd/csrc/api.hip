@@ -182,8 +182,12 @@ int run_lmhead(const aurora_accept_desc* desc, const void* hidden, const void* l
 }
 
 bool have_device() {
-  int n = 0;
-  return hipGetDeviceCount(&n) == hipSuccess && n > 0;
+  static int cached = -1;  // the answer does not change during a process's life
+  if (cached < 0) {
+    int n = 0;
+    cached = (hipGetDeviceCount(&n) == hipSuccess && n > 0) ? 1 : 0;
+  }
+  return cached == 1;
 }
 
 }  // namespace

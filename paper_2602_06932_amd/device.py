@@ -71,21 +71,57 @@ class DeviceVerify:
         self.p_at_draft = torch.full((Bn, Nq), float("nan"), dtype=torch.float32, device="cuda")
         self.row_lse = torch.full((Bn, Nq), float("nan"), dtype=torch.float32, device="cuda")
 
-    # -- calls through the C ABI ---------------------------------------------------------------
+        # argument lists marshalled once: the buffers of a DeviceVerify never move
+        import ctypes as C
+        lib = B.load()
+        P = B._ptr
+        ws, wsb = P(self.workspace), self.ws_bytes
+        attn_args = (P(self.q), P(self.k_pages), P(self.v_pages), P(self.block_table), P(self.seq_lens),
+                     P(self.parents))
+        acc_in = (P(self.hidden), P(self.lm_head), P(self.draft_tokens), P(self.draft_probs), P(self.uniforms))
+        acc_out = (P(self.accept_len), P(self.next_token), P(self.accept_mask), P(self.p_at_draft), P(self.row_lse))
+        ad, cd = C.byref(self.attn_desc), C.byref(self.accept_desc)
+        self._fast = {
+            "attn": (lib.aurora_verify_attn, (ad,) + attn_args + (P(self.attn_out), ws, wsb)),
+            "accept": (lib.aurora_verify_accept, (cd,) + acc_in + (P(self.parents),) + acc_out + (ws, wsb)),
+            "lmhead": (lib.aurora_verify_lmhead, (cd, P(self.hidden), P(self.lm_head), ws, wsb)),
+            "verify": (lib.aurora_verify, (ad, cd) + attn_args + (P(self.attn_out),) + acc_in + acc_out + (ws, wsb)),
+        }
+
+    def _call(self, name, stream):
+        fn, args = self._fast[name]
+        st = fn(*args, B._stream(stream))
+        if st != B.AURORA_OK:
+            raise B.AuroraError(st, fn.__name__)
+        return st
+
+    # -- calls through the C ABI (the *_via_binding forms marshal through binding.py on every call) ----------
     def attn(self, stream=None):
+        return self._call("attn", stream)
+
+    def accept(self, stream=None):
+        return self._call("accept", stream)
+
+    def lmhead(self, stream=None):
+        return self._call("lmhead", stream)
+
+    def verify(self, stream=None):
+        return self._call("verify", stream)
+
+    def attn_via_binding(self, stream=None):
         return B.aurora_verify_attn(self.attn_desc, self.q, self.k_pages, self.v_pages, self.block_table,
                                     self.seq_lens, self.parents, self.attn_out, self.workspace, stream)
 
-    def accept(self, stream=None):
+    def accept_via_binding(self, stream=None):
         return B.aurora_verify_accept(self.accept_desc, self.hidden, self.lm_head, self.draft_tokens,
                                       self.draft_probs, self.uniforms, self.parents, self.accept_len,
                                       self.next_token, self.accept_mask, self.p_at_draft, self.row_lse,
                                       self.workspace, stream)
 
-    def lmhead(self, stream=None):
+    def lmhead_via_binding(self, stream=None):
         return B.aurora_verify_lmhead(self.accept_desc, self.hidden, self.lm_head, self.workspace, stream)
 
-    def verify(self, stream=None):
+    def verify_via_binding(self, stream=None):
         return B.aurora_verify(self.attn_desc, self.accept_desc, self.q, self.k_pages, self.v_pages,
                                self.block_table, self.seq_lens, self.parents, self.attn_out, self.hidden,
                                self.lm_head, self.draft_tokens, self.draft_probs, self.uniforms, self.accept_len,

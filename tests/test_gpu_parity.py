@@ -154,8 +154,8 @@ def test_halves_equal_whole_and_runs_are_deterministic(gpu_lib):
     from paper_2602_06932_amd.device import DeviceVerify
     w = gen.llama_chain(10, batch=6, len_lo=40, len_hi=700, vocab=4000, hidden_size=256)
     a = DeviceVerify(w); a.verify(); ra = a.results_host(); oa = a.attn_out_host()
-    b = DeviceVerify(w); b.attn(); b.accept(); rb = b.results_host(); ob = b.attn_out_host()
-    a.verify(); ra2 = a.results_host(); oa2 = a.attn_out_host()
+    b = DeviceVerify(w); b.attn_via_binding(); b.accept_via_binding(); rb = b.results_host(); ob = b.attn_out_host()
+    a.verify_via_binding(); ra2 = a.results_host(); oa2 = a.attn_out_host()
     assert np.array_equal(oa, ob) and np.array_equal(oa, oa2)
     for k in ra:
         assert np.array_equal(ra[k], rb[k], equal_nan=True), k
