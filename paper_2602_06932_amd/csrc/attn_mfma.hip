@@ -90,6 +90,137 @@ __device__ __forceinline__ int units_per_wg(int U, int wgs) {
   return (c + 3) & ~3;  // a multiple of four tiles: the four wavefronts of a workgroup stay balanced
 }
 
+// ---- pieces shared by the two sweep kernels -----------------------------------------------------------
+struct SoftmaxState {
+  f32x16_t o[4];   // O^T accumulators: block db, register r <-> column 32 db + 8(r/4) + 4*lh + r%4
+  float m_run;     // running max of the scaled scores of this lane's query row, log2 units
+  float l_half;    // running sum over the tokens this half-lane owns
+};
+
+__device__ __forceinline__ void softmax_state_reset(SoftmaxState& st) {
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
+  st.m_run = -INFINITY;
+  st.l_half = 0.f;
+}
+
+// S^T = K Q^T for one 32-token tile: tokens are MFMA rows, the 32 query rows MFMA columns
+__device__ __forceinline__ f32x16_t tile_scores(const char* kbuf, const char* qtile, int li, int lh) {
+  f32x16_t s_acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s_acc[r] = 0.f;
+  const int sw = li & 15;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const int coff = li * kAtRowBytes + (((2 * s + lh) ^ sw) * 16);
+    const bf16x8_t ka = *(const bf16x8_t*)(kbuf + coff);
+    const bf16x8_t qa = *(const bf16x8_t*)(qtile + coff);
+    s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qa, s_acc, 0, 0, 0);
+  }
+  return s_acc;
+}
+
+// online softmax of the tile (register r holds token j0 + 8(r/4) + 4*lh + r%4 of this lane's row);
+// returns the exp'd scores rounded to bf16, already laid out as the B operand of the P.V product
+__device__ __forceinline__ void tile_softmax(f32x16_t s_acc, SoftmaxState& st, u16x8_t pb2[2], float scale_log2, int j0,
+                                             int prefix, int L, unsigned long long anc, int lh) {
+  const bool need_mask = j0 + kAtTile > prefix;
+  float tmax = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float x = s_acc[r] * scale_log2;
+    if (need_mask) {
+      const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+      const bool seen = j < prefix || (j < L && ((anc >> (j - prefix)) & 1ull));
+      x = seen ? x : -INFINITY;
+    }
+    s_acc[r] = x;
+    tmax = fmaxf(tmax, x);
+  }
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
+  const float m_new = fmaxf(st.m_run, tmax);
+  const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+  const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_safe);
+  st.m_run = m_new;
+  float psum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const float pexp = __builtin_amdgcn_exp2f(s_acc[r] - m_safe);
+    psum += pexp;
+    pb2[r >> 3][r & 7] = f32_to_bf16(pexp);
+  }
+  st.l_half = st.l_half * alpha + psum;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
+}
+
+// O^T += V^T P^T
+__device__ __forceinline__ void tile_pv(const char* vbuf, const u16x8_t pb2[2], SoftmaxState& st, int li, int lh) {
+#pragma unroll
+  for (int uu = 0; uu < 2; ++uu) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      // slot j of this half-lane is token 16u + 8(j/4) + 4*lh + j%4, column d = 32 db + li
+      const int d = 32 * db + li;
+      u16x8_t va;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int t = 16 * uu + 8 * (j >> 2) + 4 * lh + (j & 3);
+        va[j] = *(const unsigned short*)(vbuf + t * kAtRowBytes + (((d >> 3) ^ (t & 15)) * 16) + (d & 7) * 2);
+      }
+      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, va),
+                                                         __builtin_bit_cast(bf16x8_t, pb2[uu]), st.o[db], 0, 0, 0);
+    }
+  }
+}
+
+// one of the 8 load instructions of a K or V tile: token rows 4j .. 4j+3 of the tile starting at j0
+__device__ __forceinline__ void issue_rows(const bf16_t* pool, char* buf, int j, int j0, int L, int page_shift, int Hkv,
+                                           int hk, int pid_a, int pid_b, int lane) {
+  const int lrow = lane >> 4, lpos = lane & 15;
+  const int pa = j0 >> page_shift;
+  const int tok = min(j0 + 4 * j + lrow, L - 1);
+  const int pid = (tok >> page_shift) == pa ? pid_a : pid_b;
+  const int r = 4 * j + lrow;
+  const int chunk = lpos ^ (r & 15);
+  const bf16_t* src =
+      pool + ((((size_t)pid * Hkv + hk) << page_shift) + (tok & ((1 << page_shift) - 1))) * kAtD + chunk * 8;
+  load_to_lds_16(src, buf + j * 1024);
+}
+
+// prefix of tiles per request (see attn_plan_kernel) built by the whole workgroup into s_pb[0..B], B <= 1024
+__device__ __forceinline__ void build_prefix(const int32_t* __restrict__ seq_lens, int B, int Hkv, int* s_pb,
+                                             int* s_wsum) {
+  const int t4 = threadIdx.x * 4;
+  int un[4], loc = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    un[i] = t4 + i < B ? ((seq_lens[t4 + i] + kAtTile - 1) / kAtTile) * Hkv : 0;
+    loc += un[i];
+  }
+  int incl = loc;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int y = __shfl_up(incl, o, kWave);
+    if ((int)(threadIdx.x & 63) >= o) incl += y;
+  }
+  if ((threadIdx.x & 63) == 63) s_wsum[threadIdx.x >> 6] = incl;
+  __syncthreads();
+  int run = incl - loc;
+  for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) run += s_wsum[w];
+  if (threadIdx.x == 0) s_pb[0] = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    run += un[i];
+    if (t4 + i < B) s_pb[t4 + i + 1] = run;
+  }
+  __syncthreads();
+}
+
 constexpr int kLocalPlanMax = 1024;  // up to this many requests every workgroup builds the prefix itself
 
 template <bool kLocalPlan>
@@ -109,32 +240,8 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
   __shared__ int s_pb[kLocalPlan ? kLocalPlanMax + 1 : 1];
   __shared__ int s_wsum[4];
   if (kLocalPlan) {
-    // prefix of tiles per request (see attn_plan_kernel), built by every workgroup: thread t owns
-    // requests 4t .. 4t+3; workgroup (0,0) also publishes it for the merge kernel
-    const int t4 = threadIdx.x * 4;
-    int un[4], loc = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      un[i] = t4 + i < B ? ((seq_lens[t4 + i] + kAtTile - 1) / kAtTile) * Hkv : 0;
-      loc += un[i];
-    }
-    int incl = loc;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-      const int y = __shfl_up(incl, o, kWave);
-      if ((int)(threadIdx.x & 63) >= o) incl += y;
-    }
-    if ((threadIdx.x & 63) == 63) s_wsum[threadIdx.x >> 6] = incl;
-    __syncthreads();
-    int run = incl - loc;
-    for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) run += s_wsum[w];
-    if (threadIdx.x == 0) s_pb[0] = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      run += un[i];
-      if (t4 + i < B) s_pb[t4 + i + 1] = run;
-    }
-    __syncthreads();
+    // every workgroup builds the prefix itself; workgroup (0,0) also publishes it for the merge kernel
+    build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
     if (blockIdx.x == 0 && blockIdx.y == 0)
       for (int i = threadIdx.x; i <= B; i += kAtThreads) PB[i] = s_pb[i];
   }
@@ -154,10 +261,6 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
   const int li = lane & 31, lh = lane >> 5;
   char* kbuf = kbuf_all + wv * kAtTileBytes;
   char* vbuf = vbuf_all + wv * kAtTileBytes;
-  const int lrow = lane >> 4;    // token row within a 4-row load instruction
-  const int lpos = lane & 15;    // 16-byte slot within the row
-  const int page_mask = (1 << page_shift) - 1;
-  const int sw = li & 15;
 
   // this lane's query row (MFMA column li) within the group: node n, head g
   const int mrow = rt * 32 + li;
@@ -228,26 +331,12 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
     };
     auto issue_tile = [&](const bf16_t* pool, char* buf, int tt, int pid_a, int pid_b) {
       const int j0 = start + tt * kAtTile;
-      const int pa = j0 >> page_shift;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int tok = min(j0 + 4 * j + lrow, L - 1);
-        const int pid = (tok >> page_shift) == pa ? pid_a : pid_b;
-        const int r = 4 * j + lrow;
-        const int chunk = lpos ^ (r & 15);
-        const bf16_t* src =
-            pool + ((((size_t)pid * Hkv + hk) << page_shift) + (tok & page_mask)) * kAtD + chunk * 8;
-        load_to_lds_16(src, buf + j * 1024);
-      }
+      for (int j = 0; j < 8; ++j) issue_rows(pool, buf, j, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
     };
 
-    f32x16_t o_acc[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
-    float m_run = -INFINITY;  // running max of scaled scores, log2 units
-    float l_half = 0.f;       // running sum over the tokens this half-lane owns
+    SoftmaxState st;
+    softmax_state_reset(st);
 
     __syncthreads();  // query rows staged (nothing is in flight yet, so the fence costs nothing)
     int tt = wv;
@@ -262,78 +351,21 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
       // page ids of the next tile: scalar loads issued a whole tile ahead of their use
       int npa = 0, npb = 0;
       if (more) tile_pages(tt + 4, npa, npb);
-      // ---- S^T = K Q^T ----------------------------------------------------------------------------
       WAIT_VMCNT(8);  // K(t) landed (V(t) may still be in flight)
-      f32x16_t s_acc;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s_acc[r] = 0.f;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const int coff = li * kAtRowBytes + (((2 * s + lh) ^ sw) * 16);
-        const bf16x8_t ka = *(const bf16x8_t*)(kbuf + coff);
-        const bf16x8_t qa = *(const bf16x8_t*)(qbuf + coff);
-        s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qa, s_acc, 0, 0, 0);
-      }
+      const f32x16_t s_acc = tile_scores(kbuf, qbuf, li, lh);
       // the K buffer is free once the products above have their operands; the memory clobber keeps
       // the compiler from moving the LDS reads below the overwrite
       asm volatile("" ::: "memory");
       if (more) issue_tile(kp, kbuf, tt + 4, npa, npb);
-
-      // ---- online softmax (register r holds token j0 + 8(r/4) + 4*lh + r%4 of this lane's row) --
-      const int j0 = start + tt * kAtTile;
-      const bool need_mask = j0 + kAtTile > prefix;
-      float tmax = -INFINITY;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float x = s_acc[r] * scale_log2;
-        if (need_mask) {
-          const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-          const bool seen = j < prefix || (j < L && ((anc >> (j - prefix)) & 1ull));
-          x = seen ? x : -INFINITY;
-        }
-        s_acc[r] = x;
-        tmax = fmaxf(tmax, x);
-      }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-      const float m_new = fmaxf(m_run, tmax);
-      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-      m_run = m_new;
-      float psum = 0.f;
       u16x8_t pb2[2];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pexp = __builtin_amdgcn_exp2f(s_acc[r] - m_safe);
-        psum += pexp;
-        pb2[r >> 3][r & 7] = f32_to_bf16(pexp);
-      }
-      l_half = l_half * alpha + psum;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
-
-      // ---- O^T += V^T P^T -------------------------------------------------------------------------
+      tile_softmax(s_acc, st, pb2, scale_log2, start + tt * kAtTile, prefix, L, anc, lh);
       if (more) WAIT_VMCNT(8); else WAIT_VMCNT(0);  // V(t) landed (K(t+1) may be in flight)
-#pragma unroll
-      for (int uu = 0; uu < 2; ++uu) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          // slot j of this half-lane is token 16u + 8(j/4) + 4*lh + j%4, column d = 32 db + li
-          const int d = 32 * db + li;
-          u16x8_t va;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const int t = 16 * uu + 8 * (j >> 2) + 4 * lh + (j & 3);
-            va[j] = *(const unsigned short*)(vbuf + t * kAtRowBytes + (((d >> 3) ^ (t & 15)) * 16) + (d & 7) * 2);
-          }
-          o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, va),
-                                                              __builtin_bit_cast(bf16x8_t, pb2[uu]), o_acc[db], 0, 0, 0);
-        }
-      }
+      tile_pv(vbuf, pb2, st, li, lh);
       asm volatile("" ::: "memory");
       if (more) issue_tile(vp, vbuf, tt + 4, npa, npb);
     }
+    f32x16_t(&o_acc)[4] = st.o;
+    const float m_run = st.m_run, l_half = st.l_half;
 
     // ---- merge the four wavefronts and write this segment's partial (m, l, O) -------------------------
     float l_row = l_half + __shfl_xor(l_half, 32, kWave);
