@@ -54,7 +54,8 @@ AttnPlan plan_attn(const aurora_attn_desc* d) {
   p.part_o_off = pb_bytes;
   if (p.mfma) {
     p.row_tiles = (p.rows_per_group + 31) / 32;
-    p.slots = kAttnWorkgroups + d->batch * d->num_kv_heads;
+    // the wide-row kernel (more than one row tile) writes two partials per segment
+    p.slots = (kAttnWorkgroups + d->batch * d->num_kv_heads) * (p.row_tiles > 1 ? 2 : 1);
     const size_t nrows = (size_t)p.slots * p.row_tiles * 32;
     p.part_ml_off = p.part_o_off + align_up(nrows * d->head_dim * sizeof(float));
     p.bytes = p.part_ml_off + align_up(nrows * 2 * sizeof(float));

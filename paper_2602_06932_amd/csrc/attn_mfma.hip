@@ -122,63 +122,94 @@ __device__ __forceinline__ f32x16_t tile_scores(const char* kbuf, const char* qt
   return s_acc;
 }
 
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+
+// The running reference of a row's scaled scores only moves when a tile's maximum exceeds it by more
+// than 2^kLazyBits: exp'd scores stay below 2^kLazyBits (exact in fp32, same relative rounding in
+// bf16), and on most tiles no accumulator needs rescaling.
+constexpr float kLazyBits = 8.0f;
+
+// LDS position of 16-byte chunk c of V-tile row r: chunk ^ v_key(r).  Four consecutive token rows land in
+// four different 64-byte groups, which is what the transposing reads below need to be conflict-free.
+__device__ __forceinline__ int v_key(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
 // online softmax of the tile (register r holds token j0 + 8(r/4) + 4*lh + r%4 of this lane's row);
-// returns the exp'd scores rounded to bf16, already laid out as the B operand of the P.V product
-__device__ __forceinline__ void tile_softmax(f32x16_t s_acc, SoftmaxState& st, u16x8_t pb2[2], float scale_log2, int j0,
+// returns the exp'd scores rounded to bf16 (hardware round-to-nearest-even), already laid out as the
+// B operand of the P.V product
+__device__ __forceinline__ void tile_softmax(f32x16_t s_acc, SoftmaxState& st, bf16x8_t pb2[2], float scale_log2, int j0,
                                              int prefix, int L, unsigned long long anc, int lh) {
   const bool need_mask = j0 + kAtTile > prefix;
   float tmax = -INFINITY;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    float x = s_acc[r] * scale_log2;
+    float x = s_acc[r];
     if (need_mask) {
       const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
       const bool seen = j < prefix || (j < L && ((anc >> (j - prefix)) & 1ull));
       x = seen ? x : -INFINITY;
+      s_acc[r] = x;
     }
-    s_acc[r] = x;
     tmax = fmaxf(tmax, x);
   }
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave));
-  const float m_new = fmaxf(st.m_run, tmax);
-  const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-  const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_safe);
-  st.m_run = m_new;
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, kWave)) * scale_log2;  // scale > 0: the max commutes with it
+  if (__any(tmax > st.m_run + kLazyBits)) {  // wave-uniform branch
+    const float m_new = tmax > st.m_run + kLazyBits ? tmax : st.m_run;
+    const float alpha = __builtin_amdgcn_exp2f(st.m_run - (m_new == -INFINITY ? 0.f : m_new));
+    st.m_run = m_new;
+    st.l_half *= alpha;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
+  }
+  const float neg_m = st.m_run == -INFINITY ? 0.f : -st.m_run;
   float psum = 0.f;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const float pexp = __builtin_amdgcn_exp2f(s_acc[r] - m_safe);
-    psum += pexp;
-    pb2[r >> 3][r & 7] = f32_to_bf16(pexp);
+  for (int r = 0; r < 16; r += 2) {
+    const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[r], scale_log2, neg_m));
+    const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[r + 1], scale_log2, neg_m));
+    psum += p0 + p1;
+    const f32x2_t pp = {p0, p1};
+    const bf16x2_t pk = __builtin_convertvector(pp, bf16x2_t);
+    pb2[r >> 3][r & 7] = pk[0];
+    pb2[r >> 3][(r & 7) + 1] = pk[1];
   }
-  st.l_half = st.l_half * alpha + psum;
-#pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
+  st.l_half += psum;
 }
 
-// O^T += V^T P^T
-__device__ __forceinline__ void tile_pv(const char* vbuf, const u16x8_t pb2[2], SoftmaxState& st, int li, int lh) {
+// O^T += V^T P^T.  The A operand needs, per lane, one column of V for eight tokens: two transposing LDS
+// reads (ds_read_b64_tr_b16: within 16 lanes, lane i receives element i%4 of the 8-byte vectors
+// addressed by lanes i/4, 4+i/4, 8+i/4, 12+i/4) fetch four tokens each.  Lane k of a 16-lane group
+// therefore addresses token row tb + k/4, columns 4(k%4)..4(k%4)+3 of the group's 16 columns.
+__device__ __forceinline__ void tile_pv(const char* vbuf, const bf16x8_t pb2[2], SoftmaxState& st, int lane) {
+  const int lh = lane >> 5, k = lane & 15, kq = k >> 2;
+  const int g1 = (lane >> 4) & 1;  // which 16 of the 32 columns of a block
+  // byte address = row*256 + ((chunk ^ v_key(row)) * 16) + (col % 8) * 2 with
+  //   row = 16u + 8e + 4lh + kq,  col = 32db + 16g1 + 4(k%4)   (see v_key; derivation in comments below)
+  // v_key(row) = (kq << 2) | ((2e + lh) & 3);  chunk = 4db + 2g1 + (k%4)/2
+  const int lo0 = ((2 * g1 + ((k & 3) >> 1)) ^ (lh & 3)) * 16;
+  const int lo1 = ((2 * g1 + ((k & 3) >> 1)) ^ ((2 + lh) & 3)) * 16;
+  const int common = lh * 1024 + kq * 256 + (k & 1) * 8 + kq * 64;
+  const int base0 = common + lo0;          // e = 0
+  const int base1 = common + lo1 + 2048;   // e = 1 (token rows + 8)
 #pragma unroll
   for (int uu = 0; uu < 2; ++uu) {
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
-      // slot j of this half-lane is token 16u + 8(j/4) + 4*lh + j%4, column d = 32 db + li
-      const int d = 32 * db + li;
-      u16x8_t va;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int t = 16 * uu + 8 * (j >> 2) + 4 * lh + (j & 3);
-        va[j] = *(const unsigned short*)(vbuf + t * kAtRowBytes + (((d >> 3) ^ (t & 15)) * 16) + (d & 7) * 2);
-      }
-      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, va),
-                                                         __builtin_bit_cast(bf16x8_t, pb2[uu]), st.o[db], 0, 0, 0);
+      typedef __attribute__((address_space(3))) s16x4_t* lds_v4;
+      const s16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(vbuf + uu * 4096 + (base0 ^ (db * 64))));
+      const s16x4_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(vbuf + uu * 4096 + (base1 ^ (db * 64))));
+      const u16x8_t va = {(unsigned short)r0[0], (unsigned short)r0[1], (unsigned short)r0[2], (unsigned short)r0[3],
+                          (unsigned short)r1[0], (unsigned short)r1[1], (unsigned short)r1[2], (unsigned short)r1[3]};
+      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, va), pb2[uu], st.o[db], 0, 0, 0);
     }
   }
 }
 
 // one of the 8 load instructions of a K or V tile: token rows 4j .. 4j+3 of the tile starting at j0
+template <bool kIsV>
 __device__ __forceinline__ void issue_rows(const bf16_t* pool, char* buf, int j, int j0, int L, int page_shift, int Hkv,
                                            int hk, int pid_a, int pid_b, int lane) {
   const int lrow = lane >> 4, lpos = lane & 15;
@@ -186,7 +217,7 @@ __device__ __forceinline__ void issue_rows(const bf16_t* pool, char* buf, int j,
   const int tok = min(j0 + 4 * j + lrow, L - 1);
   const int pid = (tok >> page_shift) == pa ? pid_a : pid_b;
   const int r = 4 * j + lrow;
-  const int chunk = lpos ^ (r & 15);
+  const int chunk = lpos ^ (kIsV ? v_key(r) : (r & 15));
   const bf16_t* src =
       pool + ((((size_t)pid * Hkv + hk) << page_shift) + (tok & ((1 << page_shift) - 1))) * kAtD + chunk * 8;
   load_to_lds_16(src, buf + j * 1024);
@@ -329,10 +360,15 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
       pid_a = bt[j0 >> page_shift];
       pid_b = bt[min(j0 + 16, L - 1) >> page_shift];
     };
-    auto issue_tile = [&](const bf16_t* pool, char* buf, int tt, int pid_a, int pid_b) {
+    auto issue_k = [&](int tt, int pid_a, int pid_b) {
       const int j0 = start + tt * kAtTile;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) issue_rows(pool, buf, j, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
+      for (int j = 0; j < 8; ++j) issue_rows<false>(kp, kbuf, j, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
+    };
+    auto issue_v = [&](int tt, int pid_a, int pid_b) {
+      const int j0 = start + tt * kAtTile;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) issue_rows<true>(vp, vbuf, j, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
     };
 
     SoftmaxState st;
@@ -343,8 +379,8 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
     if (tt < ntile) {
       int pa0, pb0;
       tile_pages(tt, pa0, pb0);
-      issue_tile(kp, kbuf, tt, pa0, pb0);
-      issue_tile(vp, vbuf, tt, pa0, pb0);
+      issue_k(tt, pa0, pb0);
+      issue_v(tt, pa0, pb0);
     }
     for (; tt < ntile; tt += 4) {
       const bool more = tt + 4 < ntile;
@@ -356,13 +392,13 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
       // the K buffer is free once the products above have their operands; the memory clobber keeps
       // the compiler from moving the LDS reads below the overwrite
       asm volatile("" ::: "memory");
-      if (more) issue_tile(kp, kbuf, tt + 4, npa, npb);
-      u16x8_t pb2[2];
+      if (more) issue_k(tt + 4, npa, npb);
+      bf16x8_t pb2[2];
       tile_softmax(s_acc, st, pb2, scale_log2, start + tt * kAtTile, prefix, L, anc, lh);
       if (more) WAIT_VMCNT(8); else WAIT_VMCNT(0);  // V(t) landed (K(t+1) may be in flight)
-      tile_pv(vbuf, pb2, st, li, lh);
+      tile_pv(vbuf, pb2, st, lane);
       asm volatile("" ::: "memory");
-      if (more) issue_tile(vp, vbuf, tt + 4, npa, npb);
+      if (more) issue_v(tt + 4, npa, npb);
     }
     f32x16_t(&o_acc)[4] = st.o;
     const float m_run = st.m_run, l_half = st.l_half;
@@ -418,13 +454,198 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
   }
 }
 
+// ---- wide-row variant: more than 32 query rows per (request, KV head) pair (draft trees) ----------------
+// Eight wavefronts: wavefront (g, w) owns the 32-row query tile w and the KV tiles of parity g, so a KV
+// byte is still read once per pair while two wavefronts per SIMD hide each other's latencies.  K/V
+// tiles go through a ring of LDS stages of two tiles each (every wavefront loads an eighth of both),
+// one workgroup barrier per step; one workgroup per compute unit.  Work is dealt out exactly as in the
+// narrow kernel; each wavefront writes its own partial, two per segment and query tile.
+constexpr int kWideThreads = 512;
+constexpr int kWideStages = 3;
+constexpr int kWideStageBytes = 2 * 2 * kAtTileBytes;                // two tiles, K and V
+constexpr int kWideQBytes = 4 * 32 * kAtRowBytes;                    // four query tiles
+constexpr int kWideLdsBytes = kWideQBytes + kWideStages * kWideStageBytes;
+
+template <bool kLocalPlan>
+__global__ __launch_bounds__(kWideThreads, 1) void attn_mfma_wide_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens,
+    const int32_t* __restrict__ parents, int32_t* __restrict__ PB, float* __restrict__ part_o,
+    float* __restrict__ part_ml, int B, int Nq, int Hq, int Hkv, int page_shift, int max_pages, int row_tiles,
+    float scale_log2) {
+  extern __shared__ __attribute__((aligned(1024))) char wlds[];
+  char* qall = wlds;
+  char* ring = wlds + kWideQBytes;
+  __shared__ int s_pb[kLocalPlan ? kLocalPlanMax + 1 : 1];
+  __shared__ int s_wsum[kWideThreads / kWave];
+  if (kLocalPlan) {
+    // as build_prefix, for 512 threads (threads 256.. own requests beyond 1024: none)
+    {
+      const int t4 = threadIdx.x * 4;
+      int un[4], loc = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        un[i] = t4 + i < B ? ((seq_lens[t4 + i] + kAtTile - 1) / kAtTile) * Hkv : 0;
+        loc += un[i];
+      }
+      int incl = loc;
+#pragma unroll
+      for (int o = 1; o < kWave; o <<= 1) {
+        const int y = __shfl_up(incl, o, kWave);
+        if ((int)(threadIdx.x & 63) >= o) incl += y;
+      }
+      if ((threadIdx.x & 63) == 63) s_wsum[threadIdx.x >> 6] = incl;
+      __syncthreads();
+      int run = incl - loc;
+      for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) run += s_wsum[w];
+      if (threadIdx.x == 0) s_pb[0] = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        run += un[i];
+        if (t4 + i < B) s_pb[t4 + i + 1] = run;
+      }
+      __syncthreads();
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0)
+      for (int i = threadIdx.x; i <= B; i += kWideThreads) PB[i] = s_pb[i];
+  }
+  auto pbv = [&](int i) -> int { return kLocalPlan ? s_pb[i] : PB[i]; };
+
+  const int U = pbv(B);
+  const int c = units_per_wg(U, gridDim.x);
+  int u = blockIdx.x * c;
+  const int u_end = min(U, u + c);
+  if (u >= u_end) return;
+
+  const int G = Hq / Hkv;
+  const int R = G * Nq;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2, wq = wave & 3;
+  const int li = lane & 31, lh = lane >> 5;
+  const int rt = blockIdx.y * 4 + wq;          // this wavefront's query tile
+  const bool rt_ok = rt < row_tiles;           // wave-uniform
+  const int mrow = rt * 32 + li;
+  const bool row_ok = rt_ok && mrow < R;
+  const int node = row_ok ? mrow / G : 0;
+  const char* qtile = qall + wq * (32 * kAtRowBytes);
+  const int qs_row = (tid & 255) >> 3;  // staging: 8 threads per query row, 32 B each
+  const int qs_half = tid >> 8;         // threads 0..255 stage tiles 0 and 1, threads 256..511 tiles 2 and 3
+
+  int b = 0;
+  {
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (pbv(mid) <= u) lo = mid; else hi = mid - 1;
+    }
+    b = lo;
+  }
+
+  while (u < u_end) {
+    while (pbv(b + 1) <= u) ++b;
+    const int L = seq_lens[b];
+    const int n_b = (L + kAtTile - 1) / kAtTile;
+    const int rel = u - pbv(b);
+    const int hk = __builtin_amdgcn_readfirstlane(rel / n_b);
+    const int t0 = rel - hk * n_b;
+    const int t1 = min(n_b, t0 + (u_end - u));
+    const int slot = blockIdx.x + b * Hkv + hk;
+    u += t1 - t0;
+    const int start = t0 * kAtTile;
+    const int prefix = L - Nq;
+    const int ntile = t1 - t0;
+    const int nstep = (ntile + 1) >> 1;
+    const int last_tile_start = ((L - 1) >> 5) << 5;
+    const int32_t* bt = block_table + (size_t)b * max_pages;
+
+    // the four query tiles -> LDS
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int ti = qs_half * 2 + i;
+      const int m = (blockIdx.y * 4 + ti) * 32 + qs_row;
+      const bool ok = m < R;
+      const int nd = ok ? m / G : 0, g = ok ? m % G : 0;
+      const u32x4_t* qp = (const u32x4_t*)(q + (((size_t)b * Nq + nd) * Hq + hk * G + g) * kAtD);
+      const int c0 = (tid & 7) * 2;
+      u32x4_t z = {0u, 0u, 0u, 0u};
+      const u32x4_t v0 = ok ? qp[c0] : z;
+      const u32x4_t v1 = ok ? qp[c0 + 1] : z;
+      char* dst = qall + ti * (32 * kAtRowBytes) + qs_row * kAtRowBytes;
+      *(u32x4_t*)(dst + ((c0 ^ (qs_row & 15)) * 16)) = v0;
+      *(u32x4_t*)(dst + (((c0 + 1) ^ (qs_row & 15)) * 16)) = v1;
+    }
+    unsigned long long anc;
+    if (parents) {
+      anc = 0;
+      for (int a = node, hops = 0; a >= 0 && hops <= Nq; a = parents[(size_t)b * Nq + a], ++hops) anc |= 1ull << a;
+    } else {
+      anc = node == 63 ? ~0ull : ((1ull << (node + 1)) - 1);
+    }
+
+    // this wavefront's eighth of a step: load instruction `wave` of K and of V, for both tiles of the step
+    // (a tile past the end of the sequence re-reads the last one; it is never multiplied)
+    auto issue_step = [&](int sidx) {
+      char* stage = ring + (sidx % kWideStages) * kWideStageBytes;
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        const int j0 = min(start + (2 * sidx + g) * kAtTile, last_tile_start);
+        const int pid_a = bt[j0 >> page_shift];
+        const int pid_b = bt[min(j0 + 16, L - 1) >> page_shift];
+        char* kb = stage + g * (2 * kAtTileBytes);
+        issue_rows<false>(kp, kb, wave, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
+        issue_rows<true>(vp, kb + kAtTileBytes, wave, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
+      }
+    };
+
+    SoftmaxState st;
+    softmax_state_reset(st);
+    __syncthreads();  // query tiles staged; the ring is idle
+    for (int i = 0; i < kWideStages - 1 && i < nstep; ++i) issue_step(i);
+    for (int sidx = 0; sidx < nstep; ++sidx) {
+      // steps sidx+1 .. sidx+kWideStages-2 may stay in flight; near the end of the segment fewer were issued
+      if (nstep - 1 - sidx >= kWideStages - 2) WAIT_VMCNT(4 * (kWideStages - 2)); else WAIT_VMCNT(0);
+      __builtin_amdgcn_s_barrier();  // step complete from all eight wavefronts; the previous step's stage is free
+      asm volatile("" ::: "memory");
+      if (sidx + kWideStages - 1 < nstep) issue_step(sidx + kWideStages - 1);
+      const int tt = 2 * sidx + grp;
+      if (rt_ok && tt < ntile) {
+        const char* kb = ring + (sidx % kWideStages) * kWideStageBytes + grp * (2 * kAtTileBytes);
+        const f32x16_t s_acc = tile_scores(kb, qtile, li, lh);
+        bf16x8_t pb2[2];
+        tile_softmax(s_acc, st, pb2, scale_log2, start + tt * kAtTile, prefix, L, anc, lh);
+        tile_pv(kb + kAtTileBytes, pb2, st, lane);
+      }
+      asm volatile("" ::: "memory");
+    }
+
+    // each wavefront writes the partial of its own query tile and tile parity
+    const float l_row = st.l_half + __shfl_xor(st.l_half, 32, kWave);
+    if (row_ok) {
+      const size_t prow = (((size_t)slot * 2 + grp) * row_tiles + rt) * 32 + li;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4_t o = {st.o[db][4 * g], st.o[db][4 * g + 1], st.o[db][4 * g + 2], st.o[db][4 * g + 3]};
+          *(f32x4_t*)(part_o + prow * kAtD + 32 * db + 8 * g + 4 * lh) = o;
+        }
+      if (lh == 0) {
+        part_ml[prow * 2 + 0] = st.m_run * (1.0f / kLog2e);  // natural-log units (-inf if nothing was visible)
+        part_ml[prow * 2 + 1] = l_row;
+      }
+    }
+    __syncthreads();  // the query tiles and the ring are about to be rewritten
+  }
+}
+
 // Merge the partials of one output row (request b, node n, query head hq): the segments of its
 // (request, KV head) pair sit in slots w + pair for the workgroups w whose unit range meets the pair's.
 __global__ __launch_bounds__(kAtD) void attn_mfma_combine(const float* __restrict__ part_o,
                                                           const float* __restrict__ part_ml,
                                                           const int32_t* __restrict__ seq_lens,
                                                           const int32_t* __restrict__ PB, bf16_t* __restrict__ out, int B,
-                                                          int Nq, int Hq, int Hkv, int wgs, int row_tiles) {
+                                                          int Nq, int Hq, int Hkv, int wgs, int row_tiles, int groups) {
   const size_t row = blockIdx.x;  // (b*Nq + n)*Hq + hq
   const int hq = (int)(row % Hq);
   const int n = (int)((row / Hq) % Nq);
@@ -439,14 +660,18 @@ __global__ __launch_bounds__(kAtD) void attn_mfma_combine(const float* __restric
   const int w0 = u0 / c, w1 = (u1 - 1) / c;
   const int pair = b * Hkv + hk;
   const int d = threadIdx.x;
-  // online merge, four segments' loads in flight at a time
+  // online merge, four partials' loads in flight at a time; partial p of the pair is segment
+  // (w0 + p / groups), tile parity p % groups
   float M = -INFINITY, num = 0.f, den = 0.f;
-  for (int w = w0; w <= w1; w += 4) {
+  const int np = (w1 - w0 + 1) * groups;
+  for (int p0 = 0; p0 < np; p0 += 4) {
     float ms[4], ls[4], os[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const bool ok = w + i <= w1;
-      const size_t prow = ((size_t)(ok ? w + i + pair : w + pair) * row_tiles + rt) * 32 + li;
+      const int pp = p0 + i < np ? p0 + i : 0;
+      const bool ok = p0 + i < np;
+      const size_t sl = (size_t)(w0 + pp / groups + pair) * groups + pp % groups;
+      const size_t prow = (sl * row_tiles + rt) * 32 + li;
       ms[i] = ok ? part_ml[prow * 2] : -INFINITY;
       ls[i] = ok ? part_ml[prow * 2 + 1] : 0.f;
       os[i] = ok ? part_o[prow * kAtD + d] : 0.f;
@@ -469,29 +694,59 @@ bool attn_mfma_supported(const AttnLaunch& a) {
   return a.bf16 && a.D == kAtD && a.page >= 16 && (a.page & (a.page - 1)) == 0;
 }
 
+constexpr int kWideWorkgroups = 256;  // one per compute unit
+
 hipError_t launch_attn_mfma(const AttnLaunch& a, hipStream_t st) {
   const int R = a.Hq / a.Hkv * a.Nq;
   const int row_tiles = (R + 31) / 32;
+  const bool local_plan = a.B <= kLocalPlanMax;
   hipError_t e;
-  if (a.B <= kLocalPlanMax) {
-    hipLaunchKernelGGL(attn_mfma_kernel<true>, dim3(kAttnWorkgroups, row_tiles), dim3(kAtThreads), 0, st,
-                       (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
-                       a.plan_pb, a.part_o, a.part_ml, a.B, a.Nq, a.Hq, a.Hkv, __builtin_ctz(a.page), a.max_pages,
-                       a.scale * kLog2e);
-  } else {
+  if (!local_plan) {
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, st, a.seq_lens, a.B, a.Hkv, a.plan_pb);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attn_mfma_kernel<false>, dim3(kAttnWorkgroups, row_tiles), dim3(kAtThreads), 0, st,
-                       (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
-                       a.plan_pb, a.part_o, a.part_ml, a.B, a.Nq, a.Hq, a.Hkv, __builtin_ctz(a.page), a.max_pages,
-                       a.scale * kLog2e);
+  }
+  const int shift = __builtin_ctz(a.page);
+  const float sc = a.scale * kLog2e;
+  int wgs;
+  if (row_tiles == 1) {
+    wgs = kAttnWorkgroups;
+    dim3 grid(wgs, 1);
+    if (local_plan)
+      hipLaunchKernelGGL(attn_mfma_kernel<true>, grid, dim3(kAtThreads), 0, st, (const bf16_t*)a.q, (const bf16_t*)a.k,
+                         (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, a.plan_pb, a.part_o, a.part_ml, a.B,
+                         a.Nq, a.Hq, a.Hkv, shift, a.max_pages, sc);
+    else
+      hipLaunchKernelGGL(attn_mfma_kernel<false>, grid, dim3(kAtThreads), 0, st, (const bf16_t*)a.q, (const bf16_t*)a.k,
+                         (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, a.plan_pb, a.part_o, a.part_ml, a.B,
+                         a.Nq, a.Hq, a.Hkv, shift, a.max_pages, sc);
+  } else {
+    wgs = kWideWorkgroups;
+    static bool attr_set = false;
+    if (!attr_set) {
+      e = hipFuncSetAttribute((const void*)attn_mfma_wide_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              kWideLdsBytes);
+      if (e != hipSuccess) return e;
+      e = hipFuncSetAttribute((const void*)attn_mfma_wide_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              kWideLdsBytes);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    dim3 grid(wgs, (row_tiles + 3) / 4);
+    if (local_plan)
+      hipLaunchKernelGGL(attn_mfma_wide_kernel<true>, grid, dim3(kWideThreads), kWideLdsBytes, st, (const bf16_t*)a.q,
+                         (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, a.plan_pb,
+                         a.part_o, a.part_ml, a.B, a.Nq, a.Hq, a.Hkv, shift, a.max_pages, row_tiles, sc);
+    else
+      hipLaunchKernelGGL(attn_mfma_wide_kernel<false>, grid, dim3(kWideThreads), kWideLdsBytes, st, (const bf16_t*)a.q,
+                         (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, a.plan_pb,
+                         a.part_o, a.part_ml, a.B, a.Nq, a.Hq, a.Hkv, shift, a.max_pages, row_tiles, sc);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const unsigned rows = (unsigned)((size_t)a.B * a.Nq * a.Hq);
   hipLaunchKernelGGL(attn_mfma_combine, dim3(rows), dim3(kAtD), 0, st, a.part_o, a.part_ml, a.seq_lens, a.plan_pb,
-                     (bf16_t*)a.out, a.B, a.Nq, a.Hq, a.Hkv, kAttnWorkgroups, row_tiles);
+                     (bf16_t*)a.out, a.B, a.Nq, a.Hq, a.Hkv, wgs, row_tiles, row_tiles == 1 ? 1 : 2);
   return hipGetLastError();
 }
 
