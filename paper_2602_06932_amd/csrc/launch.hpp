@@ -42,7 +42,9 @@ hipError_t launch_attn_combine(const AttnLaunch& a, hipStream_t st);
 // LM head + softmax statistics
 bool lmhead_mfma_supported(const AcceptLaunch& a);
 int lmhead_mfma_stat_tile();
-hipError_t launch_lmhead_mfma(const AcceptLaunch& a, hipStream_t st);
+hipError_t launch_lmhead_mfma(const AcceptLaunch& a, hipStream_t st);  // picks the small- or large-M kernel
+bool lmhead_mfma_big_supported(const AcceptLaunch& a);
+hipError_t launch_lmhead_mfma_big(const AcceptLaunch& a, hipStream_t st);
 hipError_t launch_lmhead_generic(const AcceptLaunch& a, hipStream_t st);
 
 // acceptance walk + residual / bonus draw

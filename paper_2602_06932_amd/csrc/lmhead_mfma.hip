@@ -5,7 +5,7 @@
 //   logits[m, v] = sum_h hidden[m, h] * W[v, h]      hidden [M, H] bf16, W [V, H] bf16, fp32 out
 //
 // The weight matrix is streamed from HBM exactly once; it is the dominant traffic of the whole
-// verify step.  One workgroup (4 wavefronts) owns 256 vocabulary rows and up to 160 token rows
+// verify step.  One workgroup (4 multiplying + 4 loading wavefronts) owns 256 vocabulary rows and up to 160 token rows
 // and walks the hidden dimension in steps of 64.  Each step's operands are brought in with
 // direct global->LDS loads (16 B per lane, fully coalesced 128-B rows) into a 3-deep ring of
 // LDS stages, so two steps are always in flight while one is being multiplied.  The 16-byte
@@ -15,14 +15,10 @@
 // Vocabulary rows are the MFMA "A" rows and tokens its "B" columns: a lane then holds 16 vocab
 // entries of ONE token per accumulator tile, so row statistics (max, arg-max, sum exp) reduce
 // inside a lane and need a single cross-lane step.
-#include "common.hpp"
 #include "launch.hpp"
+#include "lmhead_tile.hpp"
 
 namespace aurora {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 constexpr int kLmThreads = 512;                // 4 consumer + 4 producer wavefronts
 constexpr int kLmBK = 64;                      // hidden elements per stage
@@ -35,11 +31,7 @@ constexpr int kLmWBytes = kLmVTile * kLmRowBytes;  // 32 KB
 // not displace the hidden-state rows that every workgroup re-reads from L2.
 constexpr int kCpolNT = 2;
 
-#define LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
-#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
-
-// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14])
-#define WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | (7 << 4) | (15 << 8))
+#define WAIT_VMCNT(n) LM_WAIT_VMCNT(n)
 
 template <int NT>
 __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
@@ -155,103 +147,33 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
   }
 
   // ---- epilogue: logits out, and (max, arg-max, sum exp) of the workgroup's 256 vocab rows ---------
-  // accumulator register r of tile a holds vocab row  vrow0 + 32a + 8(r/4) + 4*lh + r%4  of token m0 + 32t + li.
   // Each wavefront reduces its 64 rows per token in registers and parks the triple in an LDS stage
   // that the main loop no longer touches; after one barrier the first 32*NT threads merge the four
-  // wavefronts (ascending vocab order, so ties keep the lowest index).
+  // wavefronts.  The logits go out through this wavefront's own W rows of stage 0 (idle now).
   float* st_max = (float*)(lds + (nk % kLmStages) * kStageBytes + kLmWBytes);  // hidden part of an idle stage
   float* st_sum = st_max + 4 * NT * 32;
   int* st_arg = (int*)(st_sum + 4 * NT * 32);
   const int vrow0 = vbase + wv * kLmWaveV;
   const bool vec_ok = (V & 3) == 0;
+  char* tb = lds + wv * (kLmWaveV * kLmRowBytes);
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
-    float mx = -INFINITY;
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int v = vrow0 + 32 * a + 8 * (r >> 2) + 4 * lh + (r & 3);
-        if (v >= V) acc[a][t][r] = -INFINITY;
-        mx = fmaxf(mx, acc[a][t][r]);
-      }
-    int arg = 0x7fffffff;
-#pragma unroll
-    for (int a = 1; a >= 0; --a)
-#pragma unroll
-      for (int r = 15; r >= 0; --r) {
-        const int v = vrow0 + 32 * a + 8 * (r >> 2) + 4 * lh + (r & 3);
-        arg = (acc[a][t][r] == mx) ? v : arg;
-      }
-    // merge the two lane halves (they hold interleaved groups of 4 rows of the same token)
-    const float omx = __shfl_xor(mx, 32, kWave);
-    const int oarg = __shfl_xor(arg, 32, kWave);
-    if (omx > mx || (omx == mx && oarg < arg)) { mx = omx; arg = oarg; }
-    const float mx_safe = mx == -INFINITY ? 0.f : mx;
-    float sum = 0.f;
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f((acc[a][t][r] - mx_safe) * exp_scale);
-    sum += __shfl_xor(sum, 32, kWave);
+    float mx, sum;
+    int arg;
+    lm_tile_out(acc[0][t], acc[1][t], vrow0, V, m0 + 32 * t, M, exp_scale, tb, logits, vec_ok, lane, mx, sum, arg);
     if (lh == 0) {
       st_max[wv * NT * 32 + t * 32 + li] = mx;
       st_sum[wv * NT * 32 + t * 32 + li] = sum;
       st_arg[wv * NT * 32 + t * 32 + li] = arg;
-    }
-    // Logits out.  In the accumulator layout a lane holds 4 consecutive vocab entries of ONE token, so a
-    // direct store would touch 64 different rows per instruction.  The 64 x 32 tile is turned through
-    // this wavefront's private 8 KB of LDS (its W rows of stage 0, idle now) so that every store
-    // instruction writes four token rows of 256 contiguous bytes.  16-byte slots are XOR-swizzled by
-    // the token row on both sides: no bank conflicts.  LDS operations of one wavefront execute in
-    // order, so the next tile's writes cannot overtake this tile's reads.
-    {
-      char* tb = lds + wv * (kLmWaveV * kLmRowBytes);
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int slot = 8 * a + 2 * g + lh;  // 16-byte slot of vocab 32a + 8g + 4lh within the 64-wide row
-          f32x4_t o = {acc[a][t][4 * g], acc[a][t][4 * g + 1], acc[a][t][4 * g + 2], acc[a][t][4 * g + 3]};
-          *(f32x4_t*)(tb + li * 256 + ((slot ^ (li & 15)) * 16)) = o;
-        }
-      const int srow = lane >> 4, sslot = lane & 15;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int n = 4 * j + srow;  // token row of the tile
-        const f32x4_t o = *(const f32x4_t*)(tb + n * 256 + ((sslot ^ (n & 15)) * 16));
-        const int mm = m0 + 32 * t + n;
-        const int v = vrow0 + 4 * sslot;
-        if (mm < M) {
-          float* dst = logits + (size_t)mm * V + v;
-          if (vec_ok && v + 3 < V) {
-            *(f32x4_t*)dst = o;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (v + e < V) dst[e] = o[e];
-          }
-        }
-      }
     }
   }
   __syncthreads();  // the producers' last barrier pairs with this one
   if (tid < NT * 32) {
     const int m = m0 + tid;
     if (m < M) {
-      float mx = -INFINITY;
-      int arg = 0x7fffffff;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float x = st_max[w * NT * 32 + tid];
-        if (x > mx) { mx = x; arg = st_arg[w * NT * 32 + tid]; }
-      }
-      float sum = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float x = st_max[w * NT * 32 + tid];
-        if (x > -INFINITY) sum += st_sum[w * NT * 32 + tid] * __builtin_amdgcn_exp2f((x - mx) * exp_scale);
-      }
+      float mx, sum;
+      int arg;
+      lm_merge_waves(st_max, st_sum, st_arg, NT * 32, tid, exp_scale, mx, sum, arg);
       const size_t o = (size_t)m * n_tiles + vt;
       pmax[o] = mx;
       psum[o] = sum;
@@ -287,6 +209,12 @@ static hipError_t launch_nt(const AcceptLaunch& a, hipStream_t st, int m_tiles) 
 
 hipError_t launch_lmhead_mfma(const AcceptLaunch& a, hipStream_t st) {
   const int M = (int)a.plan.rows;
+  // Beyond one 160-row pass the contraction is bound by the matrix cores: the 256 x 256-tile kernel, in
+  // which all wavefronts multiply, is faster whenever the token rows fill its tiles to 90 % or more.
+  if (M > 160 && lmhead_mfma_big_supported(a)) {
+    const int tiles32 = (M + 31) / 32, big_tiles = (M + 255) / 256;
+    if (10 * tiles32 >= 9 * 8 * big_tiles) return launch_lmhead_mfma_big(a, st);
+  }
   // token rows per workgroup: the fewest 160-row passes over W, each as narrow as the rows allow
   const int passes = (M + 159) / 160;
   const int per = (M + passes - 1) / passes;

@@ -264,3 +264,19 @@ def test_lmhead_stage_alone_matches_oracle_logits(gpu_lib):
     torch.cuda.synchronize()
     ref = oracle.logits(hidden=w.hidden, lm_head=w.lm_head, dtype=w.dtype)
     check_logits(dv.logits_host(after="accept"), ref, w.dtype)
+
+
+@pytest.mark.parametrize("batch,num_q,vocab,hidden", [(33, 7, 5003, 256), (52, 5, 2304, 128), (101, 5, 1100, 192)])
+def test_lmhead_many_token_rows(gpu_lib, batch, num_q, vocab, hidden):
+    """More than 160 token rows: the 256 x 256-tile LM-head kernel (231 rows: one token tile with clamped
+    rows and whole 32-row tiles past the end; 260 rows would not fill it and stays on the small-M kernel;
+    505 rows: two token tiles), ragged vocabulary tail, statistics checked through row_lse / accept."""
+    from paper_2602_06932_amd.device import DeviceVerify
+    w = gen.llama_chain(18, batch=batch, num_q=num_q, len_lo=20, len_hi=40, vocab=vocab, hidden_size=hidden,
+                        num_q_heads=4, num_kv_heads=2)
+    dv = DeviceVerify(w)
+    dv.lmhead()
+    torch.cuda.synchronize()
+    ref = oracle.logits(hidden=w.hidden, lm_head=w.lm_head, dtype=w.dtype)
+    check_logits(dv.logits_host(after="accept"), ref, w.dtype)
+    _full_check(gpu_lib, w)
