@@ -24,7 +24,7 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(_build.build(force=False))
         for name in ("oracle_attn", "oracle_logits", "oracle_accept_logits", "oracle_accept",
-                     "oracle_num_threads"):
+                     "oracle_num_threads", "oracle_trace_topk", "oracle_trace_records"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -168,3 +168,30 @@ def verify(w, want_cdf=False, want_logits=False):
                draft_probs=w.draft_probs, uniforms=w.uniforms, parents=w.parents, dtype=w.dtype,
                temperature=w.temperature, want_cdf=want_cdf, want_logits=want_logits)
     return o, a
+
+
+def trace_topk(logits: np.ndarray, top_k: int):
+    """K largest entries of each row of float32 logits [rows, V]: (ids int32 [rows, K], bf16 bits uint16 [rows, K])."""
+    logits = _chk(logits, np.float32)
+    rows, V = logits.shape
+    ids = np.empty((rows, top_k), np.int32)
+    vals = np.empty((rows, top_k), np.uint16)
+    st = lib().oracle_trace_topk(C.c_int64(rows), V, int(top_k), _p(logits), _p(ids), _p(vals))
+    if st != 0:
+        raise ValueError(f"oracle_trace_topk status {st}")
+    return ids, vals
+
+
+def trace_records(*, draft_tokens, parents, next_token, accept_mask):
+    """(y_out int32 [B, Nq], trajectory codes int8 [B, Nq]) from the acceptance outputs."""
+    draft_tokens = _chk(draft_tokens, np.int32)
+    B, Nq = draft_tokens.shape
+    parents = _chk(parents, np.int32, (B, Nq))
+    next_token = _chk(next_token, np.int32, (B,))
+    accept_mask = _chk(accept_mask, np.uint8, (B, Nq))
+    y = np.empty((B, Nq), np.int32)
+    r = np.empty((B, Nq), np.int8)
+    st = lib().oracle_trace_records(B, Nq, _p(draft_tokens), _p(parents), _p(next_token), _p(accept_mask), _p(y), _p(r))
+    if st != 0:
+        raise ValueError(f"oracle_trace_records status {st}")
+    return y, r

@@ -9,15 +9,15 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "aurora_oracle.c")
+SRCS = [os.path.join(HERE, "aurora_oracle.c"), os.path.join(HERE, "trace_oracle.c")]
 LIB = os.path.join(HERE, "liboracle.so")
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(s) for s in SRCS):
         return LIB
     cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
-           "-Wall", "-Wextra", "-shared", "-fPIC", SRC, "-o", LIB, "-lm"]
+           "-Wall", "-Wextra", "-shared", "-fPIC"] + SRCS + ["-o", LIB, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 
