@@ -160,6 +160,51 @@ int aurora_verify(const aurora_attn_desc* attn_desc, const aurora_accept_desc* a
 const float* aurora_verify_logits_ptr(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,
                                       const void* workspace);
 
+/*
+ * Trace emission: what the inference server hands to the training side after a verify step
+ * (paper section 3.1: outcomes of accepted and rejected tokens are both streamed; appendix A.1,
+ * eq. 4: a record is (h, l, x_in, y_out, R); appendix A.2: only the K largest target logits of a
+ * token are kept, K = 1024, 2 bytes each instead of the whole vocabulary row).  h (the hidden rows)
+ * and x_in (the draft tokens) are the caller's own buffers and are not copied; this call produces
+ * the filtered logits, y_out and R.
+ *
+ *   top-K half (skipped when topk_ids and topk_logits are both NULL; one NULL alone is an error):
+ *     for every token row m of `logits`, topk_ids[m, 0..K) are the ids of its K largest entries,
+ *     ordered by value descending, equal values (-0.0 and +0.0 are equal) by ascending id;
+ *     topk_logits[m, j] is the value rounded to bfloat16 (nearest, ties to even), stored as its
+ *     16-bit pattern.  If V < K the tail holds id -1 / value -inf (0xFF80).  -inf entries are
+ *     ordinary smallest values; NaN entries are not allowed (order unspecified).  The result is
+ *     unique, so it is bit-reproducible.
+ *   record half (skipped when y_out and traj are both NULL; one NULL alone is an error):
+ *     y_out[b, n] = token emitted after node n: the token of n's accepted child, next_token[b] for
+ *     the last node of the accepted path, -1 for nodes off the path.
+ *     traj[b, n] (R) = 1 for nodes on the accepted path (root included); 2 for drafts that were
+ *     tested and rejected - the acceptance step tries the children of a path node in index order
+ *     until one is kept, so these are the children before the kept one, or all of them if none is
+ *     kept; 0 for nodes that were never tested.
+ *
+ * No workspace.  Returns AURORA_ERR_INVALID_ARG for null / inconsistent pointers or a `logits`
+ * pointer that is not 4-byte aligned, AURORA_ERR_UNSUPPORTED for top_k > 1024 or num_q > 64.
+ */
+typedef struct {
+  int32_t batch; /* B >= 0 (0: nothing is enqueued)   */
+  int32_t num_q; /* Nq, 1..64                         */
+  int32_t vocab; /* V >= 1                            */
+  int32_t top_k; /* K, 1..1024 (the paper uses 1024)  */
+} aurora_trace_desc;
+
+int aurora_trace_emit(const aurora_trace_desc* desc,
+                      const float* logits,         /* [B*Nq, V] fp32 target logits, e.g. aurora_verify_logits_ptr() */
+                      const int32_t* draft_tokens, /* [B, Nq]; entry 0 (root) ignored          */
+                      const int32_t* parents,      /* [B, Nq] or NULL => chain                 */
+                      const int32_t* next_token,   /* [B]     from the acceptance step         */
+                      const uint8_t* accept_mask,  /* [B, Nq] from the acceptance step         */
+                      int32_t* topk_ids,           /* [B*Nq, K]                                */
+                      uint16_t* topk_logits,       /* [B*Nq, K] bfloat16 bit patterns          */
+                      int32_t* y_out,              /* [B, Nq]                                  */
+                      int8_t* traj,                /* [B, Nq]                                  */
+                      void* hip_stream);
+
 /* Human-readable name of a status code; never NULL. */
 const char* aurora_status_string(int status);
 

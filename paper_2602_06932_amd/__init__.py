@@ -1,11 +1,13 @@
 """MI355X-native verification step of speculative decoding (chunk attention over a paged GQA KV
-cache; LM head + softmax + rejection-sampling acceptance) behind a C ABI.
+cache; LM head + softmax + rejection-sampling acceptance; trace emission for the training side)
+behind a C ABI.
 
 `binding` mirrors the C entry points; `device.DeviceVerify` is memory plumbing for tests and the
 benchmark.  The package never falls back to a CPU implementation.
 """
 from .binding import (AURORA_BF16, AURORA_ERR_HIP, AURORA_ERR_INVALID_ARG, AURORA_ERR_UNSUPPORTED,  # noqa: F401
                       AURORA_ERR_WORKSPACE, AURORA_F32, AURORA_OK, EXPORTS, LIB_PATH, AuroraError,
-                      aurora_accept_desc, aurora_attn_desc, aurora_verify, aurora_verify_accept,
+                      aurora_accept_desc, aurora_attn_desc, aurora_trace_desc, aurora_trace_emit, aurora_verify,
+                      aurora_verify_accept,
                       aurora_verify_attn, aurora_verify_lmhead, aurora_verify_logits_ptr, aurora_verify_workspace_bytes, load,
                       status_string)

@@ -21,7 +21,7 @@ AURORA_BF16 = 1
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_verify.so")
 
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
-           "aurora_verify_lmhead",
+           "aurora_verify_lmhead", "aurora_trace_emit",
            "aurora_verify_logits_ptr", "aurora_status_string")
 
 
@@ -35,6 +35,10 @@ class aurora_attn_desc(C.Structure):
 class aurora_accept_desc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("hidden", C.c_int32), ("vocab", C.c_int32),
                 ("dtype", C.c_int32), ("temperature", C.c_float)]
+
+
+class aurora_trace_desc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("vocab", C.c_int32), ("top_k", C.c_int32)]
 
 
 class AuroraError(RuntimeError):
@@ -69,6 +73,8 @@ def load():
     lib.aurora_verify.argtypes = [ad, cd, vp, vp, vp, i32p, i32p, i32p, vp, vp, vp, i32p, f32p, f32p, i32p, i32p,
                                   u8p, f32p, f32p, vp, C.c_size_t, vp]
     lib.aurora_verify.restype = C.c_int
+    lib.aurora_trace_emit.argtypes = [C.POINTER(aurora_trace_desc), vp, i32p, i32p, i32p, u8p, i32p, vp, i32p, vp, vp]
+    lib.aurora_trace_emit.restype = C.c_int
     lib.aurora_verify_logits_ptr.argtypes = [ad, cd, vp]
     lib.aurora_verify_logits_ptr.restype = C.c_void_p
     lib.aurora_status_string.argtypes = [C.c_int]
@@ -141,6 +147,18 @@ def aurora_verify_lmhead(desc, hidden, lm_head, workspace, stream=None, workspac
     st = load().aurora_verify_lmhead(_ref(desc), _ptr(hidden), _ptr(lm_head), _ptr(workspace), wb, _stream(stream))
     if check and st != AURORA_OK:
         raise AuroraError(st, "aurora_verify_lmhead")
+    return st
+
+
+def aurora_trace_emit(desc, logits, draft_tokens, parents, next_token, accept_mask, topk_ids, topk_logits, y_out, traj,
+                      stream=None, check=True) -> int:
+    """`logits` may be a tensor or a raw device address (int), e.g. from aurora_verify_logits_ptr()."""
+    lp = logits if isinstance(logits, int) or logits is None else _ptr(logits)
+    st = load().aurora_trace_emit(_ref(desc), lp, _ptr(draft_tokens), _ptr(parents), _ptr(next_token),
+                                  _ptr(accept_mask), _ptr(topk_ids), _ptr(topk_logits), _ptr(y_out), _ptr(traj),
+                                  _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_trace_emit")
     return st
 
 

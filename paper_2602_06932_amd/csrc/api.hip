@@ -283,6 +283,27 @@ const float* aurora_verify_logits_ptr(const aurora_attn_desc* attn_desc, const a
   return (const float*)((const char*)workspace + off + plan_accept(accept_desc).logits_off);
 }
 
+int aurora_trace_emit(const aurora_trace_desc* d, const float* logits, const int32_t* draft_tokens,
+                      const int32_t* parents, const int32_t* next_token, const uint8_t* accept_mask,
+                      int32_t* topk_ids, uint16_t* topk_logits, int32_t* y_out, int8_t* traj, void* hip_stream) {
+  if (!d || d->batch < 0 || d->num_q < 1 || d->vocab < 1 || d->top_k < 1) return AURORA_ERR_INVALID_ARG;
+  if (d->num_q > kMaxNq || d->top_k > trace_max_k()) return AURORA_ERR_UNSUPPORTED;
+  const bool want_topk = topk_ids || topk_logits, want_rec = y_out || traj;
+  if (!want_topk && !want_rec) return AURORA_ERR_INVALID_ARG;
+  if (want_topk && (!topk_ids || !topk_logits || !logits || ((uintptr_t)logits & 3))) return AURORA_ERR_INVALID_ARG;
+  if (want_rec && (!y_out || !traj || !draft_tokens || !next_token || !accept_mask)) return AURORA_ERR_INVALID_ARG;
+  if (!have_device()) return AURORA_ERR_HIP;
+  if (d->batch == 0) return AURORA_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (want_topk &&
+      launch_trace_topk(logits, (int64_t)d->batch * d->num_q, d->vocab, d->top_k, topk_ids, topk_logits, st) != hipSuccess)
+    return AURORA_ERR_HIP;
+  if (want_rec && launch_trace_records(d->batch, d->num_q, draft_tokens, parents, next_token, accept_mask, y_out, traj,
+                                       st) != hipSuccess)
+    return AURORA_ERR_HIP;
+  return AURORA_OK;
+}
+
 const char* aurora_status_string(int status) {
   switch (status) {
     case AURORA_OK: return "ok";

@@ -45,6 +45,21 @@ def test_host_validation_without_device():
     bad.temperature = -1.0
     with pytest.raises(av.AuroraError):
         av.aurora_verify_workspace_bytes(None, bad)
+    # trace emission: descriptor and pointer checks come before any device is touched
+    td = av.aurora_trace_desc(batch=2, num_q=5, vocab=100, top_k=8)
+    assert av.aurora_trace_emit(None, 16, None, None, None, None, 16, 16, None, None, stream=0, check=False) \
+        == av.AURORA_ERR_INVALID_ARG
+    assert av.aurora_trace_emit(td, None, None, None, None, None, None, None, None, None, stream=0, check=False) \
+        == av.AURORA_ERR_INVALID_ARG  # nothing requested
+    assert av.aurora_trace_emit(td, 16, None, None, None, None, 16, None, None, None, stream=0, check=False) \
+        == av.AURORA_ERR_INVALID_ARG  # ids without values
+    assert av.aurora_trace_emit(td, 18, None, None, None, None, 16, 16, None, None, stream=0, check=False) \
+        == av.AURORA_ERR_INVALID_ARG  # logits not 4-byte aligned
+    assert av.aurora_trace_emit(td, None, None, None, None, None, None, None, 16, 16, stream=0, check=False) \
+        == av.AURORA_ERR_INVALID_ARG  # records without the acceptance outputs
+    big = av.aurora_trace_desc(batch=2, num_q=5, vocab=100, top_k=4096)
+    assert av.aurora_trace_emit(big, 16, None, None, None, None, 16, 16, None, None, stream=0, check=False) \
+        == av.AURORA_ERR_UNSUPPORTED
     assert av.status_string(av.AURORA_ERR_UNSUPPORTED) == "unsupported configuration"
     assert av.status_string(12345) == "unknown status"
 
