@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--workload", default="llama", choices=["llama", "tiny", "qwen_greedy", "tree", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
-    ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "copy"],
+    ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy"],
                     help="profiling aid: launch only this stage --steps times (after --warmup) and exit; "
                          "'copy' runs a plain device-to-device copy of 1 GiB for counter calibration")
     args = ap.parse_args()
@@ -92,6 +92,8 @@ def main():
             dst = torch.empty_like(src)
             fn = lambda: dst.copy_(src)
         else:
+            if args.stage == "trace":
+                dv.verify()  # the emission reads the logits and acceptance outputs of a verify step
             fn = getattr(dv, args.stage)
         for _ in range(args.warmup):
             fn()
@@ -109,6 +111,7 @@ def main():
     ms_lmhead = event_time_ms(dv.lmhead, it, torch)
     ms_accept_half = event_time_ms(dv.accept, it, torch)
     ms_verify_ev = event_time_ms(dv.verify, it, torch)
+    ms_trace = event_time_ms(dv.trace, it, torch)  # not part of a step: the emission that follows a verify
 
     # ---- timed region: K whole verify steps -------------------------------------------------------
     for _ in range(args.warmup):
@@ -154,7 +157,7 @@ def main():
         "emitted_tokens_per_s": emitted / (ms_step * 1e-3),
         "mean_accept_len": float(res["accept_len"].mean()),
         "stage_ms": {"attn": ms_attn, "lmhead": ms_lmhead, "accept_half(lmhead+walk)": ms_accept_half,
-                     "verify_by_events": ms_verify_ev},
+                     "verify_by_events": ms_verify_ev, "trace_emit_after_verify(top-1024)": ms_trace},
         "roofline": {"kernel": "lmhead (LM-head GEMM + softmax statistics)", "bound": "hbm",
                      "achieved": lm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": lm_gbs / HBM_PEAK_GBS,
                      "traffic": (tr_lm["read_bytes"] + tr_lm["write_bytes"]) if tr_lm else None,

@@ -6,15 +6,17 @@
 //                         descending (equal values by ascending id), values rounded to bfloat16.
 //   trace_records_kernel  y_out and the rejection trajectory R from the acceptance outputs.
 //
-// Selection.  A float is mapped to an unsigned key with the same order (-0.0 folded onto +0.0); a
-// candidate is the 64-bit word (key << 32 | ~id), so one descending sort gives value order with the
-// lowest id first among equals.  Common case, one pass over the row: a cut-off is taken from a sorted
-// sample of 4096 entries so that about 2K entries pass it; the row is streamed once (16-byte loads),
-// the few entries at or above the cut-off are appended to a list in LDS, the list is sorted there
-// (bitonic) and its first K entries are the answer.  If the list comes out shorter than K or longer
-// than its capacity (heavily repeated values, adversarial rows), an exact radix select over the keys
-// (four passes of 8 bits, LDS histograms) finds the K-th key, and the entries above it plus the first
-// ones equal to it in id order are collected instead.  Both routes give the same, unique answer.
+// Selection.  A float is mapped to an unsigned key with the same order (-0.0 folded onto +0.0); an
+// entry is the 64-bit word (key << 32 | ~id): words are distinct, and descending word order is value
+// order with the lowest id first among equals.  "The K largest words" is therefore a unique set, and
+// a radix select (8 bits per pass, histogram in LDS, stop as soon as the threshold bin is taken whole)
+// finds the threshold word T with exactly K words >= T.
+// Common case, one pass over the row: a cut-off key is selected from a sample of 4096 entries so that
+// about 2K entries reach it; the row is streamed once (16-byte loads, sixteen in flight per thread) and
+// the few entries at or above the cut-off are appended to a list in LDS; the list is cut to exactly K
+// by a radix select inside LDS, compacted, sorted (bitonic, 1024 words) and written out.  If the list
+// comes out shorter than K or longer than its capacity (heavily repeated values, adversarial rows),
+// the radix select runs over the whole row in global memory instead.  Both routes give the same set.
 #include "common.hpp"
 #include "launch.hpp"
 
@@ -30,22 +32,31 @@ __device__ __forceinline__ uint32_t order_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+__device__ __forceinline__ uint64_t entry_word(float x, int id) {
+  return ((uint64_t)order_key(x) << 32) | (uint32_t)~id;
+}
+
 __device__ __forceinline__ uint16_t bf16_rne_bits(float f) {
   const uint32_t u = __float_as_uint(f);
   if ((u & 0x7fffffffu) == 0x7f800000u) return (uint16_t)(u >> 16);
   return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 
-// descending bitonic sort of n (a power of two, <= kTrCap) 64-bit words in LDS by the whole workgroup
-__device__ __forceinline__ void bitonic_desc(uint64_t* a, int n) {
-  for (int size = 2; size <= n; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      __syncthreads();
+// Descending bitonic sort of n (a power of two, 2..kTrCap) words in LDS by the whole workgroup.  A
+// wavefront's 64 pairs of a step span 128 consecutive words whenever the step's stride is at most 64,
+// so those steps need no workgroup barrier: LDS operations of one wavefront execute in order.
+template <typename T>
+__device__ __forceinline__ void bitonic_desc(T* a, int n) {
+  for (int size = 2, lsize = 1; size <= n; size <<= 1, ++lsize) {
+    for (int ls = lsize - 1; ls >= 0; --ls) {
+      const int stride = 1 << ls;
+      if (stride >= 64 || ls == lsize - 1) __syncthreads();  // the step reads words other wavefronts wrote
+      else __builtin_amdgcn_wave_barrier();
       for (int t = threadIdx.x; t < (n >> 1); t += kTrThreads) {
-        const int lo = ((t / stride) * stride << 1) + (t % stride);
+        const int lo = ((t >> ls) << (ls + 1)) + (t & (stride - 1));
         const int hi = lo + stride;
         const bool desc = ((lo & size) == 0);
-        const uint64_t x = a[lo], y = a[hi];
+        const T x = a[lo], y = a[hi];
         if ((x < y) == desc) { a[lo] = y; a[hi] = x; }
       }
     }
@@ -53,37 +64,114 @@ __device__ __forceinline__ void bitonic_desc(uint64_t* a, int n) {
   __syncthreads();
 }
 
+struct SelectShared {
+  int hist[256];
+  int digit, remaining, whole;  // written by pick_digit
+};
+
+// One histogram increment per calling lane (inactive lanes pass valid = false).  Lanes of a wavefront
+// that hit the same bin are first combined (up to four distinct bins), because same-address LDS
+// atomics serialise and the high digits of similar values are nearly all equal.
+__device__ __forceinline__ void hist_add(int* hist, int digit, bool valid) {
+  unsigned long long active = __ballot(valid);
+  const int lane = threadIdx.x & 63;
+#pragma unroll 1
+  for (int round = 0; round < 4 && active; ++round) {
+    const int leader = __ffsll((long long)active) - 1;
+    const int v = __shfl(digit, leader, kWave);
+    const unsigned long long same = __ballot(valid && digit == v) & active;
+    if (lane == leader) atomicAdd(&hist[v], __popcll(same));
+    active &= ~same;
+  }
+  if (valid && ((active >> lane) & 1ull)) atomicAdd(&hist[digit], 1);
+}
+
+// Called by every thread of wavefront 0 after the histogram is complete (and a barrier).  Finds the
+// highest digit d whose bins d..255 hold at least `rem` entries; remaining = entries still to take from
+// bin d, whole = that is all of bin d.
+__device__ __forceinline__ void pick_digit(SelectShared& sh, int rem) {
+  const int lane = threadIdx.x & 63;
+  int c[4], tot = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) { c[j] = sh.hist[4 * lane + j]; tot += c[j]; }
+  int suffix = tot;  // entries in the bins of lanes >= this one
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int y = __shfl_down(suffix, o, kWave);
+    if (lane + o < kWave) suffix += y;
+  }
+  int above = suffix - tot;
+  if (above < rem && rem <= suffix) {
+#pragma unroll
+    for (int j = 3; j >= 0; --j) {
+      if (above < rem && rem <= above + c[j]) {
+        sh.digit = 4 * lane + j;
+        sh.remaining = rem - above;
+        sh.whole = (rem - above) == c[j];
+      }
+      above += c[j];
+    }
+  }
+}
+
+// Threshold word T such that exactly `want` of the n words produced by word(i), i in [0, n), are >= T
+// (1 <= want <= n; the words are distinct).  kBits = 32 or 64: the width that carries information.
+// With kStop > 0 the digits below bit kStop are not examined: the result is then the threshold's prefix,
+// zero-extended, and at least `want` words are >= it (the whole last bin is included).
+// Whole workgroup; `word` is evaluated once per pass and entry.
+template <int kBits, int kStop, typename F>
+__device__ __forceinline__ uint64_t radix_threshold(SelectShared& sh, int n, int want, F word) {
+  uint64_t prefix = 0, mask = 0;
+  int rem = want;
+  for (int shift = kBits - 8; shift >= kStop; shift -= 8) {
+    __syncthreads();
+    if (threadIdx.x < 256) sh.hist[threadIdx.x] = 0;
+    __syncthreads();
+    for (int i0 = 0; i0 < n; i0 += kTrThreads) {
+      const int i = i0 + threadIdx.x;
+      uint64_t w = 0;
+      const bool in = i < n;
+      if (in) w = word(i);
+      hist_add(sh.hist, (int)((w >> shift) & 255), in && (w & mask) == prefix);
+    }
+    __syncthreads();
+    if (threadIdx.x < kWave) pick_digit(sh, rem);
+    __syncthreads();
+    prefix |= (uint64_t)sh.digit << shift;
+    mask |= 255ull << shift;
+    rem = sh.remaining;
+    if (sh.whole) break;  // every word that shares the prefix is taken: prefix, zero-extended, is the threshold
+  }
+  return prefix;
+}
+
 __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __restrict__ logits, int V, int K,
                                                                int32_t* __restrict__ out_ids,
                                                                uint16_t* __restrict__ out_vals) {
-  __shared__ uint64_t s_cand[kTrCap];  // 32 KB
-  __shared__ int s_hist[256];
-  __shared__ int s_scan[kTrThreads / 64];
+  __shared__ uint64_t s_cand[kTrCap];   // 32 KB: the sample (as 32-bit keys), then the candidate list
+  __shared__ uint64_t s_top[kTrMaxK];   // 8 KB: the K selected words, sorted at the end
+  __shared__ SelectShared s_sel;
   __shared__ unsigned s_count;
-  __shared__ uint32_t s_prefix;
-  __shared__ int s_remaining, s_eq_base;
   const int tid = threadIdx.x;
   const float* row = logits + (size_t)blockIdx.x * V;
   int32_t* ids = out_ids + (size_t)blockIdx.x * K;
   uint16_t* vals = out_vals + (size_t)blockIdx.x * K;
   const int want = K < V ? K : V;  // entries that exist
-  int count;                       // entries in s_cand, sorted, after the selection below (>= want)
+  int count;                       // entries in the candidate list
+  bool from_row = false;           // select over the whole row instead of the list
 
   if (V <= kTrCap) {
-    // the whole row fits the list
-    for (int i = tid; i < kTrCap; i += kTrThreads)
-      s_cand[i] = i < V ? ((uint64_t)order_key(row[i]) << 32) | (uint32_t)~i : 0ull;
+    for (int i = tid; i < V; i += kTrThreads) s_cand[i] = entry_word(row[i], i);
     count = V;
   } else {
-    // ---- cut-off from a sorted sample --------------------------------------------------------------
-    // the sample is sorted as 64-bit words with the key in the high half
+    // ---- cut-off key from a sample ---------------------------------------------------------------------
+    uint32_t* s_sample = (uint32_t*)s_cand;
     const int stride = V / kTrCap;
-    for (int i = tid; i < kTrCap; i += kTrThreads) s_cand[i] = (uint64_t)order_key(row[(size_t)i * stride]) << 32;
-    bitonic_desc(s_cand, kTrCap);
-    // rank in the sample whose key is expected to have about 2K row entries at or above it
-    long long r = (2ll * K * kTrCap + V - 1) / V + 8;
-    uint32_t cut = 0;  // 0: below every key, everything passes (the list then overflows and the exact route runs)
-    if (r < kTrCap) cut = (uint32_t)(s_cand[r] >> 32);
+    for (int i = tid; i < kTrCap; i += kTrThreads) s_sample[i] = order_key(row[(size_t)i * stride]);
+    // sample rank whose key is expected to have about 2K row entries at or above it (always < kTrCap); the
+    // cut-off only needs the key's upper 16 bits (sign, exponent, 7 mantissa bits): a few more entries pass
+    const int r = (int)((2ll * K * kTrCap + V - 1) / V) + 8;
+    const uint32_t cut = (uint32_t)radix_threshold<32, 16>(s_sel, kTrCap, r + 1, [&](int i) { return (uint64_t)s_sample[i]; });
     __syncthreads();
     if (tid == 0) s_count = 0;
     __syncthreads();
@@ -98,16 +186,29 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
       }
     }
     const int nvec = (V - h) >> 2;
-    const float4* rv = (const float4*)(row + h);
-    for (int i = tid; i < nvec; i += kTrThreads) {
-      const float4 x = rv[i];
-      const float e[4] = {x.x, x.y, x.z, x.w};
+    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+    const f32x4_t* rv = (const f32x4_t*)(row + h);
+    // sixteen 16-byte loads in flight per thread: the pass is bound by memory latency otherwise
+    constexpr int kU = 16;
+    for (int i0 = tid; i0 < nvec; i0 += kU * kTrThreads) {
+      f32x4_t x[kU];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t k = order_key(e[j]);
-        if (k >= cut) {
-          const unsigned slot = atomicAdd(&s_count, 1u);
-          if (slot < (unsigned)kTrCap) s_cand[slot] = ((uint64_t)k << 32) | (uint32_t) ~(h + 4 * i + j);
+      for (int u = 0; u < kU; ++u) {
+        const int i = i0 + u * kTrThreads;
+        x[u] = i < nvec ? rv[i] : f32x4_t{0.f, 0.f, 0.f, 0.f};
+      }
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const int i = i0 + u * kTrThreads;
+        if (i < nvec) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t k = order_key(x[u][j]);
+            if (k >= cut) {
+              const unsigned slot = atomicAdd(&s_count, 1u);
+              if (slot < (unsigned)kTrCap) s_cand[slot] = ((uint64_t)k << 32) | (uint32_t) ~(h + 4 * i + j);
+            }
+          }
         }
       }
     }
@@ -120,79 +221,42 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
     }
     __syncthreads();
     count = (int)s_count;
+    from_row = count < want || count > kTrCap;
+  }
+
+  // ---- cut to exactly `want` words and compact them into s_top ------------------------------------------
+  __syncthreads();
+  if (tid == 0) s_count = 0;
+  if (!from_row) {
+    uint64_t thr = 0;  // count == want: everything is taken
+    if (count > want) thr = radix_threshold<64, 0>(s_sel, count, want, [&](int i) { return s_cand[i]; });
     __syncthreads();
-    if (count < want || count > kTrCap) {
-      // ---- exact route: radix select of the want-th largest key, 8 bits per pass -----------------------
-      if (tid == 0) { s_prefix = 0; s_remaining = want; }
-      uint32_t mask = 0;
-      for (int shift = 24; shift >= 0; shift -= 8) {
-        if (tid < 256) s_hist[tid] = 0;
-        __syncthreads();
-        const uint32_t prefix = s_prefix;
-        for (int i = tid; i < V; i += kTrThreads) {
-          const uint32_t k = order_key(row[i]);
-          if ((k & mask) == prefix) atomicAdd(&s_hist[(k >> shift) & 255], 1);
-        }
-        __syncthreads();
-        if (tid == 0) {
-          int rem = s_remaining, d = 255;
-          while (d > 0 && s_hist[d] < rem) { rem -= s_hist[d]; --d; }
-          s_remaining = rem;  // entries still to take from digit d (>= 1, <= s_hist[d])
-          s_prefix = prefix | ((uint32_t)d << shift);
-        }
-        mask |= 255u << shift;
-        __syncthreads();
+    for (int i = tid; i < count; i += kTrThreads) {
+      const uint64_t w = s_cand[i];
+      if (w >= thr) {
+        const unsigned slot = atomicAdd(&s_count, 1u);
+        if (slot < (unsigned)kTrMaxK) s_top[slot] = w;
       }
-      const uint32_t kth = s_prefix;      // the want-th largest key
-      const int need_eq = s_remaining;    // entries equal to it that belong to the answer: the lowest ids
-      if (tid == 0) { s_count = 0; s_eq_base = 0; }
-      __syncthreads();
-      // entries above the K-th key in any order; entries equal to it ranked in id order by a running scan
-      for (int base = 0; base < V; base += kTrThreads) {
-        const int i = base + tid;
-        uint32_t k = 0;
-        bool gt = false, eq = false;
-        if (i < V) {
-          k = order_key(row[i]);
-          gt = k > kth;
-          eq = k == kth;
-        }
-        if (gt) {
-          const unsigned slot = atomicAdd(&s_count, 1u);
-          // fewer than want <= kTrMaxK of these exist; the bound only guards the list against a broken row (NaN)
-          if (slot < (unsigned)kTrCap) s_cand[slot] = ((uint64_t)k << 32) | (uint32_t)~i;
-        }
-        const unsigned long long bal = __ballot(eq);
-        const int lane = tid & 63, wv = tid >> 6;
-        if (lane == 0) s_scan[wv] = __popcll(bal);
-        __syncthreads();
-        int before = s_eq_base;
-        for (int w2 = 0; w2 < wv; ++w2) before += s_scan[w2];
-        const int rank = before + __popcll(bal & ((1ull << lane) - 1ull));
-        if (eq && rank < need_eq) {
-          const unsigned slot = atomicAdd(&s_count, 1u);
-          if (slot < (unsigned)kTrCap) s_cand[slot] = ((uint64_t)k << 32) | (uint32_t)~i;
-        }
-        __syncthreads();
-        if (tid == 0) {
-          int tot = 0;
-          for (int w2 = 0; w2 < kTrThreads / 64; ++w2) tot += s_scan[w2];
-          s_eq_base += tot;
-        }
-        __syncthreads();
+    }
+  } else {
+    const uint64_t thr = radix_threshold<64, 0>(s_sel, V, want, [&](int i) { return entry_word(row[i], i); });
+    __syncthreads();
+    for (int i = tid; i < V; i += kTrThreads) {
+      const uint64_t w = entry_word(row[i], i);
+      if (w >= thr) {
+        const unsigned slot = atomicAdd(&s_count, 1u);
+        if (slot < (unsigned)kTrMaxK) s_top[slot] = w;  // exactly `want` of these exist
       }
-      count = (int)s_count;  // == want
-      if (count > kTrCap) count = kTrCap;
     }
   }
-  // sort the list (padded to a power of two with words that sort last)
+  // ---- sort and write out ------------------------------------------------------------------------------------
   int n2 = 2;
-  while (n2 < count) n2 <<= 1;
-  for (int i = count + tid; i < n2; i += kTrThreads) s_cand[i] = 0ull;
-  bitonic_desc(s_cand, n2);
+  while (n2 < want) n2 <<= 1;
+  for (int i = want + tid; i < n2; i += kTrThreads) s_top[i] = 0ull;  // sorts last: no entry word is zero
+  bitonic_desc(s_top, n2);
   for (int k = tid; k < K; k += kTrThreads) {
     if (k < want) {
-      const int id = (int)~(uint32_t)(s_cand[k] & 0xffffffffull);
+      const int id = (int)~(uint32_t)(s_top[k] & 0xffffffffull);
       ids[k] = id;
       vals[k] = bf16_rne_bits(row[id]);
     } else {

@@ -108,6 +108,23 @@ class DeviceVerify:
     def verify(self, stream=None):
         return self._call("verify", stream)
 
+    def trace(self, top_k=1024, after="verify", stream=None):
+        """Trace emission from the logits and acceptance outputs the last verify / accept call left."""
+        w = self.w
+        if getattr(self, "_trace_k", None) != (top_k, after):
+            rows = w.batch * w.num_q
+            self.trace_desc = B.aurora_trace_desc(batch=w.batch, num_q=w.num_q, vocab=w.vocab, top_k=top_k)
+            self.topk_ids = torch.empty((rows, top_k), dtype=torch.int32, device="cuda")
+            self.topk_logits = torch.empty((rows, top_k), dtype=torch.int16, device="cuda")
+            self.y_out = torch.empty((w.batch, w.num_q), dtype=torch.int32, device="cuda")
+            self.traj = torch.empty((w.batch, w.num_q), dtype=torch.int8, device="cuda")
+            self._trace_logits = B.aurora_verify_logits_ptr(self.attn_desc if after == "verify" else None,
+                                                            self.accept_desc, self.workspace)
+            self._trace_k = (top_k, after)
+        return B.aurora_trace_emit(self.trace_desc, self._trace_logits, self.draft_tokens, self.parents,
+                                   self.next_token, self.accept_mask, self.topk_ids, self.topk_logits, self.y_out,
+                                   self.traj, stream)
+
     def attn_via_binding(self, stream=None):
         return B.aurora_verify_attn(self.attn_desc, self.q, self.k_pages, self.v_pages, self.block_table,
                                     self.seq_lens, self.parents, self.attn_out, self.workspace, stream)
