@@ -59,8 +59,8 @@ def event_time_ms(fn, iters, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="llama", choices=["llama", "tiny", "qwen_greedy", "tree", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
@@ -102,18 +102,18 @@ def main():
         print(json.dumps({"stage": args.stage, "steps": args.steps, "avg_ms": ms, "workload": w.name}))
         return
 
-    # ---- per-stage HIP-event timing (same launches, same stream) ---------------------------------
+    # ---- per-stage HIP-event timing (back-to-back launches of one stage, same stream) ----------------
     # Done first: it also brings the GPU out of its idle clocks before the timed region.
-    it = max(args.steps, 10)
+    it = 20
     dv.verify()
     torch.cuda.synchronize()
-    ms_attn = event_time_ms(dv.attn, it, torch)
-    ms_lmhead = event_time_ms(dv.lmhead, it, torch)
+    ms_attn_b2b = event_time_ms(dv.attn, it, torch)
+    ms_lmhead_b2b = event_time_ms(dv.lmhead, it, torch)
     ms_accept_half = event_time_ms(dv.accept, it, torch)
     ms_verify_ev = event_time_ms(dv.verify, it, torch)
     ms_trace = event_time_ms(dv.trace, it, torch)  # not part of a step: the emission that follows a verify
 
-    # ---- timed region: K whole verify steps -------------------------------------------------------
+    # ---- timed region: K whole verify steps (one aurora_verify call each) ---------------------------
     for _ in range(args.warmup):
         dv.verify()
     torch.cuda.synchronize()
@@ -126,6 +126,27 @@ def main():
     res = dv.results_host()
     draft_tokens = w.batch * (w.num_q - 1)
     emitted = int(res["accept_len"].sum()) + w.batch
+
+    # ---- the same K steps again as three calls (attention, LM head, acceptance on its logits: the very
+    # kernels aurora_verify enqueues, in its order) with HIP events on the launch stream around the
+    # attention and LM-head stages of every step: the kernels' durations inside the step sequence --------
+    st = torch.cuda.current_stream()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for e in ev:
+        e[0].record(st)
+        dv.attn()
+        e[1].record(st)
+        dv.lmhead()
+        e[2].record(st)
+        dv.accept_logits()
+    torch.cuda.synchronize()
+    ms_step_split = 1e3 * (time.perf_counter() - t0) / args.steps
+    ms_attn = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    ms_lmhead = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    res2 = dv.results_host()
+    assert all(np.array_equal(res[k], res2[k]) for k in ("accept_len", "next_token", "accept_mask"))
 
     esz = 2 if w.dtype == "bf16" else 4
     w_bytes = w.vocab * w.hidden_size * esz + w.batch * w.num_q * w.hidden_size * esz
@@ -156,8 +177,10 @@ def main():
                    "vocab": w.vocab, "temperature": w.temperature, "seed": w.seed},
         "emitted_tokens_per_s": emitted / (ms_step * 1e-3),
         "mean_accept_len": float(res["accept_len"].mean()),
-        "stage_ms": {"attn": ms_attn, "lmhead": ms_lmhead, "accept_half(lmhead+walk)": ms_accept_half,
-                     "verify_by_events": ms_verify_ev, "trace_emit_after_verify(top-1024)": ms_trace},
+        "stage_ms": {"attn_in_step": ms_attn, "lmhead_in_step": ms_lmhead, "step_as_three_calls": ms_step_split,
+                     "attn_back_to_back": ms_attn_b2b, "lmhead_back_to_back": ms_lmhead_b2b,
+                     "accept_half(lmhead+walk)": ms_accept_half, "verify_by_events": ms_verify_ev,
+                     "trace_emit_after_verify(top-1024)": ms_trace},
         "roofline": {"kernel": "lmhead (LM-head GEMM + softmax statistics)", "bound": "hbm",
                      "achieved": lm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": lm_gbs / HBM_PEAK_GBS,
                      "traffic": (tr_lm["read_bytes"] + tr_lm["write_bytes"]) if tr_lm else None,

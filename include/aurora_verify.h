@@ -142,6 +142,19 @@ int aurora_verify_lmhead(const aurora_accept_desc* desc,
                          const void* lm_head, /* [V, H] row-major */
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Second stage of aurora_verify_accept on its own: the acceptance walk and the residual / bonus draw
+ * (section 2.1's rule, as specified at aurora_verify_accept) on the logits and statistics that a
+ * preceding aurora_verify_lmhead call with the same descriptor left in `workspace`.
+ * aurora_verify_lmhead followed by this call enqueues exactly the kernels of aurora_verify_accept;
+ * the split exists so that a caller can put its own events (or other work) between the two stages.
+ */
+int aurora_verify_accept_logits(const aurora_accept_desc* desc, const int32_t* draft_tokens,
+                                const float* draft_probs, const float* uniforms, const int32_t* parents,
+                                int32_t* accept_len, int32_t* next_token, uint8_t* accept_mask,
+                                float* p_at_draft, float* row_lse,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Both halves on the same stream: attention, then acceptance.  The halves share no data
  * (the hidden states entering the LM head are an independent input). */
 int aurora_verify(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,

@@ -21,7 +21,7 @@ AURORA_BF16 = 1
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_verify.so")
 
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
-           "aurora_verify_lmhead", "aurora_trace_emit",
+           "aurora_verify_lmhead", "aurora_verify_accept_logits", "aurora_trace_emit",
            "aurora_verify_logits_ptr", "aurora_status_string")
 
 
@@ -73,6 +73,8 @@ def load():
     lib.aurora_verify.argtypes = [ad, cd, vp, vp, vp, i32p, i32p, i32p, vp, vp, vp, i32p, f32p, f32p, i32p, i32p,
                                   u8p, f32p, f32p, vp, C.c_size_t, vp]
     lib.aurora_verify.restype = C.c_int
+    lib.aurora_verify_accept_logits.argtypes = [cd, i32p, f32p, f32p, i32p, i32p, i32p, u8p, f32p, f32p, vp, C.c_size_t, vp]
+    lib.aurora_verify_accept_logits.restype = C.c_int
     lib.aurora_trace_emit.argtypes = [C.POINTER(aurora_trace_desc), vp, i32p, i32p, i32p, u8p, i32p, vp, i32p, vp, vp]
     lib.aurora_trace_emit.restype = C.c_int
     lib.aurora_verify_logits_ptr.argtypes = [ad, cd, vp]
@@ -147,6 +149,17 @@ def aurora_verify_lmhead(desc, hidden, lm_head, workspace, stream=None, workspac
     st = load().aurora_verify_lmhead(_ref(desc), _ptr(hidden), _ptr(lm_head), _ptr(workspace), wb, _stream(stream))
     if check and st != AURORA_OK:
         raise AuroraError(st, "aurora_verify_lmhead")
+    return st
+
+
+def aurora_verify_accept_logits(desc, draft_tokens, draft_probs, uniforms, parents, accept_len, next_token, accept_mask,
+                                p_at_draft, row_lse, workspace, stream=None, workspace_bytes=None, check=True) -> int:
+    wb = workspace_bytes if workspace_bytes is not None else (workspace.numel() * workspace.element_size())
+    st = load().aurora_verify_accept_logits(_ref(desc), _ptr(draft_tokens), _ptr(draft_probs), _ptr(uniforms),
+                                            _ptr(parents), _ptr(accept_len), _ptr(next_token), _ptr(accept_mask),
+                                            _ptr(p_at_draft), _ptr(row_lse), _ptr(workspace), wb, _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_verify_accept_logits")
     return st
 
 

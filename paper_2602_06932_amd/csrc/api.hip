@@ -128,14 +128,14 @@ int run_attn(const aurora_attn_desc* desc, const void* q, const void* k_pages, c
 int run_accept(const aurora_accept_desc* desc, const void* hidden, const void* lm_head, const int32_t* draft_tokens,
                const float* draft_probs, const float* uniforms, const int32_t* parents, int32_t* accept_len,
                int32_t* next_token, uint8_t* accept_mask, float* p_at_draft, float* row_lse, void* workspace,
-               size_t workspace_bytes, hipStream_t st) {
+               size_t workspace_bytes, hipStream_t st, bool with_lmhead = true) {
   int rc = check_accept_desc(desc);
   if (rc != AURORA_OK) return rc;
   if (desc->batch == 0) return AURORA_OK;
-  if (!hidden || !lm_head || !draft_tokens || !accept_len || !next_token || !accept_mask)
-    return AURORA_ERR_INVALID_ARG;
+  if (!draft_tokens || !accept_len || !next_token || !accept_mask) return AURORA_ERR_INVALID_ARG;
+  if (with_lmhead && (!hidden || !lm_head)) return AURORA_ERR_INVALID_ARG;
   if (desc->temperature > 0.f && (!draft_probs || !uniforms)) return AURORA_ERR_INVALID_ARG;
-  if (((uintptr_t)hidden | (uintptr_t)lm_head) & 15) return AURORA_ERR_INVALID_ARG;
+  if (with_lmhead && (((uintptr_t)hidden | (uintptr_t)lm_head) & 15)) return AURORA_ERR_INVALID_ARG;
   // the one-workgroup tree walk keeps one partial sum per 256 tokens in LDS
   if (desc->temperature > 0.f && parents && desc->vocab > (1 << 20)) return AURORA_ERR_UNSUPPORTED;
   AcceptPlan plan = plan_accept(desc);
@@ -155,10 +155,11 @@ int run_accept(const aurora_accept_desc* desc, const void* hidden, const void* l
   a.gsum = (double*)(ws + plan.gsum_off);
   a.lastpos = (int32_t*)(ws + plan.lastpos_off);
   a.plan = plan;
-  hipError_t e = lmhead_mfma_supported(a) ? launch_lmhead_mfma(a, st) : launch_lmhead_generic(a, st);
-  if (e != hipSuccess) return AURORA_ERR_HIP;
-  e = launch_accept(a, st);
-  return e == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
+  if (with_lmhead) {
+    hipError_t e = lmhead_mfma_supported(a) ? launch_lmhead_mfma(a, st) : launch_lmhead_generic(a, st);
+    if (e != hipSuccess) return AURORA_ERR_HIP;
+  }
+  return launch_accept(a, st) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
 }
 
 int run_lmhead(const aurora_accept_desc* desc, const void* hidden, const void* lm_head, void* workspace,
@@ -240,6 +241,17 @@ int aurora_verify_lmhead(const aurora_accept_desc* desc, const void* hidden, con
   if (rc != AURORA_OK) return rc;
   if (!have_device()) return AURORA_ERR_HIP;
   return run_lmhead(desc, hidden, lm_head, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+int aurora_verify_accept_logits(const aurora_accept_desc* desc, const int32_t* draft_tokens, const float* draft_probs,
+                                const float* uniforms, const int32_t* parents, int32_t* accept_len,
+                                int32_t* next_token, uint8_t* accept_mask, float* p_at_draft, float* row_lse,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_accept_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (!have_device()) return AURORA_ERR_HIP;
+  return run_accept(desc, nullptr, nullptr, draft_tokens, draft_probs, uniforms, parents, accept_len, next_token,
+                    accept_mask, p_at_draft, row_lse, workspace, workspace_bytes, (hipStream_t)hip_stream, false);
 }
 
 int aurora_verify(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc, const void* q,

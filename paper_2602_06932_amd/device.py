@@ -85,6 +85,8 @@ class DeviceVerify:
             "attn": (lib.aurora_verify_attn, (ad,) + attn_args + (P(self.attn_out), ws, wsb)),
             "accept": (lib.aurora_verify_accept, (cd,) + acc_in + (P(self.parents),) + acc_out + (ws, wsb)),
             "lmhead": (lib.aurora_verify_lmhead, (cd, P(self.hidden), P(self.lm_head), ws, wsb)),
+            "accept_logits": (lib.aurora_verify_accept_logits,
+                              (cd,) + acc_in[2:] + (P(self.parents),) + acc_out + (ws, wsb)),
             "verify": (lib.aurora_verify, (ad, cd) + attn_args + (P(self.attn_out),) + acc_in + acc_out + (ws, wsb)),
         }
 
@@ -104,6 +106,10 @@ class DeviceVerify:
 
     def lmhead(self, stream=None):
         return self._call("lmhead", stream)
+
+    def accept_logits(self, stream=None):
+        """Second stage of accept() on the logits a preceding lmhead() left in the workspace."""
+        return self._call("accept_logits", stream)
 
     def verify(self, stream=None):
         return self._call("verify", stream)

@@ -280,3 +280,27 @@ def test_lmhead_many_token_rows(gpu_lib, batch, num_q, vocab, hidden):
     ref = oracle.logits(hidden=w.hidden, lm_head=w.lm_head, dtype=w.dtype)
     check_logits(dv.logits_host(after="accept"), ref, w.dtype)
     _full_check(gpu_lib, w)
+
+
+@pytest.mark.parametrize("tree", [False, True])
+def test_lmhead_then_accept_logits_equals_accept(gpu_lib, tree):
+    """The two stages of the acceptance half called one after the other enqueue the same kernels as the
+    single call: identical outputs, and parity with the oracle."""
+    from paper_2602_06932_amd.device import DeviceVerify
+    w = gen.llama_chain(19, batch=7, len_lo=20, len_hi=60, vocab=3333, hidden_size=128) if not tree else \
+        gen.llama_tree(19, batch=5, num_q=16, vocab=3333, hidden_size=128, context=64, num_q_heads=4, num_kv_heads=2)
+    dv = DeviceVerify(w)
+    dv.accept()
+    one = dv.results_host()
+    for t in (dv.accept_len, dv.next_token):
+        t.fill_(-7)
+    dv.accept_mask.fill_(9)
+    dv.lmhead()
+    dv.accept_logits()
+    two = dv.results_host()
+    for k in one:
+        assert np.array_equal(one[k], two[k], equal_nan=True), k
+    ref = oracle.accept(hidden=w.hidden, lm_head=w.lm_head, draft_tokens=w.draft_tokens, draft_probs=w.draft_probs,
+                        uniforms=w.uniforms, parents=w.parents, dtype=w.dtype, temperature=w.temperature,
+                        want_cdf=True, want_logits=True)
+    check_accept(two, ref, w)
