@@ -11,7 +11,8 @@
 // order with the lowest id first among equals.  "The K largest words" is therefore a unique set, and
 // a radix select (8 bits per pass, histogram in LDS, stop as soon as the threshold bin is taken whole)
 // finds the threshold word T with exactly K words >= T.
-// Common case, one pass over the row: a cut-off key is selected from a sample of 4096 entries so that
+// Common case, one pass over the row: a cut-off key is selected from a sample of 4096 entries (1024
+// evenly spaced 16-byte vectors) so that
 // about 2K entries reach it; the row is streamed once (16-byte loads, sixteen in flight per thread) and
 // the few entries at or above the cut-off are appended to a list in LDS; the list is cut to exactly K
 // by a radix select inside LDS, compacted, sorted (bitonic, 1024 words) and written out.  If the list
@@ -164,10 +165,21 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
     for (int i = tid; i < V; i += kTrThreads) s_cand[i] = entry_word(row[i], i);
     count = V;
   } else {
+    const int head = (int)(((16 - ((uintptr_t)row & 15)) & 15) >> 2);  // entries before the first 16-byte boundary
+    const int h = head < V ? head : V;
+    const int nvec = (V - h) >> 2;  // >= 1023 here
+    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+    const f32x4_t* rv = (const f32x4_t*)(row + h);
     // ---- cut-off key from a sample ---------------------------------------------------------------------
+    // 1024 evenly spaced 16-byte vectors (one 128-byte line in several is touched, not every line)
     uint32_t* s_sample = (uint32_t*)s_cand;
-    const int stride = V / kTrCap;
-    for (int i = tid; i < kTrCap; i += kTrThreads) s_sample[i] = order_key(row[(size_t)i * stride]);
+    {
+      const int vstride = nvec / (kTrCap / 4);
+      const int vi = vstride ? tid * vstride : (tid < nvec ? tid : nvec - 1);
+      const f32x4_t x = rv[vi];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) s_sample[4 * tid + j] = order_key(x[j]);
+    }
     // sample rank whose key is expected to have about 2K row entries at or above it (always < kTrCap); the
     // cut-off only needs the key's upper 16 bits (sign, exponent, 7 mantissa bits): a few more entries pass
     const int r = (int)((2ll * K * kTrCap + V - 1) / V) + 8;
@@ -176,8 +188,6 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
     if (tid == 0) s_count = 0;
     __syncthreads();
     // ---- one pass over the row: keep what reaches the cut-off ------------------------------------------
-    const int head = (int)(((16 - ((uintptr_t)row & 15)) & 15) >> 2);  // entries before the first 16-byte boundary
-    const int h = head < V ? head : V;
     if (tid < h) {
       const uint32_t k = order_key(row[tid]);
       if (k >= cut) {
@@ -185,9 +195,6 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
         if (slot < (unsigned)kTrCap) s_cand[slot] = ((uint64_t)k << 32) | (uint32_t)~tid;
       }
     }
-    const int nvec = (V - h) >> 2;
-    typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-    const f32x4_t* rv = (const f32x4_t*)(row + h);
     // sixteen 16-byte loads in flight per thread: the pass is bound by memory latency otherwise
     constexpr int kU = 16;
     for (int i0 = tid; i0 < nvec; i0 += kU * kTrThreads) {
