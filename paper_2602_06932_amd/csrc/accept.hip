@@ -43,14 +43,15 @@ __device__ __forceinline__ double node_weight(float l, float qv, double lse, dou
 // function the LM-head epilogue used for the statistics lse was merged from - a bias of that
 // function cancels between the two.  The fp32 rounding is an independent ~1e-7 relative
 // perturbation per token and averages out of the running sums.  skip_last leaves the last residual
-// step unnormalised (weights whose sum is Z_{nres-1}).
-__device__ __forceinline__ double sweep_weight(float l, float qv, double lse, double inv_t, int nres, const double* Zs,
-                                               bool skip_last) {
+// step unnormalised (weights whose sum is Z_{nres-1}).  The normalisers enter as reciprocals: a
+// multiplication per token and level instead of an fp64 division.
+__device__ __forceinline__ double sweep_weight(float l, float qv, double lse, double inv_t, int nres,
+                                               const double* invZs, bool skip_last) {
   const double a = ((double)l * inv_t - lse) * 1.4426950408889634;
   double x = (double)__builtin_amdgcn_exp2f((float)a);
   for (int s = 0; s < nres; ++s) {
     x = fmax(0.0, x - (double)qv);
-    if (!(skip_last && s == nres - 1)) x /= Zs[s];
+    if (!(skip_last && s == nres - 1)) x *= invZs[s];
   }
   return x;
 }
@@ -166,10 +167,10 @@ __device__ __forceinline__ Lane4 lane_load(const float* __restrict__ lrow, const
 }
 // their draw weights (0 past the end of the vocabulary)
 __device__ __forceinline__ void lane_weights(const Lane4& r, int v0, int V, double lse, double inv_t, int nres,
-                                             double x[4], const double* Zs = nullptr, bool skip_last = true) {
+                                             double x[4], const double* invZs = nullptr, bool skip_last = true) {
 #pragma unroll
   for (int e = 0; e < 4; ++e)
-    x[e] = v0 + e < V ? sweep_weight(r.l[e], r.q[e], lse, inv_t, nres, Zs, skip_last) : 0.0;
+    x[e] = v0 + e < V ? sweep_weight(r.l[e], r.q[e], lse, inv_t, nres, invZs, skip_last) : 0.0;
 }
 
 // Kernel 1: S workgroups per request.  Every workgroup repeats the (cheap) walk - merge the tile
@@ -381,11 +382,16 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams 
 __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P) {
   __shared__ double s_lse[kMaxNq];
   __shared__ int s_arg[kMaxNq];
-  __shared__ double s_Z[kMaxNq];
+  __shared__ double s_Z[kMaxNq], s_invZ[kMaxNq];
   __shared__ double s_gsum[kMaxGroups];
   __shared__ double s_wtot[kAccWaves];
   __shared__ int s_cur, s_depth, s_nres, s_last_child, s_state, s_have_gsum, s_pick, s_lastpos;
   __shared__ double s_pick_prefix;
+  // the request's tree, tokens and uniforms: the walk below is one thread chasing them, so they are
+  // staged once instead of being fetched from global memory one dependent load at a time
+  __shared__ int s_par[kMaxNq], s_tok[kMaxNq];
+  __shared__ float s_u0[kMaxNq], s_u1[kMaxNq];
+  __shared__ float s_ltok[kMaxNq], s_qtok[kMaxNq];  // logit and draft probability of node n's token in its parent's row
 
   const int b = blockIdx.x;
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
@@ -394,6 +400,12 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   const double T = greedy ? 1.0 : (double)P.temperature;
   const double inv_t = 1.0 / T;
   const size_t row0 = (size_t)b * Nq;
+  if (tid < Nq) {
+    s_par[tid] = P.parents ? P.parents[row0 + tid] : tid - 1;
+    s_tok[tid] = P.tok[row0 + tid];
+    s_u0[tid] = greedy ? 0.f : P.un[(row0 + tid) * 2 + 0];
+    s_u1[tid] = greedy ? 0.f : P.un[(row0 + tid) * 2 + 1];
+  }
 
   // ---- 1. per-row (logsumexp, arg-max) from the tile statistics ---------------------------------
   for (int n = wv; n < Nq; n += kAccWaves) {
@@ -407,16 +419,20 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   if (tid < Nq) {
     const int n = tid;
     if (P.row_lse) P.row_lse[row0 + n] = (float)s_lse[n];
-    if (P.p_at_draft) {
-      float pv = 0.f;
-      if (n > 0) {
-        const int par = P.parents ? P.parents[row0 + n] : n - 1;
-        const int tk = P.tok[row0 + n];
-        if (greedy) pv = (tk == s_arg[par]) ? 1.f : 0.f;
-        else pv = (float)exp((double)P.logits[(row0 + par) * V + tk] / T - s_lse[par]);
+    float pv = 0.f;
+    if (n > 0) {
+      const int par = s_par[n];
+      const int tk = s_tok[n];
+      if (greedy) {
+        pv = (tk == s_arg[par]) ? 1.f : 0.f;
+      } else {
+        const float l = P.logits[(row0 + par) * V + tk];
+        s_ltok[n] = l;
+        s_qtok[n] = P.q[(row0 + par) * V + tk];
+        pv = (float)exp((double)l / T - s_lse[par]);
       }
-      P.p_at_draft[row0 + n] = pv;
     }
+    if (P.p_at_draft) P.p_at_draft[row0 + n] = pv;
     P.accept_mask[row0 + n] = n == 0 ? 1 : 0;
   }
   __syncthreads();
@@ -428,8 +444,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       for (;;) {
         int moved = 0;
         for (int c = cur + 1; c < Nq && !moved; ++c) {
-          const int par = P.parents ? P.parents[row0 + c] : c - 1;
-          if (par == cur && P.tok[row0 + c] == s_arg[cur]) {
+          if (s_par[c] == cur && s_tok[c] == s_arg[cur]) {
             cur = c;
             ++depth;
             P.accept_mask[row0 + c] = 1;
@@ -456,18 +471,15 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
     if (tid == 0) {
       const int cur = s_cur;
       int c = s_last_child + 1;
-      for (; c < Nq; ++c) {
-        const int par = P.parents ? P.parents[row0 + c] : c - 1;
-        if (par == cur) break;
-      }
+      for (; c < Nq; ++c)
+        if (s_par[c] == cur) break;
       if (c >= Nq) {
         s_state = ST_DONE;
       } else {
-        const int tk = P.tok[row0 + c];
-        const float l = P.logits[(row0 + cur) * V + tk];
-        const float qv = P.q[(row0 + cur) * V + tk];
+        const float l = s_ltok[c];
+        const float qv = s_qtok[c];
         const double p = node_weight(l, qv, s_lse[cur], T, s_nres, s_Z);
-        const double u = (double)P.un[(row0 + c) * 2 + 0];
+        const double u = (double)s_u0[c];
         s_last_child = c;
         if (u * (double)qv < p) {
           s_cur = c;
@@ -496,7 +508,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       const int nres = state == ST_REJECTED ? s_nres + 1 : s_nres;
       const bool skip_last = state == ST_REJECTED;
       int lastpos = -1;
-      constexpr int kBatch = 4;  // groups whose loads a wavefront keeps in flight together
+      constexpr int kBatch = 5;  // groups whose loads a wavefront keeps in flight together (160 KB per workgroup)
       for (int g = wv; g < ngroups; g += kBatch * kAccWaves) {
         Lane4 r[kBatch];
 #pragma unroll
@@ -510,7 +522,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
           if (gi < ngroups) {  // wave-uniform
             const int v0 = gi * kGroup + lane * 4;
             double x[4];
-            lane_weights(r[i], v0, V, lse, inv_t, nres, x, s_Z, skip_last);
+            lane_weights(r[i], v0, V, lse, inv_t, nres, x, s_invZ, skip_last);
 #pragma unroll
             for (int e = 0; e < 4; ++e)
               if (x[e] > 0.0) lastpos = max(lastpos, v0 + e);
@@ -550,6 +562,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       if (tid == 0) {
         if (total > 0.0) {
           s_Z[s_nres] = total;
+          s_invZ[s_nres] = 1.0 / total;
           s_nres = s_nres + 1;
           s_have_gsum = 1;
         } else {
@@ -560,7 +573,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
     }
 
     // ---- 3. state == ST_DONE: inverse-CDF draw --------------------------------------------------
-    const double u = (double)P.un[(row0 + cur) * 2 + 1];
+    const double u = (double)s_u1[cur];
     const double thr = u * total;
     if (tid == 0) s_pick = 0x7fffffff;
     __syncthreads();
@@ -590,7 +603,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
         const int nres = s_nres;
         const int v0 = pick * kGroup + lane * 4;
         double x[4];
-        lane_weights(lane_load(lrow, qrow, v0, V, vec_ok), v0, V, lse, inv_t, nres, x, s_Z, have);
+        lane_weights(lane_load(lrow, qrow, v0, V, vec_ok), v0, V, lse, inv_t, nres, x, s_invZ, have);
         const double lane_tot = (x[0] + x[1]) + (x[2] + x[3]);
         const double lane_incl = wave_incl_scan(lane_tot, lane) + s_pick_prefix;
         const unsigned long long hit = __ballot(lane_incl > thr);
