@@ -154,6 +154,18 @@ class Workload:
     # sparse pools only: k_pages/v_pages hold one compact slot per referenced page and
     # page_ids[i] is the pool id (the value block_table uses) of compact slot i
     page_ids: Optional[np.ndarray] = None
+    # draft model with its own, smaller vocabulary: draft_probs is [B, Nq, draft_vocab] and
+    # draft_to_target[j] is the target id of draft entry j (ascending); 0 / None otherwise
+    draft_vocab: int = 0
+    draft_to_target: Optional[np.ndarray] = None
+
+    def target_to_draft(self) -> Optional[np.ndarray]:
+        """Inverse of draft_to_target over the target vocabulary, -1 where the draft model has no entry."""
+        if self.draft_to_target is None:
+            return None
+        inv = np.full(self.vocab, -1, dtype=np.int32)
+        inv[self.draft_to_target] = np.arange(len(self.draft_to_target), dtype=np.int32)
+        return inv
 
     @property
     def num_draft(self) -> int:
@@ -267,7 +279,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
                   seq_lens, draft: str, draft_noise: float = 1.0,
                   tree: bool = False, greedy_hit: float = 0.7,
                   shuffle_pages: bool = True, pool_pages: Optional[int] = None,
-                  distinct_siblings: bool = False, recipe: str = "") -> Workload:
+                  distinct_siblings: bool = False, draft_vocab: Optional[int] = None,
+                  recipe: str = "") -> Workload:
     """Build one workload.
 
     draft = "independent": draft logits ~ N(0,1), draft tokens uniform over the vocab.
@@ -275,6 +288,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
             i.e. softmax((target + noise)/T); each draft token is drawn from its parent's row.
     draft = "greedy_mix": token = argmax of the stand-in target logits of the parent row with
             probability `greedy_hit`, else uniform; draft_probs/uniforms are None.
+    draft_vocab (with "noisy_target"): the draft model's vocabulary is a random subset of that many
+            target ids; draft_probs is over the subset, tokens are drawn from it and stored as target ids.
     """
     ss = np.random.SeedSequence([int(seed), 0x2602_06932 & 0xFFFFFFFF])
     s_q, s_kv, s_h, s_w, s_misc = ss.spawn(5)
@@ -296,6 +311,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
     draft_tokens = np.zeros((B, Nq), dtype=np.int32)
     draft_probs = None
     uniforms = None
+    d2t = None
+    assert not draft_vocab or draft == "noisy_target"
     if draft == "independent":
         draft_tokens[:, 1:] = rng.integers(0, V, size=(B, Nq - 1), dtype=np.int64)
         z = rng.standard_normal((B * Nq, V), dtype=np.float32)
@@ -304,12 +321,16 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
     elif draft == "noisy_target":
         t = _standin_target_logits(hidden, lm_head, dtype)
         T = np.float32(temperature if temperature > 0 else 1.0)
+        if draft_vocab:
+            d2t = np.sort(rng.choice(V, size=int(draft_vocab), replace=False)).astype(np.int32)
+            t = np.ascontiguousarray(t[:, d2t])
         noise = rng.standard_normal(t.shape, dtype=np.float32) * np.float32(draft_noise)
-        draft_probs = _softmax_rows_f32((t + noise) / T).reshape(B, Nq, V)
+        draft_probs = _softmax_rows_f32((t + noise) / T).reshape(B, Nq, t.shape[1])
         del t, noise
         for n in range(1, Nq):
             rows = draft_probs[np.arange(B), par[:, n]]
-            draft_tokens[:, n] = _draw_from_rows(rng, rows)
+            idx = _draw_from_rows(rng, rows)
+            draft_tokens[:, n] = d2t[idx] if draft_vocab else idx
         uniforms = _uniform24(rng, (B, Nq, 2))
     elif draft == "greedy_mix":
         t = _standin_target_logits(hidden, lm_head, dtype).reshape(B, Nq, V)
@@ -334,7 +355,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
                  temperature=float(temperature), q=q, k_pages=k_pages, v_pages=v_pages,
                  block_table=block_table, seq_lens=seq_lens, parents=parents, hidden=hidden,
                  lm_head=lm_head, draft_tokens=draft_tokens, draft_probs=draft_probs,
-                 uniforms=uniforms, recipe=recipe, page_ids=page_ids)
+                 uniforms=uniforms, recipe=recipe, page_ids=page_ids,
+                 draft_vocab=int(draft_vocab or 0), draft_to_target=d2t)
     return w
 
 

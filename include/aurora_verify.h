@@ -69,6 +69,14 @@ typedef struct {
   int32_t vocab;     /* V (tree sampling, i.e. parents != NULL with T > 0: V <= 2^20)           */
   int32_t dtype;     /* type of hidden and lm_head                                           */
   float temperature; /* 0 => greedy (arg-max prefix); > 0 => speculative rejection sampling  */
+  /* Draft model with a smaller vocabulary than the target (section 4.1: a 32K-entry draft head;
+   * appendix A.2: 32K vs 128K / 152K).  draft_vocab = 0: draft_probs rows are dense over V.
+   * draft_vocab = Vd in 1..V: draft_probs is [B, Nq, Vd] over the draft vocabulary and
+   * target_to_draft (DEVICE pointer, [V] int32) gives for every target id its index in a row of
+   * draft_probs, or -1 for ids the draft model cannot emit - there q = 0, so the residual
+   * max(0, p - q) keeps all of p's mass.  draft_tokens stay target ids.  Ignored when T == 0. */
+  int32_t draft_vocab;
+  const int32_t* target_to_draft;
 } aurora_accept_desc;
 
 /* Bytes of workspace needed by aurora_verify / _attn / _accept for these descriptors.
@@ -118,8 +126,8 @@ int aurora_verify_accept(const aurora_accept_desc* desc,
                          const void* hidden,          /* [B, Nq, H]                           */
                          const void* lm_head,         /* [V, H] row-major                     */
                          const int32_t* draft_tokens, /* [B, Nq]; entry 0 (root) ignored      */
-                         const float* draft_probs,    /* [B, Nq, V] fp32, row n = distribution of n's
-                                                         children; NULL allowed iff T == 0    */
+                         const float* draft_probs,    /* [B, Nq, V] fp32 (or [B, Nq, Vd], see desc), row n =
+                                                         distribution of n's children; NULL allowed iff T == 0 */
                          const float* uniforms,       /* [B, Nq, 2] in [0,1); NULL allowed iff T == 0 */
                          const int32_t* parents,      /* [B, Nq] or NULL => chain             */
                          int32_t* accept_len,         /* [B] accepted draft tokens = depth of the stop node */

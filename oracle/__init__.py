@@ -114,10 +114,25 @@ def _alloc_results(B, Nq, V, want_cdf):
         final_cdf=np.empty((B, V), np.float64) if want_cdf else None)
 
 
+def _dense_draft_probs(draft_probs, draft_to_target, V):
+    """A draft model with a smaller vocabulary (paper section 4.1: a 32K-entry draft head) gives
+    q over its own vocabulary; on the target vocabulary q(v) = q_sub[j] where v = draft_to_target[j]
+    and 0 everywhere else.  The oracle works on that dense form: the definition, written out."""
+    if draft_to_target is None or draft_probs is None:
+        return draft_probs
+    d2t = np.asarray(draft_to_target, dtype=np.int64)
+    B, Nq, Vd = draft_probs.shape
+    assert d2t.shape == (Vd,) and len(np.unique(d2t)) == Vd and d2t.min() >= 0 and d2t.max() < V
+    dense = np.zeros((B, Nq, V), np.float32)
+    dense[:, :, d2t] = draft_probs
+    return dense
+
+
 def accept_from_logits(*, logits, draft_tokens, draft_probs=None, uniforms=None, parents=None,
-                       temperature, want_cdf=False) -> AcceptResult:
+                       temperature, want_cdf=False, draft_to_target=None) -> AcceptResult:
     lg = _chk(logits, np.float64)
     B, Nq, V = lg.shape
+    draft_probs = _dense_draft_probs(draft_probs, draft_to_target, V)
     draft_tokens = _chk(draft_tokens, np.int32, (B, Nq))
     draft_probs = _chk(draft_probs, np.float32, (B, Nq, V))
     uniforms = _chk(uniforms, np.float32, (B, Nq, 2))
@@ -134,7 +149,7 @@ def accept_from_logits(*, logits, draft_tokens, draft_probs=None, uniforms=None,
 
 
 def accept(*, hidden, lm_head, draft_tokens, draft_probs=None, uniforms=None, parents=None, dtype,
-           temperature, want_cdf=False, want_logits=False) -> AcceptResult:
+           temperature, want_cdf=False, want_logits=False, draft_to_target=None) -> AcceptResult:
     """LM head + acceptance.  hidden [B, Nq, H], lm_head [V, H].  The temperature is first
     rounded to float32 (the type it has at the library boundary), then widened."""
     ed = _elem_dtype(dtype)
@@ -144,7 +159,7 @@ def accept(*, hidden, lm_head, draft_tokens, draft_probs=None, uniforms=None, pa
     V = lm_head.shape[0]
     assert lm_head.shape[1] == H
     draft_tokens = _chk(draft_tokens, np.int32, (B, Nq))
-    draft_probs = _chk(draft_probs, np.float32, (B, Nq, V))
+    draft_probs = _chk(_dense_draft_probs(draft_probs, draft_to_target, V), np.float32, (B, Nq, V))
     uniforms = _chk(uniforms, np.float32, (B, Nq, 2))
     parents = _chk(parents, np.int32, (B, Nq))
     r = _alloc_results(B, Nq, V, want_cdf and temperature > 0)
@@ -166,7 +181,8 @@ def verify(w, want_cdf=False, want_logits=False):
              seq_lens=w.seq_lens, parents=w.parents, dtype=w.dtype)
     a = accept(hidden=w.hidden, lm_head=w.lm_head, draft_tokens=w.draft_tokens,
                draft_probs=w.draft_probs, uniforms=w.uniforms, parents=w.parents, dtype=w.dtype,
-               temperature=w.temperature, want_cdf=want_cdf, want_logits=want_logits)
+               temperature=w.temperature, want_cdf=want_cdf, want_logits=want_logits,
+               draft_to_target=getattr(w, "draft_to_target", None))
     return o, a
 
 

@@ -73,7 +73,9 @@ struct AcceptParams {
   const float* psum;
   const int32_t* parg;
   const int32_t* tok;
-  const float* q;
+  const float* q;       // draft probabilities, row stride Vq
+  const int32_t* t2d;   // target id -> index into a row of q, or -1 (q = 0 there); NULL: q rows are dense over V
+  int Vq;               // entries per row of q: the draft vocabulary, or V
   const float* un;
   const int32_t* parents;
   int32_t* accept_len;
@@ -148,19 +150,44 @@ constexpr int kGroup = 256;
 
 // the logits and draft probabilities of the four tokens v0 .. v0+3 a lane owns
 struct Lane4 { float l[4], q[4]; };
-__device__ __forceinline__ Lane4 lane_load(const float* __restrict__ lrow, const float* __restrict__ qrow, int v0, int V,
-                                           bool vec_ok) {
+// One row of draft probabilities: dense over the target vocabulary, or compact over the draft vocabulary
+// with the target -> draft index map (entries off the draft vocabulary have probability 0).
+struct QRow {
+  const float* row;
+  const int32_t* t2d;
+};
+// 16-byte loads of the logits row and of the q row (or of the index map) are possible
+__device__ __forceinline__ bool rows_vec_ok(const AcceptParams& P) {
+  const uintptr_t qa = P.t2d ? (uintptr_t)P.t2d : (uintptr_t)P.q;
+  return (P.V & 3) == 0 && ((qa | (uintptr_t)P.logits) & 15) == 0;
+}
+__device__ __forceinline__ QRow q_row(const AcceptParams& P, size_t r) { return QRow{P.q + r * (size_t)P.Vq, P.t2d}; }
+__device__ __forceinline__ float q_at(const QRow& q, int v) {
+  if (!q.t2d) return q.row[v];
+  const int j = q.t2d[v];
+  return j >= 0 ? q.row[j] : 0.f;
+}
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+__device__ __forceinline__ Lane4 lane_load(const float* __restrict__ lrow, const QRow& q, int v0, int V, bool vec_ok) {
   Lane4 r;
   if (vec_ok && v0 + 3 < V) {
     const f32x4_t lv = *(const f32x4_t*)(lrow + v0);
-    const f32x4_t qv = *(const f32x4_t*)(qrow + v0);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { r.l[e] = lv[e]; r.q[e] = qv[e]; }
+    for (int e = 0; e < 4; ++e) r.l[e] = lv[e];
+    if (!q.t2d) {
+      const f32x4_t qv = *(const f32x4_t*)(q.row + v0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r.q[e] = qv[e];
+    } else {
+      const i32x4_t jv = *(const i32x4_t*)(q.t2d + v0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r.q[e] = jv[e] >= 0 ? q.row[jv[e]] : 0.f;
+    }
   } else {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       r.l[e] = v0 + e < V ? lrow[v0 + e] : -INFINITY;
-      r.q[e] = v0 + e < V ? qrow[v0 + e] : 0.f;
+      r.q[e] = v0 + e < V ? q_at(q, v0 + e) : 0.f;
     }
   }
   return r;
@@ -199,7 +226,7 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams
     if (n > 0) {
       const int tk = P.tok[row0 + n];
       const float l = P.logits[(row0 + n - 1) * V + tk];
-      const float qv = P.q[(row0 + n - 1) * V + tk];
+      const float qv = q_at(q_row(P, row0 + n - 1), tk);
       const double p = exp((double)l / T - s_lse[n - 1]);
       const double u = (double)P.un[(row0 + n) * 2 + 0];
       ok = (u * (double)qv < p) ? 1 : 0;
@@ -230,8 +257,8 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams
 
   const double inv_t = 1.0 / T;
   const float* lrow = P.logits + (row0 + row) * V;
-  const float* qrow = P.q + (row0 + row) * V;
-  const bool vec_ok = (V & 3) == 0 && (((uintptr_t)P.q | (uintptr_t)P.logits) & 15) == 0;
+  const QRow qrow = q_row(P, row0 + row);
+  const bool vec_ok = rows_vec_ok(P);
   const int per = (P.ngroups + P.slices - 1) / P.slices;
   const int g0 = slice * per, g1 = min(P.ngroups, g0 + per);
   int lastpos = -1;
@@ -283,8 +310,8 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams 
   const double lse = P.st_lse[b];
   const double inv_t = 1.0 / (double)P.temperature;
   const float* lrow = P.logits + ((size_t)b * P.Nq + row) * V;
-  const float* qrow = P.q + ((size_t)b * P.Nq + row) * V;
-  const bool vec_ok = (V & 3) == 0 && (((uintptr_t)P.q | (uintptr_t)P.logits) & 15) == 0;
+  const QRow qrow = q_row(P, (size_t)b * P.Nq + row);
+  const bool vec_ok = rows_vec_ok(P);
   double* gs = P.gsum + (size_t)b * ng;
   const int per = (ng + kSmallThreads - 1) / kSmallThreads;
   const int ga = min(ng, tid * per), gb = min(ng, ga + per);
@@ -428,7 +455,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       } else {
         const float l = P.logits[(row0 + par) * V + tk];
         s_ltok[n] = l;
-        s_qtok[n] = P.q[(row0 + par) * V + tk];
+        s_qtok[n] = q_at(q_row(P, row0 + par), tk);
         pv = (float)exp((double)l / T - s_lse[par]);
       }
     }
@@ -461,7 +488,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
 
   // ---- 2b. sampling walk ------------------------------------------------------------------------
   const int ngroups = (V + kGroup - 1) / kGroup;  // <= kMaxGroups (checked by the launcher)
-  const bool vec_ok = (V & 3) == 0 && (((uintptr_t)P.q | (uintptr_t)P.logits) & 15) == 0;
+  const bool vec_ok = rows_vec_ok(P);
   if (tid == 0) {
     s_cur = 0; s_depth = 0; s_nres = 0; s_last_child = 0; s_have_gsum = 0;
   }
@@ -499,7 +526,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
 
     const int cur = s_cur;
     const float* lrow = P.logits + (row0 + cur) * V;
-    const float* qrow = P.q + (row0 + cur) * V;
+    const QRow qrow = q_row(P, row0 + cur);
     const double lse = s_lse[cur];
 
     if (state == ST_REJECTED || !s_have_gsum) {
@@ -655,6 +682,7 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st) {
   P.Nq = a.Nq; P.V = a.V; P.n_tiles = a.plan.n_tiles; P.temperature = a.temperature;
   P.logits = a.logits; P.pmax = a.pmax; P.psum = a.psum; P.parg = a.parg;
   P.tok = a.draft_tokens; P.q = a.draft_probs; P.un = a.uniforms; P.parents = a.parents;
+  P.t2d = a.target_to_draft; P.Vq = a.target_to_draft ? a.Vd : a.V;
   P.accept_len = a.accept_len; P.next_token = a.next_token; P.accept_mask = a.accept_mask;
   P.p_at_draft = a.p_at_draft; P.row_lse = a.row_lse;
   P.slices = a.plan.slices; P.gmul = a.plan.gmul; P.ngroups = a.plan.ngroups;

@@ -30,6 +30,8 @@ int check_accept_desc(const aurora_accept_desc* d) {
   if (d->num_q > kMaxNq) return AURORA_ERR_UNSUPPORTED;
   if ((int64_t)d->batch * d->num_q > 65535) return AURORA_ERR_UNSUPPORTED;
   if (d->dtype == AURORA_BF16 && d->hidden % 8) return AURORA_ERR_UNSUPPORTED;
+  if (d->draft_vocab < 0 || d->draft_vocab > d->vocab) return AURORA_ERR_INVALID_ARG;
+  if (d->draft_vocab > 0 && d->temperature > 0.f && !d->target_to_draft) return AURORA_ERR_INVALID_ARG;
   return AURORA_OK;
 }
 
@@ -77,6 +79,7 @@ AcceptLaunch accept_launch_from(const aurora_accept_desc* d) {
   AcceptLaunch a = {};
   a.B = d->batch; a.Nq = d->num_q; a.H = d->hidden; a.V = d->vocab; a.bf16 = d->dtype == AURORA_BF16;
   a.temperature = d->temperature;
+  if (d->draft_vocab > 0 && d->temperature > 0.f) { a.Vd = d->draft_vocab; a.target_to_draft = d->target_to_draft; }
   return a;
 }
 

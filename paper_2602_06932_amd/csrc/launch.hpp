@@ -18,6 +18,8 @@ struct AttnLaunch {
 
 struct AcceptLaunch {
   int B, Nq, H, V;
+  int Vd;                          // draft vocabulary (entries per row of draft_probs) when target_to_draft is set
+  const int32_t* target_to_draft;  // or NULL: draft_probs rows are dense over V
   bool bf16;
   float temperature;
   const void *hidden, *lm_head;

@@ -57,8 +57,13 @@ class DeviceVerify:
             batch=w.batch, num_q=w.num_q, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
             head_dim=w.head_dim, page_size=w.page_size, max_pages_per_seq=int(w.block_table.shape[1]),
             num_pages=int(w.num_pages), dtype=self.dt, sm_scale=0.0)
-        self.accept_desc = B.aurora_accept_desc(batch=w.batch, num_q=w.num_q, hidden=w.hidden_size,
-                                                vocab=w.vocab, dtype=self.dt, temperature=w.temperature)
+        # a draft model with its own vocabulary: the target -> draft index map goes with the descriptor
+        t2d = w.target_to_draft() if getattr(w, "draft_to_target", None) is not None else None
+        self.target_to_draft = _to_dev(t2d, None)
+        self.accept_desc = B.aurora_accept_desc(
+            batch=w.batch, num_q=w.num_q, hidden=w.hidden_size, vocab=w.vocab, dtype=self.dt,
+            temperature=w.temperature, draft_vocab=int(getattr(w, "draft_vocab", 0) or 0),
+            target_to_draft=None if t2d is None else self.target_to_draft.data_ptr())
         self.ws_bytes = B.aurora_verify_workspace_bytes(self.attn_desc, self.accept_desc)
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
         assert self.workspace.data_ptr() % 256 == 0

@@ -304,3 +304,34 @@ def test_lmhead_then_accept_logits_equals_accept(gpu_lib, tree):
                         uniforms=w.uniforms, parents=w.parents, dtype=w.dtype, temperature=w.temperature,
                         want_cdf=True, want_logits=True)
     check_accept(two, ref, w)
+
+
+@pytest.mark.parametrize("vocab,draft_vocab", [(4000, 1000), (3001, 777)])
+def test_draft_subvocabulary_chain(gpu_lib, vocab, draft_vocab):
+    """Draft probabilities over a smaller vocabulary with the target -> draft index map (16-byte loads of
+    the map when V % 4 == 0, scalar path otherwise)."""
+    w = gen.llama_chain(20, batch=9, len_lo=20, len_hi=70, vocab=vocab, hidden_size=128, draft_vocab=draft_vocab,
+                        draft_noise=0.5)
+    _, a = _full_check(gpu_lib, w)
+    assert a.accept_len.max() > 0
+
+
+def test_draft_subvocabulary_token_outside_the_draft_vocabulary(gpu_lib):
+    """A drafted id the draft model has no entry for has q = 0: it is kept iff the target gives it any mass."""
+    w = gen.llama_chain(21, batch=6, len_lo=20, len_hi=50, vocab=2000, hidden_size=64, draft_vocab=500)
+    off = np.setdiff1d(np.arange(w.vocab), w.draft_to_target)
+    w.draft_tokens[:, 1] = off[:6]
+    _, a = _full_check(gpu_lib, w)
+    assert np.all(a.accept_len >= 1)
+
+
+def test_draft_subvocabulary_tree(gpu_lib):
+    w = gen.llama_tree(22, batch=5, num_q=16, vocab=4000, hidden_size=128, context=64, num_q_heads=4, num_kv_heads=2,
+                       draft_vocab=1000, draft_noise=0.5)
+    _full_check(gpu_lib, w)
+
+
+def test_full_size_llama_chain_with_32k_draft_vocabulary(gpu_lib):
+    """Config 2's shapes with the 32K-entry draft vocabulary of the paper's drafter."""
+    w = gen.llama_chain(1, draft_vocab=32000, draft_noise=0.5)
+    _full_check(gpu_lib, w, sample=[0, 7, 19, 31])

@@ -312,3 +312,61 @@ def test_monte_carlo_tree_emits_target_distribution():
     # more candidates per node => strictly more acceptance than the first-child-only chain
     first_only = 1 - np.minimum(p[0], q[0].astype(np.float64)).sum()
     assert (r.accept_len == 0).mean() < first_only
+
+
+# ------------------------------------------------------------------ draft model with a smaller vocabulary
+def test_monte_carlo_subvocabulary_draft_still_emits_target_distribution():
+    """q lives on 6 of the 16 target ids (ids the draft model cannot emit have q = 0).  Speculative
+    sampling is exact for any q, so the emitted token is still distributed as p - which fails if the
+    compact rows are scattered to the wrong ids, or if mass off the draft vocabulary is dropped from
+    the residual."""
+    rng = np.random.default_rng(7)
+    B, k, V, Vd = 250_000, 3, 16, 6
+    Nq = k + 1
+    d2t = np.sort(rng.choice(V, size=Vd, replace=False)).astype(np.int32)
+    lrow = rng.standard_normal((Nq, V)) * 1.2
+    p = _softmax64(lrow)
+    q_sub = _softmax64(lrow[:, d2t] + rng.standard_normal((Nq, Vd)) * 0.7).astype(np.float32)
+    toks = np.zeros((B, Nq), np.int32)
+    for i in range(1, Nq):
+        toks[:, i] = d2t[_draw(rng, q_sub[i - 1].astype(np.float64), B)]
+    un = gen.workloads._uniform24(rng, (B, Nq, 2))
+    r = oracle.accept_from_logits(logits=np.broadcast_to(lrow, (B, Nq, V)).copy(), draft_tokens=toks,
+                                  draft_probs=np.broadcast_to(q_sub, (B, Nq, Vd)).copy(), uniforms=un,
+                                  temperature=1.0, draft_to_target=d2t)
+    L = r.accept_len
+    q_dense = np.zeros((Nq, V))
+    q_dense[:, d2t] = q_sub
+    alpha = np.minimum(p, q_dense).sum(-1)
+    reach = 1.0
+    for i in range(Nq):
+        sel = L >= i
+        n = int(sel.sum())
+        assert abs(n / B - reach) <= 4 * np.sqrt(reach * (1 - reach) / B) + 1e-9
+        emitted = np.where(L[sel] >= i + 1, toks[sel, min(i + 1, k)], r.next_token[sel]) if i < k else r.next_token[sel]
+        f = np.bincount(emitted, minlength=V) / n
+        assert _within(f, p[i], n), (i, f, p[i])
+        if i < k:
+            reach *= alpha[i]
+    # ids off the draft vocabulary can only ever appear as corrected / bonus tokens
+    off = np.setdiff1d(np.arange(V), d2t)
+    assert np.isin(r.next_token, off).mean() > 0.2
+
+
+def test_full_draft_vocabulary_with_identity_map_equals_dense_call():
+    w = gen.tiny_chain(5)
+    a = oracle.accept(hidden=w.hidden, lm_head=w.lm_head, draft_tokens=w.draft_tokens, draft_probs=w.draft_probs,
+                      uniforms=w.uniforms, dtype=w.dtype, temperature=w.temperature)
+    b = oracle.accept(hidden=w.hidden, lm_head=w.lm_head, draft_tokens=w.draft_tokens, draft_probs=w.draft_probs,
+                      uniforms=w.uniforms, dtype=w.dtype, temperature=w.temperature,
+                      draft_to_target=np.arange(w.vocab, dtype=np.int32))
+    assert np.array_equal(a.accept_len, b.accept_len) and np.array_equal(a.next_token, b.next_token)
+
+
+def test_subvocabulary_generator_is_consistent():
+    w = gen.llama_chain(31, batch=6, len_lo=20, len_hi=40, vocab=1000, hidden_size=64, draft_vocab=250)
+    assert w.draft_probs.shape == (6, 5, 250) and w.draft_vocab == 250
+    d2t, t2d = w.draft_to_target, w.target_to_draft()
+    assert np.all(np.diff(d2t) > 0) and np.array_equal(t2d[d2t], np.arange(250))
+    assert (t2d >= 0).sum() == 250 and np.all(t2d[w.draft_tokens[:, 1:]] >= 0)
+    assert np.allclose(w.draft_probs.sum(-1), 1.0, atol=1e-4)
