@@ -31,6 +31,8 @@ def make_workload(name, seed):
     import gen
     if name == "llama":
         return gen.llama_chain(seed)
+    if name == "llama_draft32k":
+        return gen.llama_chain(seed, draft_vocab=32000, draft_noise=0.5)
     if name == "tiny":
         return gen.tiny_chain(seed)
     if name == "qwen_greedy":
@@ -61,7 +63,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="llama", choices=["llama", "tiny", "qwen_greedy", "tree", "stress"])
+    ap.add_argument("--workload", default="llama", choices=["llama", "llama_draft32k", "tiny", "qwen_greedy", "tree", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
     ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy"],

@@ -212,6 +212,12 @@ typedef struct {
   int32_t num_q; /* Nq, 1..64                         */
   int32_t vocab; /* V >= 1                            */
   int32_t top_k; /* K, 1..1024 (the paper uses 1024)  */
+  /* Logits over the draft vocabulary only (appendix A.2: the draft model's vocabulary is 4-5 x smaller,
+   * so only those logits are transmitted).  draft_vocab = 0: select over all V entries.  draft_vocab =
+   * Vd in 1..V: select over logits[m, draft_to_target[j]], j < Vd (DEVICE pointer, [Vd] int32 target
+   * ids, distinct); topk_ids then hold draft indices j, ties by ascending j, padding when Vd < K. */
+  int32_t draft_vocab;
+  const int32_t* draft_to_target;
 } aurora_trace_desc;
 
 int aurora_trace_emit(const aurora_trace_desc* desc,

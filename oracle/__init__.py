@@ -186,8 +186,12 @@ def verify(w, want_cdf=False, want_logits=False):
     return o, a
 
 
-def trace_topk(logits: np.ndarray, top_k: int):
-    """K largest entries of each row of float32 logits [rows, V]: (ids int32 [rows, K], bf16 bits uint16 [rows, K])."""
+def trace_topk(logits: np.ndarray, top_k: int, draft_to_target=None):
+    """K largest entries of each row of float32 logits [rows, V]: (ids int32 [rows, K], bf16 bits uint16 [rows, K]).
+    With draft_to_target the selection runs over logits[:, draft_to_target] (the logits of the draft
+    vocabulary, paper appendix A.2) and the ids are positions in that list."""
+    if draft_to_target is not None:
+        logits = np.ascontiguousarray(np.asarray(logits)[:, np.asarray(draft_to_target, dtype=np.int64)])
     logits = _chk(logits, np.float32)
     rows, V = logits.shape
     ids = np.empty((rows, top_k), np.int32)

@@ -39,7 +39,8 @@ class aurora_accept_desc(C.Structure):
 
 
 class aurora_trace_desc(C.Structure):
-    _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("vocab", C.c_int32), ("top_k", C.c_int32)]
+    _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("vocab", C.c_int32), ("top_k", C.c_int32),
+                ("draft_vocab", C.c_int32), ("draft_to_target", C.c_void_p)]
 
 
 class AuroraError(RuntimeError):

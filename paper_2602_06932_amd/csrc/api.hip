@@ -302,6 +302,8 @@ int aurora_trace_emit(const aurora_trace_desc* d, const float* logits, const int
                       const int32_t* parents, const int32_t* next_token, const uint8_t* accept_mask,
                       int32_t* topk_ids, uint16_t* topk_logits, int32_t* y_out, int8_t* traj, void* hip_stream) {
   if (!d || d->batch < 0 || d->num_q < 1 || d->vocab < 1 || d->top_k < 1) return AURORA_ERR_INVALID_ARG;
+  if (d->draft_vocab < 0 || d->draft_vocab > d->vocab || (d->draft_vocab > 0 && !d->draft_to_target))
+    return AURORA_ERR_INVALID_ARG;
   if (d->num_q > kMaxNq || d->top_k > trace_max_k()) return AURORA_ERR_UNSUPPORTED;
   const bool want_topk = topk_ids || topk_logits, want_rec = y_out || traj;
   if (!want_topk && !want_rec) return AURORA_ERR_INVALID_ARG;
@@ -311,7 +313,9 @@ int aurora_trace_emit(const aurora_trace_desc* d, const float* logits, const int
   if (d->batch == 0) return AURORA_OK;
   hipStream_t st = (hipStream_t)hip_stream;
   if (want_topk &&
-      launch_trace_topk(logits, (int64_t)d->batch * d->num_q, d->vocab, d->top_k, topk_ids, topk_logits, st) != hipSuccess)
+      launch_trace_topk(logits, (int64_t)d->batch * d->num_q, d->vocab, d->top_k,
+                        d->draft_vocab > 0 ? d->draft_to_target : nullptr, d->draft_vocab, topk_ids, topk_logits,
+                        st) != hipSuccess)
     return AURORA_ERR_HIP;
   if (want_rec && launch_trace_records(d->batch, d->num_q, draft_tokens, parents, next_token, accept_mask, y_out, traj,
                                        st) != hipSuccess)

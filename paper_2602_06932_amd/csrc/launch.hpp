@@ -55,8 +55,8 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st);
 
 // trace emission: top-K target logits per token row, y_out and rejection trajectory
 int trace_max_k();
-hipError_t launch_trace_topk(const float* logits, int64_t rows, int V, int K, int32_t* ids, uint16_t* vals,
-                             hipStream_t st);
+hipError_t launch_trace_topk(const float* logits, int64_t rows, int V, int K, const int32_t* map, int n_map,
+                             int32_t* ids, uint16_t* vals, hipStream_t st);
 hipError_t launch_trace_records(int B, int Nq, const int32_t* draft_tokens, const int32_t* parents,
                                 const int32_t* next_token, const uint8_t* accept_mask, int32_t* y_out, int8_t* traj,
                                 hipStream_t st);

@@ -146,7 +146,11 @@ __device__ __forceinline__ uint64_t radix_threshold(SelectShared& sh, int n, int
   return prefix;
 }
 
-__global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __restrict__ logits, int V, int K,
+// kMapped: the selection runs over the V entries row[map[0]], .., row[map[V-1]] of a row of Vrow logits
+// (the draft vocabulary, appendix A.2) and the ids written are positions in that list.
+template <bool kMapped>
+__global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __restrict__ logits, int Vrow, int V, int K,
+                                                               const int32_t* __restrict__ map,
                                                                int32_t* __restrict__ out_ids,
                                                                uint16_t* __restrict__ out_vals) {
   __shared__ uint64_t s_cand[kTrCap];   // 32 KB: the sample (as 32-bit keys), then the candidate list
@@ -154,7 +158,8 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
   __shared__ SelectShared s_sel;
   __shared__ unsigned s_count;
   const int tid = threadIdx.x;
-  const float* row = logits + (size_t)blockIdx.x * V;
+  const float* row = logits + (size_t)blockIdx.x * Vrow;
+  auto at = [&](int i) -> float { return kMapped ? row[map[i]] : row[i]; };
   int32_t* ids = out_ids + (size_t)blockIdx.x * K;
   uint16_t* vals = out_vals + (size_t)blockIdx.x * K;
   const int want = K < V ? K : V;  // entries that exist
@@ -162,21 +167,28 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
   bool from_row = false;           // select over the whole row instead of the list
 
   if (V <= kTrCap) {
-    for (int i = tid; i < V; i += kTrThreads) s_cand[i] = entry_word(row[i], i);
+    for (int i = tid; i < V; i += kTrThreads) s_cand[i] = entry_word(at(i), i);
     count = V;
   } else {
-    const int head = (int)(((16 - ((uintptr_t)row & 15)) & 15) >> 2);  // entries before the first 16-byte boundary
+    // entries before the first 16-byte boundary (of the row, or of the index list when mapped)
+    const uintptr_t vec_base = kMapped ? (uintptr_t)map : (uintptr_t)row;
+    const int head = (int)(((16 - (vec_base & 15)) & 15) >> 2);
     const int h = head < V ? head : V;
     const int nvec = (V - h) >> 2;  // >= 1023 here
     typedef __attribute__((ext_vector_type(4))) float f32x4_t;
-    const f32x4_t* rv = (const f32x4_t*)(row + h);
+    typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+    auto load4 = [&](int i) -> f32x4_t {  // entries h + 4i .. h + 4i + 3
+      if (!kMapped) return ((const f32x4_t*)(row + h))[i];
+      const i32x4_t j = ((const i32x4_t*)(map + h))[i];
+      return f32x4_t{row[j[0]], row[j[1]], row[j[2]], row[j[3]]};
+    };
     // ---- cut-off key from a sample ---------------------------------------------------------------------
     // 1024 evenly spaced 16-byte vectors (one 128-byte line in several is touched, not every line)
     uint32_t* s_sample = (uint32_t*)s_cand;
     {
       const int vstride = nvec / (kTrCap / 4);
       const int vi = vstride ? tid * vstride : (tid < nvec ? tid : nvec - 1);
-      const f32x4_t x = rv[vi];
+      const f32x4_t x = load4(vi);
 #pragma unroll
       for (int j = 0; j < 4; ++j) s_sample[4 * tid + j] = order_key(x[j]);
     }
@@ -189,7 +201,7 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
     __syncthreads();
     // ---- one pass over the row: keep what reaches the cut-off ------------------------------------------
     if (tid < h) {
-      const uint32_t k = order_key(row[tid]);
+      const uint32_t k = order_key(at(tid));
       if (k >= cut) {
         const unsigned slot = atomicAdd(&s_count, 1u);
         if (slot < (unsigned)kTrCap) s_cand[slot] = ((uint64_t)k << 32) | (uint32_t)~tid;
@@ -202,7 +214,7 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
 #pragma unroll
       for (int u = 0; u < kU; ++u) {
         const int i = i0 + u * kTrThreads;
-        x[u] = i < nvec ? rv[i] : f32x4_t{0.f, 0.f, 0.f, 0.f};
+        x[u] = i < nvec ? load4(i) : f32x4_t{0.f, 0.f, 0.f, 0.f};
       }
 #pragma unroll
       for (int u = 0; u < kU; ++u) {
@@ -220,7 +232,7 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
       }
     }
     for (int i = h + 4 * nvec + tid; i < V; i += kTrThreads) {
-      const uint32_t k = order_key(row[i]);
+      const uint32_t k = order_key(at(i));
       if (k >= cut) {
         const unsigned slot = atomicAdd(&s_count, 1u);
         if (slot < (unsigned)kTrCap) s_cand[slot] = ((uint64_t)k << 32) | (uint32_t)~i;
@@ -246,10 +258,10 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
       }
     }
   } else {
-    const uint64_t thr = radix_threshold<64, 0>(s_sel, V, want, [&](int i) { return entry_word(row[i], i); });
+    const uint64_t thr = radix_threshold<64, 0>(s_sel, V, want, [&](int i) { return entry_word(at(i), i); });
     __syncthreads();
     for (int i = tid; i < V; i += kTrThreads) {
-      const uint64_t w = entry_word(row[i], i);
+      const uint64_t w = entry_word(at(i), i);
       if (w >= thr) {
         const unsigned slot = atomicAdd(&s_count, 1u);
         if (slot < (unsigned)kTrMaxK) s_top[slot] = w;  // exactly `want` of these exist
@@ -265,7 +277,7 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
     if (k < want) {
       const int id = (int)~(uint32_t)(s_top[k] & 0xffffffffull);
       ids[k] = id;
-      vals[k] = bf16_rne_bits(row[id]);
+      vals[k] = bf16_rne_bits(at(id));
     } else {
       ids[k] = -1;
       vals[k] = 0xff80u;  // -inf
@@ -306,10 +318,15 @@ __global__ void trace_records_kernel(int B, int Nq, const int32_t* __restrict__ 
   y[cur] = next_token[b];
 }
 
-hipError_t launch_trace_topk(const float* logits, int64_t rows, int V, int K, int32_t* ids, uint16_t* vals,
-                             hipStream_t st) {
+hipError_t launch_trace_topk(const float* logits, int64_t rows, int V, int K, const int32_t* map, int n_map,
+                             int32_t* ids, uint16_t* vals, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(trace_topk_kernel, dim3((unsigned)rows), dim3(kTrThreads), 0, st, logits, V, K, ids, vals);
+  if (map)
+    hipLaunchKernelGGL(trace_topk_kernel<true>, dim3((unsigned)rows), dim3(kTrThreads), 0, st, logits, V, n_map, K, map,
+                       ids, vals);
+  else
+    hipLaunchKernelGGL(trace_topk_kernel<false>, dim3((unsigned)rows), dim3(kTrThreads), 0, st, logits, V, V, K,
+                       (const int32_t*)nullptr, ids, vals);
   return hipGetLastError();
 }
 

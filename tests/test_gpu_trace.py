@@ -11,9 +11,11 @@ import oracle
 pytestmark = pytest.mark.gpu
 
 
-def _emit_topk(av, logits, k):
+def _emit_topk(av, logits, k, d2t=None):
     rows, V = logits.shape
-    d = av.aurora_trace_desc(batch=rows, num_q=1, vocab=V, top_k=k)
+    dmap = None if d2t is None else torch.from_numpy(d2t).cuda()
+    d = av.aurora_trace_desc(batch=rows, num_q=1, vocab=V, top_k=k, draft_vocab=0 if d2t is None else len(d2t),
+                             draft_to_target=None if d2t is None else dmap.data_ptr())
     dl = torch.from_numpy(logits).cuda()
     ids = torch.full((rows, k), -9, dtype=torch.int32, device="cuda")
     vals = torch.full((rows, k), 0x1234, dtype=torch.int16, device="cuda")
@@ -22,10 +24,11 @@ def _emit_topk(av, logits, k):
     return ids.cpu().numpy(), vals.cpu().numpy().view(np.uint16)
 
 
-def _check_topk(av, logits, k):
-    print(f"[case] top-k rows={logits.shape[0]} V={logits.shape[1]} K={k}", flush=True)
-    ids, vals = _emit_topk(av, logits, k)
-    rid, rvals = oracle.trace_topk(logits, k)
+def _check_topk(av, logits, k, d2t=None):
+    print(f"[case] top-k rows={logits.shape[0]} V={logits.shape[1]} K={k} "
+          f"draft_vocab={None if d2t is None else len(d2t)}", flush=True)
+    ids, vals = _emit_topk(av, logits, k, d2t)
+    rid, rvals = oracle.trace_topk(logits, k, d2t)
     assert np.array_equal(ids, rid), f"first mismatch at {np.argwhere(ids != rid)[:3].tolist()}"
     assert np.array_equal(vals, rvals)
 
@@ -49,6 +52,18 @@ def test_topk_sizes(gpu_lib, vocab, k):
 def test_topk_full_size_llama_vocab(gpu_lib):
     """The benchmark's shape: 160 token rows of the 128256-entry vocabulary, K = 1024."""
     _check_topk(gpu_lib, gen.trace_logits(1, 160, 128256, "normal"), 1024)
+
+
+@pytest.mark.parametrize("vocab,draft_vocab,k", [(128256, 32000, 1024), (50001, 4097, 1000), (20000, 3000, 1024),
+                                                 (9999, 500, 1024), (151936, 32003, 1024)])
+def test_topk_over_the_draft_vocabulary(gpu_lib, vocab, draft_vocab, k):
+    """Selection restricted to the draft model's vocabulary (a sorted random subset of target ids, or an
+    unsorted one): ids are positions in the subset."""
+    rng = np.random.default_rng([vocab, draft_vocab])
+    d2t = np.sort(rng.choice(vocab, size=draft_vocab, replace=False)).astype(np.int32)
+    for kind in ("normal", "ties", "masked"):
+        _check_topk(gpu_lib, gen.trace_logits(25, 4, vocab, kind), k, d2t)
+    _check_topk(gpu_lib, gen.trace_logits(26, 3, vocab, "normal"), k, rng.permutation(d2t).astype(np.int32))
 
 
 def test_topk_qwen_vocab_with_ties(gpu_lib):

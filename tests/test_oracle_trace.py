@@ -43,6 +43,16 @@ def test_topk_matches_brute_force_with_ties(seed):
         assert ids[m].tolist() == want
 
 
+def test_topk_over_a_sub_vocabulary_matches_brute_force_on_the_gathered_row():
+    rng = np.random.default_rng(3)
+    x = rng.integers(-5, 6, size=(4, 50)).astype(np.float32)   # many ties
+    d2t = rng.permutation(50)[:17].astype(np.int32)
+    ids, vals = oracle.trace_topk(x, 9, d2t)
+    for m in range(4):
+        assert ids[m].tolist() == _brute_topk([float(t) for t in x[m, d2t]], 9)
+        assert np.array_equal(gen.bf16_bits_to_f32(vals[m]), x[m, d2t[ids[m]]])
+
+
 def test_topk_of_a_permutation_is_the_permutation_prefix():
     rng = np.random.default_rng(11)
     V, k = 5000, 1024
