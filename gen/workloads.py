@@ -59,6 +59,26 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def quantize_e4m3_rows(x: np.ndarray):
+    """Per-row 8-bit storage of a float32 matrix: codes (uint8, OCP E4M3) and one float32 scale per
+    row with scale = max|row| / 448, so that scale * decode(code) approximates x.  The rounding is the
+    library's float32 -> float8_e4m3fn conversion.  Storage format only: both sides of a parity test
+    consume the codes and scales this returns."""
+    import torch
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    amax = np.abs(x).max(axis=-1, keepdims=True)
+    scale = np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    q = torch.from_numpy(x / scale).to(torch.float8_e4m3fn)
+    return q.view(torch.uint8).numpy(), scale.reshape(x.shape[:-1])
+
+
+def e4m3_rows_to_f32(codes: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """The values a per-row quantised matrix stands for, as float32 (library decode times the scale)."""
+    import torch
+    v = torch.from_numpy(np.ascontiguousarray(codes)).view(torch.float8_e4m3fn).float().numpy()
+    return v * np.asarray(scale, dtype=np.float32)[..., None]
+
+
 def as_f32(x: np.ndarray, dtype: str) -> np.ndarray:
     """The values a stored tensor holds, as float32 (exact for both dtypes)."""
     return bf16_bits_to_f32(x) if dtype == BF16 else np.asarray(x, dtype=np.float32)
@@ -158,6 +178,11 @@ class Workload:
     # draft_to_target[j] is the target id of draft entry j (ascending); 0 / None otherwise
     draft_vocab: int = 0
     draft_to_target: Optional[np.ndarray] = None
+    # LM-head operands in 8-bit floating point: head_dtype == "fp8" => hidden / lm_head hold uint8 E4M3
+    # codes and hidden_scale [B, Nq] / lm_head_scale [V] the per-row float32 scales ("" = as `dtype`)
+    head_dtype: str = ""
+    hidden_scale: Optional[np.ndarray] = None
+    lm_head_scale: Optional[np.ndarray] = None
 
     def target_to_draft(self) -> Optional[np.ndarray]:
         """Inverse of draft_to_target over the target vocabulary, -1 where the draft model has no entry."""
@@ -190,7 +215,7 @@ class Workload:
             self, batch=len(idx), q=sl(self.q), block_table=sl(self.block_table),
             seq_lens=sl(self.seq_lens), parents=sl(self.parents), hidden=sl(self.hidden),
             draft_tokens=sl(self.draft_tokens), draft_probs=sl(self.draft_probs),
-            uniforms=sl(self.uniforms))
+            uniforms=sl(self.uniforms), hidden_scale=sl(self.hidden_scale))
 
 
 # --------------------------------------------------------------------------
@@ -280,7 +305,7 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
                   tree: bool = False, greedy_hit: float = 0.7,
                   shuffle_pages: bool = True, pool_pages: Optional[int] = None,
                   distinct_siblings: bool = False, draft_vocab: Optional[int] = None,
-                  recipe: str = "") -> Workload:
+                  head_fp8: bool = False, recipe: str = "") -> Workload:
     """Build one workload.
 
     draft = "independent": draft logits ~ N(0,1), draft tokens uniform over the vocab.
@@ -290,6 +315,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
             probability `greedy_hit`, else uniform; draft_probs/uniforms are None.
     draft_vocab (with "noisy_target"): the draft model's vocabulary is a random subset of that many
             target ids; draft_probs is over the subset, tokens are drawn from it and stored as target ids.
+    head_fp8: hidden and lm_head are drawn as float32 with the same recipe, then stored as E4M3 codes
+            with one scale per row; the stand-in target logits use the values the codes stand for.
     """
     ss = np.random.SeedSequence([int(seed), 0x2602_06932 & 0xFFFFFFFF])
     s_q, s_kv, s_h, s_w, s_misc = ss.spawn(5)
@@ -302,8 +329,20 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
     k_pages, v_pages, block_table, P, max_pages, page_ids = make_kv(
         s_kv, rng, seq_lens, num_kv_heads, head_dim, page_size, dtype,
         shuffle=shuffle_pages, pool_pages=pool_pages)
-    hidden = _normal_tensor(s_h, (B, Nq, hidden_size), 1.0, dtype)
-    lm_head = _normal_tensor(s_w, (V, hidden_size), 0.02, dtype)
+    hidden_scale = lm_head_scale = None
+    head_values = None  # (hidden, lm_head) as float32 when they are not stored in `dtype`
+    if head_fp8:
+        hidden, hidden_scale = quantize_e4m3_rows(_normal_tensor(s_h, (B, Nq, hidden_size), 1.0, F32))
+        lm_head, lm_head_scale = quantize_e4m3_rows(_normal_tensor(s_w, (V, hidden_size), 0.02, F32))
+        head_values = (e4m3_rows_to_f32(hidden, hidden_scale), e4m3_rows_to_f32(lm_head, lm_head_scale))
+    else:
+        hidden = _normal_tensor(s_h, (B, Nq, hidden_size), 1.0, dtype)
+        lm_head = _normal_tensor(s_w, (V, hidden_size), 0.02, dtype)
+
+    def standin():
+        if head_values is not None:
+            return _standin_target_logits(head_values[0], head_values[1], F32)
+        return _standin_target_logits(hidden, lm_head, dtype)
 
     parents = random_tree_parents(rng, B, Nq) if tree else None
     par = parents if tree else chain_parents(B, Nq)
@@ -319,7 +358,7 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
         draft_probs = _softmax_rows_f32(z).reshape(B, Nq, V)
         uniforms = _uniform24(rng, (B, Nq, 2))
     elif draft == "noisy_target":
-        t = _standin_target_logits(hidden, lm_head, dtype)
+        t = standin()
         T = np.float32(temperature if temperature > 0 else 1.0)
         if draft_vocab:
             d2t = np.sort(rng.choice(V, size=int(draft_vocab), replace=False)).astype(np.int32)
@@ -333,7 +372,7 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
             draft_tokens[:, n] = d2t[idx] if draft_vocab else idx
         uniforms = _uniform24(rng, (B, Nq, 2))
     elif draft == "greedy_mix":
-        t = _standin_target_logits(hidden, lm_head, dtype).reshape(B, Nq, V)
+        t = standin().reshape(B, Nq, V)
         top = t.argmax(axis=-1).astype(np.int32)
         del t
         for n in range(1, Nq):
@@ -356,7 +395,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
                  block_table=block_table, seq_lens=seq_lens, parents=parents, hidden=hidden,
                  lm_head=lm_head, draft_tokens=draft_tokens, draft_probs=draft_probs,
                  uniforms=uniforms, recipe=recipe, page_ids=page_ids,
-                 draft_vocab=int(draft_vocab or 0), draft_to_target=d2t)
+                 draft_vocab=int(draft_vocab or 0), draft_to_target=d2t,
+                 head_dtype="fp8" if head_fp8 else "", hidden_scale=hidden_scale, lm_head_scale=lm_head_scale)
     return w
 
 

@@ -24,7 +24,8 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(_build.build(force=False))
         for name in ("oracle_attn", "oracle_logits", "oracle_accept_logits", "oracle_accept",
-                     "oracle_num_threads", "oracle_trace_topk", "oracle_trace_records"):
+                     "oracle_num_threads", "oracle_trace_topk", "oracle_trace_records", "oracle_logits_fp8",
+                     "oracle_decode_e4m3"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -88,6 +89,32 @@ def logits(*, hidden, lm_head, dtype) -> np.ndarray:
                              _p(hidden), _p(lm_head), _p(out))
     if st != 0:
         raise ValueError(f"oracle_logits status {st}")
+    return out.reshape(hidden.shape[:-1] + (V,))
+
+
+def decode_e4m3(codes: np.ndarray) -> np.ndarray:
+    """OCP E4M3 codes (uint8) -> float64."""
+    codes = _chk(codes, np.uint8)
+    out = np.empty(codes.shape, np.float64)
+    lib().oracle_decode_e4m3(C.c_int64(codes.size), _p(codes), _p(out))
+    return out
+
+
+def logits_fp8(*, hidden, hidden_scale, lm_head, lm_head_scale) -> np.ndarray:
+    """LM head on E4M3 operands: hidden [..., H] uint8 codes with one float32 scale per row, lm_head [V, H]
+    codes with one scale per vocabulary row -> float64 [..., V]."""
+    hidden = _chk(hidden, np.uint8)
+    lm_head = _chk(lm_head, np.uint8)
+    H = hidden.shape[-1]
+    V = lm_head.shape[0]
+    rows = int(np.prod(hidden.shape[:-1]))
+    hs = _chk(np.asarray(hidden_scale, np.float32).reshape(rows), np.float32, (rows,))
+    ws = _chk(lm_head_scale, np.float32, (V,))
+    out = np.empty((rows, V), dtype=np.float64)
+    st = lib().oracle_logits_fp8(C.c_int64(rows), C.c_int(H), C.c_int(V), _p(hidden), _p(hs), _p(lm_head), _p(ws),
+                                 _p(out))
+    if st != 0:
+        raise ValueError(f"oracle_logits_fp8 status {st}")
     return out.reshape(hidden.shape[:-1] + (V,))
 
 
@@ -179,11 +206,25 @@ def verify(w, want_cdf=False, want_logits=False):
     """Both halves on a gen.Workload; returns (attention float64, AcceptResult)."""
     o = attn(q=w.q, k_pages=w.k_pages, v_pages=w.v_pages, block_table=w.host_block_table(),
              seq_lens=w.seq_lens, parents=w.parents, dtype=w.dtype)
-    a = accept(hidden=w.hidden, lm_head=w.lm_head, draft_tokens=w.draft_tokens,
-               draft_probs=w.draft_probs, uniforms=w.uniforms, parents=w.parents, dtype=w.dtype,
-               temperature=w.temperature, want_cdf=want_cdf, want_logits=want_logits,
-               draft_to_target=getattr(w, "draft_to_target", None))
+    a = accept_workload(w, want_cdf=want_cdf, want_logits=want_logits)
     return o, a
+
+
+def accept_workload(w, want_cdf=False, want_logits=False) -> AcceptResult:
+    """The acceptance half on a gen.Workload (bf16 / f32 operands, or E4M3 operands with scales)."""
+    if getattr(w, "head_dtype", "") == "fp8":
+        lg = logits_fp8(hidden=w.hidden, hidden_scale=w.hidden_scale, lm_head=w.lm_head,
+                        lm_head_scale=w.lm_head_scale)
+        a = accept_from_logits(logits=lg, draft_tokens=w.draft_tokens, draft_probs=w.draft_probs,
+                               uniforms=w.uniforms, parents=w.parents, temperature=w.temperature, want_cdf=want_cdf,
+                               draft_to_target=getattr(w, "draft_to_target", None))
+        if want_logits:
+            a.logits = lg
+        return a
+    return accept(hidden=w.hidden, lm_head=w.lm_head, draft_tokens=w.draft_tokens,
+                  draft_probs=w.draft_probs, uniforms=w.uniforms, parents=w.parents, dtype=w.dtype,
+                  temperature=w.temperature, want_cdf=want_cdf, want_logits=want_logits,
+                  draft_to_target=getattr(w, "draft_to_target", None))
 
 
 def trace_topk(logits: np.ndarray, top_k: int, draft_to_target=None):

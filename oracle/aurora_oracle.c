@@ -17,6 +17,7 @@
  *                        tree (ancestor) masked: the plain definition
  *                        softmax(scale * Q K^T + mask) V.
  *   oracle_logits        l[m, v] = sum_h hidden[m, h] * W[v, h].
+ *   oracle_logits_fp8    the same with E4M3 operands and per-row scales.
  *   oracle_accept_logits target distribution per row, acceptance walk over the
  *                        chain or tree, residual / bonus sampling.
  *   oracle_accept        oracle_logits followed by oracle_accept_logits.
@@ -192,6 +193,66 @@ int oracle_logits(int64_t rows, int hidden_size, int vocab, int dtype,
         for (int64_t v = 0; v < vocab; ++v) {
             if (!wrow) continue;
             for (int h = 0; h < hidden_size; ++h) wrow[h] = widen(lm_head, v * hidden_size + h, dtype);
+            for (int64_t m = 0; m < rows; ++m) {
+                const double *x = hid + m * hidden_size;
+                double acc = 0.0;
+                for (int h = 0; h < hidden_size; ++h) acc += x[h] * wrow[h];
+                out[m * vocab + v] = acc;
+            }
+        }
+        free(wrow);
+    }
+    free(hid);
+    return status;
+}
+
+/* ------------------------------------------------------------------------
+ * LM head with 8-bit floating-point operands (the paper serves its frontier
+ * targets in FP8, sections 1 and 4.3; it does not give a quantisation recipe).
+ * Reading taken: OCP E4M3 codes (1 sign, 4 exponent bits with bias 7, 3
+ * mantissa bits; no infinities, S.1111.111 is NaN) with one float32 scale per
+ * token row of `hidden` and one per vocabulary row of `lm_head`; a stored
+ * element stands for scale * decode(code), and the logit is the plain dot
+ * product of the dequantised rows.
+ * ---------------------------------------------------------------------- */
+static double decode_e4m3(uint8_t c)
+{
+    const int sign = c >> 7, e = (c >> 3) & 15, m = c & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m / 8.0, -6);
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+int oracle_decode_e4m3(int64_t n, const uint8_t *codes, double *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = decode_e4m3(codes[i]);
+    return ORACLE_OK;
+}
+
+int oracle_logits_fp8(int64_t rows, int hidden_size, int vocab, const uint8_t *hidden, const float *hidden_scale,
+                      const uint8_t *lm_head, const float *lm_scale, double *out)
+{
+    if (rows < 0 || hidden_size < 1 || vocab < 1 || !hidden_scale || !lm_scale) return ORACLE_BAD_ARG;
+    double *hid = (double *)malloc(sizeof(double) * (size_t)(rows > 0 ? rows : 1) * hidden_size);
+    if (!hid) return ORACLE_NOMEM;
+    for (int64_t m = 0; m < rows; ++m)
+        for (int h = 0; h < hidden_size; ++h)
+            hid[m * hidden_size + h] = (double)hidden_scale[m] * decode_e4m3(hidden[m * hidden_size + h]);
+    int status = ORACLE_OK;
+#pragma omp parallel
+    {
+        double *wrow = (double *)malloc(sizeof(double) * (size_t)hidden_size);
+        if (!wrow) {
+#pragma omp atomic write
+            status = ORACLE_NOMEM;
+        }
+#pragma omp for schedule(static)
+        for (int64_t v = 0; v < vocab; ++v) {
+            if (!wrow) continue;
+            for (int h = 0; h < hidden_size; ++h)
+                wrow[h] = (double)lm_scale[v] * decode_e4m3(lm_head[v * hidden_size + h]);
             for (int64_t m = 0; m < rows; ++m) {
                 const double *x = hid + m * hidden_size;
                 double acc = 0.0;
