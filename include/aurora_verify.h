@@ -44,7 +44,7 @@ enum {
   AURORA_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed               */
 };
 
-enum { AURORA_F32 = 0, AURORA_BF16 = 1 };
+enum { AURORA_F32 = 0, AURORA_BF16 = 1, AURORA_FP8_E4M3 = 2 /* LM-head operands only, see aurora_accept_desc */ };
 
 /* Attention half.  Nq query positions per request (k+1 for a chain of k drafts, or the
  * number of nodes of a draft tree, root included) attend to a paged GQA KV cache. */
@@ -67,7 +67,7 @@ typedef struct {
   int32_t num_q;     /* Nq, 1..64                                                            */
   int32_t hidden;    /* H (bf16: multiple of 8)                                              */
   int32_t vocab;     /* V (tree sampling, i.e. parents != NULL with T > 0: V <= 2^20)           */
-  int32_t dtype;     /* type of hidden and lm_head                                           */
+  int32_t dtype;     /* type of hidden and lm_head: AURORA_F32, AURORA_BF16 or AURORA_FP8_E4M3      */
   float temperature; /* 0 => greedy (arg-max prefix); > 0 => speculative rejection sampling  */
   /* Draft model with a smaller vocabulary than the target (section 4.1: a 32K-entry draft head;
    * appendix A.2: 32K vs 128K / 152K).  draft_vocab = 0: draft_probs rows are dense over V.
@@ -77,6 +77,14 @@ typedef struct {
    * max(0, p - q) keeps all of p's mass.  draft_tokens stay target ids.  Ignored when T == 0. */
   int32_t draft_vocab;
   const int32_t* target_to_draft;
+  /* dtype == AURORA_FP8_E4M3 (the paper serves its frontier targets in FP8, sections 1 and 4.3; format
+   * and scaling are this library's choice): hidden and lm_head hold OCP E4M3 codes, one byte per element
+   * (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; no infinities), and a stored element stands
+   * for scale * decode(code) with one float32 scale per token row, hidden_scale [B*Nq], and one per
+   * vocabulary row, lm_head_scale [V] (DEVICE pointers).  H must be a multiple of 128.  Logits and
+   * everything after them are fp32 / fp64 as for the other types. */
+  const float* hidden_scale;
+  const float* lm_head_scale;
 } aurora_accept_desc;
 
 /* Bytes of workspace needed by aurora_verify / _attn / _accept for these descriptors.

@@ -5,7 +5,7 @@ behind a C ABI.
 `binding` mirrors the C entry points; `device.DeviceVerify` is memory plumbing for tests and the
 benchmark.  The package never falls back to a CPU implementation.
 """
-from .binding import (AURORA_BF16, AURORA_ERR_HIP, AURORA_ERR_INVALID_ARG, AURORA_ERR_UNSUPPORTED,  # noqa: F401
+from .binding import (AURORA_BF16, AURORA_FP8_E4M3, AURORA_ERR_HIP, AURORA_ERR_INVALID_ARG, AURORA_ERR_UNSUPPORTED,  # noqa: F401
                       AURORA_ERR_WORKSPACE, AURORA_F32, AURORA_OK, EXPORTS, LIB_PATH, AuroraError,
                       aurora_accept_desc, aurora_attn_desc, aurora_trace_desc, aurora_trace_emit, aurora_verify,
                       aurora_verify_accept, aurora_verify_accept_logits,

@@ -25,11 +25,15 @@ int check_attn_desc(const aurora_attn_desc* d) {
 int check_accept_desc(const aurora_accept_desc* d) {
   if (!d) return AURORA_ERR_INVALID_ARG;
   if (d->batch < 0 || d->num_q < 1 || d->hidden < 1 || d->vocab < 1) return AURORA_ERR_INVALID_ARG;
-  if (d->dtype != AURORA_F32 && d->dtype != AURORA_BF16) return AURORA_ERR_INVALID_ARG;
+  if (d->dtype != AURORA_F32 && d->dtype != AURORA_BF16 && d->dtype != AURORA_FP8_E4M3) return AURORA_ERR_INVALID_ARG;
   if (!(d->temperature >= 0.f)) return AURORA_ERR_INVALID_ARG;
   if (d->num_q > kMaxNq) return AURORA_ERR_UNSUPPORTED;
   if ((int64_t)d->batch * d->num_q > 65535) return AURORA_ERR_UNSUPPORTED;
   if (d->dtype == AURORA_BF16 && d->hidden % 8) return AURORA_ERR_UNSUPPORTED;
+  if (d->dtype == AURORA_FP8_E4M3) {
+    if (!d->hidden_scale || !d->lm_head_scale) return AURORA_ERR_INVALID_ARG;
+    if (d->hidden % 128) return AURORA_ERR_UNSUPPORTED;  // only the matrix-core kernel takes 8-bit operands
+  }
   if (d->draft_vocab < 0 || d->draft_vocab > d->vocab) return AURORA_ERR_INVALID_ARG;
   if (d->draft_vocab > 0 && d->temperature > 0.f && !d->target_to_draft) return AURORA_ERR_INVALID_ARG;
   return AURORA_OK;
@@ -78,6 +82,8 @@ AttnPlan plan_attn(const aurora_attn_desc* d) {
 AcceptLaunch accept_launch_from(const aurora_accept_desc* d) {
   AcceptLaunch a = {};
   a.B = d->batch; a.Nq = d->num_q; a.H = d->hidden; a.V = d->vocab; a.bf16 = d->dtype == AURORA_BF16;
+  a.fp8 = d->dtype == AURORA_FP8_E4M3;
+  a.hidden_scale = d->hidden_scale; a.lm_scale = d->lm_head_scale;
   a.temperature = d->temperature;
   if (d->draft_vocab > 0 && d->temperature > 0.f) { a.Vd = d->draft_vocab; a.target_to_draft = d->target_to_draft; }
   return a;

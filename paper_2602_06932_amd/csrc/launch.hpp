@@ -21,6 +21,8 @@ struct AcceptLaunch {
   int Vd;                          // draft vocabulary (entries per row of draft_probs) when target_to_draft is set
   const int32_t* target_to_draft;  // or NULL: draft_probs rows are dense over V
   bool bf16;
+  bool fp8;                              // hidden / lm_head are E4M3 codes with per-row scales
+  const float *hidden_scale, *lm_scale;  // [B*Nq], [V] when fp8
   float temperature;
   const void *hidden, *lm_head;
   const int32_t *draft_tokens, *parents;

@@ -21,8 +21,7 @@
 namespace aurora {
 
 constexpr int kLmThreads = 512;                // 4 consumer + 4 producer wavefronts
-constexpr int kLmBK = 64;                      // hidden elements per stage
-constexpr int kLmRowBytes = kLmBK * 2;         // 128
+constexpr int kLmRowBytes = 128;               // bytes of a row segment per stage: 64 bf16 or 128 fp8 elements
 constexpr int kLmVTile = 256;                  // vocab rows per workgroup
 constexpr int kLmWaveV = 64;                   // vocab rows per wavefront (= statistics tile)
 constexpr int kLmStages = 3;
@@ -33,12 +32,19 @@ constexpr int kCpolNT = 2;
 
 #define WAIT_VMCNT(n) LM_WAIT_VMCNT(n)
 
-template <int NT>
+// kFp8: operands are OCP E4M3 codes (1 byte) with one float32 scale per token row and per vocabulary
+// row; the products run on v_mfma_f32_32x32x16_fp8_fp8, whose operand layout is the bf16 one with
+// bytes for halfwords, and the scales are applied to the fp32 accumulators in the epilogue.  A stage
+// then holds 128 hidden elements per row instead of 64 - the same 128 bytes.
+template <int NT, bool kFp8>
 __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
-    const bf16_t* __restrict__ hidden, const bf16_t* __restrict__ w, float* __restrict__ logits,
-    float* __restrict__ pmax, float* __restrict__ psum, int32_t* __restrict__ parg, int M, int H, int V, int n_tiles,
-    int m_tiles, float exp_scale /* log2(e) / T */) {
+    const char* __restrict__ hidden, const char* __restrict__ w, const float* __restrict__ h_scale,
+    const float* __restrict__ w_scale, float* __restrict__ logits, float* __restrict__ pmax,
+    float* __restrict__ psum, int32_t* __restrict__ parg, int M, int H, int V, int n_tiles, int m_tiles,
+    float exp_scale /* log2(e) / T */) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  constexpr int kEsz = kFp8 ? 1 : 2;             // bytes per operand element
+  constexpr int kLmBK = kLmRowBytes / kEsz;      // hidden elements per stage
   constexpr int kStageBytes = kLmWBytes + NT * 32 * kLmRowBytes;
   constexpr int kLoadsPerStage = 8 + NT;  // global->LDS instructions per producer wavefront per stage
 
@@ -69,26 +75,26 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     // put one chunk index into sixteen different 16-byte bank groups of the 64-bank LDS
     const int chunk_even = (lane & 7) ^ (sub >> 1);        // instructions whose first row is 0 mod 16
     const int chunk_odd = (lane & 7) ^ (4 + (sub >> 1));   // ... 8 mod 16
-    const bf16_t* wsrc[8];
+    const char* wsrc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       int row = vbase + wv * kLmWaveV + 8 * j + sub;
       row = row < V ? row : V - 1;
-      wsrc[j] = w + (size_t)row * H + ((j & 1) ? chunk_odd : chunk_even) * 8;
+      wsrc[j] = w + (size_t)row * H * kEsz + ((j & 1) ? chunk_odd : chunk_even) * 16;
     }
-    const bf16_t* hsrc[NT];
+    const char* hsrc[NT];
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
       const int q8 = wv * NT + j;  // 8-row group of the hidden tile
       int row = m0 + 8 * q8 + sub;
       row = row < M ? row : M - 1;
-      hsrc[j] = hidden + (size_t)row * H + ((q8 & 1) ? chunk_odd : chunk_even) * 8;
+      hsrc[j] = hidden + (size_t)row * H * kEsz + ((q8 & 1) ? chunk_odd : chunk_even) * 16;
     }
     auto issue = [&](int ks, int buf) {
       char* base = lds + buf * kStageBytes;
       int kk = ks + ks0;
       kk = kk >= nk ? kk - nk : kk;
-      const int koff = kk * kLmBK;
+      const int koff = kk * kLmRowBytes;  // bytes
 #pragma unroll
       for (int j = 0; j < 8; ++j)
         __builtin_amdgcn_global_load_lds(GLB_PTR(wsrc[j] + koff),
@@ -129,19 +135,45 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     const char* base = lds + (ks % kLmStages) * kStageBytes;
+    if constexpr (!kFp8) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int coff = ((2 * s + lh) ^ sw) * 16;
-      bf16x8_t wa[2], hb[NT];
+      for (int s = 0; s < 4; ++s) {
+        const int coff = ((2 * s + lh) ^ sw) * 16;
+        bf16x8_t wa[2], hb[NT];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) wa[a] = *(const bf16x8_t*)(base + wrow_off + a * 32 * kLmRowBytes + coff);
+        for (int a = 0; a < 2; ++a) wa[a] = *(const bf16x8_t*)(base + wrow_off + a * 32 * kLmRowBytes + coff);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) hb[t] = *(const bf16x8_t*)(base + hrow_off + t * 32 * kLmRowBytes + coff);
+        for (int t = 0; t < NT; ++t) hb[t] = *(const bf16x8_t*)(base + hrow_off + t * 32 * kLmRowBytes + coff);
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+        for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
-          acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[t], acc[a][t], 0, 0, 0);
+          for (int t = 0; t < NT; ++t)
+            acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[t], acc[a][t], 0, 0, 0);
+      }
+    } else {
+      // step s covers hidden elements 16 s .. 16 s + 15 of the stage: 16-byte chunk s, lane half lh takes
+      // 8 bytes.  An fp8 MFMA lasts half as long as a bf16 one, so the LDS latency of a step's operands
+      // is hidden explicitly: the reads of step s+1 are issued before the MFMAs of step s.
+      long wa[2][2], hb[2][NT];
+      auto load_step = [&](int s, long (&wf)[2], long (&hf)[NT]) {
+        const int coff = ((s ^ sw) * 16) + 8 * lh;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) wf[a] = *(const long*)(base + wrow_off + a * 32 * kLmRowBytes + coff);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) hf[t] = *(const long*)(base + hrow_off + t * 32 * kLmRowBytes + coff);
+      };
+      load_step(0, wa[0], hb[0]);
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        if (s + 1 < 8) load_step(s + 1, wa[(s + 1) & 1], hb[(s + 1) & 1]);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(wa[s & 1][a], hb[s & 1][t], acc[a][t], 0, 0, 0);
+        if (s + 1 < 8) __builtin_amdgcn_sched_group_barrier(0x100, 2 + NT, 0);  // next step's LDS reads first
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NT, 0);                 // then this step's MFMAs
+      }
     }
     asm volatile("" ::: "memory");
   }
@@ -156,6 +188,29 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
   const int vrow0 = vbase + wv * kLmWaveV;
   const bool vec_ok = (V & 3) == 0;
   char* tb = lds + wv * (kLmWaveV * kLmRowBytes);
+  if constexpr (kFp8) {
+    // dequantise: accumulator (vocab row v, token m) times w_scale[v] * h_scale[m]
+    float hs[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int m = m0 + 32 * t + li;
+      hs[t] = h_scale[m < M ? m : M - 1];
+    }
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        // four consecutive vocabulary rows: 8(r/4) + 4 lh + r%4 for r = 4g .. 4g+3
+        const int v = vrow0 + 32 * a + 8 * g + 4 * lh;
+        float wsc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) wsc[e] = w_scale[v + e < V ? v + e : V - 1];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[a][t][4 * g + e] *= wsc[e] * hs[t];
+      }
+  }
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
     float mx, sum;
@@ -183,17 +238,18 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
 }
 
 bool lmhead_mfma_supported(const AcceptLaunch& a) {
-  return a.bf16 && a.H % kLmBK == 0 && a.H >= kLmBK && a.V >= 1;
+  const int bk = a.fp8 ? kLmRowBytes : kLmRowBytes / 2;  // hidden elements per stage
+  return (a.bf16 || a.fp8) && a.H % bk == 0 && a.H >= bk && a.V >= 1;
 }
 
 int lmhead_mfma_stat_tile() { return kLmVTile; }
 
-template <int NT>
-static hipError_t launch_nt(const AcceptLaunch& a, hipStream_t st, int m_tiles) {
+template <int NT, bool kFp8>
+static hipError_t launch_nt_t(const AcceptLaunch& a, hipStream_t st, int m_tiles) {
   constexpr int lds_bytes = kLmStages * (kLmWBytes + NT * 32 * kLmRowBytes);
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)lmhead_mfma_kernel<NT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)lmhead_mfma_kernel<NT, kFp8>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        lds_bytes);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -201,10 +257,15 @@ static hipError_t launch_nt(const AcceptLaunch& a, hipStream_t st, int m_tiles) 
   const float exp_scale = 1.4426950408889634f / (a.temperature > 0.f ? a.temperature : 1.f);
   const int v_tiles = (a.V + kLmVTile - 1) / kLmVTile;
   dim3 grid((v_tiles + 7) / 8 * 8 * m_tiles);
-  hipLaunchKernelGGL(lmhead_mfma_kernel<NT>, grid, dim3(kLmThreads), lds_bytes, st, (const bf16_t*)a.hidden,
-                     (const bf16_t*)a.lm_head, a.logits, a.pmax, a.psum, a.parg, (int)a.plan.rows, a.H, a.V,
-                     a.plan.n_tiles, m_tiles, exp_scale);
+  hipLaunchKernelGGL((lmhead_mfma_kernel<NT, kFp8>), grid, dim3(kLmThreads), lds_bytes, st, (const char*)a.hidden,
+                     (const char*)a.lm_head, a.hidden_scale, a.lm_scale, a.logits, a.pmax, a.psum, a.parg,
+                     (int)a.plan.rows, a.H, a.V, a.plan.n_tiles, m_tiles, exp_scale);
   return hipGetLastError();
+}
+
+template <int NT>
+static hipError_t launch_nt(const AcceptLaunch& a, hipStream_t st, int m_tiles) {
+  return a.fp8 ? launch_nt_t<NT, true>(a, st, m_tiles) : launch_nt_t<NT, false>(a, st, m_tiles);
 }
 
 hipError_t launch_lmhead_mfma(const AcceptLaunch& a, hipStream_t st) {

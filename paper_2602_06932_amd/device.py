@@ -47,8 +47,11 @@ class DeviceVerify:
         self.block_table = _to_dev(w.block_table, None)
         self.seq_lens = _to_dev(w.seq_lens, None)
         self.parents = _to_dev(w.parents, None)
-        self.hidden = _to_dev(w.hidden, w.dtype)
+        self.hidden = _to_dev(w.hidden, w.dtype)    # uint8 codes stay uint8 (8-bit floating-point head)
         self.lm_head = _to_dev(w.lm_head, w.dtype)
+        head_fp8 = getattr(w, "head_dtype", "") == "fp8"
+        self.hidden_scale = _to_dev(w.hidden_scale, None) if head_fp8 else None
+        self.lm_head_scale = _to_dev(w.lm_head_scale, None) if head_fp8 else None
         self.draft_tokens = _to_dev(w.draft_tokens, None)
         self.draft_probs = _to_dev(w.draft_probs, None)
         self.uniforms = _to_dev(w.uniforms, None)
@@ -61,9 +64,12 @@ class DeviceVerify:
         t2d = w.target_to_draft() if getattr(w, "draft_to_target", None) is not None else None
         self.target_to_draft = _to_dev(t2d, None)
         self.accept_desc = B.aurora_accept_desc(
-            batch=w.batch, num_q=w.num_q, hidden=w.hidden_size, vocab=w.vocab, dtype=self.dt,
+            batch=w.batch, num_q=w.num_q, hidden=w.hidden_size, vocab=w.vocab,
+            dtype=B.AURORA_FP8_E4M3 if head_fp8 else self.dt,
             temperature=w.temperature, draft_vocab=int(getattr(w, "draft_vocab", 0) or 0),
-            target_to_draft=None if t2d is None else self.target_to_draft.data_ptr())
+            target_to_draft=None if t2d is None else self.target_to_draft.data_ptr(),
+            hidden_scale=self.hidden_scale.data_ptr() if head_fp8 else None,
+            lm_head_scale=self.lm_head_scale.data_ptr() if head_fp8 else None)
         self.ws_bytes = B.aurora_verify_workspace_bytes(self.attn_desc, self.accept_desc)
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
         assert self.workspace.data_ptr() % 256 == 0

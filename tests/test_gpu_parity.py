@@ -335,3 +335,38 @@ def test_full_size_llama_chain_with_32k_draft_vocabulary(gpu_lib):
     """Config 2's shapes with the 32K-entry draft vocabulary of the paper's drafter."""
     w = gen.llama_chain(1, draft_vocab=32000, draft_noise=0.5)
     _full_check(gpu_lib, w, sample=[0, 7, 19, 31])
+
+
+@pytest.mark.parametrize("batch,vocab,hidden", [(6, 3001, 256), (50, 2304, 128)])
+def test_fp8_lm_head_chain(gpu_lib, batch, vocab, hidden):
+    """LM-head operands as E4M3 codes with per-row scales (fp8 matrix-core products, scales applied to
+    the fp32 accumulators); 250 token rows exercise the multi-pass launch."""
+    w = gen.llama_chain(30, batch=batch, len_lo=20, len_hi=60, vocab=vocab, hidden_size=hidden, head_fp8=True,
+                        draft_noise=0.5)
+    _, a = _full_check(gpu_lib, w)
+    assert a.accept_len.max() > 0
+
+
+def test_fp8_lm_head_tree_and_draft_subvocabulary(gpu_lib):
+    w = gen.llama_tree(31, batch=5, num_q=16, vocab=4000, hidden_size=256, context=64, num_q_heads=4, num_kv_heads=2,
+                       head_fp8=True, draft_vocab=1000, draft_noise=0.5)
+    _full_check(gpu_lib, w)
+
+
+def test_fp8_lm_head_rejects_unsupported_hidden_size(gpu_lib):
+    av = gpu_lib
+    d = av.aurora_accept_desc(batch=1, num_q=2, hidden=192, vocab=100, dtype=av.AURORA_FP8_E4M3, temperature=1.0,
+                              hidden_scale=256, lm_head_scale=256)
+    with pytest.raises(av.AuroraError) as e:
+        av.aurora_verify_workspace_bytes(None, d)
+    assert e.value.status == av.AURORA_ERR_UNSUPPORTED
+    d = av.aurora_accept_desc(batch=1, num_q=2, hidden=256, vocab=100, dtype=av.AURORA_FP8_E4M3, temperature=1.0)
+    with pytest.raises(av.AuroraError) as e:
+        av.aurora_verify_workspace_bytes(None, d)
+    assert e.value.status == av.AURORA_ERR_INVALID_ARG
+
+
+def test_full_size_llama_chain_with_fp8_lm_head(gpu_lib):
+    """Config 2's shapes with the LM head in FP8."""
+    w = gen.llama_chain(1, head_fp8=True)
+    _full_check(gpu_lib, w, sample=[0, 11, 22, 31])
