@@ -722,16 +722,11 @@ hipError_t launch_attn_mfma(const AttnLaunch& a, hipStream_t st) {
                          a.Nq, a.Hq, a.Hkv, shift, a.max_pages, sc);
   } else {
     wgs = kWideWorkgroups;
-    static bool attr_set = false;
-    if (!attr_set) {
-      e = hipFuncSetAttribute((const void*)attn_mfma_wide_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              kWideLdsBytes);
-      if (e != hipSuccess) return e;
-      e = hipFuncSetAttribute((const void*)attn_mfma_wide_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              kWideLdsBytes);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
+    static LdsAttrOnce attr_local, attr_global;
+    e = attr_local.ensure((const void*)attn_mfma_wide_kernel<true>, kWideLdsBytes);
+    if (e != hipSuccess) return e;
+    e = attr_global.ensure((const void*)attn_mfma_wide_kernel<false>, kWideLdsBytes);
+    if (e != hipSuccess) return e;
     dim3 grid(wgs, (row_tiles + 3) / 4);
     if (local_plan)
       hipLaunchKernelGGL(attn_mfma_wide_kernel<true>, grid, dim3(kWideThreads), kWideLdsBytes, st, (const bf16_t*)a.q,

@@ -77,4 +77,21 @@ struct AcceptPlan {
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
+// Kernels that use more than 64 KB of dynamic LDS need hipFuncSetAttribute once per device (the
+// attribute belongs to the device's copy of the function).  One of these per kernel, function-local
+// static; the flags only ever go from false to true, so a race between host threads repeats the call.
+struct LdsAttrOnce {
+  bool done[64] = {};
+  hipError_t ensure(const void* fn, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool track = dev >= 0 && dev < 64;
+    if (track && done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && track) done[dev] = true;
+    return e;
+  }
+};
+
 }  // namespace aurora

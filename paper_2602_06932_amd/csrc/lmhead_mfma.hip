@@ -247,13 +247,8 @@ int lmhead_mfma_stat_tile() { return kLmVTile; }
 template <int NT, bool kFp8>
 static hipError_t launch_nt_t(const AcceptLaunch& a, hipStream_t st, int m_tiles) {
   constexpr int lds_bytes = kLmStages * (kLmWBytes + NT * 32 * kLmRowBytes);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)lmhead_mfma_kernel<NT, kFp8>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce attr;
+  if (hipError_t e = attr.ensure((const void*)lmhead_mfma_kernel<NT, kFp8>, lds_bytes); e != hipSuccess) return e;
   const float exp_scale = 1.4426950408889634f / (a.temperature > 0.f ? a.temperature : 1.f);
   const int v_tiles = (a.V + kLmVTile - 1) / kLmVTile;
   dim3 grid((v_tiles + 7) / 8 * 8 * m_tiles);

@@ -213,13 +213,8 @@ bool lmhead_mfma_big_supported(const AcceptLaunch& a) {
 }
 
 hipError_t launch_lmhead_mfma_big(const AcceptLaunch& a, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)lmhead_mfma_big_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kBgLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsAttrOnce attr;
+  if (hipError_t e = attr.ensure((const void*)lmhead_mfma_big_kernel, kBgLdsBytes); e != hipSuccess) return e;
   const int M = (int)a.plan.rows;
   const int m_tiles = (M + kBgMTile - 1) / kBgMTile;
   const float exp_scale = 1.4426950408889634f / (a.temperature > 0.f ? a.temperature : 1.f);
