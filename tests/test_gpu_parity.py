@@ -370,3 +370,38 @@ def test_full_size_llama_chain_with_fp8_lm_head(gpu_lib):
     """Config 2's shapes with the LM head in FP8."""
     w = gen.llama_chain(1, head_fp8=True)
     _full_check(gpu_lib, w, sample=[0, 11, 22, 31])
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_randomized_small_configurations(gpu_lib, seed):
+    """Seeded random shapes across the dispatch space: chains and trees, greedy and sampled, page sizes that
+    take the matrix-core or the generic attention kernel, hidden sizes on and off the matrix-core LM-head
+    path, ragged vocabularies, draft sub-vocabularies, FP8 heads, GQA group sizes, head dims 64 / 128."""
+    rng = np.random.default_rng(1000 + seed)
+    tree = bool(rng.integers(0, 2))
+    greedy = bool(rng.integers(0, 4) == 0)
+    head_dim = int(rng.choice([64, 128]))
+    hkv = int(rng.choice([1, 2, 4]))
+    group = int(rng.choice([1, 2, 4, 8]))
+    page = int(rng.choice([16, 16, 32, 8, 24, 128]))
+    num_q = int(rng.integers(2, 20)) if tree else int(rng.integers(1, 9))
+    batch = int(rng.integers(1, 12))
+    fp8 = bool(rng.integers(0, 4) == 0)
+    hidden = int(rng.choice([128, 256, 384])) if fp8 else int(rng.choice([64, 72, 128, 192, 320]))
+    vocab = int(rng.integers(300, 6000))
+    sub = (not greedy) and bool(rng.integers(0, 3) == 0)
+    len_lo = num_q + int(rng.integers(0, 40))
+    len_hi = len_lo + int(rng.integers(0, 700))
+    kw = dict(batch=batch, num_q=num_q, num_q_heads=hkv * group, num_kv_heads=hkv, head_dim=head_dim, page_size=page,
+              vocab=vocab, hidden_size=hidden, head_fp8=fp8, draft_noise=float(rng.choice([0.3, 1.0])))
+    if greedy:  # greedy trees have their own test; a greedy draw is always a chain here
+        num_q = min(num_q, 9)
+        kw["num_q"] = num_q
+        w = gen.qwen_greedy_chain(seed, len_lo=len_lo, len_hi=len_hi, **{k: v for k, v in kw.items()
+                                                                       if k not in ("draft_noise",)})
+    elif tree:
+        w = gen.llama_tree(seed, context=len_hi, draft_vocab=int(vocab // 3) if sub else None, **kw)
+    else:
+        w = gen.llama_chain(seed, len_lo=len_lo, len_hi=len_hi, temperature=float(rng.choice([1.0, 0.6])),
+                            draft_vocab=int(vocab // 3) if sub else None, **kw)
+    _full_check(gpu_lib, w)
