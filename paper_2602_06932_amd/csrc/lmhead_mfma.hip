@@ -131,52 +131,76 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
   const int hrow_off = kLmWBytes + li * kLmRowBytes;
   const int sw = (li >> 1) & 7;
 
-  for (int ks = 0; ks < nk; ++ks) {
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    const char* base = lds + (ks % kLmStages) * kStageBytes;
+  // A stage is walked in four steps of one 16-byte chunk pair per row: lane half lh takes chunk 2s + lh.
+  // For bf16 that is one MFMA step (k = 16); for fp8 the 16 bytes feed two MFMA steps (low and high 8
+  // bytes) - which hidden elements meet in which step does not matter as long as both operands are read
+  // the same way.  The operands of step s+1 are read from LDS while the MFMAs of step s run (fragments
+  // double-buffered in registers), and the barrier that opens the next stage sits before the last step
+  // of the current one, so that the matrix pipe never waits for LDS latency or for the barrier.
+  typedef __attribute__((ext_vector_type(2))) long i64x2_t;
+  struct Frag { i64x2_t w[2], h[NT]; };
+  auto load_frag = [&](int stage, int s, Frag& f) {
+    const char* base = lds + stage * kStageBytes;
+    const int coff = ((2 * s + lh) ^ sw) * 16;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) f.w[a] = *(const i64x2_t*)(base + wrow_off + a * 32 * kLmRowBytes + coff);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) f.h[t] = *(const i64x2_t*)(base + hrow_off + t * 32 * kLmRowBytes + coff);
+  };
+  auto multiply = [&](const Frag& f) {
     if constexpr (!kFp8) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const int coff = ((2 * s + lh) ^ sw) * 16;
-        bf16x8_t wa[2], hb[NT];
+      for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int a = 0; a < 2; ++a) wa[a] = *(const bf16x8_t*)(base + wrow_off + a * 32 * kLmRowBytes + coff);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) hb[t] = *(const bf16x8_t*)(base + hrow_off + t * 32 * kLmRowBytes + coff);
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-            acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[t], acc[a][t], 0, 0, 0);
-      }
+        for (int t = 0; t < NT; ++t)
+          acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, f.w[a]),
+                                                              __builtin_bit_cast(bf16x8_t, f.h[t]), acc[a][t], 0, 0, 0);
     } else {
-      // step s covers hidden elements 16 s .. 16 s + 15 of the stage: 16-byte chunk s, lane half lh takes
-      // 8 bytes.  An fp8 MFMA lasts half as long as a bf16 one, so the LDS latency of a step's operands
-      // is hidden explicitly: the reads of step s+1 are issued before the MFMAs of step s.
-      long wa[2][2], hb[2][NT];
-      auto load_step = [&](int s, long (&wf)[2], long (&hf)[NT]) {
-        const int coff = ((s ^ sw) * 16) + 8 * lh;
 #pragma unroll
-        for (int a = 0; a < 2; ++a) wf[a] = *(const long*)(base + wrow_off + a * 32 * kLmRowBytes + coff);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) hf[t] = *(const long*)(base + hrow_off + t * 32 * kLmRowBytes + coff);
-      };
-      load_step(0, wa[0], hb[0]);
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        if (s + 1 < 8) load_step(s + 1, wa[(s + 1) & 1], hb[(s + 1) & 1]);
+      for (int e = 0; e < 2; ++e)
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
           for (int t = 0; t < NT; ++t)
-            acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(wa[s & 1][a], hb[s & 1][t], acc[a][t], 0, 0, 0);
-        if (s + 1 < 8) __builtin_amdgcn_sched_group_barrier(0x100, 2 + NT, 0);  // next step's LDS reads first
-        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NT, 0);                 // then this step's MFMAs
-      }
+            acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(f.w[a][e], f.h[t][e], acc[a][t], 0, 0, 0);
     }
-    asm volatile("" ::: "memory");
+  };
+  constexpr int kMfmaPerStep = (kFp8 ? 2 : 1) * 2 * NT;
+  // pins "this step's LDS reads, then the previous step's MFMAs" against the compiler's own ordering
+#define LM_STEP_ORDER()                                                 \
+  do {                                                                  \
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 + NT, 0);             \
+    __builtin_amdgcn_sched_group_barrier(0x008, kMfmaPerStep, 0);       \
+    __builtin_amdgcn_sched_barrier(0);                                  \
+  } while (0)
+
+  Frag f0, f1;
+  __builtin_amdgcn_s_barrier();  // stage 0 visible
+  asm volatile("" ::: "memory");
+  load_frag(0, 0, f0);
+  int stage = 0;
+  for (int ks = 0; ks < nk; ++ks) {
+    load_frag(stage, 1, f1);
+    multiply(f0);
+    LM_STEP_ORDER();
+    load_frag(stage, 2, f0);
+    multiply(f1);
+    LM_STEP_ORDER();
+    load_frag(stage, 3, f1);
+    multiply(f0);
+    LM_STEP_ORDER();
+    if (ks + 1 < nk) {
+      // every LDS read of this stage has returned before the producers are told its buffer may be refilled
+      __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0) only
+      __builtin_amdgcn_s_barrier();  // stage ks+1 visible
+      asm volatile("" ::: "memory");
+      stage = stage + 1 == kLmStages ? 0 : stage + 1;
+      load_frag(stage, 0, f0);
+    }
+    multiply(f1);
+    LM_STEP_ORDER();
   }
+#undef LM_STEP_ORDER
 
   // ---- epilogue: logits out, and (max, arg-max, sum exp) of the workgroup's 256 vocab rows ---------
   // Each wavefront reduces its 64 rows per token in registers and parks the triple in an LDS stage
