@@ -405,3 +405,33 @@ def test_randomized_small_configurations(gpu_lib, seed):
         w = gen.llama_chain(seed, len_lo=len_lo, len_hi=len_hi, temperature=float(rng.choice([1.0, 0.6])),
                             draft_vocab=int(vocab // 3) if sub else None, **kw)
     _full_check(gpu_lib, w)
+
+
+def test_verify_step_replays_from_a_captured_graph(gpu_lib):
+    """The library allocates nothing and keeps no state, so a verify step can be captured into a HIP graph.
+    Every replay - with eager work and synchronisation between them - must reproduce the eager outputs."""
+    from paper_2602_06932_amd.device import DeviceVerify
+    w = gen.llama_chain(27, batch=8, len_lo=40, len_hi=300, vocab=6000, hidden_size=256)
+    dv = DeviceVerify(w)
+    dv.verify()
+    torch.cuda.synchronize()
+    ref, ref_o = dv.results_host(), dv.attn_out_host().copy()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dv.verify(stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for i in range(4):
+        dv.accept_len.fill_(-1)
+        dv.next_token.fill_(-1)
+        dv.accept_mask.fill_(7)
+        dv.attn_out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = dv.results_host()
+        for k in ("accept_len", "next_token", "accept_mask"):
+            assert np.array_equal(ref[k], got[k]), (i, k)
+        assert np.array_equal(ref_o, dv.attn_out_host())
+        dv.lmhead()  # eager work on the same workspace between replays
+        torch.cuda.synchronize()
