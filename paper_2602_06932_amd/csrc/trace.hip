@@ -200,11 +200,19 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
     if (tid == 0) s_count = 0;
     __syncthreads();
     // ---- one pass over the row: keep what reaches the cut-off ------------------------------------------
+    // The pass compares floats: key(x) >= cut  <=>  x >= cut_f for the float cut_f whose key is `cut` (keys
+    // are monotone, and -0.0 >= +0.0 holds just as their keys are equal); only survivors pay for a key.
+    float cut_f;
+    {
+      const uint32_t u = (cut & 0x80000000u) ? (cut ^ 0x80000000u) : ~cut;
+      cut_f = __uint_as_float(u);
+      if (cut_f != cut_f) cut_f = -INFINITY;  // a prefix below every finite key: everything passes
+    }
     if (tid < h) {
-      const uint32_t k = order_key(at(tid));
-      if (k >= cut) {
+      const float x = at(tid);
+      if (x >= cut_f) {
         const unsigned slot = atomicAdd(&s_count, 1u);
-        if (slot < (unsigned)kTrCap) s_cand[slot] = ((uint64_t)k << 32) | (uint32_t)~tid;
+        if (slot < (unsigned)kTrCap) s_cand[slot] = entry_word(x, tid);
       }
     }
     // sixteen 16-byte loads in flight per thread: the pass is bound by memory latency otherwise
@@ -222,20 +230,19 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
         if (i < nvec) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const uint32_t k = order_key(x[u][j]);
-            if (k >= cut) {
+            if (x[u][j] >= cut_f) {
               const unsigned slot = atomicAdd(&s_count, 1u);
-              if (slot < (unsigned)kTrCap) s_cand[slot] = ((uint64_t)k << 32) | (uint32_t) ~(h + 4 * i + j);
+              if (slot < (unsigned)kTrCap) s_cand[slot] = entry_word(x[u][j], h + 4 * i + j);
             }
           }
         }
       }
     }
     for (int i = h + 4 * nvec + tid; i < V; i += kTrThreads) {
-      const uint32_t k = order_key(at(i));
-      if (k >= cut) {
+      const float x = at(i);
+      if (x >= cut_f) {
         const unsigned slot = atomicAdd(&s_count, 1u);
-        if (slot < (unsigned)kTrCap) s_cand[slot] = ((uint64_t)k << 32) | (uint32_t)~i;
+        if (slot < (unsigned)kTrCap) s_cand[slot] = entry_word(x, i);
       }
     }
     __syncthreads();
