@@ -74,7 +74,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding of the "
-                         "verify step is described in DESIGN.md but not built")
+                         "verify step is a design note in the repository's documentation, not built")
 
     import numpy as np
     import torch

@@ -401,7 +401,7 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
 
 
 # --------------------------------------------------------------------------
-# the five named configurations (BASELINE.json "configs"), with size overrides
+# the five named benchmark configurations, with size overrides
 # for reduced parity cases
 # --------------------------------------------------------------------------
 def tiny_chain(seed: int = 1, **kw) -> Workload:
