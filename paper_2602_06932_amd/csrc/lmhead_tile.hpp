@@ -87,7 +87,7 @@ __device__ __forceinline__ void lm_tile_out(f32x16_t& a0, f32x16_t& a1, int vrow
     if (mm < M) {
       float* dst = logits + (size_t)mm * V + v;
       if (vec_ok && v + 3 < V) {
-        *(f32x4_t*)dst = o;
+        __builtin_nontemporal_store(o, (f32x4_t*)dst);  // written once, read much later: keep it out of the way of W
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
