@@ -48,7 +48,7 @@ __device__ __forceinline__ void load_to_lds_16(const void* gptr, const void* lds
   const unsigned base = (unsigned)(uintptr_t)lds_base;  // LDS pointers are 32-bit offsets
   // m0 holds the LDS base; one wait state is required between writing m0 and the load that reads it.
   // Nothing else in this kernel uses m0.
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(base)),
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(__builtin_amdgcn_readfirstlane(base)),
                "v"(gptr)
                : "memory");
 }
