@@ -22,8 +22,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # default workload (seed 1), scaled by what the same counters read for `--stage copy` (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0); the summaries are in profiles/.  None for workloads that were not profiled.
 MEASURED_TRAFFIC = {
-    ("llama", 1, "lmhead"): {"read_bytes": 523400 * 1024 * 2, "write_bytes": 87700 * 1024},
-    ("llama", 1, "attn"): {"read_bytes": (153600 + 4128) * 1024 * 2, "write_bytes": (7248 + 1280) * 1024},
+    ("llama", 1, "lmhead"): {"read_bytes": 518300 * 1024 * 2, "write_bytes": 88010 * 1024},
+    ("llama", 1, "attn"): {"read_bytes": (153500 + 4128) * 1024 * 2, "write_bytes": (7236 + 1280) * 1024},
 }
 
 
