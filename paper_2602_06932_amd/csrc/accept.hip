@@ -28,6 +28,7 @@ constexpr int kAccThreads = 1024;
 constexpr int kAccWaves = kAccThreads / kWave;
 constexpr int kMaxGroups = 4096;  // group sums kept in LDS by the tree kernel (32 KB of doubles): V <= 2^20
 constexpr int kSmallThreads = 256;
+constexpr int kSweepThreads = 512;  // chain sweep: eight wavefronts, so five rows merge and a 32-group slice sweeps in one round
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 // Probability of token v at the current node after `nres` residual steps, in fp64 throughout (used
@@ -204,16 +205,24 @@ __device__ __forceinline__ void lane_weights(const Lane4& r, int v0, int V, doub
 // statistics of the request's rows, evaluate the k accept tests in parallel in fp64, find the first
 // failure - then sums the draw weights over its slice of the vocabulary.  Slice 0 writes the
 // per-request outputs and the state the draw kernel needs.
-__global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams P) {
+__global__ __launch_bounds__(kSweepThreads) void accept_chain_sweep(AcceptParams P) {
   __shared__ double s_lse[kMaxNq];
   __shared__ int s_ok[kMaxNq];
-  __shared__ int s_last[kSmallThreads / kWave];
+  __shared__ int s_last[kSweepThreads / kWave];
   const int slice = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
   const int Nq = P.Nq, V = P.V;
   const double T = (double)P.temperature;
   const size_t row0 = (size_t)b * Nq;
-  for (int n = wv; n < Nq; n += kSmallThreads / kWave) {
+  // operands of the accept tests: their addresses are known up front, so the loads fly during the merge
+  float t_l = 0.f, t_q = 0.f, t_u = 0.f;
+  if (tid > 0 && tid < Nq) {
+    const int tk = P.tok[row0 + tid];
+    t_l = P.logits[(row0 + tid - 1) * V + tk];
+    t_q = q_at(q_row(P, row0 + tid - 1), tk);
+    t_u = P.un[(row0 + tid) * 2 + 0];
+  }
+  for (int n = wv; n < Nq; n += kSweepThreads / kWave) {
     float mx; double lse; int arg;
     merge_row_stats(P, row0 + n, T, lane, &mx, &lse, &arg);
     if (lane == 0) s_lse[n] = lse;
@@ -224,12 +233,8 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams
     float pv = 0.f;
     int ok = 1;
     if (n > 0) {
-      const int tk = P.tok[row0 + n];
-      const float l = P.logits[(row0 + n - 1) * V + tk];
-      const float qv = q_at(q_row(P, row0 + n - 1), tk);
-      const double p = exp((double)l / T - s_lse[n - 1]);
-      const double u = (double)P.un[(row0 + n) * 2 + 0];
-      ok = (u * (double)qv < p) ? 1 : 0;
+      const double p = exp((double)t_l / T - s_lse[n - 1]);
+      ok = ((double)t_u * (double)t_q < p) ? 1 : 0;
       pv = (float)p;
     }
     s_ok[n] = ok;
@@ -263,7 +268,7 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams
   const int g0 = slice * per, g1 = min(P.ngroups, g0 + per);
   int lastpos = -1;
   constexpr int kBatch = 4;  // groups whose loads a wavefront keeps in flight together
-  constexpr int kStep = kSmallThreads / kWave;
+  constexpr int kStep = kSweepThreads / kWave;
   for (int g = g0 + wv; g < g1; g += kBatch * kStep) {
     Lane4 r[kBatch];
 #pragma unroll
@@ -291,7 +296,7 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_sweep(AcceptParams
   __syncthreads();
   if (tid == 0) {
     int m = -1;
-    for (int i = 0; i < kSmallThreads / kWave; ++i) m = max(m, s_last[i]);
+    for (int i = 0; i < kSweepThreads / kWave; ++i) m = max(m, s_last[i]);
     P.lastpos[(size_t)b * P.slices + slice] = m;
   }
 }
@@ -693,7 +698,7 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st) {
     hipLaunchKernelGGL(accept_tree_kernel, dim3(a.B), dim3(kAccThreads), 0, st, P);
     return hipGetLastError();
   }
-  hipLaunchKernelGGL(accept_chain_sweep, dim3(P.slices, a.B), dim3(kSmallThreads), 0, st, P);
+  hipLaunchKernelGGL(accept_chain_sweep, dim3(P.slices, a.B), dim3(kSweepThreads), 0, st, P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(accept_chain_pick, dim3(a.B), dim3(kSmallThreads), 0, st, P);
