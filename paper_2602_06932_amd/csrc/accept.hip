@@ -15,9 +15,10 @@
 //                       accept_len / accept_mask / p_at_draft / row_lse;
 //   accept_chain_pick   one workgroup per request: scan the group sums, find the group holding
 //                       u * total, rescan that group with a wavefront prefix sum for the token.
-// Trees at T > 0 may need one sweep per rejected sibling, each depending on the previous one; they
-// run in one workgroup per request (accept_tree_kernel), which also serves every greedy (T = 0)
-// call, where no sweep exists.
+// Trees at T > 0 may need one sweep per rejected sibling, each depending on the previous one:
+// accept_tree_kernel walks a request in up to 16 workgroups that split every sweep and exchange their
+// partial sums behind a counting barrier.  The same kernel, one workgroup per request, serves every
+// greedy (T = 0) call, where no sweep exists.
 // All sums are fp64 in a fixed order: results are reproducible bit for bit.
 #include "common.hpp"
 #include "launch.hpp"
@@ -90,6 +91,10 @@ struct AcceptParams {
   int32_t* st_rej;    // [B] 1: draw from max(0, p - q); 0: draw from p
   double* gsum;       // [B, ngroups]
   int32_t* lastpos;   // [B, slices] largest token with positive weight per slice, or -1
+  // tree path with several workgroups per request: gsum is [B, 2, ngroups] and lastpos [B, 2, tree_slices]
+  // (two copies, alternating by sweep), tree_bar [B] counts workgroup arrivals (zero at launch)
+  int tree_slices;
+  int32_t* tree_bar;
 };
 
 // (max, logsumexp(l / T), arg-max) of one logits row, merged from its tile statistics by one
@@ -409,15 +414,47 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams 
 }
 
 // ============================================================================================
-// One workgroup per request: trees at T > 0, and every greedy call.
+// Trees at T > 0, and every greedy call.  Grid (S, B): S workgroups per request.  With S = 1 the
+// request's walk and all its vocabulary sweeps run in one workgroup.  With S > 1 every workgroup of a
+// request repeats the walk (the same inputs give the same decisions, bit for bit) and sweeps only its
+// slice of the vocabulary; after each sweep the group sums are exchanged through global memory behind a
+// counting barrier, and every workgroup scans all of them in the same order as the one-workgroup form -
+// so both forms return identical results.  The launcher keeps S * B within the number of compute units,
+// so all workgroups of a request are resident together; the wait on the counter is bounded all the same.
 // ============================================================================================
+constexpr int kTreeMaxSlices = 16;
+constexpr int kSpinLimit = 1 << 21;  // polls of the arrival counter (about a second) before giving up
+
+// The values exchanged between the workgroups of a request are written and read with device-scope
+// atomic accesses: on this multi-die part they go past the die-local L2 to the point all dies see, so the
+// hand-over needs no L2 write-back or invalidate - only "my stores have been acknowledged" before the
+// arrival is counted.
+__device__ __forceinline__ void store_agent(int32_t* p, int v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_agent(double* p, double v) {
+  __hip_atomic_store((unsigned long long*)p, __builtin_bit_cast(unsigned long long, v), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_stores_acknowledged() {
+  __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));  // vmcnt(0), nothing else
+  asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ int load_agent(const int32_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ double load_agent(const double* p) {
+  const unsigned long long u = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return __builtin_bit_cast(double, u);
+}
+
 __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P) {
   __shared__ double s_lse[kMaxNq];
   __shared__ int s_arg[kMaxNq];
   __shared__ double s_Z[kMaxNq], s_invZ[kMaxNq];
   __shared__ double s_gsum[kMaxGroups];
   __shared__ double s_wtot[kAccWaves];
-  __shared__ int s_cur, s_depth, s_nres, s_last_child, s_state, s_have_gsum, s_pick, s_lastpos;
+  __shared__ int s_cur, s_depth, s_nres, s_last_child, s_state, s_have_gsum, s_pick, s_lastpos, s_fail;
   __shared__ double s_pick_prefix;
   // the request's tree, tokens and uniforms: the walk below is one thread chasing them, so they are
   // staged once instead of being fetched from global memory one dependent load at a time
@@ -425,7 +462,9 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   __shared__ float s_u0[kMaxNq], s_u1[kMaxNq];
   __shared__ float s_ltok[kMaxNq], s_qtok[kMaxNq];  // logit and draft probability of node n's token in its parent's row
 
-  const int b = blockIdx.x;
+  const int b = blockIdx.y;
+  const int S = (int)gridDim.x, slice = blockIdx.x;  // S > 1 only for sampling walks
+  const bool writer = slice == 0;                     // the workgroup that stores the request's outputs
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
   const int Nq = P.Nq, V = P.V;
   const bool greedy = !(P.temperature > 0.f);
@@ -450,7 +489,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   // ---- per-node outputs ------------------------------------------------------------------------
   if (tid < Nq) {
     const int n = tid;
-    if (P.row_lse) P.row_lse[row0 + n] = (float)s_lse[n];
+    if (P.row_lse && writer) P.row_lse[row0 + n] = (float)s_lse[n];
     float pv = 0.f;
     if (n > 0) {
       const int par = s_par[n];
@@ -464,8 +503,10 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
         pv = (float)exp((double)l / T - s_lse[par]);
       }
     }
-    if (P.p_at_draft) P.p_at_draft[row0 + n] = pv;
-    P.accept_mask[row0 + n] = n == 0 ? 1 : 0;
+    if (writer) {
+      if (P.p_at_draft) P.p_at_draft[row0 + n] = pv;
+      P.accept_mask[row0 + n] = n == 0 ? 1 : 0;
+    }
   }
   __syncthreads();
 
@@ -494,8 +535,12 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   // ---- 2b. sampling walk ------------------------------------------------------------------------
   const int ngroups = (V + kGroup - 1) / kGroup;  // <= kMaxGroups (checked by the launcher)
   const bool vec_ok = rows_vec_ok(P);
+  const int per_slice = (ngroups + S - 1) / S;
+  const int g_lo = slice * per_slice;
+  const int g_hi = min(ngroups, g_lo + per_slice);
+  int sweeps = 0;  // sweeps done so far: the same in every workgroup of the request
   if (tid == 0) {
-    s_cur = 0; s_depth = 0; s_nres = 0; s_last_child = 0; s_have_gsum = 0;
+    s_cur = 0; s_depth = 0; s_nres = 0; s_last_child = 0; s_have_gsum = 0; s_fail = 0;
   }
   enum { ST_DONE = 0, ST_ACCEPTED = 1, ST_REJECTED = 2 };
   for (;;) {
@@ -518,7 +563,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
           s_depth = s_depth + 1;
           s_nres = 0;
           s_have_gsum = 0;
-          P.accept_mask[row0 + c] = 1;
+          if (writer) P.accept_mask[row0 + c] = 1;
           s_state = ST_ACCEPTED;
         } else {
           s_state = ST_REJECTED;
@@ -541,17 +586,18 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       const bool skip_last = state == ST_REJECTED;
       int lastpos = -1;
       constexpr int kBatch = 5;  // groups whose loads a wavefront keeps in flight together (160 KB per workgroup)
-      for (int g = wv; g < ngroups; g += kBatch * kAccWaves) {
+      double* gs_out = P.gsum + ((size_t)b * 2 + (sweeps & 1)) * ngroups;  // used when S > 1
+      for (int g = g_lo + wv; g < g_hi; g += kBatch * kAccWaves) {
         Lane4 r[kBatch];
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
           const int gi = g + i * kAccWaves;
-          if (gi < ngroups) r[i] = lane_load(lrow, qrow, gi * kGroup + lane * 4, V, vec_ok);
+          if (gi < g_hi) r[i] = lane_load(lrow, qrow, gi * kGroup + lane * 4, V, vec_ok);
         }
 #pragma unroll
         for (int i = 0; i < kBatch; ++i) {
           const int gi = g + i * kAccWaves;
-          if (gi < ngroups) {  // wave-uniform
+          if (gi < g_hi) {  // wave-uniform
             const int v0 = gi * kGroup + lane * 4;
             double x[4];
             lane_weights(r[i], v0, V, lse, inv_t, nres, x, s_invZ, skip_last);
@@ -559,7 +605,9 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
             for (int e = 0; e < 4; ++e)
               if (x[e] > 0.0) lastpos = max(lastpos, v0 + e);
             const double sg = wave_sum((x[0] + x[1]) + (x[2] + x[3]));
-            if (lane == 0) s_gsum[gi] = sg;
+            if (lane == 0) {
+              if (S > 1) store_agent(&gs_out[gi], sg); else s_gsum[gi] = sg;
+            }
           }
         }
       }
@@ -567,6 +615,29 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       if (tid == 0) s_lastpos = -1;
       __syncthreads();
       if (lane == 0) atomicMax(&s_lastpos, lastpos);
+      if (S > 1) {
+        // ---- exchange with the request's other workgroups ----------------------------------------
+        wait_stores_acknowledged();  // this thread's group sums, before the arrival is counted
+        __syncthreads();
+        int32_t* lp = P.lastpos + ((size_t)b * 2 + (sweeps & 1)) * S;
+        if (tid == 0) {
+          store_agent(&lp[slice], s_lastpos);
+          wait_stores_acknowledged();
+          atomicAdd(&P.tree_bar[b], 1);
+          const int target = S * (sweeps + 1);
+          int polls = 0;
+          while (load_agent(&P.tree_bar[b]) < target) {
+            __builtin_amdgcn_s_sleep(4);
+            if (++polls > kSpinLimit) { s_fail = 1; break; }
+          }
+        }
+        __syncthreads();
+        if (s_fail) return;  // a workgroup of the request never arrived: give up rather than wait for ever
+        // loads that bypass this compute unit's L1, which may still hold the copy of two sweeps ago
+        for (int g = tid; g < ngroups; g += kAccThreads) s_gsum[g] = load_agent(&gs_out[g]);
+        if (tid < S) atomicMax(&s_lastpos, load_agent(&lp[tid]));
+        ++sweeps;
+      }
       __syncthreads();
     }
 
@@ -622,6 +693,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
     }
     __syncthreads();
     const int pick = s_pick;
+    if (!writer) return;  // no barrier between workgroups follows
     if (pick != 0x7fffffff && pick / 4 == tid) {
       double run = excl;
       for (int i = 0; i < pick % 4; ++i) run += mine[i];
@@ -682,6 +754,23 @@ void accept_chain_geometry(int batch, int vocab, int* slices, int* gmul, int* ng
   *ngroups = ng;
 }
 
+__global__ void zero_i32_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+int accept_tree_max_slices() { return kTreeMaxSlices; }
+
+// Workgroups per request for a sampling tree walk: as many as leave every workgroup at least 16 groups
+// to sweep, at most kTreeMaxSlices, and S * B within the number of compute units (all of them resident
+// at once); 1 when that leaves fewer than two.
+static int tree_slices_for(int B, int ngroups, int cus) {
+  int s = ngroups / 16;
+  if (s > kTreeMaxSlices) s = kTreeMaxSlices;
+  if (B > 0 && s > cus / B) s = cus / B;
+  return s >= 2 ? s : 1;
+}
+
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st) {
   AcceptParams P = {};
   P.Nq = a.Nq; P.V = a.V; P.n_tiles = a.plan.n_tiles; P.temperature = a.temperature;
@@ -692,10 +781,23 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st) {
   P.p_at_draft = a.p_at_draft; P.row_lse = a.row_lse;
   P.slices = a.plan.slices; P.gmul = a.plan.gmul; P.ngroups = a.plan.ngroups;
   P.st_lse = a.st_lse; P.st_row = a.st_row; P.st_rej = a.st_rej; P.gsum = a.gsum; P.lastpos = a.lastpos;
+  P.tree_bar = a.tree_bar;
   const bool chain_sampling = a.temperature > 0.f && a.parents == nullptr;
   if (!chain_sampling) {
-    if (a.temperature > 0.f && (a.V + kGroup - 1) / kGroup > kMaxGroups) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(accept_tree_kernel, dim3(a.B), dim3(kAccThreads), 0, st, P);
+    const int ngroups = (a.V + kGroup - 1) / kGroup;
+    if (a.temperature > 0.f && ngroups > kMaxGroups) return hipErrorInvalidValue;
+    int S = 1;
+    if (a.temperature > 0.f) {
+      int cus = 0;
+      if (hipError_t e = device_cu_count(&cus); e != hipSuccess) return e;
+      S = tree_slices_for(a.B, ngroups, cus);
+    }
+    if (S > 1) {
+      hipLaunchKernelGGL(zero_i32_kernel, dim3((a.B + 255) / 256), dim3(256), 0, st, a.tree_bar, a.B);
+      if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    }
+    P.tree_slices = S;
+    hipLaunchKernelGGL(accept_tree_kernel, dim3(S, a.B), dim3(kAccThreads), 0, st, P);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(accept_chain_sweep, dim3(P.slices, a.B), dim3(kSweepThreads), 0, st, P);

@@ -106,8 +106,11 @@ AcceptPlan plan_accept(const aurora_accept_desc* d) {
   p.st_row_off = p.st_lse_off + align_up(B * sizeof(double));
   p.st_rej_off = p.st_row_off + align_up(B * sizeof(int32_t));
   p.gsum_off = p.st_rej_off + align_up(B * sizeof(int32_t));
-  p.lastpos_off = p.gsum_off + align_up(B * p.ngroups * sizeof(double));
-  p.bytes = p.lastpos_off + align_up(B * p.slices * sizeof(int32_t));
+  // the tree walk keeps two copies of the group sums and of the per-slice last positions (alternating by sweep)
+  p.lastpos_off = p.gsum_off + align_up(2 * B * p.ngroups * sizeof(double));
+  const size_t lp_slices = (size_t)std::max(p.slices, 2 * accept_tree_max_slices());
+  p.tree_bar_off = p.lastpos_off + align_up(B * lp_slices * sizeof(int32_t));
+  p.bytes = p.tree_bar_off + align_up(B * sizeof(int32_t));
   return p;
 }
 
@@ -163,6 +166,7 @@ int run_accept(const aurora_accept_desc* desc, const void* hidden, const void* l
   a.st_rej = (int32_t*)(ws + plan.st_rej_off);
   a.gsum = (double*)(ws + plan.gsum_off);
   a.lastpos = (int32_t*)(ws + plan.lastpos_off);
+  a.tree_bar = (int32_t*)(ws + plan.tree_bar_off);
   a.plan = plan;
   if (with_lmhead) {
     hipError_t e = lmhead_mfma_supported(a) ? launch_lmhead_mfma(a, st) : launch_lmhead_generic(a, st);

@@ -72,7 +72,7 @@ struct AcceptPlan {
   int slices;       // chain draw: workgroups per request in the vocabulary sweep
   int gmul;         // chain draw: a group is 64 * gmul consecutive tokens
   int ngroups;      // chain draw: ceil(V / (64 * gmul))
-  size_t logits_off, pmax_off, psum_off, parg_off, st_lse_off, st_row_off, st_rej_off, gsum_off, lastpos_off, bytes;
+  size_t logits_off, pmax_off, psum_off, parg_off, st_lse_off, st_row_off, st_rej_off, gsum_off, lastpos_off, tree_bar_off, bytes;
 };
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -93,5 +93,21 @@ struct LdsAttrOnce {
     return e;
   }
 };
+
+// Number of compute units of the current device (cached per device).
+inline hipError_t device_cu_count(int* out) {
+  static int count[64];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const bool track = dev >= 0 && dev < 64;
+  if (track && count[dev] > 0) { *out = count[dev]; return hipSuccess; }
+  int n = 0;
+  e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  if (track) count[dev] = n;
+  *out = n;
+  return hipSuccess;
+}
 
 }  // namespace aurora

@@ -34,6 +34,7 @@ struct AcceptLaunch {
   int32_t* parg;
   double *st_lse, *gsum;
   int32_t *st_row, *st_rej, *lastpos;
+  int32_t* tree_bar;  // [B] arrival counters of the several-workgroups-per-request tree walk
   AcceptPlan plan;
 };
 
@@ -53,6 +54,7 @@ hipError_t launch_lmhead_generic(const AcceptLaunch& a, hipStream_t st);
 
 // acceptance walk + residual / bonus draw
 void accept_chain_geometry(int batch, int vocab, int* slices, int* gmul, int* ngroups);
+int accept_tree_max_slices();  // workgroups per request the tree walk may use (sizes its exchange buffers)
 hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st);
 
 // trace emission: top-K target logits per token row, y_out and rejection trajectory

@@ -435,3 +435,51 @@ def test_verify_step_replays_from_a_captured_graph(gpu_lib):
         assert np.array_equal(ref_o, dv.attn_out_host())
         dv.lmhead()  # eager work on the same workspace between replays
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("batch,num_q,vocab", [(6, 16, 8200), (5, 16, 20011), (4, 12, 50257), (40, 9, 33000)])
+def test_tree_walk_with_several_workgroups_per_request(gpu_lib, batch, num_q, vocab):
+    """Vocabularies large enough that the sampling tree walk splits every sweep over 2 .. 16 workgroups per
+    request (the split follows the vocabulary and the batch); results against the oracle, and two runs of
+    the acceptance stage on the same logits must agree bit for bit."""
+    w = gen.llama_tree(41 + batch, batch=batch, num_q=num_q, vocab=vocab, hidden_size=128, context=48, num_q_heads=4,
+                       num_kv_heads=2)
+    dv, a = _full_check(gpu_lib, w)
+    first = dv.results_host()
+    dv.lmhead()  # the two-call form keeps its logits at the start of the workspace
+    for _ in range(2):
+        dv.accept_len.fill_(-1)
+        dv.next_token.fill_(-1)
+        dv.accept_logits()
+        torch.cuda.synchronize()
+        again = dv.results_host()
+        for k in first:
+            assert np.array_equal(first[k], again[k], equal_nan=True), k
+
+
+def test_tree_verify_step_replays_from_a_captured_graph(gpu_lib):
+    """The several-workgroup tree walk clears its arrival counters with a kernel of the same call, so it
+    replays from a graph like the rest."""
+    from paper_2602_06932_amd.device import DeviceVerify
+    w = gen.llama_tree(52, batch=6, num_q=16, vocab=20011, hidden_size=128, context=48, num_q_heads=4, num_kv_heads=2)
+    dv = DeviceVerify(w)
+    dv.verify()
+    torch.cuda.synchronize()
+    ref = dv.results_host()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        dv.verify(stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for i in range(3):
+        dv.accept_len.fill_(-1)
+        dv.next_token.fill_(-1)
+        dv.accept_mask.fill_(7)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = dv.results_host()
+        for k in ("accept_len", "next_token", "accept_mask"):
+            assert np.array_equal(ref[k], got[k]), (i, k)
+        dv.accept()  # eager work on the same workspace between replays
+        torch.cuda.synchronize()
