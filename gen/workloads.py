@@ -79,6 +79,17 @@ def e4m3_rows_to_f32(codes: np.ndarray, scale: np.ndarray) -> np.ndarray:
     return v * np.asarray(scale, dtype=np.float32)[..., None]
 
 
+def quantize_e4m3_heads(x: np.ndarray):
+    """8-bit storage of a paged pool [P, Hkv, page, D] (float32): uint8 E4M3 codes and one float32 scale
+    per KV head, scale[h] = max|x[:, h]| / 448.  Same rounding as quantize_e4m3_rows."""
+    import torch
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    amax = np.abs(x).max(axis=(0, 2, 3))
+    scale = np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    q = torch.from_numpy(x / scale[None, :, None, None]).to(torch.float8_e4m3fn)
+    return q.view(torch.uint8).numpy(), scale
+
+
 def as_f32(x: np.ndarray, dtype: str) -> np.ndarray:
     """The values a stored tensor holds, as float32 (exact for both dtypes)."""
     return bf16_bits_to_f32(x) if dtype == BF16 else np.asarray(x, dtype=np.float32)
@@ -183,6 +194,11 @@ class Workload:
     head_dtype: str = ""
     hidden_scale: Optional[np.ndarray] = None
     lm_head_scale: Optional[np.ndarray] = None
+    # KV cache in 8-bit floating point: kv_dtype == "fp8" => k_pages / v_pages hold uint8 E4M3 codes and
+    # k_scale / v_scale [num_kv_heads] the float32 scale of each KV head ("" = as `dtype`)
+    kv_dtype: str = ""
+    k_scale: Optional[np.ndarray] = None
+    v_scale: Optional[np.ndarray] = None
 
     def target_to_draft(self) -> Optional[np.ndarray]:
         """Inverse of draft_to_target over the target vocabulary, -1 where the draft model has no entry."""
@@ -223,8 +239,11 @@ class Workload:
 # --------------------------------------------------------------------------
 def make_kv(ss: np.random.SeedSequence, rng: np.random.Generator, seq_lens: np.ndarray,
             num_kv_heads: int, head_dim: int, page_size: int, dtype: str,
-            slack: float = 0.10, shuffle: bool = True, pool_pages: Optional[int] = None):
+            slack: float = 0.10, shuffle: bool = True, pool_pages: Optional[int] = None, kv_fp8: bool = False):
     """Paged K/V pools and a block table.
+
+    kv_fp8: the pools are drawn as float32 N(0,1), KV head h scaled by 2^(h mod 3 - 1) (so that the heads'
+    scales differ), and stored as E4M3 codes with one scale per head; two more values are returned.
 
     pool_pages=None: the pool holds the referenced pages plus `slack` spare
     ones and the block table is a random permutation of pool ids (shuffle) or
@@ -255,6 +274,11 @@ def make_kv(ss: np.random.SeedSequence, rng: np.random.Generator, seq_lens: np.n
     kss, vss = ss.spawn(2)
     n_store = P if pool_pages is None else used
     shape = (n_store, num_kv_heads, page_size, head_dim)
+    if kv_fp8:
+        gain = np.exp2((np.arange(num_kv_heads) % 3 - 1).astype(np.float32))[None, :, None, None]
+        k_pages, k_scale = quantize_e4m3_heads(_normal_tensor(kss, shape, 1.0, F32) * gain)
+        v_pages, v_scale = quantize_e4m3_heads(_normal_tensor(vss, shape, 1.0, F32) * gain[:, ::-1])
+        return k_pages, v_pages, block_table, P, max_pages, page_ids, k_scale, v_scale
     k_pages = _normal_tensor(kss, shape, 1.0, dtype)
     v_pages = _normal_tensor(vss, shape, 1.0, dtype)
     return k_pages, v_pages, block_table, P, max_pages, page_ids
@@ -305,7 +329,7 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
                   tree: bool = False, greedy_hit: float = 0.7,
                   shuffle_pages: bool = True, pool_pages: Optional[int] = None,
                   distinct_siblings: bool = False, draft_vocab: Optional[int] = None,
-                  head_fp8: bool = False, recipe: str = "") -> Workload:
+                  head_fp8: bool = False, kv_fp8: bool = False, recipe: str = "") -> Workload:
     """Build one workload.
 
     draft = "independent": draft logits ~ N(0,1), draft tokens uniform over the vocab.
@@ -317,6 +341,7 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
             target ids; draft_probs is over the subset, tokens are drawn from it and stored as target ids.
     head_fp8: hidden and lm_head are drawn as float32 with the same recipe, then stored as E4M3 codes
             with one scale per row; the stand-in target logits use the values the codes stand for.
+    kv_fp8: the K/V pools are stored as E4M3 codes with one scale per KV head (see make_kv).
     """
     ss = np.random.SeedSequence([int(seed), 0x2602_06932 & 0xFFFFFFFF])
     s_q, s_kv, s_h, s_w, s_misc = ss.spawn(5)
@@ -326,9 +351,13 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
     assert seq_lens.shape == (B,) and int(seq_lens.min()) >= Nq
 
     q = _normal_tensor(s_q, (B, Nq, num_q_heads, head_dim), 1.0, dtype)
-    k_pages, v_pages, block_table, P, max_pages, page_ids = make_kv(
-        s_kv, rng, seq_lens, num_kv_heads, head_dim, page_size, dtype,
-        shuffle=shuffle_pages, pool_pages=pool_pages)
+    k_scale = v_scale = None
+    kv = make_kv(s_kv, rng, seq_lens, num_kv_heads, head_dim, page_size, dtype,
+                 shuffle=shuffle_pages, pool_pages=pool_pages, kv_fp8=kv_fp8)
+    if kv_fp8:
+        k_pages, v_pages, block_table, P, max_pages, page_ids, k_scale, v_scale = kv
+    else:
+        k_pages, v_pages, block_table, P, max_pages, page_ids = kv
     hidden_scale = lm_head_scale = None
     head_values = None  # (hidden, lm_head) as float32 when they are not stored in `dtype`
     if head_fp8:
@@ -396,7 +425,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
                  lm_head=lm_head, draft_tokens=draft_tokens, draft_probs=draft_probs,
                  uniforms=uniforms, recipe=recipe, page_ids=page_ids,
                  draft_vocab=int(draft_vocab or 0), draft_to_target=d2t,
-                 head_dtype="fp8" if head_fp8 else "", hidden_scale=hidden_scale, lm_head_scale=lm_head_scale)
+                 head_dtype="fp8" if head_fp8 else "", hidden_scale=hidden_scale, lm_head_scale=lm_head_scale,
+                 kv_dtype="fp8" if kv_fp8 else "", k_scale=k_scale, v_scale=v_scale)
     return w
 
 

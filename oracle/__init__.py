@@ -25,7 +25,7 @@ def lib():
         _lib = C.CDLL(_build.build(force=False))
         for name in ("oracle_attn", "oracle_logits", "oracle_accept_logits", "oracle_accept",
                      "oracle_num_threads", "oracle_trace_topk", "oracle_trace_records", "oracle_logits_fp8",
-                     "oracle_decode_e4m3"):
+                     "oracle_decode_e4m3", "oracle_attn_fp8kv"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -52,24 +52,34 @@ def num_threads() -> int:
     return int(lib().oracle_num_threads())
 
 
-def attn(*, q, k_pages, v_pages, block_table, seq_lens, parents=None, dtype, sm_scale=0.0) -> np.ndarray:
-    """Chunk attention; returns float64 [B, Nq, Hq, D]."""
+def attn(*, q, k_pages, v_pages, block_table, seq_lens, parents=None, dtype, sm_scale=0.0,
+         k_scale=None, v_scale=None) -> np.ndarray:
+    """Chunk attention; returns float64 [B, Nq, Hq, D].  With k_scale / v_scale (float32 [Hkv]) the pools
+    hold uint8 E4M3 codes and a value is scale[head] * decode(code); q stays in `dtype`."""
     ed = _elem_dtype(dtype)
+    fp8kv = k_scale is not None
+    kvd = np.uint8 if fp8kv else ed
     q = _chk(q, ed)
     B, Nq, Hq, D = q.shape
-    k_pages = _chk(k_pages, ed)
+    k_pages = _chk(k_pages, kvd)
     P, Hkv, page, D2 = k_pages.shape
     assert D2 == D
-    v_pages = _chk(v_pages, ed, k_pages.shape)
+    v_pages = _chk(v_pages, kvd, k_pages.shape)
     block_table = _chk(block_table, np.int32)
     assert block_table.shape[0] == B
     seq_lens = _chk(seq_lens, np.int32, (B,))
     parents = _chk(parents, np.int32, (B, Nq))
     out = np.empty((B, Nq, Hq, D), dtype=np.float64)
-    st = lib().oracle_attn(C.c_int(B), C.c_int(Nq), C.c_int(Hq), C.c_int(Hkv), C.c_int(D),
-                           C.c_int(page), C.c_int(block_table.shape[1]), C.c_int64(P),
-                           C.c_int(_DT[dtype]), C.c_double(sm_scale), _p(q), _p(k_pages), _p(v_pages),
-                           _p(block_table), _p(seq_lens), _p(parents), _p(out))
+    head = (C.c_int(B), C.c_int(Nq), C.c_int(Hq), C.c_int(Hkv), C.c_int(D), C.c_int(page),
+            C.c_int(block_table.shape[1]), C.c_int64(P), C.c_int(_DT[dtype]), C.c_double(sm_scale))
+    if fp8kv:
+        k_scale = _chk(k_scale, np.float32, (Hkv,))
+        v_scale = _chk(v_scale, np.float32, (Hkv,))
+        st = lib().oracle_attn_fp8kv(*head, _p(q), _p(k_pages), _p(v_pages), _p(k_scale), _p(v_scale),
+                                     _p(block_table), _p(seq_lens), _p(parents), _p(out))
+    else:
+        st = lib().oracle_attn(*head, _p(q), _p(k_pages), _p(v_pages), _p(block_table), _p(seq_lens),
+                               _p(parents), _p(out))
     if st != 0:
         raise ValueError(f"oracle_attn status {st}")
     return out
@@ -204,10 +214,17 @@ def accept(*, hidden, lm_head, draft_tokens, draft_probs=None, uniforms=None, pa
 
 def verify(w, want_cdf=False, want_logits=False):
     """Both halves on a gen.Workload; returns (attention float64, AcceptResult)."""
-    o = attn(q=w.q, k_pages=w.k_pages, v_pages=w.v_pages, block_table=w.host_block_table(),
-             seq_lens=w.seq_lens, parents=w.parents, dtype=w.dtype)
+    o = attn_workload(w)
     a = accept_workload(w, want_cdf=want_cdf, want_logits=want_logits)
     return o, a
+
+
+def attn_workload(w) -> np.ndarray:
+    """The attention half on a gen.Workload (K/V in the workload's dtype, or E4M3 codes with per-head scales)."""
+    fp8 = getattr(w, "kv_dtype", "") == "fp8"
+    return attn(q=w.q, k_pages=w.k_pages, v_pages=w.v_pages, block_table=w.host_block_table(),
+                seq_lens=w.seq_lens, parents=w.parents, dtype=w.dtype,
+                k_scale=w.k_scale if fp8 else None, v_scale=w.v_scale if fp8 else None)
 
 
 def accept_workload(w, want_cdf=False, want_logits=False) -> AcceptResult:

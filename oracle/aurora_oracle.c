@@ -78,11 +78,24 @@ static int parent_of(const int32_t *parents, int64_t b, int num_q, int n)
  * Query head hq reads KV head hq / (Hq / Hkv).
  * out: double [B, Nq, Hq, D].
  * ---------------------------------------------------------------------- */
-int oracle_attn(int batch, int num_q, int num_q_heads, int num_kv_heads, int head_dim,
-                int page_size, int max_pages_per_seq, int64_t num_pages, int dtype, double sm_scale,
-                const void *q, const void *k_pages, const void *v_pages,
-                const int32_t *block_table, const int32_t *seq_lens, const int32_t *parents,
-                double *out)
+static double decode_e4m3(uint8_t c);
+
+/* Element i of a K or V pool of KV head hk.  kv_dtype ORACLE_KV_E4M3: the pool holds 8-bit E4M3 codes and
+ * the value is scale[hk] * decode(code) (the cache is kept in 8-bit floating point with one float32 scale
+ * per KV head, separately for K and V; queries, scores and the output stay as before). */
+#define ORACLE_KV_E4M3 2
+static double widen_kv(const void *base, int64_t i, int kv_dtype, const float *scale, int hk)
+{
+    if (kv_dtype == ORACLE_KV_E4M3) return (double)scale[hk] * decode_e4m3(((const uint8_t *)base)[i]);
+    return widen(base, i, kv_dtype);
+}
+
+static int attn_impl(int batch, int num_q, int num_q_heads, int num_kv_heads, int head_dim,
+                     int page_size, int max_pages_per_seq, int64_t num_pages, int dtype, int kv_dtype,
+                     double sm_scale, const void *q, const void *k_pages, const void *v_pages,
+                     const float *k_scale, const float *v_scale,
+                     const int32_t *block_table, const int32_t *seq_lens, const int32_t *parents,
+                     double *out)
 {
     if (batch < 0 || num_q < 1 || num_kv_heads < 1 || num_q_heads % num_kv_heads || head_dim < 1 ||
         page_size < 1)
@@ -141,7 +154,7 @@ int oracle_attn(int batch, int num_q, int num_q_heads, int num_kv_heads, int hea
                         (((int64_t)page * num_kv_heads + hk) * page_size + j % page_size) * head_dim;
                     double dot = 0.0;
                     for (int d = 0; d < head_dim; ++d)
-                        dot += widen(q, qoff + d, dtype) * widen(k_pages, koff + d, dtype);
+                        dot += widen(q, qoff + d, dtype) * widen_kv(k_pages, koff + d, kv_dtype, k_scale, hk);
                     score[j] = sm_scale * dot;
                     if (score[j] > smax) smax = score[j];
                 }
@@ -159,7 +172,7 @@ int oracle_attn(int batch, int num_q, int num_q_heads, int num_kv_heads, int hea
                     const int64_t voff =
                         (((int64_t)page * num_kv_heads + hk) * page_size + j % page_size) * head_dim;
                     const double w = score[j] / denom;
-                    for (int d = 0; d < head_dim; ++d) o[d] += w * widen(v_pages, voff + d, dtype);
+                    for (int d = 0; d < head_dim; ++d) o[d] += w * widen_kv(v_pages, voff + d, kv_dtype, v_scale, hk);
                 }
             }
         }
@@ -167,6 +180,30 @@ int oracle_attn(int batch, int num_q, int num_q_heads, int num_kv_heads, int hea
         free(visible);
     }
     return status;
+}
+
+int oracle_attn(int batch, int num_q, int num_q_heads, int num_kv_heads, int head_dim,
+                int page_size, int max_pages_per_seq, int64_t num_pages, int dtype, double sm_scale,
+                const void *q, const void *k_pages, const void *v_pages,
+                const int32_t *block_table, const int32_t *seq_lens, const int32_t *parents,
+                double *out)
+{
+    return attn_impl(batch, num_q, num_q_heads, num_kv_heads, head_dim, page_size, max_pages_per_seq, num_pages,
+                     dtype, dtype, sm_scale, q, k_pages, v_pages, NULL, NULL, block_table, seq_lens, parents, out);
+}
+
+/* The same attention over a cache held as E4M3 codes: k_scale / v_scale are float32 [num_kv_heads]. */
+int oracle_attn_fp8kv(int batch, int num_q, int num_q_heads, int num_kv_heads, int head_dim,
+                      int page_size, int max_pages_per_seq, int64_t num_pages, int dtype, double sm_scale,
+                      const void *q, const uint8_t *k_pages, const uint8_t *v_pages,
+                      const float *k_scale, const float *v_scale,
+                      const int32_t *block_table, const int32_t *seq_lens, const int32_t *parents,
+                      double *out)
+{
+    if (!k_scale || !v_scale) return ORACLE_BAD_ARG;
+    return attn_impl(batch, num_q, num_q_heads, num_kv_heads, head_dim, page_size, max_pages_per_seq, num_pages,
+                     dtype, ORACLE_KV_E4M3, sm_scale, q, k_pages, v_pages, k_scale, v_scale, block_table, seq_lens,
+                     parents, out);
 }
 
 /* ------------------------------------------------------------------------
