@@ -33,6 +33,10 @@ def make_workload(name, seed):
         return gen.llama_chain(seed)
     if name == "llama_fp8head":
         return gen.llama_chain(seed, head_fp8=True)
+    if name == "llama_fp8kv":
+        return gen.llama_chain(seed, kv_fp8=True)
+    if name == "llama_fp8":
+        return gen.llama_chain(seed, kv_fp8=True, head_fp8=True)
     if name == "llama_draft32k":
         return gen.llama_chain(seed, draft_vocab=32000, draft_noise=0.5)
     if name == "tiny":
@@ -65,7 +69,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_draft32k", "tiny", "qwen_greedy", "tree", "stress"])
+    ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_fp8kv", "llama_fp8", "llama_draft32k", "tiny", "qwen_greedy", "tree", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
     ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy"],
@@ -155,7 +159,8 @@ def main():
     esz = 2 if w.dtype == "bf16" else 4
     hsz = 1 if getattr(w, "head_dtype", "") == "fp8" else esz  # bytes per LM-head operand element
     w_bytes = w.vocab * w.hidden_size * hsz + w.batch * w.num_q * w.hidden_size * hsz
-    kv_bytes = int(w.seq_lens.astype(np.int64).sum()) * 2 * w.num_kv_heads * w.head_dim * esz
+    ksz = 1 if getattr(w, "kv_dtype", "") == "fp8" else esz    # bytes per cached K / V element
+    kv_bytes = int(w.seq_lens.astype(np.int64).sum()) * 2 * w.num_kv_heads * w.head_dim * ksz
     lm_gbs = w_bytes / (ms_lmhead * 1e-3) / 1e9
     kv_gbs = kv_bytes / (ms_attn * 1e-3) / 1e9
     lm_flops = 2.0 * w.batch * w.num_q * w.hidden_size * w.vocab
@@ -174,7 +179,8 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": w.dtype if hsz == esz else f"{w.dtype} attention, fp8 (e4m3, per-row scales) LM head",
+        "dtype": w.dtype + ("" if ksz == esz else ", KV cache fp8 (e4m3, per-head scales)")
+                 + ("" if hsz == esz else ", LM head fp8 (e4m3, per-row scales)"),
         "data": "synthetic",
         "config": {"workload": w.recipe, "name": w.name, "batch": w.batch, "k": w.num_q - 1,
                    "context": [int(w.seq_lens.min()), int(w.seq_lens.max())], "page_size": w.page_size,

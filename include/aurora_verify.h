@@ -59,6 +59,16 @@ typedef struct {
   int64_t num_pages;         /* P, pages in each of the K and V pools                        */
   int32_t dtype;             /* AURORA_F32 / AURORA_BF16: type of q, k_pages, v_pages, out   */
   float sm_scale;            /* softmax scale; 0 => 1/sqrt(head_dim)                         */
+  /* KV cache in 8-bit floating point (the paper serves its frontier targets in FP8, sections 1 and 4.3;
+   * what is stored in 8 bits, the format and the scaling are this library's choice).  kv_fp8 = 0: k_pages
+   * and v_pages are of type `dtype`.  kv_fp8 = 1: they hold OCP E4M3 codes, one byte per element, same
+   * [P, Hkv, page_size, D] layout, and a stored element of KV head h stands for k_scale[h] * decode(code)
+   * (v_scale[h] for V); k_scale and v_scale are DEVICE pointers to float32 [Hkv].  q and out stay of type
+   * `dtype`.  The codes are widened exactly to the type the products run in, so the only rounding this
+   * adds is the one the caller made when it quantised the cache. */
+  int32_t kv_fp8;
+  const float* k_scale;
+  const float* v_scale;
 } aurora_attn_desc;
 
 /* Acceptance half: LM head, softmax statistics, acceptance walk, residual / bonus draw. */
@@ -107,7 +117,7 @@ int aurora_verify_workspace_bytes(const aurora_attn_desc* attn, const aurora_acc
  */
 int aurora_verify_attn(const aurora_attn_desc* desc,
                        const void* q,              /* [B, Nq, Hq, D]                          */
-                       const void* k_pages,        /* [P, Hkv, page_size, D]                  */
+                       const void* k_pages,        /* [P, Hkv, page_size, D] (E4M3 codes if kv_fp8) */
                        const void* v_pages,        /* [P, Hkv, page_size, D]                  */
                        const int32_t* block_table, /* [B, max_pages_per_seq]; unused = -1     */
                        const int32_t* seq_lens,    /* [B] KV length INCLUDING the Nq chunk tokens */

@@ -30,7 +30,7 @@ class aurora_attn_desc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("num_q_heads", C.c_int32),
                 ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("page_size", C.c_int32),
                 ("max_pages_per_seq", C.c_int32), ("num_pages", C.c_int64), ("dtype", C.c_int32),
-                ("sm_scale", C.c_float)]
+                ("sm_scale", C.c_float), ("kv_fp8", C.c_int32), ("k_scale", C.c_void_p), ("v_scale", C.c_void_p)]
 
 
 class aurora_accept_desc(C.Structure):

@@ -15,6 +15,8 @@ int check_attn_desc(const aurora_attn_desc* d) {
   if (d->num_q_heads % d->num_kv_heads) return AURORA_ERR_INVALID_ARG;
   if (d->dtype != AURORA_F32 && d->dtype != AURORA_BF16) return AURORA_ERR_INVALID_ARG;
   if (!(d->sm_scale >= 0.f)) return AURORA_ERR_INVALID_ARG;
+  if (d->kv_fp8 != 0 && d->kv_fp8 != 1) return AURORA_ERR_INVALID_ARG;
+  if (d->kv_fp8 && (!d->k_scale || !d->v_scale)) return AURORA_ERR_INVALID_ARG;
   if (d->num_q > kMaxNq) return AURORA_ERR_UNSUPPORTED;
   if (d->head_dim != 64 && d->head_dim != 128) return AURORA_ERR_UNSUPPORTED;
   if ((int64_t)d->batch * d->num_q > 65535 || d->num_q_heads > 65535) return AURORA_ERR_UNSUPPORTED;
@@ -44,6 +46,7 @@ AttnLaunch attn_launch_from(const aurora_attn_desc* d) {
   a.B = d->batch; a.Nq = d->num_q; a.Hq = d->num_q_heads; a.Hkv = d->num_kv_heads; a.D = d->head_dim;
   a.page = d->page_size; a.max_pages = d->max_pages_per_seq; a.bf16 = d->dtype == AURORA_BF16;
   a.scale = d->sm_scale > 0.f ? d->sm_scale : 1.0f / sqrtf((float)d->head_dim);
+  a.kv_fp8 = d->kv_fp8 != 0; a.k_scale = d->k_scale; a.v_scale = d->v_scale;
   return a;
 }
 

@@ -1,5 +1,5 @@
-// Generic chunk attention (any head_dim <= 256, any page size, fp32 or bf16 storage, fp32
-// arithmetic).  It is the fp32 path of the library and the fallback for bf16 shapes the MFMA
+// Generic chunk attention (any head_dim <= 256, any page size, fp32 or bf16 storage - or a KV cache of
+// E4M3 codes with one scale per KV head - fp32 arithmetic).  It is the fp32 path of the library and the fallback for bf16 shapes the MFMA
 // kernel does not cover.  One workgroup per (split, query head, request x node): scores for
 // the split's visible KV positions, a block-wide max / sum, then the weighted value sum; a
 // second kernel merges the splits (sections 3.1 and 3.2 of the paper define what is computed:
@@ -12,9 +12,12 @@ namespace aurora {
 constexpr int kGenThreads = 256;
 constexpr int kGenMaxSplit = 4096;
 
-template <typename T>
+// TKV = T, or e4m3_t with k_scale / v_scale [Hkv]: the scale of the KV head multiplies the scores and
+// the weighted value sum (both are linear in it).
+template <typename T, typename TKV>
 __global__ __launch_bounds__(kGenThreads) void attn_generic_partial(
-    const T* __restrict__ q, const T* __restrict__ kp, const T* __restrict__ vp,
+    const T* __restrict__ q, const TKV* __restrict__ kp, const TKV* __restrict__ vp,
+    const float* __restrict__ k_scale, const float* __restrict__ v_scale,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens,
     const int32_t* __restrict__ parents, float* __restrict__ part_o, float* __restrict__ part_ml,
     int Nq, int Hq, int Hkv, int D, int page, int max_pages, int split_len, int max_splits, float scale) {
@@ -32,6 +35,8 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_partial(
   const int end = min(L, start + split_len);
   const int prefix = L - Nq;
   const int hk = hq / (Hq / Hkv);
+  if (k_scale) scale *= k_scale[hk];
+  const float vs = v_scale ? v_scale[hk] : 1.f;
 
   if (tid == 0) {
     unsigned long long m = 0;
@@ -53,9 +58,9 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_partial(
     float s = -INFINITY;
     if (seen) {
       const int pg = block_table[(size_t)b * max_pages + j / page];
-      const T* kr = kp + (((size_t)pg * Hkv + hk) * page + j % page) * D;
+      const TKV* kr = kp + (((size_t)pg * Hkv + hk) * page + j % page) * D;
       float acc = 0.f;
-      for (int d = 0; d < D; ++d) acc = fmaf(q_s[d], to_f32<T>(kr[d]), acc);
+      for (int d = 0; d < D; ++d) acc = fmaf(q_s[d], to_f32<TKV>(kr[d]), acc);
       s = acc * scale;
     }
     sc[j - start] = s;
@@ -97,7 +102,7 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_partial(
         const float p = sc[j - start];
         if (p != 0.f) {
           const int pg = block_table[(size_t)b * max_pages + j / page];
-          acc = fmaf(p, to_f32<T>(vp[(((size_t)pg * Hkv + hk) * page + j % page) * D + d]), acc);
+          acc = fmaf(p, to_f32<TKV>(vp[(((size_t)pg * Hkv + hk) * page + j % page) * D + d]), acc);
         }
       }
     }
@@ -106,7 +111,7 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_partial(
     if (g == 0 && d < D) {
       float tot = 0.f;
       for (int gg = 0; gg < groups; ++gg) tot += red[gg * D + tid];
-      part_o[pidx * D + d] = tot;
+      part_o[pidx * D + d] = tot * vs;
     }
     __syncthreads();
   }
@@ -143,9 +148,16 @@ __global__ void attn_combine(const float* __restrict__ part_o, const float* __re
 template <typename T>
 static hipError_t launch_generic_t(const AttnLaunch& a, hipStream_t st) {
   dim3 grid(a.plan.max_splits, a.Hq, a.B * a.Nq);
-  hipLaunchKernelGGL(attn_generic_partial<T>, grid, dim3(kGenThreads), 0, st, (const T*)a.q, (const T*)a.k,
-                     (const T*)a.v, a.block_table, a.seq_lens, a.parents, a.part_o, a.part_ml, a.Nq, a.Hq, a.Hkv,
-                     a.D, a.page, a.max_pages, a.plan.split_len, a.plan.max_splits, a.scale);
+  if (a.kv_fp8)
+    hipLaunchKernelGGL((attn_generic_partial<T, e4m3_t>), grid, dim3(kGenThreads), 0, st, (const T*)a.q,
+                       (const e4m3_t*)a.k, (const e4m3_t*)a.v, a.k_scale, a.v_scale, a.block_table, a.seq_lens,
+                       a.parents, a.part_o, a.part_ml, a.Nq, a.Hq, a.Hkv, a.D, a.page, a.max_pages, a.plan.split_len,
+                       a.plan.max_splits, a.scale);
+  else
+    hipLaunchKernelGGL((attn_generic_partial<T, T>), grid, dim3(kGenThreads), 0, st, (const T*)a.q, (const T*)a.k,
+                       (const T*)a.v, (const float*)nullptr, (const float*)nullptr, a.block_table, a.seq_lens,
+                       a.parents, a.part_o, a.part_ml, a.Nq, a.Hq, a.Hkv, a.D, a.page, a.max_pages, a.plan.split_len,
+                       a.plan.max_splits, a.scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return launch_attn_combine(a, st);

@@ -223,6 +223,65 @@ __device__ __forceinline__ void issue_rows(const bf16_t* pool, char* buf, int j,
   load_to_lds_16(src, buf + j * 1024);
 }
 
+// ---- KV cache held as E4M3 codes (one byte per element, one scale per KV head) ----------------------------
+// A 32-token tile of codes is 32 rows x 128 B.  It is loaded into registers (four 16-byte loads per lane for
+// K, four for V: 8 lanes cover a token row, so an instruction covers 8 rows = 1 KB of a page), widened
+// exactly to bf16 in registers and written to the wavefront's LDS tile in the layout the LDS-direct loads
+// of the bf16 path produce, so that the score and P.V code is shared.  The scales are applied outside the
+// products: K's folds into the softmax scale, V's multiplies the segment's partial O.
+struct Tile8 { u32x4_t k[4], v[4]; };
+
+// row of a V load instruction's lane group g: consecutive groups take rows four apart, whose swizzle keys
+// have different parity, so that the sixteen lanes an LDS write instruction serves at a time hit distinct banks
+__device__ __forceinline__ int v_row_of_group(int g) { return ((g & 1) << 2) | (g >> 1); }
+
+__device__ __forceinline__ void load_tile8(Tile8& t, const uint8_t* __restrict__ kp, const uint8_t* __restrict__ vp, int j0,
+                                           int L, int page_shift, int Hkv, int hk, int pid_a, int pid_b, int lane) {
+  const int pa = j0 >> page_shift;
+  const int g = lane >> 3, f = lane & 7;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int tok_k = min(j0 + 8 * i + g, L - 1);
+    const int tok_v = min(j0 + 8 * i + v_row_of_group(g), L - 1);
+    const int pid_k = (tok_k >> page_shift) == pa ? pid_a : pid_b;
+    const int pid_v = (tok_v >> page_shift) == pa ? pid_a : pid_b;
+    const size_t ok = ((((size_t)pid_k * Hkv + hk) << page_shift) + (tok_k & ((1 << page_shift) - 1))) * kAtD + f * 16;
+    const size_t ov = ((((size_t)pid_v * Hkv + hk) << page_shift) + (tok_v & ((1 << page_shift) - 1))) * kAtD + f * 16;
+    t.k[i] = __builtin_nontemporal_load((const u32x4_t*)(kp + ok));
+    t.v[i] = __builtin_nontemporal_load((const u32x4_t*)(vp + ov));
+  }
+}
+
+// sixteen E4M3 codes -> sixteen bf16 (exact: 3 mantissa bits and the exponent range fit), as two 16-byte chunks
+__device__ __forceinline__ void widen16(const u32x4_t c, u32x4_t& lo, u32x4_t& hi) {
+  unsigned int out[8];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)c[w], false);  // bytes 0, 1
+    const f32x2_t b = __builtin_amdgcn_cvt_pk_f32_fp8((int)c[w], true);   // bytes 2, 3
+    out[2 * w] = __builtin_bit_cast(unsigned int, __builtin_convertvector(a, bf16x2_t));
+    out[2 * w + 1] = __builtin_bit_cast(unsigned int, __builtin_convertvector(b, bf16x2_t));
+  }
+  lo = u32x4_t{out[0], out[1], out[2], out[3]};
+  hi = u32x4_t{out[4], out[5], out[6], out[7]};
+}
+
+__device__ __forceinline__ void spill_tile8(const Tile8& t, char* kbuf, char* vbuf, int lane) {
+  const int g = lane >> 3, f = lane & 7;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    u32x4_t lo, hi;
+    const int rk = 8 * i + g;
+    widen16(t.k[i], lo, hi);
+    *(u32x4_t*)(kbuf + rk * kAtRowBytes + (((2 * f) ^ (rk & 15)) * 16)) = lo;
+    *(u32x4_t*)(kbuf + rk * kAtRowBytes + (((2 * f + 1) ^ (rk & 15)) * 16)) = hi;
+    const int rv = 8 * i + v_row_of_group(g);
+    widen16(t.v[i], lo, hi);
+    *(u32x4_t*)(vbuf + rv * kAtRowBytes + (((2 * f) ^ v_key(rv)) * 16)) = lo;
+    *(u32x4_t*)(vbuf + rv * kAtRowBytes + (((2 * f + 1) ^ v_key(rv)) * 16)) = hi;
+  }
+}
+
 // prefix of tiles per request (see attn_plan_kernel) built by the whole workgroup into s_pb[0..B], B <= 1024
 __device__ __forceinline__ void build_prefix(const int32_t* __restrict__ seq_lens, int B, int Hkv, int* s_pb,
                                              int* s_wsum) {
@@ -254,12 +313,17 @@ __device__ __forceinline__ void build_prefix(const int32_t* __restrict__ seq_len
 
 constexpr int kLocalPlanMax = 1024;  // up to this many requests every workgroup builds the prefix itself
 
-template <bool kLocalPlan>
+// kFp8KV: kp_ / vp_ hold E4M3 codes and k_scale / v_scale [Hkv] their per-head scales (see Tile8 above);
+// otherwise bf16 pools, loaded straight into LDS.
+template <bool kLocalPlan, bool kFp8KV>
 __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
+    const bf16_t* __restrict__ q, const void* __restrict__ kp_, const void* __restrict__ vp_,
+    const float* __restrict__ k_scale, const float* __restrict__ v_scale,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens,
     const int32_t* __restrict__ parents, int32_t* __restrict__ PB, float* __restrict__ part_o,
-    float* __restrict__ part_ml, int B, int Nq, int Hq, int Hkv, int page_shift, int max_pages, float scale_log2) {
+    float* __restrict__ part_ml, int B, int Nq, int Hq, int Hkv, int page_shift, int max_pages, float scale_log2_q) {
+  const bf16_t* kp = (const bf16_t*)kp_;
+  const bf16_t* vp = (const bf16_t*)vp_;
   // K and V tiles live in separate LDS objects: the compiler tracks pending LDS-direct loads per object,
   // so a read of a K tile does not wait for the V tile still in flight (and vice versa)
   __shared__ __attribute__((aligned(1024))) char kbuf_all[4 * kAtTileBytes];
@@ -329,6 +393,7 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
 
     const int start = t0 * kAtTile;
     const int prefix = L - Nq;
+    const float scale_log2 = kFp8KV ? scale_log2_q * k_scale[hk] : scale_log2_q;
     {
       // 32 query rows -> LDS, 16-byte chunks swizzled like the K rows (they are read the same way)
       const u32x4_t* qp = (const u32x4_t*)(q + (((size_t)b * Nq + qs_node) * Hq + hk * G + qs_g) * kAtD);
@@ -375,6 +440,41 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
     softmax_state_reset(st);
 
     __syncthreads();  // query rows staged (nothing is in flight yet, so the fence costs nothing)
+    if constexpr (kFp8KV) {
+      // This wavefront's tiles are wv, wv + 4, ...; two of them are always on their way into registers.
+      // Loads past the wavefront's last tile re-read that tile (cache hits), so the loop body is straight
+      // code and the compiler's wait counts leave the younger tile in flight.
+      const int n_my = ntile > wv ? (ntile - wv + 3) >> 2 : 0;
+      if (n_my > 0) {
+        const uint8_t* kp8 = (const uint8_t*)kp_;
+        const uint8_t* vp8 = (const uint8_t*)vp_;
+        auto fetch = [&](Tile8& t, int i) {
+          const int tile = wv + 4 * min(i, n_my - 1);
+          int pa, pb;
+          tile_pages(tile, pa, pb);
+          load_tile8(t, kp8, vp8, start + tile * kAtTile, L, page_shift, Hkv, hk, pa, pb, lane);
+        };
+        // `live` is wave-uniform; a dead turn (odd tile count) still spills and fetches, so that the order
+        // of loads and waits is the same on every path
+        auto consume = [&](Tile8& t, int i, bool live) {
+          spill_tile8(t, kbuf, vbuf, lane);
+          fetch(t, i + 2);
+          if (live) {
+            const f32x16_t s_acc = tile_scores(kbuf, qbuf, li, lh);
+            bf16x8_t pb2[2];
+            tile_softmax(s_acc, st, pb2, scale_log2, start + (wv + 4 * i) * kAtTile, prefix, L, anc, lh);
+            tile_pv(vbuf, pb2, st, lane);
+          }
+        };
+        Tile8 ta, tb;
+        fetch(ta, 0);
+        fetch(tb, 1);
+        for (int i = 0; i < n_my; i += 2) {
+          consume(ta, i, true);
+          consume(tb, i + 1, i + 1 < n_my);
+        }
+      }
+    } else {
     int tt = wv;
     if (tt < ntile) {
       int pa0, pb0;
@@ -400,6 +500,7 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
       asm volatile("" ::: "memory");
       if (more) issue_v(tt + 4, npa, npb);
     }
+    }
     f32x16_t(&o_acc)[4] = st.o;
     const float m_run = st.m_run, l_half = st.l_half;
 
@@ -414,7 +515,7 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
     float l_tot = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) l_tot += s_l[w][li] * __builtin_amdgcn_exp2f(s_m[w][li] - M_safe);
-    const float f_own = __builtin_amdgcn_exp2f(m_run - M_safe);
+    const float f_own = __builtin_amdgcn_exp2f(m_run - M_safe) * (kFp8KV ? v_scale[hk] : 1.f);
     // each wavefront parks its rescaled O^T as [row li][64 d] floats in its K buffer (columns 0..63)
     // and its V buffer (columns 64..127)
 #pragma unroll
@@ -691,7 +792,9 @@ __global__ __launch_bounds__(kAtD) void attn_mfma_combine(const float* __restric
 }
 
 bool attn_mfma_supported(const AttnLaunch& a) {
-  return a.bf16 && a.D == kAtD && a.page >= 16 && (a.page & (a.page - 1)) == 0;
+  if (!(a.bf16 && a.D == kAtD && a.page >= 16 && (a.page & (a.page - 1)) == 0)) return false;
+  // an 8-bit KV cache is taken by the 32-row kernel only (chains; trees of few nodes)
+  return !a.kv_fp8 || a.Hq / a.Hkv * a.Nq <= 32;
 }
 
 constexpr int kWideWorkgroups = 256;  // one per compute unit
@@ -712,14 +815,16 @@ hipError_t launch_attn_mfma(const AttnLaunch& a, hipStream_t st) {
   if (row_tiles == 1) {
     wgs = kAttnWorkgroups;
     dim3 grid(wgs, 1);
-    if (local_plan)
-      hipLaunchKernelGGL(attn_mfma_kernel<true>, grid, dim3(kAtThreads), 0, st, (const bf16_t*)a.q, (const bf16_t*)a.k,
-                         (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, a.plan_pb, a.part_o, a.part_ml, a.B,
-                         a.Nq, a.Hq, a.Hkv, shift, a.max_pages, sc);
-    else
-      hipLaunchKernelGGL(attn_mfma_kernel<false>, grid, dim3(kAtThreads), 0, st, (const bf16_t*)a.q, (const bf16_t*)a.k,
-                         (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, a.plan_pb, a.part_o, a.part_ml, a.B,
-                         a.Nq, a.Hq, a.Hkv, shift, a.max_pages, sc);
+#define AURORA_LAUNCH_NARROW(LOCAL, FP8)                                                                            \
+  hipLaunchKernelGGL((attn_mfma_kernel<LOCAL, FP8>), grid, dim3(kAtThreads), 0, st, (const bf16_t*)a.q, a.k, a.v,    \
+                     a.k_scale, a.v_scale, a.block_table, a.seq_lens, a.parents, a.plan_pb, a.part_o, a.part_ml, a.B, \
+                     a.Nq, a.Hq, a.Hkv, shift, a.max_pages, sc)
+    if (local_plan) {
+      if (a.kv_fp8) AURORA_LAUNCH_NARROW(true, true); else AURORA_LAUNCH_NARROW(true, false);
+    } else {
+      if (a.kv_fp8) AURORA_LAUNCH_NARROW(false, true); else AURORA_LAUNCH_NARROW(false, false);
+    }
+#undef AURORA_LAUNCH_NARROW
   } else {
     wgs = kWideWorkgroups;
     static LdsAttrOnce attr_local, attr_global;

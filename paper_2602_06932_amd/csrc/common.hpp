@@ -24,6 +24,19 @@ template <typename T> __device__ __forceinline__ float to_f32(T v);
 template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
 
+// One byte of an 8-bit floating-point tensor: OCP E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa
+// bits; exponent field 0 is subnormal, no infinities).  Decoded with integer operations here; the
+// matrix-core kernels use the hardware conversion.
+struct e4m3_t { uint8_t bits; };
+__device__ __forceinline__ float e4m3_to_f32(uint8_t c) {
+  const uint32_t sign = (uint32_t)(c & 0x80u) << 24;
+  const uint32_t e = (c >> 3) & 15u, m = c & 7u;
+  if (e == 15u && m == 7u) return __uint_as_float(sign | 0x7fc00000u);  // the format's only NaN
+  if (e == 0u) return __uint_as_float(sign | __float_as_uint((float)m * 0.001953125f));  // m * 2^-9
+  return __uint_as_float(sign | ((e + 120u) << 23) | (m << 20));
+}
+template <> __device__ __forceinline__ float to_f32<e4m3_t>(e4m3_t v) { return e4m3_to_f32(v.bits); }
+
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }

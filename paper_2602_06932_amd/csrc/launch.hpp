@@ -7,6 +7,8 @@ namespace aurora {
 struct AttnLaunch {
   int B, Nq, Hq, Hkv, D, page, max_pages;
   bool bf16;
+  bool kv_fp8;                     // k / v hold E4M3 codes; a value of KV head h is k_scale[h] * decode(code)
+  const float *k_scale, *v_scale;  // [Hkv] when kv_fp8
   float scale;
   const void *q, *k, *v;
   const int32_t *block_table, *seq_lens, *parents;

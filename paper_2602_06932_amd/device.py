@@ -30,13 +30,16 @@ class DeviceVerify:
         self.dt = B.AURORA_BF16 if bf16 else B.AURORA_F32
         self.q = _to_dev(w.q, w.dtype)
         page_ids = getattr(w, "page_ids", None)
+        kv_fp8 = getattr(w, "kv_dtype", "") == "fp8"    # uint8 E4M3 codes with one scale per KV head
+        self.k_scale = _to_dev(w.k_scale, None) if kv_fp8 else None
+        self.v_scale = _to_dev(w.v_scale, None) if kv_fp8 else None
         if page_ids is None:
             self.k_pages = _to_dev(w.k_pages, w.dtype)
             self.v_pages = _to_dev(w.v_pages, w.dtype)
         else:
             # sparse pool: allocate the whole pool, fill only the referenced pages
             shape = (int(w.num_pages),) + tuple(w.k_pages.shape[1:])
-            tdt = torch.bfloat16 if bf16 else torch.float32
+            tdt = torch.uint8 if kv_fp8 else torch.bfloat16 if bf16 else torch.float32
             self.k_pages = torch.empty(shape, dtype=tdt, device="cuda")
             self.v_pages = torch.empty(shape, dtype=tdt, device="cuda")
             idx = torch.from_numpy(np.asarray(page_ids, dtype=np.int64)).cuda()
@@ -59,7 +62,8 @@ class DeviceVerify:
         self.attn_desc = B.aurora_attn_desc(
             batch=w.batch, num_q=w.num_q, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads,
             head_dim=w.head_dim, page_size=w.page_size, max_pages_per_seq=int(w.block_table.shape[1]),
-            num_pages=int(w.num_pages), dtype=self.dt, sm_scale=0.0)
+            num_pages=int(w.num_pages), dtype=self.dt, sm_scale=0.0, kv_fp8=1 if kv_fp8 else 0,
+            k_scale=self.k_scale.data_ptr() if kv_fp8 else None, v_scale=self.v_scale.data_ptr() if kv_fp8 else None)
         # a draft model with its own vocabulary: the target -> draft index map goes with the descriptor
         t2d = w.target_to_draft() if getattr(w, "draft_to_target", None) is not None else None
         self.target_to_draft = _to_dev(t2d, None)

@@ -45,6 +45,17 @@ def test_host_validation_without_device():
     bad.temperature = -1.0
     with pytest.raises(av.AuroraError):
         av.aurora_verify_workspace_bytes(None, bad)
+    # an 8-bit KV cache needs both scale arrays; the flag is 0 or 1; the workspace does not depend on it here
+    bad = av.aurora_attn_desc.from_buffer_copy(ad)
+    bad.kv_fp8 = 1
+    with pytest.raises(av.AuroraError) as e:
+        av.aurora_verify_workspace_bytes(bad, None)
+    assert e.value.status == av.AURORA_ERR_INVALID_ARG
+    bad.k_scale, bad.v_scale = 256, 512
+    assert av.aurora_verify_workspace_bytes(bad, None) == av.aurora_verify_workspace_bytes(ad, None)
+    bad.kv_fp8 = 2
+    with pytest.raises(av.AuroraError):
+        av.aurora_verify_workspace_bytes(bad, None)
     # trace emission: descriptor and pointer checks come before any device is touched
     td = av.aurora_trace_desc(batch=2, num_q=5, vocab=100, top_k=8)
     assert av.aurora_trace_emit(None, 16, None, None, None, None, 16, 16, None, None, stream=0, check=False) \

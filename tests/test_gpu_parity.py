@@ -483,3 +483,45 @@ def test_tree_verify_step_replays_from_a_captured_graph(gpu_lib):
             assert np.array_equal(ref[k], got[k]), (i, k)
         dv.accept()  # eager work on the same workspace between replays
         torch.cuda.synchronize()
+
+
+# ---- KV cache held as E4M3 codes with one scale per KV head ------------------------------------------------
+@pytest.mark.parametrize("seed,batch,lens", [(61, 6, (40, 700)), (62, 3, (5, 33)), (63, 9, (100, 2100))])
+def test_fp8_kv_chain(gpu_lib, seed, batch, lens):
+    """Chains over an 8-bit cache: the 32-row matrix-core kernel widens the codes in registers."""
+    w = gen.llama_chain(seed, batch=batch, len_lo=lens[0], len_hi=lens[1], vocab=2000, hidden_size=128, kv_fp8=True)
+    assert w.k_pages.dtype == np.uint8
+    _full_check(gpu_lib, w)
+
+
+@pytest.mark.parametrize("page", [32, 256])
+def test_fp8_kv_larger_pages(gpu_lib, page):
+    w = gen.llama_chain(64, batch=4, len_lo=30, len_hi=900, vocab=1500, hidden_size=128, page_size=page, kv_fp8=True)
+    _full_check(gpu_lib, w)
+
+
+def test_fp8_kv_other_shapes_take_the_generic_kernel(gpu_lib):
+    """More than 32 query rows per KV head (a 16-node tree with 4 query heads per KV head), a page size that is
+    not a power of two, head_dim 64, and an fp32 query with an 8-bit cache."""
+    w = gen.llama_tree(65, batch=3, num_q=16, vocab=1500, hidden_size=128, context=200, num_q_heads=8, num_kv_heads=2,
+                       kv_fp8=True)
+    _full_check(gpu_lib, w)
+    w = gen.llama_chain(66, batch=3, len_lo=30, len_hi=300, vocab=1500, hidden_size=128, page_size=24, kv_fp8=True)
+    _full_check(gpu_lib, w)
+    w = gen.llama_chain(67, batch=3, len_lo=30, len_hi=300, vocab=1500, hidden_size=128, head_dim=64, num_q_heads=4,
+                        num_kv_heads=2, kv_fp8=True)
+    _full_check(gpu_lib, w)
+    w = gen.tiny_chain(68, kv_fp8=True)
+    _full_check(gpu_lib, w)
+
+
+def test_fp8_kv_small_tree_on_the_matrix_cores(gpu_lib):
+    w = gen.llama_tree(69, batch=4, num_q=8, vocab=1500, hidden_size=128, context=500, num_q_heads=8, num_kv_heads=2,
+                       kv_fp8=True)
+    _full_check(gpu_lib, w)
+
+
+def test_full_size_llama_chain_with_fp8_kv(gpu_lib):
+    """Config 2 with the cache in 8 bits; requests sampled for the oracle."""
+    w = gen.llama_chain(1, kv_fp8=True)
+    _full_check(gpu_lib, w, sample=[0, 13, 31])
