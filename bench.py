@@ -45,6 +45,8 @@ def make_workload(name, seed):
         return gen.qwen_greedy_chain(seed)
     if name == "tree":
         return gen.llama_tree(seed)
+    if name == "tree_fp8kv":
+        return gen.llama_tree(seed, kv_fp8=True)
     if name == "stress":
         import torch
         pool_bytes = int(0.40 * torch.cuda.get_device_properties(0).total_memory)
@@ -69,7 +71,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_fp8kv", "llama_fp8", "llama_draft32k", "tiny", "qwen_greedy", "tree", "stress"])
+    ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_fp8kv", "llama_fp8", "llama_draft32k", "tiny", "qwen_greedy", "tree", "tree_fp8kv", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
     ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy"],

@@ -567,13 +567,19 @@ constexpr int kWideStageBytes = 2 * 2 * kAtTileBytes;                // two tile
 constexpr int kWideQBytes = 4 * 32 * kAtRowBytes;                    // four query tiles
 constexpr int kWideLdsBytes = kWideQBytes + kWideStages * kWideStageBytes;
 
-template <bool kLocalPlan>
+// kFp8KV: the cache holds E4M3 codes (see Tile8 above).  A wavefront then fetches its eighth of a step - four
+// token rows of K in lanes 0..31, of V in lanes 32..63, for each of the step's two tiles - into registers
+// two steps ahead, and widens it into the ring stage right before the step's barrier.
+template <bool kLocalPlan, bool kFp8KV>
 __global__ __launch_bounds__(kWideThreads, 1) void attn_mfma_wide_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
+    const bf16_t* __restrict__ q, const void* __restrict__ kp_, const void* __restrict__ vp_,
+    const float* __restrict__ k_scale, const float* __restrict__ v_scale,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens,
     const int32_t* __restrict__ parents, int32_t* __restrict__ PB, float* __restrict__ part_o,
     float* __restrict__ part_ml, int B, int Nq, int Hq, int Hkv, int page_shift, int max_pages, int row_tiles,
-    float scale_log2) {
+    float scale_log2_q) {
+  const bf16_t* kp = (const bf16_t*)kp_;
+  const bf16_t* vp = (const bf16_t*)vp_;
   extern __shared__ __attribute__((aligned(1024))) char wlds[];
   char* qall = wlds;
   char* ring = wlds + kWideQBytes;
@@ -659,6 +665,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void attn_mfma_wide_kernel(
     const int nstep = (ntile + 1) >> 1;
     const int last_tile_start = ((L - 1) >> 5) << 5;
     const int32_t* bt = block_table + (size_t)b * max_pages;
+    const float scale_log2 = kFp8KV ? scale_log2_q * k_scale[hk] : scale_log2_q;
 
     // the four query tiles -> LDS
 #pragma unroll
@@ -702,13 +709,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void attn_mfma_wide_kernel(
     SoftmaxState st;
     softmax_state_reset(st);
     __syncthreads();  // query tiles staged; the ring is idle
-    for (int i = 0; i < kWideStages - 1 && i < nstep; ++i) issue_step(i);
-    for (int sidx = 0; sidx < nstep; ++sidx) {
-      // steps sidx+1 .. sidx+kWideStages-2 may stay in flight; near the end of the segment fewer were issued
-      if (nstep - 1 - sidx >= kWideStages - 2) WAIT_VMCNT(4 * (kWideStages - 2)); else WAIT_VMCNT(0);
-      __builtin_amdgcn_s_barrier();  // step complete from all eight wavefronts; the previous step's stage is free
-      asm volatile("" ::: "memory");
-      if (sidx + kWideStages - 1 < nstep) issue_step(sidx + kWideStages - 1);
+    auto compute_step = [&](int sidx) {
       const int tt = 2 * sidx + grp;
       if (rt_ok && tt < ntile) {
         const char* kb = ring + (sidx % kWideStages) * kWideStageBytes + grp * (2 * kAtTileBytes);
@@ -717,7 +718,68 @@ __global__ __launch_bounds__(kWideThreads, 1) void attn_mfma_wide_kernel(
         tile_softmax(s_acc, st, pb2, scale_log2, start + tt * kAtTile, prefix, L, anc, lh);
         tile_pv(kb + kAtTileBytes, pb2, st, lane);
       }
-      asm volatile("" ::: "memory");
+    };
+    if constexpr (kFp8KV) {
+      struct Step8 { u32x4_t t[2]; };
+      const bool is_v = lane >= 32;
+      const int r8 = 4 * wave + ((lane & 31) >> 3), f8 = lane & 7;  // token row of the tile, 16-byte chunk of its codes
+      const uint8_t* pool8 = (const uint8_t*)(is_v ? vp_ : kp_);
+      // steps past the segment's last re-read it: every turn of the loop below has the same loads and waits
+      auto fetch = [&](Step8& r, int sidx) {
+        const int sc = min(sidx, nstep - 1);
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          const int j0 = min(start + (2 * sc + g) * kAtTile, last_tile_start);
+          const int pid_a = bt[j0 >> page_shift];
+          const int pid_b = bt[min(j0 + 16, L - 1) >> page_shift];
+          const int tok = min(j0 + r8, L - 1);
+          const int pid = (tok >> page_shift) == (j0 >> page_shift) ? pid_a : pid_b;
+          const size_t off = ((((size_t)pid * Hkv + hk) << page_shift) + (tok & ((1 << page_shift) - 1))) * kAtD + f8 * 16;
+          r.t[g] = __builtin_nontemporal_load((const u32x4_t*)(pool8 + off));
+        }
+      };
+      auto spill = [&](const Step8& r, int sidx) {
+        char* stage = ring + (sidx % kWideStages) * kWideStageBytes + (is_v ? kAtTileBytes : 0);
+        const int key = is_v ? v_key(r8) : (r8 & 15);
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          u32x4_t lo, hi;
+          widen16(r.t[g], lo, hi);
+          char* row = stage + g * (2 * kAtTileBytes) + r8 * kAtRowBytes;
+          *(u32x4_t*)(row + (((2 * f8) ^ key) * 16)) = lo;
+          *(u32x4_t*)(row + (((2 * f8 + 1) ^ key) * 16)) = hi;
+        }
+      };
+      // A turn writes stage sidx % 3 while slower wavefronts may still read stage (sidx - 1) % 3; the stage it
+      // overwrites was last read two barriers ago.
+      auto turn = [&](Step8& r, int sidx, bool live) {
+        spill(r, sidx);
+        // LDS writes done, then the bare barrier: a fenced one would also wait for the loads in flight
+        __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0) only
+        __builtin_amdgcn_s_barrier();  // the step's stage is complete from all eight wavefronts
+        asm volatile("" ::: "memory");
+        fetch(r, sidx + 2);
+        if (live) compute_step(sidx);
+      };
+      Step8 ra, rb;
+      fetch(ra, 0);
+      __builtin_amdgcn_sched_barrier(0);  // issue order = use order, or the first wait covers both steps
+      fetch(rb, 1);
+      for (int sidx = 0; sidx < nstep; sidx += 2) {
+        turn(ra, sidx, true);
+        turn(rb, sidx + 1, sidx + 1 < nstep);  // nstep is the same for the whole workgroup
+      }
+    } else {
+      for (int i = 0; i < kWideStages - 1 && i < nstep; ++i) issue_step(i);
+      for (int sidx = 0; sidx < nstep; ++sidx) {
+        // steps sidx+1 .. sidx+kWideStages-2 may stay in flight; near the end of the segment fewer were issued
+        if (nstep - 1 - sidx >= kWideStages - 2) WAIT_VMCNT(4 * (kWideStages - 2)); else WAIT_VMCNT(0);
+        __builtin_amdgcn_s_barrier();  // step complete from all eight wavefronts; the previous step's stage is free
+        asm volatile("" ::: "memory");
+        if (sidx + kWideStages - 1 < nstep) issue_step(sidx + kWideStages - 1);
+        compute_step(sidx);
+        asm volatile("" ::: "memory");
+      }
     }
 
     // each wavefront writes the partial of its own query tile and tile parity
@@ -729,6 +791,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void attn_mfma_wide_kernel(
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           f32x4_t o = {st.o[db][4 * g], st.o[db][4 * g + 1], st.o[db][4 * g + 2], st.o[db][4 * g + 3]};
+          if constexpr (kFp8KV) o *= v_scale[hk];
           *(f32x4_t*)(part_o + prow * kAtD + 32 * db + 8 * g + 4 * lh) = o;
         }
       if (lh == 0) {
@@ -792,9 +855,7 @@ __global__ __launch_bounds__(kAtD) void attn_mfma_combine(const float* __restric
 }
 
 bool attn_mfma_supported(const AttnLaunch& a) {
-  if (!(a.bf16 && a.D == kAtD && a.page >= 16 && (a.page & (a.page - 1)) == 0)) return false;
-  // an 8-bit KV cache is taken by the 32-row kernel only (chains; trees of few nodes)
-  return !a.kv_fp8 || a.Hq / a.Hkv * a.Nq <= 32;
+  return a.bf16 && a.D == kAtD && a.page >= 16 && (a.page & (a.page - 1)) == 0;
 }
 
 constexpr int kWideWorkgroups = 256;  // one per compute unit
@@ -827,20 +888,22 @@ hipError_t launch_attn_mfma(const AttnLaunch& a, hipStream_t st) {
 #undef AURORA_LAUNCH_NARROW
   } else {
     wgs = kWideWorkgroups;
-    static LdsAttrOnce attr_local, attr_global;
-    e = attr_local.ensure((const void*)attn_mfma_wide_kernel<true>, kWideLdsBytes);
-    if (e != hipSuccess) return e;
-    e = attr_global.ensure((const void*)attn_mfma_wide_kernel<false>, kWideLdsBytes);
-    if (e != hipSuccess) return e;
     dim3 grid(wgs, (row_tiles + 3) / 4);
-    if (local_plan)
-      hipLaunchKernelGGL(attn_mfma_wide_kernel<true>, grid, dim3(kWideThreads), kWideLdsBytes, st, (const bf16_t*)a.q,
-                         (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, a.plan_pb,
-                         a.part_o, a.part_ml, a.B, a.Nq, a.Hq, a.Hkv, shift, a.max_pages, row_tiles, sc);
-    else
-      hipLaunchKernelGGL(attn_mfma_wide_kernel<false>, grid, dim3(kWideThreads), kWideLdsBytes, st, (const bf16_t*)a.q,
-                         (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, a.plan_pb,
-                         a.part_o, a.part_ml, a.B, a.Nq, a.Hq, a.Hkv, shift, a.max_pages, row_tiles, sc);
+#define AURORA_LAUNCH_WIDE(LOCAL, FP8)                                                                             \
+  do {                                                                                                              \
+    static LdsAttrOnce attr;                                                                                        \
+    e = attr.ensure((const void*)attn_mfma_wide_kernel<LOCAL, FP8>, kWideLdsBytes);                                 \
+    if (e != hipSuccess) return e;                                                                                  \
+    hipLaunchKernelGGL((attn_mfma_wide_kernel<LOCAL, FP8>), grid, dim3(kWideThreads), kWideLdsBytes, st,            \
+                       (const bf16_t*)a.q, a.k, a.v, a.k_scale, a.v_scale, a.block_table, a.seq_lens, a.parents,    \
+                       a.plan_pb, a.part_o, a.part_ml, a.B, a.Nq, a.Hq, a.Hkv, shift, a.max_pages, row_tiles, sc);  \
+  } while (0)
+    if (local_plan) {
+      if (a.kv_fp8) AURORA_LAUNCH_WIDE(true, true); else AURORA_LAUNCH_WIDE(true, false);
+    } else {
+      if (a.kv_fp8) AURORA_LAUNCH_WIDE(false, true); else AURORA_LAUNCH_WIDE(false, false);
+    }
+#undef AURORA_LAUNCH_WIDE
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;

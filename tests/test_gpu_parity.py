@@ -500,12 +500,22 @@ def test_fp8_kv_larger_pages(gpu_lib, page):
     _full_check(gpu_lib, w)
 
 
-def test_fp8_kv_other_shapes_take_the_generic_kernel(gpu_lib):
-    """More than 32 query rows per KV head (a 16-node tree with 4 query heads per KV head), a page size that is
-    not a power of two, head_dim 64, and an fp32 query with an 8-bit cache."""
-    w = gen.llama_tree(65, batch=3, num_q=16, vocab=1500, hidden_size=128, context=200, num_q_heads=8, num_kv_heads=2,
-                       kv_fp8=True)
+@pytest.mark.parametrize("num_q,context", [(16, 200), (32, 1000), (23, 77)])
+def test_fp8_kv_tree_with_many_query_rows(gpu_lib, num_q, context):
+    """More than 32 query rows per KV head: the wide matrix-core kernel stages the codes through registers into its ring."""
+    w = gen.llama_tree(65 + num_q, batch=3, num_q=num_q, vocab=1500, hidden_size=128, context=context, num_q_heads=8,
+                       num_kv_heads=2, kv_fp8=True)
     _full_check(gpu_lib, w)
+
+
+def test_full_size_tree_with_fp8_kv(gpu_lib):
+    """Config 4 with the cache in 8 bits; requests sampled for the oracle."""
+    w = gen.llama_tree(1, kv_fp8=True)
+    _full_check(gpu_lib, w, sample=[0, 9])
+
+
+def test_fp8_kv_other_shapes_take_the_generic_kernel(gpu_lib):
+    """A page size that is not a power of two, head_dim 64, and an fp32 query with an 8-bit cache."""
     w = gen.llama_chain(66, batch=3, len_lo=30, len_hi=300, vocab=1500, hidden_size=128, page_size=24, kv_fp8=True)
     _full_check(gpu_lib, w)
     w = gen.llama_chain(67, batch=3, len_lo=30, len_hi=300, vocab=1500, hidden_size=128, head_dim=64, num_q_heads=4,
