@@ -200,6 +200,35 @@ const float* aurora_verify_logits_ptr(const aurora_attn_desc* attn_desc, const a
                                       const void* workspace);
 
 /*
+ * Debug check of the device-resident inputs of a verify step.  The calls above validate descriptors and
+ * pointers on the host only; what the device arrays hold is trusted, and a page id, length, parent or
+ * token id out of range would make a kernel read or write outside its buffers.  This call (for callers
+ * who want to find such an input first; it is not part of the verify step and costs two small launches)
+ * reads the arrays - never outside the shapes the descriptors declare - and writes, asynchronously on
+ * `hip_stream`, to flags (DEVICE pointer, int32 [6]):
+ *   flags[0]  OR of AURORA_CHECK_* bits, 0 if everything is in range
+ *   flags[1 + i], i = 0..4: the lowest request index with an error of kind (1 << i), or INT32_MAX
+ * Checked, each only if its array is given (NULL arrays are skipped; attn / accept may each be NULL when
+ * none of its arrays is given):
+ *   AURORA_CHECK_SEQ_LEN   seq_lens[b] >= num_q and ceil(seq_lens[b] / page_size) <= max_pages_per_seq
+ *   AURORA_CHECK_PAGE_ID   block_table[b, i] in [0, num_pages) for the pages seq_lens[b] uses
+ *                          (skipped for a request whose length failed)
+ *   AURORA_CHECK_PARENT    parents[b, 0] == -1 and 0 <= parents[b, n] < n
+ *   AURORA_CHECK_TOKEN     draft_tokens[b, n] in [0, vocab) for n >= 1
+ *   AURORA_CHECK_UNIFORM   uniforms in [0, 1) (NaN fails)
+ * Returns AURORA_ERR_INVALID_ARG for a NULL flags pointer, an array without the descriptor that gives its
+ * shape, or descriptors that disagree on batch / num_q.
+ */
+enum {
+  AURORA_CHECK_SEQ_LEN = 1, AURORA_CHECK_PAGE_ID = 2, AURORA_CHECK_PARENT = 4, AURORA_CHECK_TOKEN = 8,
+  AURORA_CHECK_UNIFORM = 16
+};
+int aurora_verify_check_inputs(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,
+                               const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents,
+                               const int32_t* draft_tokens, const float* uniforms, int32_t* flags,
+                               void* hip_stream);
+
+/*
  * Trace emission: what the inference server hands to the training side after a verify step
  * (paper section 3.1: outcomes of accepted and rejected tokens are both streamed; appendix A.1,
  * eq. 4: a record is (h, l, x_in, y_out, R); appendix A.2: only the K largest target logits of a

@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_v
 
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
            "aurora_verify_lmhead", "aurora_verify_accept_logits", "aurora_trace_emit",
-           "aurora_verify_logits_ptr", "aurora_status_string")
+           "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs")
 
 
 class aurora_attn_desc(C.Structure):
@@ -80,6 +80,8 @@ def load():
     lib.aurora_verify_accept_logits.restype = C.c_int
     lib.aurora_trace_emit.argtypes = [C.POINTER(aurora_trace_desc), vp, i32p, i32p, i32p, u8p, i32p, vp, i32p, vp, vp]
     lib.aurora_trace_emit.restype = C.c_int
+    lib.aurora_verify_check_inputs.argtypes = [ad, cd, i32p, i32p, i32p, i32p, f32p, i32p, vp]
+    lib.aurora_verify_check_inputs.restype = C.c_int
     lib.aurora_verify_logits_ptr.argtypes = [ad, cd, vp]
     lib.aurora_verify_logits_ptr.restype = C.c_void_p
     lib.aurora_status_string.argtypes = [C.c_int]
@@ -189,6 +191,20 @@ def aurora_verify(attn_desc, accept_desc, q, k_pages, v_pages, block_table, seq_
                               _ptr(row_lse), _ptr(workspace), wb, _stream(stream))
     if check and st != AURORA_OK:
         raise AuroraError(st, "aurora_verify")
+    return st
+
+
+AURORA_CHECK_SEQ_LEN, AURORA_CHECK_PAGE_ID, AURORA_CHECK_PARENT, AURORA_CHECK_TOKEN, AURORA_CHECK_UNIFORM = 1, 2, 4, 8, 16
+
+
+def aurora_verify_check_inputs(attn_desc, accept_desc, block_table, seq_lens, parents, draft_tokens, uniforms, flags,
+                               stream=None, check=True) -> int:
+    """Debug check of device-resident inputs; `flags` is an int32 device tensor of 6 entries."""
+    st = load().aurora_verify_check_inputs(_ref(attn_desc), _ref(accept_desc), _ptr(block_table), _ptr(seq_lens),
+                                           _ptr(parents), _ptr(draft_tokens), _ptr(uniforms), _ptr(flags),
+                                           _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_verify_check_inputs")
     return st
 
 

@@ -311,6 +311,28 @@ const float* aurora_verify_logits_ptr(const aurora_attn_desc* attn_desc, const a
   return (const float*)((const char*)workspace + off + plan_accept(accept_desc).logits_off);
 }
 
+int aurora_verify_check_inputs(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,
+                               const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents,
+                               const int32_t* draft_tokens, const float* uniforms, int32_t* flags,
+                               void* hip_stream) {
+  if (!flags || (!attn_desc && !accept_desc)) return AURORA_ERR_INVALID_ARG;
+  if (attn_desc) { int rc = check_attn_desc(attn_desc); if (rc != AURORA_OK) return rc; }
+  if (accept_desc) { int rc = check_accept_desc(accept_desc); if (rc != AURORA_OK) return rc; }
+  if (attn_desc && accept_desc && (attn_desc->batch != accept_desc->batch || attn_desc->num_q != accept_desc->num_q))
+    return AURORA_ERR_INVALID_ARG;
+  if ((block_table || seq_lens) && !attn_desc) return AURORA_ERR_INVALID_ARG;
+  if (block_table && !seq_lens) return AURORA_ERR_INVALID_ARG;  // which pages are in use comes from the lengths
+  if ((draft_tokens || uniforms) && !accept_desc) return AURORA_ERR_INVALID_ARG;
+  CheckLaunch c = {};
+  c.B = attn_desc ? attn_desc->batch : accept_desc->batch;
+  c.Nq = attn_desc ? attn_desc->num_q : accept_desc->num_q;
+  if (attn_desc) { c.page = attn_desc->page_size; c.max_pages = attn_desc->max_pages_per_seq; c.num_pages = attn_desc->num_pages; }
+  if (accept_desc) c.V = accept_desc->vocab;
+  c.block_table = block_table; c.seq_lens = seq_lens; c.parents = parents; c.draft_tokens = draft_tokens;
+  c.uniforms = uniforms; c.flags = flags;
+  return launch_check_inputs(c, (hipStream_t)hip_stream) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
+}
+
 int aurora_trace_emit(const aurora_trace_desc* d, const float* logits, const int32_t* draft_tokens,
                       const int32_t* parents, const int32_t* next_token, const uint8_t* accept_mask,
                       int32_t* topk_ids, uint16_t* topk_logits, int32_t* y_out, int8_t* traj, void* hip_stream) {

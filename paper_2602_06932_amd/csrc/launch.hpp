@@ -67,4 +67,16 @@ hipError_t launch_trace_records(int B, int Nq, const int32_t* draft_tokens, cons
                                 const int32_t* next_token, const uint8_t* accept_mask, int32_t* y_out, int8_t* traj,
                                 hipStream_t st);
 
+// debug check of device-resident inputs (see check.hip); bits of flags[0]
+constexpr unsigned kCheckSeqLen = 1, kCheckPageId = 2, kCheckParent = 4, kCheckToken = 8, kCheckUniform = 16;
+constexpr int kCheckKinds = 5;
+struct CheckLaunch {
+  int B, Nq, page, max_pages, V;
+  long long num_pages;
+  const int32_t *block_table, *seq_lens, *parents, *draft_tokens;
+  const float* uniforms;
+  int32_t* flags;  // [1 + kCheckKinds]
+};
+hipError_t launch_check_inputs(const CheckLaunch& c, hipStream_t st);
+
 }  // namespace aurora

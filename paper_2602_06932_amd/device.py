@@ -129,6 +129,14 @@ class DeviceVerify:
     def verify(self, stream=None):
         return self._call("verify", stream)
 
+    def check_inputs(self, stream=None):
+        """Debug check of the device-resident inputs; returns the six flags as a host array after a sync."""
+        flags = torch.full((6,), -1, dtype=torch.int32, device="cuda")
+        B.aurora_verify_check_inputs(self.attn_desc, self.accept_desc, self.block_table, self.seq_lens, self.parents,
+                                     self.draft_tokens, self.uniforms, flags, stream)
+        torch.cuda.synchronize()
+        return flags.cpu().numpy()
+
     def trace(self, top_k=1024, after="verify", stream=None):
         """Trace emission from the logits and acceptance outputs the last verify / accept call left."""
         w = self.w
