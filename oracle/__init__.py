@@ -273,3 +273,9 @@ def trace_records(*, draft_tokens, parents, next_token, accept_mask):
     if st != 0:
         raise ValueError(f"oracle_trace_records status {st}")
     return y, r
+
+
+def draft_loss(*args, **kw):
+    """Drafter training loss of paper eq. 3 on a batch of trace rows (see oracle/loss_oracle.py)."""
+    from .loss_oracle import draft_loss as _impl
+    return _impl(*args, **kw)
