@@ -282,6 +282,42 @@ int aurora_trace_emit(const aurora_trace_desc* desc,
 /* Human-readable name of a status code; never NULL. */
 const char* aurora_status_string(int status);
 
+/*
+ * Drafter training loss on a batch of trace rows (paper section 3.3, eq. 3) - the first thing the training
+ * side computes from what aurora_trace_emit produced:
+ *
+ *   L = mean over accepted rows of KL(p_target || p_draft)
+ *       + lambda_discard * mean over discarded rows of KL(p_target || p_draft)
+ *
+ * Row m is one token position; traj[m] (the record's R) is its class: 1 accepted, 2 discarded (tested and
+ * rejected), anything else unused.  The means are over the rows of the class in this batch (an empty class
+ * contributes 0).  p_target of a row is the softmax over the kept target logits topk_logits[m, 0..K) (bf16
+ * bit patterns) on the tokens topk_ids[m, 0..K) - indices into the drafter's vocabulary, distinct, ordered
+ * by value with the largest first, as aurora_trace_emit writes them with a draft_to_target map - and zero
+ * elsewhere; entries with id -1 or value -inf carry no mass.  On discarded rows only the first
+ * discard_top_k entries are used (the paper's top-k filtering of discarded tokens; 0 = all K).  p_draft is
+ * the softmax of draft_logits[m, 0..Vd).  A row without any kept target logit has KL 0 and no gradient.
+ * Outputs (all DEVICE pointers):
+ *   row_kl   [rows] float32   KL of every row (also of unused rows)
+ *   loss_out [5]    float32   L, the accepted-rows mean, the discarded-rows mean, N_accept, N_discard
+ *   grad     [rows, Vd] float32 or NULL: dL / d draft_logits = w_m (p_draft - p_target),
+ *            w_m = 1 / N_accept, lambda_discard / N_discard or 0 by class
+ * Arithmetic: exponentials in fp32, every sum in fp64 in a fixed order (bit-reproducible).  No workspace;
+ * asynchronous on hip_stream.  AURORA_ERR_INVALID_ARG for null pointers, non-positive sizes, negative or
+ * non-finite lambda; AURORA_ERR_UNSUPPORTED for top_k > 1024.
+ */
+typedef struct {
+  int32_t rows;          /* M >= 0 (0: only loss_out is written, with zeros)  */
+  int32_t draft_vocab;   /* Vd >= 1                                            */
+  int32_t top_k;         /* K, 1..1024: entries per row of topk_ids / topk_logits */
+  int32_t discard_top_k; /* 0 => K, else 1..K                                  */
+  float lambda_discard;  /* >= 0                                               */
+} aurora_loss_desc;
+
+int aurora_draft_loss(const aurora_loss_desc* desc, const float* draft_logits, const int32_t* topk_ids,
+                      const uint16_t* topk_logits, const int8_t* traj, float* row_kl, float* loss_out, float* grad,
+                      void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_v
 
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
            "aurora_verify_lmhead", "aurora_verify_accept_logits", "aurora_trace_emit",
-           "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs")
+           "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs", "aurora_draft_loss")
 
 
 class aurora_attn_desc(C.Structure):
@@ -42,6 +42,11 @@ class aurora_accept_desc(C.Structure):
 class aurora_trace_desc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("vocab", C.c_int32), ("top_k", C.c_int32),
                 ("draft_vocab", C.c_int32), ("draft_to_target", C.c_void_p)]
+
+
+class aurora_loss_desc(C.Structure):
+    _fields_ = [("rows", C.c_int32), ("draft_vocab", C.c_int32), ("top_k", C.c_int32), ("discard_top_k", C.c_int32),
+                ("lambda_discard", C.c_float)]
 
 
 class AuroraError(RuntimeError):
@@ -82,6 +87,8 @@ def load():
     lib.aurora_trace_emit.restype = C.c_int
     lib.aurora_verify_check_inputs.argtypes = [ad, cd, i32p, i32p, i32p, i32p, f32p, i32p, vp]
     lib.aurora_verify_check_inputs.restype = C.c_int
+    lib.aurora_draft_loss.argtypes = [C.POINTER(aurora_loss_desc), f32p, i32p, vp, vp, f32p, f32p, f32p, vp]
+    lib.aurora_draft_loss.restype = C.c_int
     lib.aurora_verify_logits_ptr.argtypes = [ad, cd, vp]
     lib.aurora_verify_logits_ptr.restype = C.c_void_p
     lib.aurora_status_string.argtypes = [C.c_int]
@@ -204,7 +211,16 @@ def aurora_verify_check_inputs(attn_desc, accept_desc, block_table, seq_lens, pa
                                            _ptr(parents), _ptr(draft_tokens), _ptr(uniforms), _ptr(flags),
                                            _stream(stream))
     if check and st != AURORA_OK:
-        raise AuroraError(st, "aurora_verify_check_inputs")
+        raise AuroraError(st, "aurora_verify_check_inputs", "aurora_draft_loss")
+    return st
+
+
+def aurora_draft_loss(desc, draft_logits, topk_ids, topk_logits, traj, row_kl, loss_out, grad, stream=None,
+                      check=True) -> int:
+    st = load().aurora_draft_loss(_ref(desc), _ptr(draft_logits), _ptr(topk_ids), _ptr(topk_logits), _ptr(traj),
+                                  _ptr(row_kl), _ptr(loss_out), _ptr(grad), _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_draft_loss")
     return st
 
 

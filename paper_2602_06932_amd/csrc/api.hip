@@ -333,6 +333,25 @@ int aurora_verify_check_inputs(const aurora_attn_desc* attn_desc, const aurora_a
   return launch_check_inputs(c, (hipStream_t)hip_stream) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
 }
 
+int aurora_draft_loss(const aurora_loss_desc* d, const float* draft_logits, const int32_t* topk_ids,
+                      const uint16_t* topk_logits, const int8_t* traj, float* row_kl, float* loss_out, float* grad,
+                      void* hip_stream) {
+  if (!d || d->rows < 0 || d->draft_vocab < 1 || d->top_k < 1 || d->discard_top_k < 0 ||
+      d->discard_top_k > d->top_k || !(d->lambda_discard >= 0.f) || !(d->lambda_discard < INFINITY))
+    return AURORA_ERR_INVALID_ARG;
+  if (d->top_k > loss_max_k()) return AURORA_ERR_UNSUPPORTED;
+  if (!loss_out) return AURORA_ERR_INVALID_ARG;
+  if (d->rows > 0 && (!draft_logits || !topk_ids || !topk_logits || !traj || !row_kl)) return AURORA_ERR_INVALID_ARG;
+  if (((uintptr_t)draft_logits | (uintptr_t)grad | (uintptr_t)row_kl | (uintptr_t)loss_out | (uintptr_t)topk_ids) & 3)
+    return AURORA_ERR_INVALID_ARG;
+  if ((uintptr_t)topk_logits & 1) return AURORA_ERR_INVALID_ARG;
+  LossLaunch P = {};
+  P.M = d->rows; P.Vd = d->draft_vocab; P.K = d->top_k; P.discard_k = d->discard_top_k; P.lambda = d->lambda_discard;
+  P.draft_logits = draft_logits; P.topk_ids = topk_ids; P.topk_logits = topk_logits; P.traj = traj;
+  P.row_kl = row_kl; P.loss_out = loss_out; P.grad = grad;
+  return launch_draft_loss(P, (hipStream_t)hip_stream) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
+}
+
 int aurora_trace_emit(const aurora_trace_desc* d, const float* logits, const int32_t* draft_tokens,
                       const int32_t* parents, const int32_t* next_token, const uint8_t* accept_mask,
                       int32_t* topk_ids, uint16_t* topk_logits, int32_t* y_out, int8_t* traj, void* hip_stream) {

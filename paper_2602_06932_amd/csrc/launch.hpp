@@ -67,6 +67,19 @@ hipError_t launch_trace_records(int B, int Nq, const int32_t* draft_tokens, cons
                                 const int32_t* next_token, const uint8_t* accept_mask, int32_t* y_out, int8_t* traj,
                                 hipStream_t st);
 
+// drafter training loss on trace rows (see loss.hip)
+struct LossLaunch {
+  int M, Vd, K, discard_k;
+  float lambda;
+  const float* draft_logits;
+  const int32_t* topk_ids;
+  const uint16_t* topk_logits;
+  const int8_t* traj;
+  float *row_kl, *loss_out, *grad;
+};
+int loss_max_k();
+hipError_t launch_draft_loss(const LossLaunch& P, hipStream_t st);
+
 // debug check of device-resident inputs (see check.hip); bits of flags[0]
 constexpr unsigned kCheckSeqLen = 1, kCheckPageId = 2, kCheckParent = 4, kCheckToken = 8, kCheckUniform = 16;
 constexpr int kCheckKinds = 5;

@@ -1,0 +1,118 @@
+"""Parity of the drafter-loss kernel (paper section 3.3, eq. 3) against the float64 oracle, through the C ABI.
+
+Tolerances (fp32 exponentials, fp64 sums, fp32 outputs): a row KL is a sum of p_t * (log p_t - log p_d) with
+sum p_t = 1; log terms are formed in fp64 from fp32 inputs, p_t carries the fp32 exponential's ~3e-7 relative
+error times a log ratio of at most a few tens => |dKL| <= 2e-5 + 1e-5 |KL|.  Gradient entries are w * (p_d - p_t)
+with p <= 1 => |dg| <= 4e-6 * w.  Counts are exact."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(z, ids, bits, traj, lam, dk, want_grad=True):
+    import paper_2602_06932_amd as av
+    M, Vd = z.shape
+    K = ids.shape[1]
+    d = av.aurora_loss_desc(rows=M, draft_vocab=Vd, top_k=K, discard_top_k=dk or 0, lambda_discard=lam)
+    dz = torch.from_numpy(z).cuda()
+    di = torch.from_numpy(ids).cuda()
+    db = torch.from_numpy(bits.view(np.int16)).cuda()
+    dt = torch.from_numpy(traj).cuda()
+    row_kl = torch.full((max(M, 1),), float("nan"), device="cuda")
+    loss = torch.full((5,), float("nan"), device="cuda")
+    grad = torch.full((max(M, 1), Vd), float("nan"), device="cuda") if want_grad else None
+    av.aurora_draft_loss(d, dz if M else None, di if M else None, db if M else None, dt if M else None,
+                         row_kl if M else None, loss, grad)
+    torch.cuda.synchronize()
+    return row_kl.cpu().numpy()[:M], loss.cpu().numpy(), None if grad is None else grad.cpu().numpy()[:M]
+
+
+def _check(z, ids, bits, traj, lam, dk):
+    print(f"[case] rows={z.shape[0]} Vd={z.shape[1]} K={ids.shape[1]} discard_k={dk} lambda={lam}", flush=True)
+    ref = oracle.draft_loss(z, ids, bits, traj, lam, discard_top_k=dk)
+    kl, loss, grad = _run(z, ids, bits, traj, lam, dk)
+    assert loss[3] == ref["n_accept"] and loss[4] == ref["n_discard"]
+    assert np.all(np.abs(kl - ref["row_kl"]) <= 2e-5 + 1e-5 * np.abs(ref["row_kl"])), np.abs(kl - ref["row_kl"]).max()
+    for got, want in ((loss[0], ref["loss"]), (loss[1], ref["mean_accept"]), (loss[2], ref["mean_discard"])):
+        assert abs(got - want) <= 2e-5 + 1e-5 * abs(want)
+    wmax = max(1.0 / max(ref["n_accept"], 1), lam / max(ref["n_discard"], 1))
+    assert np.isfinite(grad).all()
+    assert np.abs(grad - ref["grad"]).max() <= 4e-6 * wmax, np.abs(grad - ref["grad"]).max() / wmax
+    return kl, loss, grad
+
+
+@pytest.mark.parametrize("rows,vd,k,dk", [(37, 32000, 1024, 64), (9, 5003, 1024, 1024), (5, 777, 1024, 10),
+                                          (12, 4096, 100, 0), (3, 8, 4, 2), (64, 20000, 256, 1)])
+def test_loss_and_gradient_match_the_oracle(gpu_lib, rows, vd, k, dk):
+    z, ids, bits, traj = gen.loss_inputs(7 + rows, rows, vd, top_k=k, pad_rows=min(3, rows))
+    _check(z, ids, bits, traj, 0.5, dk or None)
+
+
+def test_classes_missing_and_single_rows(gpu_lib):
+    z, ids, bits, traj = gen.loss_inputs(3, 6, 3000, top_k=128)
+    for t in ([1] * 6, [2] * 6, [0] * 6, [1, 0, 0, 0, 0, 2]):
+        _check(z, ids, bits, np.array(t, np.int8), 2.0, 16)
+    _check(z[:1], ids[:1], bits[:1], np.array([2], np.int8), 0.0, None)
+
+
+def test_rows_without_a_target_distribution_and_masked_drafter_logits(gpu_lib):
+    z, ids, bits, traj = gen.loss_inputs(4, 5, 1000, top_k=64)
+    traj[:] = [1, 1, 2, 2, 1]
+    ids[1, :] = -1            # nothing kept: KL 0, no gradient
+    bits[3, :] = 0xFF80       # kept ids, all values -inf: the same
+    z[0, ::3] = -np.inf       # tokens the drafter masks out (none of them kept below)
+    keep0 = ids[0][ids[0] >= 0]
+    z[0, keep0] = 0.25
+    kl, loss, grad = _check(z, ids, bits, traj, 1.0, None)
+    assert kl[1] == 0.0 and kl[3] == 0.0 and not grad[1].any() and not grad[3].any()
+
+
+def test_without_gradient_and_repeatability(gpu_lib):
+    z, ids, bits, traj = gen.loss_inputs(5, 20, 9000, top_k=512)
+    a = _run(z, ids, bits, traj, 0.3, 32)
+    b = _run(z, ids, bits, traj, 0.3, 32)
+    c = _run(z, ids, bits, traj, 0.3, 32, want_grad=False)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1]) and c[2] is None
+
+
+def test_empty_batch_and_host_errors(gpu_lib):
+    import paper_2602_06932_amd as av
+    kl, loss, _ = _run(np.zeros((0, 50), np.float32), np.zeros((0, 8), np.int32), np.zeros((0, 8), np.uint16),
+                       np.zeros((0,), np.int8), 0.5, None, want_grad=False)
+    assert loss.tolist() == [0.0, 0.0, 0.0, 0.0, 0.0]
+    loss_t = torch.zeros(5, device="cuda")
+    for bad in (dict(rows=-1), dict(draft_vocab=0), dict(top_k=0), dict(discard_top_k=9), dict(lambda_discard=-1.0),
+                dict(lambda_discard=float("nan"))):
+        kw = dict(rows=0, draft_vocab=50, top_k=8, discard_top_k=0, lambda_discard=0.5)
+        kw.update(bad)
+        st = av.aurora_draft_loss(av.aurora_loss_desc(**kw), None, None, None, None, None, loss_t, None, check=False)
+        assert st == av.AURORA_ERR_INVALID_ARG, bad
+    st = av.aurora_draft_loss(av.aurora_loss_desc(rows=0, draft_vocab=50, top_k=2048, discard_top_k=0, lambda_discard=0.5),
+                              None, None, None, None, None, loss_t, None, check=False)
+    assert st == av.AURORA_ERR_UNSUPPORTED
+    st = av.aurora_draft_loss(av.aurora_loss_desc(rows=2, draft_vocab=50, top_k=8, discard_top_k=0, lambda_discard=0.5),
+                              None, None, None, None, None, loss_t, None, check=False)
+    assert st == av.AURORA_ERR_INVALID_ARG
+
+
+def test_trace_emission_feeds_the_loss(gpu_lib):
+    """The whole hand-over: verify step -> trace emission -> loss on the emitted rows (here the drafter shares the
+    target's vocabulary, so the emitted ids index its logits directly)."""
+    from paper_2602_06932_amd.device import DeviceVerify
+    w = gen.llama_chain(81, batch=6, len_lo=20, len_hi=200, vocab=4000, hidden_size=128, draft_noise=0.5)
+    dv = DeviceVerify(w)
+    dv.verify()
+    dv.trace(top_k=256)
+    torch.cuda.synchronize()
+    ids = dv.topk_ids.cpu().numpy()
+    bits = dv.topk_logits.cpu().numpy().view(np.uint16)
+    traj = dv.traj.cpu().numpy().reshape(-1)
+    assert set(np.unique(traj)) <= {0, 1, 2} and (traj == 1).sum() >= w.batch
+    z = (np.random.default_rng(1).standard_normal((ids.shape[0], w.vocab)) * 2).astype(np.float32)
+    _check(z, np.ascontiguousarray(ids), np.ascontiguousarray(bits), np.ascontiguousarray(traj), 0.5, 32)
