@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_fp8kv", "llama_fp8", "llama_draft32k", "tiny", "qwen_greedy", "tree", "tree_fp8kv", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
-    ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy"],
+    ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy", "loss"],
                     help="profiling aid: launch only this stage --steps times (after --warmup) and exit; "
                          "'copy' runs a plain device-to-device copy of 1 GiB for counter calibration")
     args = ap.parse_args()
@@ -89,6 +89,29 @@ def main():
     import paper_2602_06932_amd as av
     from paper_2602_06932_amd.device import DeviceVerify
     av.load()
+
+    if args.stage == "loss":
+        # the training side's first kernel on a batch of trace rows: 32K-entry draft vocabulary, 1024 kept target
+        # logits per row (paper appendix A.2), 4096 rows - 25 verify steps of the headline configuration
+        import gen
+        rows, vd, k = 4096, 32000, 1024
+        z, ids, bits, traj = gen.loss_inputs(args.seed, rows, vd, top_k=k)
+        d = av.aurora_loss_desc(rows=rows, draft_vocab=vd, top_k=k, discard_top_k=64, lambda_discard=0.5)
+        dz, di = torch.from_numpy(z).cuda(), torch.from_numpy(ids).cuda()
+        db, dt = torch.from_numpy(bits.view(np.int16)).cuda(), torch.from_numpy(traj).cuda()
+        row_kl, loss = torch.empty(rows, device="cuda"), torch.empty(5, device="cuda")
+        grad = torch.empty((rows, vd), device="cuda")
+        fn = lambda: av.aurora_draft_loss(d, dz, di, db, dt, row_kl, loss, grad)
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        ms = event_time_ms(fn, args.steps, torch)
+        alg = rows * vd * 4 * 2 + rows * k * 6
+        print(json.dumps({"stage": "loss", "steps": args.steps, "avg_ms": ms, "rows": rows, "draft_vocab": vd, "top_k": k,
+                          "loss": float(loss[0].item()), "algorithmic_bytes": alg,
+                          "roofline": {"bound": "hbm", "achieved": alg / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                                       "unit": "GB/s", "frac": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}}))
+        return
 
     t0 = time.time()
     w = make_workload(args.workload, args.seed)
