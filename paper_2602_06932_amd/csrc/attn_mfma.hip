@@ -805,12 +805,18 @@ __global__ __launch_bounds__(kWideThreads, 1) void attn_mfma_wide_kernel(
 
 // Merge the partials of one output row (request b, node n, query head hq): the segments of its
 // (request, KV head) pair sit in slots w + pair for the workgroups w whose unit range meets the pair's.
-__global__ __launch_bounds__(kAtD) void attn_mfma_combine(const float* __restrict__ part_o,
-                                                          const float* __restrict__ part_ml,
-                                                          const int32_t* __restrict__ seq_lens,
-                                                          const int32_t* __restrict__ PB, bf16_t* __restrict__ out, int B,
-                                                          int Nq, int Hq, int Hkv, int wgs, int row_tiles, int groups) {
-  const size_t row = blockIdx.x;  // (b*Nq + n)*Hq + hq
+// Thirty-two threads per row (four output columns each), eight rows per workgroup: the merge is a short chain
+// of dependent loads, so what counts is how many rows a compute unit has in flight.
+constexpr int kCombineRows = 8;
+__global__ __launch_bounds__(32 * kCombineRows) void attn_mfma_combine(const float* __restrict__ part_o,
+                                                                       const float* __restrict__ part_ml,
+                                                                       const int32_t* __restrict__ seq_lens,
+                                                                       const int32_t* __restrict__ PB,
+                                                                       bf16_t* __restrict__ out, int B, int Nq, int Hq,
+                                                                       int Hkv, int wgs, int row_tiles, int groups,
+                                                                       unsigned n_rows) {
+  const size_t row = (size_t)blockIdx.x * kCombineRows + (threadIdx.x >> 5);  // (b*Nq + n)*Hq + hq
+  if (row >= n_rows) return;
   const int hq = (int)(row % Hq);
   const int n = (int)((row / Hq) % Nq);
   const int b = (int)(row / ((size_t)Hq * Nq));
@@ -823,22 +829,25 @@ __global__ __launch_bounds__(kAtD) void attn_mfma_combine(const float* __restric
   const int u0 = PB[b] + hk * n_b, u1 = u0 + n_b;
   const int w0 = u0 / c, w1 = (u1 - 1) / c;
   const int pair = b * Hkv + hk;
-  const int d = threadIdx.x;
+  const int d4 = threadIdx.x & 31;  // columns 4 d4 .. 4 d4 + 3
   // online merge, four partials' loads in flight at a time; partial p of the pair is segment
   // (w0 + p / groups), tile parity p % groups
-  float M = -INFINITY, num = 0.f, den = 0.f;
+  float M = -INFINITY, den = 0.f;
+  f32x4_t num = {0.f, 0.f, 0.f, 0.f};
   const int np = (w1 - w0 + 1) * groups;
   for (int p0 = 0; p0 < np; p0 += 4) {
-    float ms[4], ls[4], os[4];
+    float ms[4], ls[4];
+    f32x4_t os[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int pp = p0 + i < np ? p0 + i : 0;
       const bool ok = p0 + i < np;
       const size_t sl = (size_t)(w0 + pp / groups + pair) * groups + pp % groups;
       const size_t prow = (sl * row_tiles + rt) * 32 + li;
+      const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
       ms[i] = ok ? part_ml[prow * 2] : -INFINITY;
       ls[i] = ok ? part_ml[prow * 2 + 1] : 0.f;
-      os[i] = ok ? part_o[prow * kAtD + d] : 0.f;
+      os[i] = ok ? *(const f32x4_t*)(part_o + prow * kAtD + 4 * d4) : z;
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -846,12 +855,16 @@ __global__ __launch_bounds__(kAtD) void attn_mfma_combine(const float* __restric
       const float nm = fmaxf(M, ms[i]);
       const float fo = M == -INFINITY ? 0.f : __expf(M - nm);
       const float fn = __expf(ms[i] - nm);
-      num = num * fo + fn * os[i];
+      num = num * fo + os[i] * fn;
       den = den * fo + fn * ls[i];
       M = nm;
     }
   }
-  out[row * kAtD + d] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+  typedef __attribute__((ext_vector_type(4))) unsigned short u16x4_t;
+  u16x4_t o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16(den > 0.f ? num[e] / den : 0.f);
+  *(u16x4_t*)(out + row * kAtD + 4 * d4) = o;
 }
 
 bool attn_mfma_supported(const AttnLaunch& a) {
@@ -908,8 +921,9 @@ hipError_t launch_attn_mfma(const AttnLaunch& a, hipStream_t st) {
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const unsigned rows = (unsigned)((size_t)a.B * a.Nq * a.Hq);
-  hipLaunchKernelGGL(attn_mfma_combine, dim3(rows), dim3(kAtD), 0, st, a.part_o, a.part_ml, a.seq_lens, a.plan_pb,
-                     (bf16_t*)a.out, a.B, a.Nq, a.Hq, a.Hkv, wgs, row_tiles, row_tiles == 1 ? 1 : 2);
+  hipLaunchKernelGGL(attn_mfma_combine, dim3((rows + kCombineRows - 1) / kCombineRows), dim3(32 * kCombineRows), 0, st,
+                     a.part_o, a.part_ml, a.seq_lens, a.plan_pb, (bf16_t*)a.out, a.B, a.Nq, a.Hq, a.Hkv, wgs, row_tiles,
+                     row_tiles == 1 ? 1 : 2, rows);
   return hipGetLastError();
 }
 
