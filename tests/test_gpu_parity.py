@@ -535,3 +535,27 @@ def test_full_size_llama_chain_with_fp8_kv(gpu_lib):
     """Config 2 with the cache in 8 bits; requests sampled for the oracle."""
     w = gen.llama_chain(1, kv_fp8=True)
     _full_check(gpu_lib, w, sample=[0, 13, 31])
+
+
+def test_tree_walk_split_over_workgroups_with_draft_subvocabulary_and_fp8_head(gpu_lib):
+    """The several-workgroup tree walk on the other input forms: q over a draft vocabulary (index map), and logits
+    from an 8-bit LM head."""
+    w = gen.llama_tree(91, batch=5, num_q=14, vocab=20000, hidden_size=128, context=60, num_q_heads=4, num_kv_heads=2,
+                       draft_vocab=5000, draft_noise=0.5)
+    _full_check(gpu_lib, w)
+    w = gen.llama_tree(92, batch=4, num_q=12, vocab=24000, hidden_size=256, context=60, num_q_heads=4, num_kv_heads=2,
+                       head_fp8=True)
+    _full_check(gpu_lib, w)
+
+
+def test_sixty_four_node_tree(gpu_lib):
+    """The largest tree the interface takes: 64 nodes, 256 query rows per KV head (eight row tiles), bf16 and 8-bit cache."""
+    for kv8 in (False, True):
+        w = gen.llama_tree(93, batch=2, num_q=64, vocab=9000, hidden_size=128, context=300, num_q_heads=8, num_kv_heads=2,
+                           kv_fp8=kv8)
+        _full_check(gpu_lib, w)
+
+
+def test_single_request_batches(gpu_lib):
+    _full_check(gpu_lib, gen.llama_chain(94, batch=1, len_lo=700, len_hi=700, vocab=40000, hidden_size=256))
+    _full_check(gpu_lib, gen.llama_tree(95, batch=1, num_q=20, vocab=40000, hidden_size=256, context=500))
