@@ -23,7 +23,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # WRITE_SIZE x 1.0); the summaries are in profiles/.  None for workloads that were not profiled.
 MEASURED_TRAFFIC = {
     ("llama", 1, "lmhead"): {"read_bytes": 518300 * 1024 * 2, "write_bytes": 88010 * 1024},
-    ("llama", 1, "attn"): {"read_bytes": (153500 + 4128) * 1024 * 2, "write_bytes": (7236 + 1280) * 1024},
+    ("llama", 1, "attn"): {"read_bytes": (153500 + 3746) * 1024 * 2, "write_bytes": (7237 + 1280) * 1024},
 }
 
 
