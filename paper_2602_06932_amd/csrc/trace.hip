@@ -149,7 +149,7 @@ __device__ __forceinline__ uint64_t radix_threshold(SelectShared& sh, int n, int
 // kMapped: the selection runs over the V entries row[map[0]], .., row[map[V-1]] of a row of Vrow logits
 // (the draft vocabulary, appendix A.2) and the ids written are positions in that list.
 template <bool kMapped>
-__global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __restrict__ logits, int Vrow, int V, int K,
+__global__ __launch_bounds__(kTrThreads, 2) void trace_topk_kernel(const float* __restrict__ logits, int Vrow, int V, int K,
                                                                const int32_t* __restrict__ map,
                                                                int32_t* __restrict__ out_ids,
                                                                uint16_t* __restrict__ out_vals) {
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(kTrThreads) void trace_topk_kernel(const float* __r
       }
     }
     // sixteen 16-byte loads in flight per thread: the pass is bound by memory latency otherwise
-    constexpr int kU = 16;
+    constexpr int kU = 8;
     for (int i0 = tid; i0 < nvec; i0 += kU * kTrThreads) {
       f32x4_t x[kU];
 #pragma unroll
