@@ -13,7 +13,7 @@
 // finds the threshold word T with exactly K words >= T.
 // Common case, one pass over the row: a cut-off key is selected from a sample of 4096 entries (1024
 // evenly spaced 16-byte vectors) so that
-// about 2K entries reach it; the row is streamed once (16-byte loads, sixteen in flight per thread) and
+// about 2K entries reach it; the row is streamed once (16-byte loads, eight in flight per thread) and
 // the few entries at or above the cut-off are appended to a list in LDS; the list is cut to exactly K
 // by a radix select inside LDS, compacted, sorted (bitonic, 1024 words) and written out.  If the list
 // comes out shorter than K or longer than its capacity (heavily repeated values, adversarial rows),
@@ -292,37 +292,57 @@ __global__ __launch_bounds__(kTrThreads, 2) void trace_topk_kernel(const float* 
   }
 }
 
-// One thread per request: walk the accepted path from the root.  Children of a path node are tried in
-// index order until one is kept (the acceptance step's order), so those before the kept one - or all,
-// if none is kept - were tested and rejected (code 2); path nodes get code 1 and the token emitted
-// after them; everything else 0 / -1.
-__global__ void trace_records_kernel(int B, int Nq, const int32_t* __restrict__ draft_tokens,
-                                     const int32_t* __restrict__ parents, const int32_t* __restrict__ next_token,
-                                     const uint8_t* __restrict__ accept_mask, int32_t* __restrict__ y_out,
-                                     int8_t* __restrict__ traj) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B) return;
-  const int32_t* tok = draft_tokens + (size_t)b * Nq;
-  const uint8_t* mask = accept_mask + (size_t)b * Nq;
-  int32_t* y = y_out + (size_t)b * Nq;
-  int8_t* r = traj + (size_t)b * Nq;
-  for (int n = 0; n < Nq; ++n) { y[n] = -1; r[n] = 0; }
-  int cur = 0;
-  r[0] = 1;
-  for (;;) {
-    int kept = -1;
-    for (int c = cur + 1; c < Nq; ++c) {
-      const int par = parents ? parents[(size_t)b * Nq + c] : c - 1;
-      if (par != cur) continue;
-      if (mask[c]) { kept = c; break; }
-      r[c] = 2;
-    }
-    if (kept < 0) break;
-    r[kept] = 1;
-    y[cur] = tok[kept];
-    cur = kept;
+// One wavefront per request, lane n = node n (Nq <= 64).  Children of a path node are tried in index order
+// until one is kept (the acceptance step's order), so those before the kept one - or all, if none is kept -
+// were tested and rejected (code 2); path nodes get code 1 and the token emitted after them; everything
+// else 0 / -1.  The walk from the root is written per node: kc[p] is the first child of p whose mask is set;
+// a node is on the path iff it is the root, or it is kc of a parent that is on the path (parents precede
+// their children, so Nq rounds of that rule reach every node).
+constexpr int kRecWaves = 4;
+__global__ __launch_bounds__(kRecWaves * kWave) void trace_records_kernel(
+    int B, int Nq, const int32_t* __restrict__ draft_tokens, const int32_t* __restrict__ parents,
+    const int32_t* __restrict__ next_token, const uint8_t* __restrict__ accept_mask, int32_t* __restrict__ y_out,
+    int8_t* __restrict__ traj) {
+  __shared__ int s_par[kRecWaves][kMaxNq], s_kc[kRecWaves][kMaxNq];
+  __shared__ unsigned char s_mask[kRecWaves][kMaxNq], s_on[kRecWaves][kMaxNq];
+  const int wv = threadIdx.x / kWave, n = threadIdx.x % kWave;
+  const int b = blockIdx.x * kRecWaves + wv;
+  if (b >= B) return;  // whole wavefronts leave; the rest of the kernel has no workgroup barrier
+  const bool node = n < Nq;
+  const size_t at = (size_t)b * Nq + n;
+  const int par = node ? (parents ? parents[at] : n - 1) : -1;
+  const int tok = node ? draft_tokens[at] : -1;
+  const int msk = node ? (accept_mask[at] != 0) : 0;
+  const int nxt = next_token[b];
+  if (node) {
+    s_par[wv][n] = par;
+    s_mask[wv][n] = (unsigned char)msk;
+    s_on[wv][n] = n == 0;
   }
-  y[cur] = next_token[b];
+  __builtin_amdgcn_wave_barrier();  // LDS operations of one wavefront execute in order
+  int kc = Nq;  // first kept child of node n
+  if (node)
+    for (int c = Nq - 1; c > n; --c)
+      if (s_par[wv][c] == n && s_mask[wv][c]) kc = c;
+  if (node) s_kc[wv][n] = kc;
+  const int tok_kc = __shfl(tok, kc < Nq ? kc : 0, kWave);  // all 64 lanes are still active here
+  __builtin_amdgcn_wave_barrier();
+  bool on = n == 0;
+  for (int round = 1; round < Nq; ++round) {
+    if (node && n > 0 && !on && par >= 0 && par < n) on = msk && s_on[wv][par] && s_kc[wv][par] == n;
+    if (node) s_on[wv][n] = on;
+    __builtin_amdgcn_wave_barrier();
+  }
+  if (!node) return;
+  int code = 0, y = -1;
+  if (on) {
+    code = 1;
+    y = kc < Nq ? tok_kc : nxt;
+  } else if (n > 0 && par >= 0 && par < n && s_on[wv][par] && n < s_kc[wv][par]) {
+    code = 2;
+  }
+  y_out[at] = y;
+  traj[at] = (int8_t)code;
 }
 
 hipError_t launch_trace_topk(const float* logits, int64_t rows, int V, int K, const int32_t* map, int n_map,
@@ -341,7 +361,7 @@ hipError_t launch_trace_records(int B, int Nq, const int32_t* draft_tokens, cons
                                 const int32_t* next_token, const uint8_t* accept_mask, int32_t* y_out, int8_t* traj,
                                 hipStream_t st) {
   if (B <= 0) return hipSuccess;
-  hipLaunchKernelGGL(trace_records_kernel, dim3((B + 127) / 128), dim3(128), 0, st, B, Nq, draft_tokens, parents,
+  hipLaunchKernelGGL(trace_records_kernel, dim3((B + kRecWaves - 1) / kRecWaves), dim3(kRecWaves * kWave), 0, st, B, Nq, draft_tokens, parents,
                      next_token, accept_mask, y_out, traj);
   return hipGetLastError();
 }
