@@ -101,20 +101,24 @@ struct AcceptParams {
 // wavefront; result valid in every lane.  Each lane folds its tiles into a running (max, scaled
 // sum) pair - the loads of eight tiles are issued together - then the lanes are folded by
 // butterfly exchanges.  Scale factors go through the hardware exp2 of an fp64-formed exponent.
+// kLanes = 32: the two halves of the wavefront merge two different rows at the same time (`row` then
+// differs between the halves), so a workgroup gets through twice as many rows per round of loads.
+template <int kLanes = kWave>
 __device__ __forceinline__ void merge_row_stats(const AcceptParams& P, size_t row, double T, int lane, float* out_max,
                                                 double* out_lse, int* out_arg) {
   const int nt = P.n_tiles;
   const float* pm = P.pmax + row * nt;
   const float* ps = P.psum + row * nt;
   const double c = 1.4426950408889634 / T;
+  const int sub = lane & (kLanes - 1);
   float m = -INFINITY;
   double s = 0.0;
   int mt = 0x7fffffff;
-  for (int t0 = 0; t0 < nt; t0 += kWave * 8) {
+  for (int t0 = 0; t0 < nt; t0 += kLanes * 8) {
     float xm[8], xs[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const int t = t0 + u * kWave + lane;
+      const int t = t0 + u * kLanes + sub;
       xm[u] = t < nt ? pm[t] : -INFINITY;
       xs[u] = t < nt ? ps[t] : 0.f;
     }
@@ -123,14 +127,14 @@ __device__ __forceinline__ void merge_row_stats(const AcceptParams& P, size_t ro
       if (xm[u] > m) {
         s = s * (double)__builtin_amdgcn_exp2f((float)(((double)m - (double)xm[u]) * c)) + (double)xs[u];
         m = xm[u];
-        mt = t0 + u * kWave + lane;
+        mt = t0 + u * kLanes + sub;
       } else if (xm[u] > -INFINITY) {
         s += (double)xs[u] * (double)__builtin_amdgcn_exp2f((float)(((double)xm[u] - (double)m) * c));
       }
     }
   }
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
+  for (int o = kLanes / 2; o > 0; o >>= 1) {
     const float om = __shfl_xor(m, o, kWave);
     const double os = __shfl_xor(s, o, kWave);
     const int ot = __shfl_xor(mt, o, kWave);
@@ -479,10 +483,13 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   }
 
   // ---- 1. per-row (logsumexp, arg-max) from the tile statistics ---------------------------------
-  for (int n = wv; n < Nq; n += kAccWaves) {
+  // half a wavefront per row: 32 rows per round
+  for (int n0 = 0; n0 < Nq; n0 += 2 * kAccWaves) {
+    const int n = n0 + 2 * wv + (lane >> 5);
+    const int nc = n < Nq ? n : Nq - 1;  // idle halves repeat the last row (the shuffles need every lane)
     float mx; double lse; int arg;
-    merge_row_stats(P, row0 + n, T, lane, &mx, &lse, &arg);
-    if (lane == 0) { s_lse[n] = lse; s_arg[n] = arg; }
+    merge_row_stats<32>(P, row0 + nc, T, lane, &mx, &lse, &arg);
+    if ((lane & 31) == 0 && n < Nq) { s_lse[n] = lse; s_arg[n] = arg; }
   }
   __syncthreads();
 
