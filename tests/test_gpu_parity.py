@@ -559,3 +559,11 @@ def test_sixty_four_node_tree(gpu_lib):
 def test_single_request_batches(gpu_lib):
     _full_check(gpu_lib, gen.llama_chain(94, batch=1, len_lo=700, len_hi=700, vocab=40000, hidden_size=256))
     _full_check(gpu_lib, gen.llama_tree(95, batch=1, num_q=20, vocab=40000, hidden_size=256, context=500))
+
+
+def test_lookahead_ten_at_llama_shapes(gpu_lib):
+    """The paper's long-lookahead setting (section 4.2: lookahead 10, Nq = 11): 44 query rows per KV head go to the
+    wide attention kernel, 11 rows per request to the chain acceptance kernels; Llama-3-8B shapes, reduced batch."""
+    w = gen.llama_chain(97, batch=6, num_q=11, len_lo=900, len_hi=2500, draft_noise=0.4)
+    _, a = _full_check(gpu_lib, w, sample=[0, 3, 5])
+    assert a.accept_len.max() >= 2
