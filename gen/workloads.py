@@ -199,6 +199,8 @@ class Workload:
     kv_dtype: str = ""
     k_scale: Optional[np.ndarray] = None
     v_scale: Optional[np.ndarray] = None
+    # one temperature per request (float32 [B]; 0 = that request is verified greedily), or None: `temperature`
+    temperatures: Optional[np.ndarray] = None
 
     def target_to_draft(self) -> Optional[np.ndarray]:
         """Inverse of draft_to_target over the target vocabulary, -1 where the draft model has no entry."""
@@ -231,7 +233,7 @@ class Workload:
             self, batch=len(idx), q=sl(self.q), block_table=sl(self.block_table),
             seq_lens=sl(self.seq_lens), parents=sl(self.parents), hidden=sl(self.hidden),
             draft_tokens=sl(self.draft_tokens), draft_probs=sl(self.draft_probs),
-            uniforms=sl(self.uniforms), hidden_scale=sl(self.hidden_scale))
+            uniforms=sl(self.uniforms), hidden_scale=sl(self.hidden_scale), temperatures=sl(self.temperatures))
 
 
 # --------------------------------------------------------------------------
@@ -329,7 +331,7 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
                   tree: bool = False, greedy_hit: float = 0.7,
                   shuffle_pages: bool = True, pool_pages: Optional[int] = None,
                   distinct_siblings: bool = False, draft_vocab: Optional[int] = None,
-                  head_fp8: bool = False, kv_fp8: bool = False, recipe: str = "") -> Workload:
+                  head_fp8: bool = False, kv_fp8: bool = False, temperatures=None, recipe: str = "") -> Workload:
     """Build one workload.
 
     draft = "independent": draft logits ~ N(0,1), draft tokens uniform over the vocab.
@@ -342,6 +344,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
     head_fp8: hidden and lm_head are drawn as float32 with the same recipe, then stored as E4M3 codes
             with one scale per row; the stand-in target logits use the values the codes stand for.
     kv_fp8: the K/V pools are stored as E4M3 codes with one scale per KV head (see make_kv).
+    temperatures (with "noisy_target"): one temperature per request; the draft distribution of request b is
+            softmax((target + noise) / T_b), with T_b = 1 standing in for a greedy request (T_b = 0).
     """
     ss = np.random.SeedSequence([int(seed), 0x2602_06932 & 0xFFFFFFFF])
     s_q, s_kv, s_h, s_w, s_misc = ss.spawn(5)
@@ -389,6 +393,10 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
     elif draft == "noisy_target":
         t = standin()
         T = np.float32(temperature if temperature > 0 else 1.0)
+        if temperatures is not None:
+            tb = np.asarray(temperatures, dtype=np.float32)
+            assert tb.shape == (B,) and (tb >= 0).all()
+            T = np.repeat(np.where(tb > 0, tb, np.float32(1.0)).astype(np.float32), Nq)[:, None]
         if draft_vocab:
             d2t = np.sort(rng.choice(V, size=int(draft_vocab), replace=False)).astype(np.int32)
             t = np.ascontiguousarray(t[:, d2t])
@@ -426,7 +434,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
                  uniforms=uniforms, recipe=recipe, page_ids=page_ids,
                  draft_vocab=int(draft_vocab or 0), draft_to_target=d2t,
                  head_dtype="fp8" if head_fp8 else "", hidden_scale=hidden_scale, lm_head_scale=lm_head_scale,
-                 kv_dtype="fp8" if kv_fp8 else "", k_scale=k_scale, v_scale=v_scale)
+                 kv_dtype="fp8" if kv_fp8 else "", k_scale=k_scale, v_scale=v_scale,
+                 temperatures=None if temperatures is None else np.asarray(temperatures, dtype=np.float32))
     return w
 
 

@@ -95,6 +95,12 @@ typedef struct {
    * everything after them are fp32 / fp64 as for the other types. */
   const float* hidden_scale;
   const float* lm_head_scale;
+  /* One temperature per request (a serving batch mixes sampling settings; the paper's formulation has one).
+   * NULL: `temperature` applies to every request.  Otherwise a DEVICE pointer to float32 [B]; `temperature`
+   * is ignored, request b is verified at temperatures[b] > 0, or greedily if temperatures[b] == 0 (its
+   * draft_probs / uniforms rows are then not read, row_lse is that of the raw logits and p_at_draft is
+   * 1 / 0 as in a greedy call).  draft_probs and uniforms must be given. */
+  const float* temperatures;
 } aurora_accept_desc;
 
 /* Bytes of workspace needed by aurora_verify / _attn / _accept for these descriptors.

@@ -228,7 +228,29 @@ def attn_workload(w) -> np.ndarray:
 
 
 def accept_workload(w, want_cdf=False, want_logits=False) -> AcceptResult:
-    """The acceptance half on a gen.Workload (bf16 / f32 operands, or E4M3 operands with scales)."""
+    """The acceptance half on a gen.Workload (bf16 / f32 operands, or E4M3 operands with scales).  A workload with
+    one temperature per request is verified request by request, each at its own temperature (0 = greedy):
+    requests are independent, so that is the definition."""
+    temps = getattr(w, "temperatures", None)
+    if temps is not None:
+        import dataclasses as _dc
+        parts = []
+        for b in range(w.batch):
+            wb = _dc.replace(w.take_requests([b]), temperatures=None, temperature=float(np.float32(temps[b])))
+            if wb.temperature == 0.0:   # a greedy call reads neither of them
+                wb = _dc.replace(wb, draft_probs=None, uniforms=None)
+            parts.append(accept_workload(wb, want_cdf=want_cdf and wb.temperature > 0, want_logits=want_logits))
+        V = w.vocab
+        def cat(name):
+            vals = [getattr(p_, name) for p_ in parts]
+            if name == "final_cdf":
+                if not want_cdf:
+                    return None
+                return np.concatenate([v if v is not None else np.full((1, V), np.nan) for v in vals], axis=0)
+            if any(v is None for v in vals):
+                return None
+            return np.concatenate(vals, axis=0)
+        return AcceptResult(**{f.name: cat(f.name) for f in dataclasses.fields(AcceptResult)})
     if getattr(w, "head_dtype", "") == "fp8":
         lg = logits_fp8(hidden=w.hidden, hidden_scale=w.hidden_scale, lm_head=w.lm_head,
                         lm_head_scale=w.lm_head_scale)

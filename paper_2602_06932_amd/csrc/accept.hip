@@ -95,7 +95,13 @@ struct AcceptParams {
   // (two copies, alternating by sweep), tree_bar [B] counts workgroup arrivals (zero at launch)
   int tree_slices;
   int32_t* tree_bar;
+  const float* temps;  // [B] one temperature per request (0 = that request is verified greedily), or NULL
 };
+
+// the temperature of request b: its own, or the call's
+__device__ __forceinline__ float request_temperature(const AcceptParams& P, int b) {
+  return P.temps ? P.temps[b] : P.temperature;
+}
 
 // (max, logsumexp(l / T), arg-max) of one logits row, merged from its tile statistics by one
 // wavefront; result valid in every lane.  Each lane folds its tiles into a running (max, scaled
@@ -216,32 +222,39 @@ __device__ __forceinline__ void lane_weights(const Lane4& r, int v0, int V, doub
 // per-request outputs and the state the draw kernel needs.
 __global__ __launch_bounds__(kSweepThreads) void accept_chain_sweep(AcceptParams P) {
   __shared__ double s_lse[kMaxNq];
-  __shared__ int s_ok[kMaxNq];
+  __shared__ int s_ok[kMaxNq], s_arg[kMaxNq];
   __shared__ int s_last[kSweepThreads / kWave];
   const int slice = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
   const int Nq = P.Nq, V = P.V;
-  const double T = (double)P.temperature;
+  // with one temperature per request, a request at T = 0 is verified greedily inside this kernel
+  const float Tf = request_temperature(P, b);
+  const bool greedy = !(Tf > 0.f);
+  const double T = greedy ? 1.0 : (double)Tf;
   const size_t row0 = (size_t)b * Nq;
   // operands of the accept tests: their addresses are known up front, so the loads fly during the merge
   float t_l = 0.f, t_q = 0.f, t_u = 0.f;
+  int t_tok = -1;
   if (tid > 0 && tid < Nq) {
-    const int tk = P.tok[row0 + tid];
-    t_l = P.logits[(row0 + tid - 1) * V + tk];
-    t_q = q_at(q_row(P, row0 + tid - 1), tk);
+    t_tok = P.tok[row0 + tid];
+    t_l = P.logits[(row0 + tid - 1) * V + t_tok];
+    t_q = q_at(q_row(P, row0 + tid - 1), t_tok);
     t_u = P.un[(row0 + tid) * 2 + 0];
   }
   for (int n = wv; n < Nq; n += kSweepThreads / kWave) {
     float mx; double lse; int arg;
     merge_row_stats(P, row0 + n, T, lane, &mx, &lse, &arg);
-    if (lane == 0) s_lse[n] = lse;
+    if (lane == 0) { s_lse[n] = lse; s_arg[n] = arg; }
   }
   __syncthreads();
   if (tid < Nq) {
     const int n = tid;
     float pv = 0.f;
     int ok = 1;
-    if (n > 0) {
+    if (n > 0 && greedy) {
+      ok = t_tok == s_arg[n - 1];
+      pv = ok ? 1.f : 0.f;
+    } else if (n > 0) {
       const double p = exp((double)t_l / T - s_lse[n - 1]);
       ok = ((double)t_u * (double)t_q < p) ? 1 : 0;
       pv = (float)p;
@@ -264,10 +277,12 @@ __global__ __launch_bounds__(kSweepThreads) void accept_chain_sweep(AcceptParams
     if (tid == 0) {
       P.accept_len[b] = row;
       P.st_row[b] = row;
-      P.st_rej[b] = nres;
+      P.st_rej[b] = greedy ? 2 : nres;  // 2: nothing left for the draw kernel
       P.st_lse[b] = lse;
+      if (greedy) P.next_token[b] = s_arg[row];
     }
   }
+  if (greedy) return;  // the whole workgroup: a greedy request has no sweep
 
   const double inv_t = 1.0 / T;
   const float* lrow = P.logits + (row0 + row) * V;
@@ -321,8 +336,9 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams 
   const int V = P.V, ng = P.ngroups;
   const int row = P.st_row[b];
   int nres = P.st_rej[b];
+  if (nres == 2) return;  // a greedy request (one temperature per request): its token is already written
   const double lse = P.st_lse[b];
-  const double inv_t = 1.0 / (double)P.temperature;
+  const double inv_t = 1.0 / (double)request_temperature(P, b);
   const float* lrow = P.logits + ((size_t)b * P.Nq + row) * V;
   const QRow qrow = q_row(P, (size_t)b * P.Nq + row);
   const bool vec_ok = rows_vec_ok(P);
@@ -471,8 +487,9 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   const bool writer = slice == 0;                     // the workgroup that stores the request's outputs
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
   const int Nq = P.Nq, V = P.V;
-  const bool greedy = !(P.temperature > 0.f);
-  const double T = greedy ? 1.0 : (double)P.temperature;
+  const float Tf = request_temperature(P, b);
+  const bool greedy = !(Tf > 0.f);
+  const double T = greedy ? 1.0 : (double)Tf;
   const double inv_t = 1.0 / T;
   const size_t row0 = (size_t)b * Nq;
   if (tid < Nq) {
@@ -519,7 +536,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
 
   // ---- 2a. greedy walk: thread 0 only -----------------------------------------------------------
   if (greedy) {
-    if (tid == 0) {
+    if (tid == 0 && writer) {
       int cur = 0, depth = 0;
       for (;;) {
         int moved = 0;
@@ -789,12 +806,14 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st) {
   P.slices = a.plan.slices; P.gmul = a.plan.gmul; P.ngroups = a.plan.ngroups;
   P.st_lse = a.st_lse; P.st_row = a.st_row; P.st_rej = a.st_rej; P.gsum = a.gsum; P.lastpos = a.lastpos;
   P.tree_bar = a.tree_bar;
-  const bool chain_sampling = a.temperature > 0.f && a.parents == nullptr;
+  P.temps = a.temps;
+  const bool sampling = a.temperature > 0.f || a.temps != nullptr;  // per-request temperatures: the sampling kernels
+  const bool chain_sampling = sampling && a.parents == nullptr;
   if (!chain_sampling) {
     const int ngroups = (a.V + kGroup - 1) / kGroup;
-    if (a.temperature > 0.f && ngroups > kMaxGroups) return hipErrorInvalidValue;
+    if (sampling && ngroups > kMaxGroups) return hipErrorInvalidValue;
     int S = 1;
-    if (a.temperature > 0.f) {
+    if (sampling) {
       int cus = 0;
       if (hipError_t e = device_cu_count(&cus); e != hipSuccess) return e;
       S = tree_slices_for(a.B, ngroups, cus);

@@ -37,7 +37,7 @@ int check_accept_desc(const aurora_accept_desc* d) {
     if (d->hidden % 128) return AURORA_ERR_UNSUPPORTED;  // only the matrix-core kernel takes 8-bit operands
   }
   if (d->draft_vocab < 0 || d->draft_vocab > d->vocab) return AURORA_ERR_INVALID_ARG;
-  if (d->draft_vocab > 0 && d->temperature > 0.f && !d->target_to_draft) return AURORA_ERR_INVALID_ARG;
+  if (d->draft_vocab > 0 && (d->temperature > 0.f || d->temperatures) && !d->target_to_draft) return AURORA_ERR_INVALID_ARG;
   return AURORA_OK;
 }
 
@@ -88,7 +88,8 @@ AcceptLaunch accept_launch_from(const aurora_accept_desc* d) {
   a.fp8 = d->dtype == AURORA_FP8_E4M3;
   a.hidden_scale = d->hidden_scale; a.lm_scale = d->lm_head_scale;
   a.temperature = d->temperature;
-  if (d->draft_vocab > 0 && d->temperature > 0.f) { a.Vd = d->draft_vocab; a.target_to_draft = d->target_to_draft; }
+  a.temps = d->temperatures;
+  if (d->draft_vocab > 0 && (d->temperature > 0.f || d->temperatures)) { a.Vd = d->draft_vocab; a.target_to_draft = d->target_to_draft; }
   return a;
 }
 
@@ -149,10 +150,10 @@ int run_accept(const aurora_accept_desc* desc, const void* hidden, const void* l
   if (desc->batch == 0) return AURORA_OK;
   if (!draft_tokens || !accept_len || !next_token || !accept_mask) return AURORA_ERR_INVALID_ARG;
   if (with_lmhead && (!hidden || !lm_head)) return AURORA_ERR_INVALID_ARG;
-  if (desc->temperature > 0.f && (!draft_probs || !uniforms)) return AURORA_ERR_INVALID_ARG;
+  if ((desc->temperature > 0.f || desc->temperatures) && (!draft_probs || !uniforms)) return AURORA_ERR_INVALID_ARG;
   if (with_lmhead && (((uintptr_t)hidden | (uintptr_t)lm_head) & 15)) return AURORA_ERR_INVALID_ARG;
   // the one-workgroup tree walk keeps one partial sum per 256 tokens in LDS
-  if (desc->temperature > 0.f && parents && desc->vocab > (1 << 20)) return AURORA_ERR_UNSUPPORTED;
+  if ((desc->temperature > 0.f || desc->temperatures) && parents && desc->vocab > (1 << 20)) return AURORA_ERR_UNSUPPORTED;
   AcceptPlan plan = plan_accept(desc);
   if (!workspace || misaligned(workspace) || workspace_bytes < plan.bytes) return AURORA_ERR_WORKSPACE;
   AcceptLaunch a = accept_launch_from(desc);
@@ -290,7 +291,7 @@ int aurora_verify(const aurora_attn_desc* attn_desc, const aurora_accept_desc* a
   if (accept_desc->batch > 0) {
     if (!hidden || !lm_head || !draft_tokens || !accept_len || !next_token || !accept_mask)
       return AURORA_ERR_INVALID_ARG;
-    if (accept_desc->temperature > 0.f && (!draft_probs || !uniforms)) return AURORA_ERR_INVALID_ARG;
+    if ((accept_desc->temperature > 0.f || accept_desc->temperatures) && (!draft_probs || !uniforms)) return AURORA_ERR_INVALID_ARG;
   }
   rc = run_attn(attn_desc, q, k_pages, v_pages, block_table, seq_lens, parents, attn_out, workspace, attn_bytes,
                 (hipStream_t)hip_stream);

@@ -26,6 +26,7 @@ struct AcceptLaunch {
   bool fp8;                              // hidden / lm_head are E4M3 codes with per-row scales
   const float *hidden_scale, *lm_scale;  // [B*Nq], [V] when fp8
   float temperature;
+  const float* temps;  // [B] one temperature per request (0 = greedy request), or NULL: `temperature` for all
   const void *hidden, *lm_head;
   const int32_t *draft_tokens, *parents;
   const float *draft_probs, *uniforms;

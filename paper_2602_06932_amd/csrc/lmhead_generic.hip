@@ -58,7 +58,8 @@ __global__ __launch_bounds__(256) void lmhead_generic(const T* __restrict__ hidd
 // sum exp((l - max) * inv_t) over the tile's columns.
 __global__ __launch_bounds__(256) void row_tile_stats(const float* __restrict__ logits, float* __restrict__ pmax,
                                                       float* __restrict__ psum, int32_t* __restrict__ parg, int V,
-                                                      int stat_tile, int n_tiles, float inv_t) {
+                                                      int stat_tile, int n_tiles, float inv_t,
+                                                      const float* __restrict__ temps, int Nq) {
   __shared__ float smax[4];
   __shared__ int sarg[4];
   __shared__ float ssum[4];
@@ -67,6 +68,10 @@ __global__ __launch_bounds__(256) void row_tile_stats(const float* __restrict__ 
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
   const int v0 = tile * stat_tile, v1 = min(V, v0 + stat_tile);
   const float* lr = logits + row * V;
+  if (temps) {  // one temperature per request; 0 = greedy, statistics at T = 1
+    const float T = temps[row / Nq];
+    inv_t = T > 0.f ? 1.f / T : 1.f;
+  }
   float mx = -INFINITY;
   int arg = 0x7fffffff;
   for (int v = v0 + tid; v < v1; v += 256) {
@@ -109,7 +114,7 @@ hipError_t launch_lmhead_generic(const AcceptLaunch& a, hipStream_t st) {
   if (e != hipSuccess) return e;
   const float inv_t = a.temperature > 0.f ? 1.f / a.temperature : 1.f;
   hipLaunchKernelGGL(row_tile_stats, dim3(a.plan.n_tiles, (unsigned)M), dim3(256), 0, st, a.logits, a.pmax, a.psum,
-                     a.parg, a.V, a.plan.stat_tile, a.plan.n_tiles, inv_t);
+                     a.parg, a.V, a.plan.stat_tile, a.plan.n_tiles, inv_t, a.temps, a.Nq);
   return hipGetLastError();
 }
 

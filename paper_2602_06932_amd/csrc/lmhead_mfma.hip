@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     const char* __restrict__ hidden, const char* __restrict__ w, const float* __restrict__ h_scale,
     const float* __restrict__ w_scale, float* __restrict__ logits, float* __restrict__ pmax,
     float* __restrict__ psum, int32_t* __restrict__ parg, int M, int H, int V, int n_tiles, int m_tiles,
-    float exp_scale /* log2(e) / T */) {
+    float exp_scale /* log2(e) / T */, const float* __restrict__ temps /* per-request T, or NULL */, int Nq) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   constexpr int kEsz = kFp8 ? 1 : 2;             // bytes per operand element
   constexpr int kLmBK = kLmRowBytes / kEsz;      // hidden elements per stage
@@ -239,7 +239,8 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
   for (int t = 0; t < NT; ++t) {
     float mx, sum;
     int arg;
-    lm_tile_out(acc[0][t], acc[1][t], vrow0, V, m0 + 32 * t, M, exp_scale, tb, logits, vec_ok, lane, mx, sum, arg);
+    lm_tile_out(acc[0][t], acc[1][t], vrow0, V, m0 + 32 * t, M, lm_row_scale(exp_scale, temps, Nq, m0 + 32 * t + li, M), tb,
+                logits, vec_ok, lane, mx, sum, arg);
     if (lh == 0) {
       st_max[wv * NT * 32 + t * 32 + li] = mx;
       st_sum[wv * NT * 32 + t * 32 + li] = sum;
@@ -252,7 +253,7 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     if (m < M) {
       float mx, sum;
       int arg;
-      lm_merge_waves(st_max, st_sum, st_arg, NT * 32, tid, exp_scale, mx, sum, arg);
+      lm_merge_waves(st_max, st_sum, st_arg, NT * 32, tid, lm_row_scale(exp_scale, temps, Nq, m, M), mx, sum, arg);
       const size_t o = (size_t)m * n_tiles + vt;
       pmax[o] = mx;
       psum[o] = sum;
@@ -278,7 +279,7 @@ static hipError_t launch_nt_t(const AcceptLaunch& a, hipStream_t st, int m_tiles
   dim3 grid((v_tiles + 7) / 8 * 8 * m_tiles);
   hipLaunchKernelGGL((lmhead_mfma_kernel<NT, kFp8>), grid, dim3(kLmThreads), lds_bytes, st, (const char*)a.hidden,
                      (const char*)a.lm_head, a.hidden_scale, a.lm_scale, a.logits, a.pmax, a.psum, a.parg,
-                     (int)a.plan.rows, a.H, a.V, a.plan.n_tiles, m_tiles, exp_scale);
+                     (int)a.plan.rows, a.H, a.V, a.plan.n_tiles, m_tiles, exp_scale, a.temps, a.Nq);
   return hipGetLastError();
 }
 

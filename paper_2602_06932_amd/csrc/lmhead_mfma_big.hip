@@ -40,7 +40,8 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
 __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
     const bf16_t* __restrict__ hidden, const bf16_t* __restrict__ w, float* __restrict__ logits,
     float* __restrict__ pmax, float* __restrict__ psum, int32_t* __restrict__ parg, int M, int H, int V, int n_tiles,
-    int m_tiles, float exp_scale /* log2(e) / T */) {
+    int m_tiles, float exp_scale /* log2(e) / T */, const float* __restrict__ temps /* per-request T, or NULL */,
+    int Nq) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -185,7 +186,8 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
     if (m0 + col0 < M) {  // tiles wholly past the last token row hold nothing
       float mx, sum;
       int arg;
-      lm_tile_out(acc[0][t], acc[1][t], vrow0, V, m0 + col0, M, exp_scale, tb, logits, vec_ok, lane, mx, sum, arg);
+      lm_tile_out(acc[0][t], acc[1][t], vrow0, V, m0 + col0, M, lm_row_scale(exp_scale, temps, Nq, m0 + col0 + li, M), tb,
+                  logits, vec_ok, lane, mx, sum, arg);
       if (lh == 0) {
         st_max[wvv * kBgMTile + col0 + li] = mx;
         st_sum[wvv * kBgMTile + col0 + li] = sum;
@@ -199,7 +201,7 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
     if (m < M) {
       float mx, sum;
       int arg;
-      lm_merge_waves(st_max, st_sum, st_arg, kBgMTile, tid, exp_scale, mx, sum, arg);
+      lm_merge_waves(st_max, st_sum, st_arg, kBgMTile, tid, lm_row_scale(exp_scale, temps, Nq, m, M), mx, sum, arg);
       const size_t o = (size_t)m * n_tiles + vt;
       pmax[o] = mx;
       psum[o] = sum;
@@ -222,7 +224,7 @@ hipError_t launch_lmhead_mfma_big(const AcceptLaunch& a, hipStream_t st) {
   dim3 grid((v_tiles + 7) / 8 * 8 * m_tiles);
   hipLaunchKernelGGL(lmhead_mfma_big_kernel, grid, dim3(kBgThreads), kBgLdsBytes, st, (const bf16_t*)a.hidden,
                      (const bf16_t*)a.lm_head, a.logits, a.pmax, a.psum, a.parg, M, a.H, a.V, a.plan.n_tiles, m_tiles,
-                     exp_scale);
+                     exp_scale, a.temps, a.Nq);
   return hipGetLastError();
 }
 

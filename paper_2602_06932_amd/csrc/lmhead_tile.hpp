@@ -97,6 +97,14 @@ __device__ __forceinline__ void lm_tile_out(f32x16_t& a0, f32x16_t& a1, int vrow
   }
 }
 
+// exp2 scale log2(e) / T of token row m: the call's scalar, or - with one temperature per request (temps[b],
+// b = m / Nq; 0 stands for a greedy request, whose statistics are taken at T = 1) - the request's own.
+__device__ __forceinline__ float lm_row_scale(float exp_scale, const float* __restrict__ temps, int Nq, int m, int M) {
+  if (!temps) return exp_scale;
+  const float T = temps[(m < M ? m : M - 1) / Nq];
+  return 1.4426950408889634f / (T > 0.f ? T : 1.f);
+}
+
 // Merge of the four wavefronts' statistics of one token (ascending vocab order, so ties keep the lowest
 // index).  st_* are laid out [4][stride].
 __device__ __forceinline__ void lm_merge_waves(const float* st_max, const float* st_sum, const int* st_arg, int stride,

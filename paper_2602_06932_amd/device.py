@@ -67,13 +67,16 @@ class DeviceVerify:
         # a draft model with its own vocabulary: the target -> draft index map goes with the descriptor
         t2d = w.target_to_draft() if getattr(w, "draft_to_target", None) is not None else None
         self.target_to_draft = _to_dev(t2d, None)
+        temps = getattr(w, "temperatures", None)     # one temperature per request, or None
+        self.temperatures = _to_dev(None if temps is None else np.asarray(temps, np.float32), None)
         self.accept_desc = B.aurora_accept_desc(
             batch=w.batch, num_q=w.num_q, hidden=w.hidden_size, vocab=w.vocab,
             dtype=B.AURORA_FP8_E4M3 if head_fp8 else self.dt,
             temperature=w.temperature, draft_vocab=int(getattr(w, "draft_vocab", 0) or 0),
             target_to_draft=None if t2d is None else self.target_to_draft.data_ptr(),
             hidden_scale=self.hidden_scale.data_ptr() if head_fp8 else None,
-            lm_head_scale=self.lm_head_scale.data_ptr() if head_fp8 else None)
+            lm_head_scale=self.lm_head_scale.data_ptr() if head_fp8 else None,
+            temperatures=None if temps is None else self.temperatures.data_ptr())
         self.ws_bytes = B.aurora_verify_workspace_bytes(self.attn_desc, self.accept_desc)
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
         assert self.workspace.data_ptr() % 256 == 0

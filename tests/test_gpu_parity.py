@@ -567,3 +567,42 @@ def test_lookahead_ten_at_llama_shapes(gpu_lib):
     w = gen.llama_chain(97, batch=6, num_q=11, len_lo=900, len_hi=2500, draft_noise=0.4)
     _, a = _full_check(gpu_lib, w, sample=[0, 3, 5])
     assert a.accept_len.max() >= 2
+
+
+# ---- one temperature per request -------------------------------------------------------------------------------
+@pytest.mark.parametrize("tree", [False, True])
+def test_one_temperature_per_request(gpu_lib, tree):
+    """A batch that mixes sampling temperatures and greedy requests (T = 0) in one call."""
+    temps = [1.0, 0.0, 0.5, 2.0, 0.0, 1.3, 0.8]
+    kw = dict(batch=7, vocab=9000, hidden_size=128, temperatures=temps, draft_noise=0.5)
+    w = gen.llama_tree(101, num_q=12, context=80, num_q_heads=4, num_kv_heads=2, **kw) if tree else \
+        gen.llama_chain(101, len_lo=30, len_hi=300, **kw)
+    dv, a = _full_check(gpu_lib, w)
+    assert a.accept_len.max() >= 1
+
+
+def test_equal_temperatures_per_request_equal_the_scalar_call(gpu_lib):
+    """temperatures[b] = T for every b must give bit for bit what the scalar temperature T gives."""
+    import dataclasses
+    from paper_2602_06932_amd.device import DeviceVerify
+    for mk in (lambda **k: gen.llama_chain(102, batch=5, len_lo=30, len_hi=200, vocab=5000, hidden_size=128, **k),
+               lambda **k: gen.llama_tree(103, batch=4, num_q=10, context=60, vocab=20000, hidden_size=128,
+                                          num_q_heads=4, num_kv_heads=2, **k)):
+        w = mk(temperature=0.7)
+        a = DeviceVerify(w); a.verify(); ra = a.results_host()
+        wt = dataclasses.replace(w, temperatures=np.full(w.batch, 0.7, np.float32))
+        b = DeviceVerify(wt); b.verify(); rb = b.results_host()
+        for k in ra:
+            assert np.array_equal(ra[k], rb[k], equal_nan=True), k
+
+
+def test_all_greedy_temperatures_equal_the_greedy_call(gpu_lib):
+    import dataclasses
+    from paper_2602_06932_amd.device import DeviceVerify
+    w = gen.llama_chain(104, batch=6, len_lo=30, len_hi=200, vocab=5000, hidden_size=128, draft_noise=0.2)
+    wg = dataclasses.replace(w, temperature=0.0)
+    a = DeviceVerify(wg); a.verify(); ra = a.results_host()
+    wt = dataclasses.replace(w, temperatures=np.zeros(w.batch, np.float32))
+    b = DeviceVerify(wt); b.verify(); rb = b.results_host()
+    for k in ("accept_len", "next_token", "accept_mask", "p_at_draft", "row_lse"):
+        assert np.array_equal(ra[k], rb[k], equal_nan=True), k

@@ -370,3 +370,26 @@ def test_subvocabulary_generator_is_consistent():
     assert np.all(np.diff(d2t) > 0) and np.array_equal(t2d[d2t], np.arange(250))
     assert (t2d >= 0).sum() == 250 and np.all(t2d[w.draft_tokens[:, 1:]] >= 0)
     assert np.allclose(w.draft_probs.sum(-1), 1.0, atol=1e-4)
+
+
+def test_one_temperature_per_request_is_the_scalar_oracle_request_by_request():
+    """A workload with its own temperature per request (0 = greedy): every request must come out as the scalar
+    oracle gives it alone at that temperature; equal temperatures must reproduce the scalar call on the batch."""
+    import dataclasses
+    temps = np.array([1.0, 0.0, 0.6, 1.7], np.float32)
+    w = gen.llama_chain(33, batch=4, len_lo=20, len_hi=50, vocab=400, hidden_size=64, temperatures=temps)
+    a = oracle.accept_workload(w)
+    for b in range(4):
+        wb = dataclasses.replace(w.take_requests([b]), temperatures=None, temperature=float(temps[b]))
+        if temps[b] == 0:
+            wb = dataclasses.replace(wb, draft_probs=None, uniforms=None)
+        one = oracle.accept_workload(wb)
+        assert one.accept_len[0] == a.accept_len[b] and one.next_token[0] == a.next_token[b]
+        assert np.array_equal(one.accept_mask[0], a.accept_mask[b]) and np.array_equal(one.row_lse[0], a.row_lse[b])
+    ws = dataclasses.replace(w, temperatures=None, temperature=0.6)
+    wt = dataclasses.replace(w, temperatures=np.full(4, 0.6, np.float32))
+    x, y = oracle.accept_workload(ws), oracle.accept_workload(wt)
+    for f in ("accept_len", "next_token", "accept_mask", "p_at_draft", "row_lse"):
+        assert np.array_equal(getattr(x, f), getattr(y, f)), f
+    # the generator draws request b's draft distribution at its own temperature: a colder request is more peaked
+    assert w.draft_probs[2].max(axis=-1).mean() > w.draft_probs[3].max(axis=-1).mean()
