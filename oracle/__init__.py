@@ -301,3 +301,9 @@ def draft_loss(*args, **kw):
     """Drafter training loss of paper eq. 3 on a batch of trace rows (see oracle/loss_oracle.py)."""
     from .loss_oracle import draft_loss as _impl
     return _impl(*args, **kw)
+
+
+def trace_pack(*args, **kw):
+    """Packing of the trace records of the rows that carry a training signal (see oracle/pack_oracle.py)."""
+    from .pack_oracle import trace_pack as _impl
+    return _impl(*args, **kw)
