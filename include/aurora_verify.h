@@ -289,6 +289,37 @@ int aurora_trace_emit(const aurora_trace_desc* desc,
 const char* aurora_status_string(int status);
 
 /*
+ * Packing of the trace records that are shipped to the training side (appendix A.1, eq. 4: a record is
+ * (h, l, x_in, y_out, R); section 3.3: accepted and rejected tokens both carry a training signal).  Of the
+ * `rows` token rows of a verify step (or of several) only those with traj[m] != 0 - on the accepted path, or
+ * tested and rejected - are kept; rows that were never tested are dropped.  Kept rows are copied in ascending
+ * row order into dense arrays:
+ *   n_out     [1]       number of kept rows n
+ *   row_index [rows]    row_index[p], p < n: the source row of packed position p (entries from n on are not written)
+ *   for every input that is given (a NULL input skips its output; topk_ids / topk_logits come as a pair), its
+ *   packed copy, position p holding source row row_index[p]:
+ *     h            [rows, h_row_bytes] bytes  -> h_out          the hidden row(s) of the token, any element type
+ *     topk_ids     [rows, K] int32            -> topk_ids_out
+ *     topk_logits  [rows, K] bf16 bits        -> topk_logits_out
+ *     x_in, y_out  [rows] int32               -> x_in_out, y_out_out
+ *     traj         [rows] int8                -> traj_out (may be NULL)
+ * Output arrays are sized for `rows` rows by the caller.  All pointers are DEVICE pointers; asynchronous on
+ * hip_stream; no workspace; the result is unique, hence bit-reproducible.  AURORA_ERR_INVALID_ARG for missing
+ * traj / n_out / row_index, an input without its output (or the reverse), or negative sizes.
+ */
+typedef struct {
+  int32_t rows;        /* M >= 0                                              */
+  int32_t top_k;       /* K >= 0 entries per row of topk_ids / topk_logits    */
+  int64_t h_row_bytes; /* bytes of one row of h (0 if h is not packed)        */
+} aurora_pack_desc;
+
+int aurora_trace_pack(const aurora_pack_desc* desc, const int8_t* traj, const void* h, const int32_t* topk_ids,
+                      const uint16_t* topk_logits, const int32_t* x_in, const int32_t* y_out,
+                      int32_t* n_out, int32_t* row_index, void* h_out, int32_t* topk_ids_out,
+                      uint16_t* topk_logits_out, int32_t* x_in_out, int32_t* y_out_out, int8_t* traj_out,
+                      void* hip_stream);
+
+/*
  * Drafter training loss on a batch of trace rows (paper section 3.3, eq. 3) - the first thing the training
  * side computes from what aurora_trace_emit produced:
  *

@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_v
 
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
            "aurora_verify_lmhead", "aurora_verify_accept_logits", "aurora_trace_emit",
-           "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs", "aurora_draft_loss")
+           "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack")
 
 
 class aurora_attn_desc(C.Structure):
@@ -43,6 +43,10 @@ class aurora_accept_desc(C.Structure):
 class aurora_trace_desc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("vocab", C.c_int32), ("top_k", C.c_int32),
                 ("draft_vocab", C.c_int32), ("draft_to_target", C.c_void_p)]
+
+
+class aurora_pack_desc(C.Structure):
+    _fields_ = [("rows", C.c_int32), ("top_k", C.c_int32), ("h_row_bytes", C.c_int64)]
 
 
 class aurora_loss_desc(C.Structure):
@@ -88,6 +92,8 @@ def load():
     lib.aurora_trace_emit.restype = C.c_int
     lib.aurora_verify_check_inputs.argtypes = [ad, cd, i32p, i32p, i32p, i32p, f32p, i32p, vp]
     lib.aurora_verify_check_inputs.restype = C.c_int
+    lib.aurora_trace_pack.argtypes = [C.POINTER(aurora_pack_desc)] + [vp] * 15
+    lib.aurora_trace_pack.restype = C.c_int
     lib.aurora_draft_loss.argtypes = [C.POINTER(aurora_loss_desc), f32p, i32p, vp, vp, f32p, f32p, f32p, vp]
     lib.aurora_draft_loss.restype = C.c_int
     lib.aurora_verify_logits_ptr.argtypes = [ad, cd, vp]
@@ -212,7 +218,18 @@ def aurora_verify_check_inputs(attn_desc, accept_desc, block_table, seq_lens, pa
                                            _ptr(parents), _ptr(draft_tokens), _ptr(uniforms), _ptr(flags),
                                            _stream(stream))
     if check and st != AURORA_OK:
-        raise AuroraError(st, "aurora_verify_check_inputs", "aurora_draft_loss")
+        raise AuroraError(st, "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack")
+    return st
+
+
+def aurora_trace_pack(desc, traj, h, topk_ids, topk_logits, x_in, y_out, n_out, row_index, h_out, topk_ids_out,
+                      topk_logits_out, x_in_out, y_out_out, traj_out, stream=None, check=True) -> int:
+    st = load().aurora_trace_pack(_ref(desc), _ptr(traj), _ptr(h), _ptr(topk_ids), _ptr(topk_logits), _ptr(x_in),
+                                  _ptr(y_out), _ptr(n_out), _ptr(row_index), _ptr(h_out), _ptr(topk_ids_out),
+                                  _ptr(topk_logits_out), _ptr(x_in_out), _ptr(y_out_out), _ptr(traj_out),
+                                  _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_trace_pack")
     return st
 
 

@@ -334,6 +334,28 @@ int aurora_verify_check_inputs(const aurora_attn_desc* attn_desc, const aurora_a
   return launch_check_inputs(c, (hipStream_t)hip_stream) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
 }
 
+int aurora_trace_pack(const aurora_pack_desc* d, const int8_t* traj, const void* h, const int32_t* topk_ids,
+                      const uint16_t* topk_logits, const int32_t* x_in, const int32_t* y_out,
+                      int32_t* n_out, int32_t* row_index, void* h_out, int32_t* topk_ids_out,
+                      uint16_t* topk_logits_out, int32_t* x_in_out, int32_t* y_out_out, int8_t* traj_out,
+                      void* hip_stream) {
+  if (!d || d->rows < 0 || d->top_k < 0 || d->h_row_bytes < 0) return AURORA_ERR_INVALID_ARG;
+  if (!n_out || (d->rows > 0 && (!traj || !row_index))) return AURORA_ERR_INVALID_ARG;
+  if ((h != nullptr) != (h_out != nullptr) || (h && d->h_row_bytes == 0)) return AURORA_ERR_INVALID_ARG;
+  if ((topk_ids != nullptr) != (topk_logits != nullptr)) return AURORA_ERR_INVALID_ARG;
+  if ((topk_ids != nullptr) != (topk_ids_out != nullptr) || (topk_logits != nullptr) != (topk_logits_out != nullptr))
+    return AURORA_ERR_INVALID_ARG;
+  if (topk_ids && d->top_k == 0) return AURORA_ERR_INVALID_ARG;
+  if ((x_in != nullptr) != (x_in_out != nullptr) || (y_out != nullptr) != (y_out_out != nullptr))
+    return AURORA_ERR_INVALID_ARG;
+  PackLaunch P = {};
+  P.M = d->rows; P.K = d->top_k; P.h_bytes = (size_t)d->h_row_bytes;
+  P.traj = traj; P.h = h; P.ids = topk_ids; P.vals = topk_logits; P.x_in = x_in; P.y = y_out;
+  P.n_out = n_out; P.row_index = row_index; P.h_out = h_out; P.ids_out = topk_ids_out; P.vals_out = topk_logits_out;
+  P.x_out = x_in_out; P.y_packed = y_out_out; P.traj_out = traj_out;
+  return launch_trace_pack(P, (hipStream_t)hip_stream) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
+}
+
 int aurora_draft_loss(const aurora_loss_desc* d, const float* draft_logits, const int32_t* topk_ids,
                       const uint16_t* topk_logits, const int8_t* traj, float* row_kl, float* loss_out, float* grad,
                       void* hip_stream) {

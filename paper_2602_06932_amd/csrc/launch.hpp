@@ -68,6 +68,24 @@ hipError_t launch_trace_records(int B, int Nq, const int32_t* draft_tokens, cons
                                 const int32_t* next_token, const uint8_t* accept_mask, int32_t* y_out, int8_t* traj,
                                 hipStream_t st);
 
+// packing of trace records (see pack.hip)
+struct PackLaunch {
+  int M, K;
+  size_t h_bytes;           // bytes of one hidden row
+  const int8_t* traj;
+  const void* h;            // or NULL
+  const int32_t* ids;       // [M, K] or NULL (then vals is NULL too)
+  const uint16_t* vals;
+  const int32_t *x_in, *y;  // [M] or NULL
+  int32_t *n_out, *row_index;
+  void* h_out;
+  int32_t* ids_out;
+  uint16_t* vals_out;
+  int32_t *x_out, *y_packed;
+  int8_t* traj_out;
+};
+hipError_t launch_trace_pack(const PackLaunch& P, hipStream_t st);
+
 // drafter training loss on trace rows (see loss.hip)
 struct LossLaunch {
   int M, Vd, K, discard_k;
