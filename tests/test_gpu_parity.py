@@ -606,3 +606,12 @@ def test_all_greedy_temperatures_equal_the_greedy_call(gpu_lib):
     b = DeviceVerify(wt); b.verify(); rb = b.results_host()
     for k in ("accept_len", "next_token", "accept_mask", "p_at_draft", "row_lse"):
         assert np.array_equal(ra[k], rb[k], equal_nan=True), k
+
+
+def test_all_optional_forms_together(gpu_lib):
+    """8-bit KV cache, 8-bit LM head, a draft vocabulary and one temperature per request in one call, chain and tree."""
+    temps = [0.9, 0.0, 1.4, 0.6, 1.0]
+    kw = dict(batch=5, vocab=12000, hidden_size=256, temperatures=temps, draft_noise=0.5, draft_vocab=3000,
+              head_fp8=True, kv_fp8=True)
+    _full_check(gpu_lib, gen.llama_chain(121, len_lo=40, len_hi=400, **kw))
+    _full_check(gpu_lib, gen.llama_tree(122, num_q=10, context=90, num_q_heads=8, num_kv_heads=2, **kw))
