@@ -307,3 +307,9 @@ def trace_pack(*args, **kw):
     """Packing of the trace records of the rows that carry a training signal (see oracle/pack_oracle.py)."""
     from .pack_oracle import trace_pack as _impl
     return _impl(*args, **kw)
+
+
+def attn_backward(*args, **kw):
+    """Backward pass of the chunk / tree attention (see oracle/attn_bwd_oracle.py)."""
+    from .attn_bwd_oracle import attn_backward as _impl
+    return _impl(*args, **kw)

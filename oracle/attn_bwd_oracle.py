@@ -1,0 +1,68 @@
+"""Oracle of the backward pass of the tree / chunk attention (paper section 3.1, "Efficient Tree Attention":
+all accepted and rejected branches of the speculative tree go through one batched forward and backward pass
+under a mask that follows the tree).
+
+TEST INFRASTRUCTURE ONLY.  Plain NumPy, float64, one (request, query head, node) row at a time - the chain
+rule of out = softmax(scale * q K^T + mask) V written out:
+
+    p_j   = softmax_j(scale * <q, k_j>)  over the visible positions j (prefix, the node itself, its ancestors)
+    delta = <dout, out>
+    dP_j  = <dout, v_j>
+    dS_j  = p_j * (dP_j - delta)
+    dq    = scale * sum_j dS_j k_j ;   dk_j += scale * dS_j q ;   dv_j += p_j dout
+
+dk / dv of a KV position collect the contributions of every query row that sees it (all nodes, all query heads
+of the KV head's group).  They are returned in the paged layout of the pools; positions no request uses stay 0.
+Reading: the gradient flows to q and to every visible K / V position, the cached prefix included (the
+drafter's own cache is a function of its weights); nothing else of the training step is part of this.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def attn_backward(q, k_pages, v_pages, block_table, seq_lens, parents, dout, sm_scale=0.0):
+    """q, dout [B,Nq,Hq,D]; pools [P,Hkv,page,D] (float arrays holding the stored values); returns
+    (out, dq, dk_pages, dv_pages), all float64."""
+    q = np.asarray(q, np.float64)
+    dout = np.asarray(dout, np.float64)
+    kp = np.asarray(k_pages, np.float64)
+    vp = np.asarray(v_pages, np.float64)
+    B, Nq, Hq, D = q.shape
+    P, Hkv, page, _ = kp.shape
+    G = Hq // Hkv
+    scale = sm_scale if sm_scale > 0 else 1.0 / np.sqrt(D)
+    out = np.zeros_like(q)
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(kp)
+    dv = np.zeros_like(vp)
+    for b in range(B):
+        L = int(seq_lens[b])
+        prefix = L - Nq
+        where = [(int(block_table[b, j // page]), j % page) for j in range(L)]
+        for n in range(Nq):
+            seen = np.zeros(L, bool)
+            seen[:prefix] = True
+            a = n
+            while a >= 0:
+                seen[prefix + a] = True
+                a = int(parents[b, a]) if parents is not None else a - 1
+            js = np.flatnonzero(seen)
+            for hq in range(Hq):
+                hk = hq // G
+                K = np.stack([kp[where[j][0], hk, where[j][1]] for j in js])
+                V = np.stack([vp[where[j][0], hk, where[j][1]] for j in js])
+                s = scale * (K @ q[b, n, hq])
+                p = np.exp(s - s.max())
+                p /= p.sum()
+                o = p @ V
+                out[b, n, hq] = o
+                g = dout[b, n, hq]
+                delta = float(g @ o)
+                dS = p * (V @ g - delta)
+                dq[b, n, hq] = scale * (dS @ K)
+                for t, j in enumerate(js):
+                    pg, off = where[j]
+                    dk[pg, hk, off] += scale * dS[t] * q[b, n, hq]
+                    dv[pg, hk, off] += p[t] * g
+    return out, dq, dk, dv
