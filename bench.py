@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_fp8kv", "llama_fp8", "llama_draft32k", "tiny", "qwen_greedy", "tree", "tree_fp8kv", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
-    ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy", "loss"],
+    ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy", "loss", "attn_bwd"],
                     help="profiling aid: launch only this stage --steps times (after --warmup) and exit; "
                          "'copy' runs a plain device-to-device copy of 1 GiB for counter calibration")
     args = ap.parse_args()
@@ -118,6 +118,34 @@ def main():
     gen_s = time.time() - t0
     dv = DeviceVerify(w)
     torch.cuda.synchronize()
+
+    if args.stage == "attn_bwd":
+        # training-side backward of the chunk / tree attention of this workload (forward included in the call)
+        dout = torch.randn(dv.q.shape, device="cuda").to(dv.q.dtype)
+        dq = torch.empty(dv.q.shape, dtype=torch.float32, device="cuda")
+        dk = torch.zeros(dv.k_pages.shape, dtype=torch.float32, device="cuda")
+        dvp = torch.zeros(dv.v_pages.shape, dtype=torch.float32, device="cuda")
+        wsb = torch.empty(av.aurora_attn_backward_workspace_bytes(dv.attn_desc), dtype=torch.uint8, device="cuda")
+        fn = lambda: av.aurora_attn_backward(dv.attn_desc, dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.seq_lens,
+                                             dv.parents, dout, dq, dk, dvp, wsb)
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        ms = event_time_ms(fn, args.steps, torch)
+        ms_fwd = event_time_ms(dv.attn, args.steps, torch)
+        tok = int(w.seq_lens.astype(np.int64).sum())
+        esz = 2 if w.dtype == "bf16" else 4
+        kv_elems = tok * w.num_kv_heads * w.head_dim
+        alg = 2 * kv_elems * esz * 2 + 2 * kv_elems * 4    # K, V read by the forward and by the backward; dK, dV written
+        rows = w.num_q * w.num_q_heads // w.num_kv_heads
+        flops = 2.0 * rows * w.head_dim * tok * w.num_kv_heads * (2 + 5)
+        print(json.dumps({"stage": "attn_bwd", "steps": args.steps, "avg_ms": ms, "forward_alone_ms": ms_fwd,
+                          "workload": w.name, "algorithmic_bytes": alg, "flops": flops,
+                          "roofline": {"bound": "alu", "achieved": flops / (ms * 1e-3) / 1e12, "peak": 157.3,
+                                       "unit": "TFLOP/s", "frac": flops / (ms * 1e-3) / 1e12 / 157.3,
+                                       "note": "fp32 vector arithmetic (first version of the kernel, no matrix cores)"},
+                          "hbm_GBps": alg / (ms * 1e-3) / 1e9}))
+        return
 
     if args.stage:
         if args.stage == "copy":

@@ -289,6 +289,29 @@ int aurora_trace_emit(const aurora_trace_desc* desc,
 const char* aurora_status_string(int status);
 
 /*
+ * Backward pass of the chunk / tree attention above (section 3.1, "Efficient Tree Attention": the training side
+ * puts the whole speculative tree - accepted and rejected branches - through one batched forward and backward
+ * pass under the tree's mask).  With out = aurora_verify_attn(q, K, V) and dout = dLoss / dout:
+ *
+ *   p_ij = softmax_j(sm_scale <q_i, k_j>) over the positions row i sees,  delta_i = <dout_i, out_i>
+ *   dS_ij = p_ij (<dout_i, v_j> - delta_i)
+ *   dq_i = sm_scale sum_j dS_ij k_j      dk_j = sm_scale sum_i dS_ij q_i      dv_j = sum_i p_ij dout_i
+ *
+ * (dk_j, dv_j sum over every node and every query head of the KV head's group that sees position j: the cached
+ * prefix receives gradient as well).  The call runs the forward pass itself (into the workspace), so `out` is
+ * not an argument.  dq is float32 [B, Nq, Hq, D]; dk_pages / dv_pages are float32 pools in the layout of
+ * k_pages / v_pages - the positions the batch's block tables address are written, every other element is
+ * left as it is.  dout has the type of q.  All sums run in a fixed order: bit-reproducible.
+ * This first version of the kernel is plain fp32 vector code (no matrix cores).  An 8-bit KV cache is not
+ * supported (AURORA_ERR_UNSUPPORTED).  Workspace: aurora_attn_backward_workspace_bytes().
+ */
+int aurora_attn_backward_workspace_bytes(const aurora_attn_desc* desc, size_t* out_bytes);
+int aurora_attn_backward(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                         const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents,
+                         const void* dout, float* dq, float* dk_pages, float* dv_pages,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Packing of the trace records that are shipped to the training side (appendix A.1, eq. 4: a record is
  * (h, l, x_in, y_out, R); section 3.3: accepted and rejected tokens both carry a training signal).  Of the
  * `rows` token rows of a verify step (or of several) only those with traj[m] != 0 - on the accepted path, or

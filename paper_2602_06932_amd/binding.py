@@ -23,7 +23,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_v
 
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
            "aurora_verify_lmhead", "aurora_verify_accept_logits", "aurora_trace_emit",
-           "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack")
+           "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack", "aurora_attn_backward",
+           "aurora_attn_backward_workspace_bytes")
 
 
 class aurora_attn_desc(C.Structure):
@@ -92,6 +93,10 @@ def load():
     lib.aurora_trace_emit.restype = C.c_int
     lib.aurora_verify_check_inputs.argtypes = [ad, cd, i32p, i32p, i32p, i32p, f32p, i32p, vp]
     lib.aurora_verify_check_inputs.restype = C.c_int
+    lib.aurora_attn_backward_workspace_bytes.argtypes = [ad, C.POINTER(C.c_size_t)]
+    lib.aurora_attn_backward_workspace_bytes.restype = C.c_int
+    lib.aurora_attn_backward.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, f32p, f32p, f32p, vp, C.c_size_t, vp]
+    lib.aurora_attn_backward.restype = C.c_int
     lib.aurora_trace_pack.argtypes = [C.POINTER(aurora_pack_desc)] + [vp] * 15
     lib.aurora_trace_pack.restype = C.c_int
     lib.aurora_draft_loss.argtypes = [C.POINTER(aurora_loss_desc), f32p, i32p, vp, vp, f32p, f32p, f32p, vp]
@@ -218,7 +223,27 @@ def aurora_verify_check_inputs(attn_desc, accept_desc, block_table, seq_lens, pa
                                            _ptr(parents), _ptr(draft_tokens), _ptr(uniforms), _ptr(flags),
                                            _stream(stream))
     if check and st != AURORA_OK:
-        raise AuroraError(st, "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack")
+        raise AuroraError(st, "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack", "aurora_attn_backward",
+           "aurora_attn_backward_workspace_bytes")
+    return st
+
+
+def aurora_attn_backward_workspace_bytes(desc) -> int:
+    out = C.c_size_t(0)
+    st = load().aurora_attn_backward_workspace_bytes(_ref(desc), C.byref(out))
+    if st != AURORA_OK:
+        raise AuroraError(st, "aurora_attn_backward_workspace_bytes")
+    return int(out.value)
+
+
+def aurora_attn_backward(desc, q, k_pages, v_pages, block_table, seq_lens, parents, dout, dq, dk_pages, dv_pages,
+                         workspace, stream=None, check=True) -> int:
+    wb = workspace.numel() * workspace.element_size()
+    st = load().aurora_attn_backward(_ref(desc), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                     _ptr(seq_lens), _ptr(parents), _ptr(dout), _ptr(dq), _ptr(dk_pages),
+                                     _ptr(dv_pages), _ptr(workspace), wb, _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_attn_backward")
     return st
 
 

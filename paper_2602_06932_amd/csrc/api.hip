@@ -122,7 +122,7 @@ bool misaligned(const void* p) { return ((uintptr_t)p & 255u) != 0; }
 
 int run_attn(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
              const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents, void* out,
-             void* workspace, size_t workspace_bytes, hipStream_t st) {
+             void* workspace, size_t workspace_bytes, hipStream_t st, float* lse_out = nullptr) {
   int rc = check_attn_desc(desc);
   if (rc != AURORA_OK) return rc;
   if (desc->batch == 0) return AURORA_OK;
@@ -133,6 +133,7 @@ int run_attn(const aurora_attn_desc* desc, const void* q, const void* k_pages, c
   AttnLaunch a = attn_launch_from(desc);
   a.q = q; a.k = k_pages; a.v = v_pages; a.block_table = block_table; a.seq_lens = seq_lens; a.parents = parents;
   a.out = out;
+  a.lse_out = lse_out;
   a.plan_pb = (int32_t*)((char*)workspace + plan.pb_off);
   a.part_o = (float*)((char*)workspace + plan.part_o_off);
   a.part_ml = (float*)((char*)workspace + plan.part_ml_off);
@@ -332,6 +333,58 @@ int aurora_verify_check_inputs(const aurora_attn_desc* attn_desc, const aurora_a
   c.block_table = block_table; c.seq_lens = seq_lens; c.parents = parents; c.draft_tokens = draft_tokens;
   c.uniforms = uniforms; c.flags = flags;
   return launch_check_inputs(c, (hipStream_t)hip_stream) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
+}
+
+namespace {
+struct BwdPlan { size_t fwd_bytes, out_off, lse_off, delta_off, bytes; };
+BwdPlan plan_bwd(const aurora_attn_desc* d) {
+  BwdPlan p = {};
+  p.fwd_bytes = plan_attn(d).bytes;
+  const size_t rows = (size_t)d->batch * d->num_q * d->num_q_heads;
+  const size_t esz = d->dtype == AURORA_BF16 ? 2 : 4;
+  p.out_off = align_up(p.fwd_bytes);
+  p.lse_off = p.out_off + align_up(rows * d->head_dim * esz);
+  p.delta_off = p.lse_off + align_up(rows * sizeof(float));
+  p.bytes = p.delta_off + align_up(rows * sizeof(float));
+  return p;
+}
+}  // namespace
+
+int aurora_attn_backward_workspace_bytes(const aurora_attn_desc* desc, size_t* out_bytes) {
+  if (!out_bytes) return AURORA_ERR_INVALID_ARG;
+  int rc = check_attn_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (desc->kv_fp8) return AURORA_ERR_UNSUPPORTED;
+  *out_bytes = plan_bwd(desc).bytes;
+  return AURORA_OK;
+}
+
+int aurora_attn_backward(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                         const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents,
+                         const void* dout, float* dq, float* dk_pages, float* dv_pages,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_attn_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (desc->kv_fp8) return AURORA_ERR_UNSUPPORTED;
+  if (desc->batch == 0) return AURORA_OK;
+  if (!dout || !dq || !dk_pages || !dv_pages) return AURORA_ERR_INVALID_ARG;
+  if (((uintptr_t)dout | (uintptr_t)dq | (uintptr_t)dk_pages | (uintptr_t)dv_pages) & 15) return AURORA_ERR_INVALID_ARG;
+  const BwdPlan bp = plan_bwd(desc);
+  if (!workspace || misaligned(workspace) || workspace_bytes < bp.bytes) return AURORA_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // forward pass into the workspace: out and the rows' logsumexp
+  float* lse = (float*)(ws + bp.lse_off);
+  rc = run_attn(desc, q, k_pages, v_pages, block_table, seq_lens, parents, ws + bp.out_off, workspace, bp.fwd_bytes, st, lse);
+  if (rc != AURORA_OK) return rc;
+  AttnBwdLaunch a = {};
+  a.B = desc->batch; a.Nq = desc->num_q; a.Hq = desc->num_q_heads; a.Hkv = desc->num_kv_heads; a.D = desc->head_dim;
+  a.page = desc->page_size; a.max_pages = desc->max_pages_per_seq; a.bf16 = desc->dtype == AURORA_BF16;
+  a.scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->head_dim);
+  a.q = q; a.k = k_pages; a.v = v_pages; a.out = ws + bp.out_off; a.dout = dout;
+  a.block_table = block_table; a.seq_lens = seq_lens; a.parents = parents;
+  a.lse = lse; a.delta = (float*)(ws + bp.delta_off); a.dq = dq; a.dk = dk_pages; a.dv = dv_pages;
+  return launch_attn_backward(a, st) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
 }
 
 int aurora_trace_pack(const aurora_pack_desc* d, const int8_t* traj, const void* h, const int32_t* topk_ids,

@@ -125,7 +125,7 @@ __global__ __launch_bounds__(kGenThreads) void attn_generic_partial(
 template <typename T>
 __global__ void attn_combine(const float* __restrict__ part_o, const float* __restrict__ part_ml,
                              const int32_t* __restrict__ seq_lens, T* __restrict__ out, int Nq, int Hq, int D,
-                             int split_len, int max_splits) {
+                             int split_len, int max_splits, float* __restrict__ lse_out) {
   const size_t row = blockIdx.x;  // (b*Nq + n)*Hq + hq
   const int b = (int)(row / ((size_t)Nq * Hq));
   const int L = seq_lens[b];
@@ -133,6 +133,14 @@ __global__ void attn_combine(const float* __restrict__ part_o, const float* __re
   const size_t base = row * max_splits;
   float M = -INFINITY;
   for (int s = 0; s < ns; ++s) M = fmaxf(M, part_ml[(base + s) * 2]);
+  if (lse_out && threadIdx.x == 0) {
+    float den = 0.f;
+    for (int s = 0; s < ns; ++s) {
+      const float ms = part_ml[(base + s) * 2];
+      if (ms > -INFINITY) den = fmaf(__expf(ms - M), part_ml[(base + s) * 2 + 1], den);
+    }
+    lse_out[row] = den > 0.f ? M + __logf(den) : -INFINITY;
+  }
   for (int d = threadIdx.x; d < D; d += blockDim.x) {
     float num = 0.f, den = 0.f;
     for (int s = 0; s < ns; ++s) {
@@ -167,10 +175,10 @@ hipError_t launch_attn_combine(const AttnLaunch& a, hipStream_t st) {
   const unsigned rows = (unsigned)((size_t)a.B * a.Nq * a.Hq);
   if (a.bf16)
     hipLaunchKernelGGL(attn_combine<bf16_t>, dim3(rows), dim3(a.D <= 64 ? 64 : 128), 0, st, a.part_o, a.part_ml,
-                       a.seq_lens, (bf16_t*)a.out, a.Nq, a.Hq, a.D, a.plan.split_len, a.plan.max_splits);
+                       a.seq_lens, (bf16_t*)a.out, a.Nq, a.Hq, a.D, a.plan.split_len, a.plan.max_splits, a.lse_out);
   else
     hipLaunchKernelGGL(attn_combine<float>, dim3(rows), dim3(a.D <= 64 ? 64 : 128), 0, st, a.part_o, a.part_ml,
-                       a.seq_lens, (float*)a.out, a.Nq, a.Hq, a.D, a.plan.split_len, a.plan.max_splits);
+                       a.seq_lens, (float*)a.out, a.Nq, a.Hq, a.D, a.plan.split_len, a.plan.max_splits, a.lse_out);
   return hipGetLastError();
 }
 

@@ -814,7 +814,7 @@ __global__ __launch_bounds__(32 * kCombineRows) void attn_mfma_combine(const flo
                                                                        const int32_t* __restrict__ PB,
                                                                        bf16_t* __restrict__ out, int B, int Nq, int Hq,
                                                                        int Hkv, int wgs, int row_tiles, int groups,
-                                                                       unsigned n_rows) {
+                                                                       unsigned n_rows, float* __restrict__ lse_out) {
   const size_t row = (size_t)blockIdx.x * kCombineRows + (threadIdx.x >> 5);  // (b*Nq + n)*Hq + hq
   if (row >= n_rows) return;
   const int hq = (int)(row % Hq);
@@ -860,6 +860,7 @@ __global__ __launch_bounds__(32 * kCombineRows) void attn_mfma_combine(const flo
       M = nm;
     }
   }
+  if (lse_out && d4 == 0) lse_out[row] = den > 0.f ? M + __logf(den) : -INFINITY;
   typedef __attribute__((ext_vector_type(4))) unsigned short u16x4_t;
   u16x4_t o;
 #pragma unroll
@@ -923,7 +924,7 @@ hipError_t launch_attn_mfma(const AttnLaunch& a, hipStream_t st) {
   const unsigned rows = (unsigned)((size_t)a.B * a.Nq * a.Hq);
   hipLaunchKernelGGL(attn_mfma_combine, dim3((rows + kCombineRows - 1) / kCombineRows), dim3(32 * kCombineRows), 0, st,
                      a.part_o, a.part_ml, a.seq_lens, a.plan_pb, (bf16_t*)a.out, a.B, a.Nq, a.Hq, a.Hkv, wgs, row_tiles,
-                     row_tiles == 1 ? 1 : 2, rows);
+                     row_tiles == 1 ? 1 : 2, rows, a.lse_out);
   return hipGetLastError();
 }
 

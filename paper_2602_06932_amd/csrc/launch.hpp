@@ -13,6 +13,7 @@ struct AttnLaunch {
   const void *q, *k, *v;
   const int32_t *block_table, *seq_lens, *parents;
   void* out;
+  float* lse_out;  // [B, Nq, Hq] natural-log logsumexp of the scaled scores of every row, or NULL (the backward pass asks for it)
   float *part_o, *part_ml;
   int32_t* plan_pb;
   AttnPlan plan;
@@ -67,6 +68,18 @@ hipError_t launch_trace_topk(const float* logits, int64_t rows, int V, int K, co
 hipError_t launch_trace_records(int B, int Nq, const int32_t* draft_tokens, const int32_t* parents,
                                 const int32_t* next_token, const uint8_t* accept_mask, int32_t* y_out, int8_t* traj,
                                 hipStream_t st);
+
+// backward pass of the chunk / tree attention (see attn_bwd.hip); out / lse come from the forward kernels
+struct AttnBwdLaunch {
+  int B, Nq, Hq, Hkv, D, page, max_pages;
+  bool bf16;
+  float scale;
+  const void *q, *k, *v, *out, *dout;
+  const int32_t *block_table, *seq_lens, *parents;
+  const float* lse;
+  float *delta, *dq, *dk, *dv;
+};
+hipError_t launch_attn_backward(const AttnBwdLaunch& a, hipStream_t st);
 
 // packing of trace records (see pack.hip)
 struct PackLaunch {

@@ -1,0 +1,97 @@
+"""Parity of the attention backward pass (paper section 3.1: the speculative tree goes through one batched forward and
+backward pass) against the float64 oracle, through the C ABI.
+
+Tolerances.  bf16 storage: p and the dot products are formed in fp32 from the bf16 inputs; delta uses the forward
+output rounded to bf16 (relative 2^-9), so dS carries a relative error of that order on top of the fp32 sums;
+gradients are compared like the forward output - absolute 2e-2 of the tensor's largest magnitude and relative RMS
+1e-2.  fp32 storage: 2e-5 of the largest magnitude."""
+import numpy as np
+import pytest
+import torch
+
+import gen
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(w, dout):
+    import paper_2602_06932_amd as av
+    from paper_2602_06932_amd.device import DeviceVerify, _to_dev
+    dv = DeviceVerify(w)
+    d_dout = _to_dev(dout, w.dtype)
+    dq = torch.full(w.q.shape, float("nan"), dtype=torch.float32, device="cuda")
+    dk = torch.zeros(dv.k_pages.shape, dtype=torch.float32, device="cuda")
+    dvp = torch.zeros(dv.v_pages.shape, dtype=torch.float32, device="cuda")
+    ws = torch.empty(av.aurora_attn_backward_workspace_bytes(dv.attn_desc), dtype=torch.uint8, device="cuda")
+    av.aurora_attn_backward(dv.attn_desc, dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.seq_lens, dv.parents, d_dout,
+                            dq, dk, dvp, ws)
+    torch.cuda.synchronize()
+    return dq.cpu().numpy(), dk.cpu().numpy(), dvp.cpu().numpy()
+
+
+def _check(w, seed=0):
+    print(f"[case] {w.name} B={w.batch} Nq={w.num_q} heads={w.num_q_heads}/{w.num_kv_heads}/{w.head_dim} "
+          f"L={int(w.seq_lens.min())}..{int(w.seq_lens.max())} page={w.page_size} {w.dtype}", flush=True)
+    rng = np.random.default_rng(seed)
+    g32 = rng.standard_normal(w.q.shape).astype(np.float32)
+    if w.dtype == "bf16":
+        dout = (g32.view(np.uint32) >> 16).astype(np.uint16)          # bf16 storage of the upstream gradient
+        g = (dout.astype(np.uint32) << 16).view(np.float32)
+    else:
+        dout, g = g32, g32
+    _, rq, rk, rv = oracle.attn_backward(gen.as_f32(w.q, w.dtype), gen.as_f32(w.k_pages, w.dtype),
+                                         gen.as_f32(w.v_pages, w.dtype), w.host_block_table(), w.seq_lens, w.parents, g)
+    dq, dk, dv = _run(w, dout)
+    for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
+        assert np.isfinite(got).all(), name
+        err = np.abs(got - ref)
+        top = np.abs(ref).max()
+        if w.dtype == "bf16":
+            assert err.max() <= 2e-2 * top, f"{name} abs err {err.max()} vs max {top}"
+            assert np.sqrt((err ** 2).mean()) <= 1e-2 * np.sqrt((ref ** 2).mean()), name
+        else:
+            assert err.max() <= 2e-5 * top, f"{name} abs err {err.max()} vs max {top}"
+    return dq, dk, dv
+
+
+def test_chain_bf16(gpu_lib):
+    _check(gen.llama_chain(131, batch=4, len_lo=40, len_hi=500, vocab=64, hidden_size=64), 1)
+
+
+def test_tree_bf16_many_query_rows(gpu_lib):
+    """A 16-node tree with four query heads per KV head: 64 query rows per pair, two passes over the pair's positions."""
+    _check(gen.llama_tree(132, batch=3, num_q=16, context=150, vocab=64, hidden_size=64, num_q_heads=8, num_kv_heads=2), 2)
+
+
+def test_fp32_head_dim_64_and_large_pages(gpu_lib):
+    _check(gen.tiny_chain(133), 3)
+    _check(gen.llama_chain(134, batch=2, len_lo=30, len_hi=200, vocab=64, hidden_size=64, page_size=24, head_dim=64,
+                           num_q_heads=4, num_kv_heads=2, dtype=gen.F32), 4)
+
+
+def test_single_position_and_repeatability(gpu_lib):
+    w = gen.llama_chain(135, batch=2, num_q=1, len_lo=70, len_hi=90, vocab=64, hidden_size=64)
+    a = _check(w, 5)
+    rng = np.random.default_rng(5)
+    dout = (rng.standard_normal(w.q.shape).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    b = _run(w, dout)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_unused_pool_positions_are_left_alone_and_host_errors(gpu_lib):
+    import paper_2602_06932_amd as av
+    from paper_2602_06932_amd.device import DeviceVerify
+    w = gen.llama_chain(136, batch=2, len_lo=20, len_hi=50, vocab=64, hidden_size=64)
+    dq, dk, dv = _check(w, 6)
+    used = np.zeros(dk.shape[:3], bool)
+    for b in range(w.batch):
+        for j in range(int(w.seq_lens[b])):
+            used[w.block_table[b, j // w.page_size], :, j % w.page_size] = True
+    assert (~used).any() and not dk[~used].any() and not dv[~used].any()
+    w8 = gen.llama_chain(137, batch=2, len_lo=20, len_hi=50, vocab=64, hidden_size=64, kv_fp8=True)
+    d8 = DeviceVerify(w8)
+    with pytest.raises(av.AuroraError) as e:
+        av.aurora_attn_backward_workspace_bytes(d8.attn_desc)
+    assert e.value.status == av.AURORA_ERR_UNSUPPORTED
