@@ -336,7 +336,7 @@ int aurora_verify_check_inputs(const aurora_attn_desc* attn_desc, const aurora_a
 }
 
 namespace {
-struct BwdPlan { size_t fwd_bytes, out_off, lse_off, delta_off, bytes; };
+struct BwdPlan { size_t fwd_bytes, out_off, lse_off, delta_off, pb_off, part_dq_off, bytes; };
 BwdPlan plan_bwd(const aurora_attn_desc* d) {
   BwdPlan p = {};
   p.fwd_bytes = plan_attn(d).bytes;
@@ -345,7 +345,11 @@ BwdPlan plan_bwd(const aurora_attn_desc* d) {
   p.out_off = align_up(p.fwd_bytes);
   p.lse_off = p.out_off + align_up(rows * d->head_dim * esz);
   p.delta_off = p.lse_off + align_up(rows * sizeof(float));
-  p.bytes = p.delta_off + align_up(rows * sizeof(float));
+  p.pb_off = p.delta_off + align_up(rows * sizeof(float));
+  // matrix-core kernel: one partial dq (32 rows x 128 columns) per run of tiles
+  p.part_dq_off = p.pb_off + align_up(((size_t)d->batch + 1) * sizeof(int32_t));
+  const size_t runs = (size_t)attn_bwd_mfma_workgroups() + (size_t)d->batch * d->num_kv_heads;
+  p.bytes = p.part_dq_off + align_up(runs * 32 * 128 * sizeof(float));
   return p;
 }
 }  // namespace
@@ -384,6 +388,7 @@ int aurora_attn_backward(const aurora_attn_desc* desc, const void* q, const void
   a.q = q; a.k = k_pages; a.v = v_pages; a.out = ws + bp.out_off; a.dout = dout;
   a.block_table = block_table; a.seq_lens = seq_lens; a.parents = parents;
   a.lse = lse; a.delta = (float*)(ws + bp.delta_off); a.dq = dq; a.dk = dk_pages; a.dv = dv_pages;
+  a.plan_pb = (int32_t*)(ws + bp.pb_off); a.part_dq = (float*)(ws + bp.part_dq_off);
   return launch_attn_backward(a, st) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
 }
 

@@ -170,6 +170,7 @@ static hipError_t launch_bwd_t(const AttnBwdLaunch& a, hipStream_t st) {
                      a.delta, rows, a.D);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (attn_bwd_mfma_supported(a)) return launch_attn_backward_mfma(a, st);
   dim3 grid(a.B * a.Hkv);
   const int lds = (int)sizeof(float) * (2 * kBwRows * a.D + kBwTok * (a.D + 4) + kBwRows * (kBwTok + 1));
   static LdsAttrOnce attr128, attr64;

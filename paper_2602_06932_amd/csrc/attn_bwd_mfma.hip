@@ -1,0 +1,354 @@
+// Backward pass of the chunk / tree attention on the matrix cores (paper section 3.1: the speculative tree goes
+// through one batched forward and backward pass under the tree's mask), for up to 32 query rows per KV head
+// (chains, small trees), head_dim 128, bf16.  Work is split exactly as in the forward kernel: 32-token tiles
+// of a (request, KV head) pair, dealt in contiguous runs to one resident workgroup per compute unit; the four
+// wavefronts of a workgroup take every fourth tile of a run with private LDS tiles.
+//
+// Per tile (tokens are the rows of the first two products, so a lane owns one query row and 16 tokens):
+//   S^T  = K Q^T,  dP^T = V dO^T                      two 32x32x128 products, operands read like the forward scores
+//   P^T  = exp2(S^T scale - lse),  dS^T = P^T o (dP^T - delta)          lane-local (lse, delta belong to the row)
+//   dQ^T += K^T dS^T                                   like the forward's V^T P^T: transposing LDS reads of the K tile
+//   dV^T  = dO^T P,  dK^T = Q^T dS                     contraction over the query rows: P and dS go through a small
+//                                                      transposed LDS tile to become B operands; the output has one
+//                                                      token per lane, which is how its row of dV / dK is stored
+// K and V tiles come in by direct global->LDS loads in the layout of the forward kernel's V tiles (it serves
+// the 128-bit row reads and the transposing reads alike); the next tile's V is requested once dP is formed,
+// its K once dQ is updated.  dq is summed over the wavefronts at the end of a run and over the runs of a pair
+// by a second kernel; dK / dV tiles are written once, by the wavefront that owns the tile.
+#include "launch.hpp"
+#include "attn_tile.hpp"
+
+namespace aurora {
+
+constexpr int kBmThreads = 256;
+constexpr int kBmXtStride = 80;                       // bytes per token row of a transposed 32 x 32 bf16 tile
+constexpr int kBmXtBytes = 32 * kBmXtStride;          // 2560
+constexpr int kBmWaveBytes = 2 * kAtTileBytes + 2 * kBmXtBytes;
+constexpr int kBmLdsBytes = 4 * kAtTileBytes + 4 * kBmWaveBytes;  // Q, dO in two layouts each + four wavefronts
+
+// S^T-type product: rows of `abuf` (V-tile layout: chunk ^ v_key(row)) against the rows of `btile` (query-tile
+// layout: chunk ^ (row & 15)), contraction over the 128 columns
+__device__ __forceinline__ f32x16_t tile_scores_v(const char* abuf, const char* btile, int li, int lh) {
+  f32x16_t acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  const int ka_key = v_key(li), kb_key = li & 15;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const bf16x8_t a = *(const bf16x8_t*)(abuf + li * kAtRowBytes + (((2 * s + lh) ^ ka_key) * 16));
+    const bf16x8_t b = *(const bf16x8_t*)(btile + li * kAtRowBytes + (((2 * s + lh) ^ kb_key) * 16));
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+  }
+  return acc;
+}
+
+// acc[db] += (A^T)(128 x 32) B(32 x 32): A is a 32-row tile in the V-tile layout read with transposing loads
+// (as in the forward's P V product), b[uu] the B operand of contraction step uu
+__device__ __forceinline__ void tile_tmm(const char* abuf, const bf16x8_t b[2], f32x16_t acc[4], int lane) {
+  const int lh = lane >> 5, k = lane & 15, kq = k >> 2;
+  const int g1 = (lane >> 4) & 1;
+  const int lo0 = ((2 * g1 + ((k & 3) >> 1)) ^ (lh & 3)) * 16;
+  const int lo1 = ((2 * g1 + ((k & 3) >> 1)) ^ ((2 + lh) & 3)) * 16;
+  const int common = lh * 1024 + kq * 256 + (k & 1) * 8 + kq * 64;
+  const int base0 = common + lo0;
+  const int base1 = common + lo1 + 2048;
+#pragma unroll
+  for (int uu = 0; uu < 2; ++uu) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      typedef __attribute__((address_space(3))) s16x4_t* lds_v4;
+      const s16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(abuf + uu * 4096 + (base0 ^ (db * 64))));
+      const s16x4_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(abuf + uu * 4096 + (base1 ^ (db * 64))));
+      const u16x8_t va = {(unsigned short)r0[0], (unsigned short)r0[1], (unsigned short)r0[2], (unsigned short)r0[3],
+                          (unsigned short)r1[0], (unsigned short)r1[1], (unsigned short)r1[2], (unsigned short)r1[3]};
+      acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, va), b[uu], acc[db], 0, 0, 0);
+    }
+  }
+}
+
+// Accumulator register r of lane (li, lh) holds tile row t(r) = 8(r/4) + 4 lh + r%4, column li.  The values are
+// rounded to bf16 and (1) packed as the B operand of a product that contracts over the tile rows (x_b, as the
+// forward does with P), (2) written to xt[row t][column li] so that they can be read back with the roles swapped.
+__device__ __forceinline__ void pack_and_transpose(const float x[16], bf16x8_t x_b[2], char* xt, int li, int lh) {
+#pragma unroll
+  for (int r = 0; r < 16; r += 2) {
+    const f32x2_t pp = {x[r], x[r + 1]};
+    const bf16x2_t pk = __builtin_convertvector(pp, bf16x2_t);
+    x_b[r >> 3][r & 7] = pk[0];
+    x_b[r >> 3][(r & 7) + 1] = pk[1];
+    const int t0 = 8 * (r >> 2) + 4 * lh + (r & 3);
+    *(__bf16*)(xt + t0 * kBmXtStride + li * 2) = pk[0];
+    *(__bf16*)(xt + (t0 + 1) * kBmXtStride + li * 2) = pk[1];
+  }
+}
+
+// B operand of a product that contracts over the 32 columns of xt (the query rows) for output column li (a token):
+// contraction step uu, element i of lane half lh  <->  column 16 uu + 8 (i / 4) + 4 lh + i % 4 - the order in which
+// tile_tmm's transposing reads deliver the rows of its A tile
+__device__ __forceinline__ void read_transposed(const char* xt, bf16x8_t b[2], int li, int lh) {
+  typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+#pragma unroll
+  for (int uu = 0; uu < 2; ++uu) {
+    const bf16x4_t lo = *(const bf16x4_t*)(xt + li * kBmXtStride + (16 * uu + 4 * lh) * 2);
+    const bf16x4_t hi = *(const bf16x4_t*)(xt + li * kBmXtStride + (16 * uu + 8 + 4 * lh) * 2);
+    b[uu] = bf16x8_t{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  }
+}
+
+__global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ parents,
+    const bf16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    int32_t* __restrict__ PB, float* __restrict__ part_dq, float* __restrict__ dk, float* __restrict__ dv, int B, int Nq,
+    int Hq, int Hkv, int page_shift, int max_pages, float scale) {
+  extern __shared__ __attribute__((aligned(1024))) char bm_lds[];
+  char* qK = bm_lds;                       // query rows, layout read by tile_scores_v's B side
+  char* doK = bm_lds + kAtTileBytes;
+  char* qV = bm_lds + 2 * kAtTileBytes;    // the same rows in the V-tile layout, for the transposing reads
+  char* doV = bm_lds + 3 * kAtTileBytes;
+  __shared__ int s_pb[kLocalPlanMax + 1];
+  __shared__ int s_wsum[4];
+  build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
+  if (blockIdx.x == 0)
+    for (int i = threadIdx.x; i <= B; i += kBmThreads) PB[i] = s_pb[i];
+
+  const int U = s_pb[B];
+  const int c = units_per_wg(U, gridDim.x);
+  int u = blockIdx.x * c;
+  const int u_end = min(U, u + c);
+  if (u >= u_end) return;
+
+  const int G = Hq / Hkv, R = G * Nq;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 31, lh = lane >> 5;
+  char* wbase = bm_lds + 4 * kAtTileBytes + wv * kBmWaveBytes;
+  char* kbuf = wbase;
+  char* vbuf = wbase + kAtTileBytes;
+  char* pt = wbase + 2 * kAtTileBytes;
+  char* dst = pt + kBmXtBytes;
+  const bool row_ok = li < R;
+  const int node = row_ok ? li / G : 0;
+  const int qs_row = tid >> 3;  // staging: 8 threads per query row, 32 bytes each
+  const bool qs_ok = qs_row < R;
+  const int qs_node = qs_ok ? qs_row / G : 0, qs_g = qs_ok ? qs_row % G : 0;
+  const float scale_log2 = scale * kLog2e;
+
+  int b = 0;
+  {
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (s_pb[mid] <= u) lo = mid; else hi = mid - 1;
+    }
+    b = lo;
+  }
+
+  while (u < u_end) {
+    while (s_pb[b + 1] <= u) ++b;
+    const int L = seq_lens[b];
+    const int n_b = (L + kAtTile - 1) / kAtTile;
+    const int rel = u - s_pb[b];
+    const int hk = __builtin_amdgcn_readfirstlane(rel / n_b);
+    const int t0 = rel - hk * n_b;
+    const int t1 = min(n_b, t0 + (u_end - u));
+    const int slot = blockIdx.x + b * Hkv + hk;
+    u += t1 - t0;
+    const int start = t0 * kAtTile;
+    const int prefix = L - Nq;
+    const int ntile = t1 - t0;
+    const int32_t* bt = block_table + (size_t)b * max_pages;
+    {
+      // the pair's query rows and their upstream gradients, each in both LDS layouts
+      const size_t at = (((size_t)b * Nq + qs_node) * Hq + hk * G + qs_g) * kAtD;
+      const u32x4_t* qp = (const u32x4_t*)(q + at);
+      const u32x4_t* gp = (const u32x4_t*)(dout + at);
+      const int c0 = (tid & 7) * 2;
+      const u32x4_t z = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const u32x4_t qv = qs_ok ? qp[c0 + i] : z;
+        const u32x4_t gv = qs_ok ? gp[c0 + i] : z;
+        const int ck = ((c0 + i) ^ (qs_row & 15)) * 16, cv = ((c0 + i) ^ v_key(qs_row)) * 16;
+        *(u32x4_t*)(qK + qs_row * kAtRowBytes + ck) = qv;
+        *(u32x4_t*)(doK + qs_row * kAtRowBytes + ck) = gv;
+        *(u32x4_t*)(qV + qs_row * kAtRowBytes + cv) = qv;
+        *(u32x4_t*)(doV + qs_row * kAtRowBytes + cv) = gv;
+      }
+    }
+    // this lane's query row: logsumexp (log2 units) and delta; rows past the group see nothing
+    float lse2 = INFINITY, dlt = 0.f;
+    if (row_ok) {
+      const size_t row = ((size_t)b * Nq + node) * Hq + hk * G + li % G;
+      lse2 = lse[row] * kLog2e;
+      dlt = delta[row];
+    }
+    unsigned long long anc;
+    if (parents) {
+      anc = 0;
+      for (int a = node, hops = 0; a >= 0 && hops <= Nq; a = parents[(size_t)b * Nq + a], ++hops) anc |= 1ull << a;
+    } else {
+      anc = node == 63 ? ~0ull : ((1ull << (node + 1)) - 1);
+    }
+
+    auto tile_pages = [&](int tt, int& pid_a, int& pid_b) {
+      const int j0 = start + tt * kAtTile;
+      pid_a = bt[j0 >> page_shift];
+      pid_b = bt[min(j0 + 16, L - 1) >> page_shift];
+    };
+    auto issue_tile = [&](const bf16_t* pool, char* buf, int tt, int pid_a, int pid_b) {
+      const int j0 = start + tt * kAtTile;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) issue_rows<true>(pool, buf, j, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
+    };
+
+    f32x16_t dq_acc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dq_acc[db][r] = 0.f;
+
+    __syncthreads();  // query rows staged
+    int tt = wv;
+    int pa = 0, pb = 0;
+    if (tt < ntile) {
+      tile_pages(tt, pa, pb);
+      issue_tile(kp, kbuf, tt, pa, pb);
+      issue_tile(vp, vbuf, tt, pa, pb);
+    }
+    for (; tt < ntile; tt += 4) {
+      const bool more = tt + 4 < ntile;
+      int npa = 0, npb = 0;
+      if (more) tile_pages(tt + 4, npa, npb);
+      WAIT_VMCNT(0);  // this tile's K and V have landed (and the previous tile's stores have left)
+      const int j0 = start + tt * kAtTile;
+      const f32x16_t s_acc = tile_scores_v(kbuf, qK, li, lh);
+      const f32x16_t dp_acc = tile_scores_v(vbuf, doK, li, lh);
+      asm volatile("" ::: "memory");
+      if (more) issue_tile(vp, vbuf, tt + 4, npa, npb);  // V is not read again
+      float p[16], ds[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+        const bool seen = j < prefix || (j < L && ((anc >> (j - prefix)) & 1ull));
+        p[r] = seen ? __builtin_amdgcn_exp2f(fmaf(s_acc[r], scale_log2, -lse2)) : 0.f;
+        ds[r] = p[r] * (dp_acc[r] - dlt);
+      }
+      bf16x8_t p_b[2], ds_b[2];
+      pack_and_transpose(p, p_b, pt, li, lh);
+      pack_and_transpose(ds, ds_b, dst, li, lh);
+      tile_tmm(kbuf, ds_b, dq_acc, lane);  // dQ^T += K^T dS^T
+      asm volatile("" ::: "memory");
+      if (more) issue_tile(kp, kbuf, tt + 4, npa, npb);  // K is not read again
+      // dV^T = dO^T P and dK^T = Q^T dS: one token per lane
+      f32x16_t dv_acc[4], dk_acc[4];
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { dv_acc[db][r] = 0.f; dk_acc[db][r] = 0.f; }
+      bf16x8_t pt_b[2], dst_b[2];
+      read_transposed(pt, pt_b, li, lh);
+      read_transposed(dst, dst_b, li, lh);
+      tile_tmm(doV, pt_b, dv_acc, lane);
+      tile_tmm(qV, dst_b, dk_acc, lane);
+      const int tok = j0 + li;
+      if (tok < L) {
+        const int pid = (tok >> page_shift) == (j0 >> page_shift) ? pa : pb;
+        const size_t at = ((((size_t)pid * Hkv + hk) << page_shift) + (tok & ((1 << page_shift) - 1))) * kAtD;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int d = 32 * db + 8 * g + 4 * lh;
+            f32x4_t ov = {dv_acc[db][4 * g], dv_acc[db][4 * g + 1], dv_acc[db][4 * g + 2], dv_acc[db][4 * g + 3]};
+            f32x4_t ok = {dk_acc[db][4 * g] * scale, dk_acc[db][4 * g + 1] * scale, dk_acc[db][4 * g + 2] * scale,
+                          dk_acc[db][4 * g + 3] * scale};
+            *(f32x4_t*)(dv + at + d) = ov;
+            *(f32x4_t*)(dk + at + d) = ok;
+          }
+      }
+      pa = npa;
+      pb = npb;
+    }
+
+    // ---- sum dQ^T over the four wavefronts and write the run's partial ---------------------------------------
+    WAIT_VMCNT(0);
+    __syncthreads();  // every wavefront is done with its tiles
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      float* obuf = (float*)(db < 2 ? kbuf : vbuf);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int dd = 32 * (db & 1) + 8 * g + 4 * lh;
+        f32x4_t o = {dq_acc[db][4 * g], dq_acc[db][4 * g + 1], dq_acc[db][4 * g + 2], dq_acc[db][4 * g + 3]};
+        *(f32x4_t*)(obuf + li * 64 + ((dd / 4 + li) & 15) * 4) = o;
+      }
+    }
+    __syncthreads();
+    {
+      const int db = wv;  // wavefront w sums and stores d-block w of all rows
+      const size_t prow = (size_t)slot * 32 + li;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int dd = 32 * (db & 1) + 8 * g + 4 * lh;
+        f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const char* wb = bm_lds + 4 * kAtTileBytes + w * kBmWaveBytes;
+          const float* ob = (const float*)(db < 2 ? wb : wb + kAtTileBytes);
+          sum += *(const f32x4_t*)(ob + li * 64 + ((dd / 4 + li) & 15) * 4);
+        }
+        if (row_ok) *(f32x4_t*)(part_dq + prow * kAtD + 32 * db + 8 * g + 4 * lh) = sum;
+      }
+    }
+    __syncthreads();  // the tiles are about to be refilled for the next run
+  }
+}
+
+// dq of one output row = scale * sum of the partials of the runs that met its (request, KV head) pair
+__global__ __launch_bounds__(256) void attn_bwd_dq_combine(const float* __restrict__ part_dq,
+                                                           const int32_t* __restrict__ seq_lens,
+                                                           const int32_t* __restrict__ PB, float* __restrict__ dq, int B,
+                                                           int Nq, int Hq, int Hkv, int wgs, unsigned n_rows, float scale) {
+  const size_t row = (size_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+  if (row >= n_rows) return;
+  const int hq = (int)(row % Hq);
+  const int n = (int)((row / Hq) % Nq);
+  const int b = (int)(row / ((size_t)Hq * Nq));
+  const int G = Hq / Hkv, hk = hq / G;
+  const int mrow = n * G + hq % G;
+  const int n_b = (seq_lens[b] + kAtTile - 1) / kAtTile;
+  const int c = units_per_wg(PB[B], wgs);
+  const int u0 = PB[b] + hk * n_b, u1 = u0 + n_b;
+  const int w0 = u0 / c, w1 = (u1 - 1) / c;
+  const int pair = b * Hkv + hk;
+  const int d4 = threadIdx.x & 31;
+  f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+  for (int w = w0; w <= w1; ++w) acc += *(const f32x4_t*)(part_dq + ((size_t)(w + pair) * 32 + mrow) * kAtD + 4 * d4);
+  *(f32x4_t*)(dq + row * kAtD + 4 * d4) = acc * scale;
+}
+
+bool attn_bwd_mfma_supported(const AttnBwdLaunch& a) {
+  return a.bf16 && a.D == kAtD && a.page >= 16 && (a.page & (a.page - 1)) == 0 && a.Hq / a.Hkv * a.Nq <= 32 &&
+         a.B <= kLocalPlanMax;
+}
+
+int attn_bwd_mfma_workgroups() { return 256; }
+
+hipError_t launch_attn_backward_mfma(const AttnBwdLaunch& a, hipStream_t st) {
+  const int rows = a.B * a.Nq * a.Hq;
+  static LdsAttrOnce attr;
+  if (hipError_t e = attr.ensure((const void*)attn_bwd_mfma_kernel, kBmLdsBytes); e != hipSuccess) return e;
+  const int wgs = attn_bwd_mfma_workgroups();
+  hipLaunchKernelGGL(attn_bwd_mfma_kernel, dim3(wgs), dim3(kBmThreads), kBmLdsBytes, st, (const bf16_t*)a.q,
+                     (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, (const bf16_t*)a.dout,
+                     a.lse, a.delta, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv, __builtin_ctz(a.page),
+                     a.max_pages, a.scale);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_bwd_dq_combine, dim3((rows + 7) / 8), dim3(256), 0, st, a.part_dq, a.seq_lens, a.plan_pb, a.dq,
+                     a.B, a.Nq, a.Hq, a.Hkv, wgs, (unsigned)rows, a.scale);
+  return hipGetLastError();
+}
+
+}  // namespace aurora

@@ -78,8 +78,15 @@ struct AttnBwdLaunch {
   const int32_t *block_table, *seq_lens, *parents;
   const float* lse;
   float *delta, *dq, *dk, *dv;
+  // matrix-core kernel only: tile prefix per request [B + 1] and the per-run partial dq
+  int32_t* plan_pb;
+  float* part_dq;
 };
 hipError_t launch_attn_backward(const AttnBwdLaunch& a, hipStream_t st);
+// matrix-core kernel (attn_bwd_mfma.hip): shapes it takes, its resident workgroups, and its launch (delta is ready)
+bool attn_bwd_mfma_supported(const AttnBwdLaunch& a);
+int attn_bwd_mfma_workgroups();
+hipError_t launch_attn_backward_mfma(const AttnBwdLaunch& a, hipStream_t st);
 
 // packing of trace records (see pack.hip)
 struct PackLaunch {
