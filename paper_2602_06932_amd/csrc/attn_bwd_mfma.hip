@@ -8,9 +8,10 @@
 //   S^T  = K Q^T,  dP^T = V dO^T                      two 32x32x128 products, operands read like the forward scores
 //   P^T  = exp2(S^T scale - lse),  dS^T = P^T o (dP^T - delta)          lane-local (lse, delta belong to the row)
 //   dQ^T += K^T dS^T                                   like the forward's V^T P^T: transposing LDS reads of the K tile
-//   dV^T  = dO^T P,  dK^T = Q^T dS                     contraction over the query rows: P and dS go through a small
-//                                                      transposed LDS tile to become B operands; the output has one
-//                                                      token per lane, which is how its row of dV / dK is stored
+//   dV    = P^T dO,  dK = dS^T Q                       contraction over the query rows: P and dS go through a small
+//                                                      transposed LDS tile to become operands; a lane ends up with one
+//                                                      column of 16 tokens, so a store instruction writes whole
+//                                                      128-byte lines of the fp32 pools (partial lines cost 2.5x)
 // K and V tiles come in by direct global->LDS loads in the layout of the forward kernel's V tiles (it serves
 // the 128-bit row reads and the transposing reads alike); the next tile's V is requested once dP is formed,
 // its K once dQ is updated.  dq is summed over the wavefronts at the end of a run and over the runs of a pair
@@ -43,7 +44,9 @@ __device__ __forceinline__ f32x16_t tile_scores_v(const char* abuf, const char* 
 }
 
 // acc[db] += (A^T)(128 x 32) B(32 x 32): A is a 32-row tile in the V-tile layout read with transposing loads
-// (as in the forward's P V product), b[uu] the B operand of contraction step uu
+// (as in the forward's P V product), b[uu] the B operand of contraction step uu.  kSwap exchanges the operands,
+// which transposes the output: acc[db] += B^T A (block db of A's columns)
+template <bool kSwap = false>
 __device__ __forceinline__ void tile_tmm(const char* abuf, const bf16x8_t b[2], f32x16_t acc[4], int lane) {
   const int lh = lane >> 5, k = lane & 15, kq = k >> 2;
   const int g1 = (lane >> 4) & 1;
@@ -61,7 +64,10 @@ __device__ __forceinline__ void tile_tmm(const char* abuf, const bf16x8_t b[2], 
       const s16x4_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(abuf + uu * 4096 + (base1 ^ (db * 64))));
       const u16x8_t va = {(unsigned short)r0[0], (unsigned short)r0[1], (unsigned short)r0[2], (unsigned short)r0[3],
                           (unsigned short)r1[0], (unsigned short)r1[1], (unsigned short)r1[2], (unsigned short)r1[3]};
-      acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, va), b[uu], acc[db], 0, 0, 0);
+      if (kSwap)
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[uu], __builtin_bit_cast(bf16x8_t, va), acc[db], 0, 0, 0);
+      else
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, va), b[uu], acc[db], 0, 0, 0);
     }
   }
 }
@@ -240,7 +246,7 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
       tile_tmm(kbuf, ds_b, dq_acc, lane);  // dQ^T += K^T dS^T
       asm volatile("" ::: "memory");
       if (more) issue_tile(kp, kbuf, tt + 4, npa, npb);  // K is not read again
-      // dV^T = dO^T P and dK^T = Q^T dS: one token per lane
+      // dV = P^T dO and dK = dS^T Q
       f32x16_t dv_acc[4], dk_acc[4];
 #pragma unroll
       for (int db = 0; db < 4; ++db)
@@ -249,23 +255,25 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
       bf16x8_t pt_b[2], dst_b[2];
       read_transposed(pt, pt_b, li, lh);
       read_transposed(dst, dst_b, li, lh);
-      tile_tmm(doV, pt_b, dv_acc, lane);
-      tile_tmm(qV, dst_b, dk_acc, lane);
-      const int tok = j0 + li;
-      if (tok < L) {
-        const int pid = (tok >> page_shift) == (j0 >> page_shift) ? pa : pb;
-        const size_t at = ((((size_t)pid * Hkv + hk) << page_shift) + (tok & ((1 << page_shift) - 1))) * kAtD;
+      // the transposed tile is the A operand: the output has one column per lane (32 db + li) and 16 tokens in the
+      // registers, so that a store instruction writes two whole 128-byte lines; the gradients are not read again
+      tile_tmm<true>(doV, pt_b, dv_acc, lane);
+      tile_tmm<true>(qV, dst_b, dk_acc, lane);
+      {
+        const int mask = (1 << page_shift) - 1;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int r = 0; r < 16; ++r) {
+          const int tok = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          if (tok < L) {
+            const int pid = r < 8 ? pa : pb;  // tokens 0..15 of the tile lie in its first page, 16..31 in the page of token 16
+            const size_t at = ((((size_t)pid * Hkv + hk) << page_shift) + (tok & mask)) * kAtD + li;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int d = 32 * db + 8 * g + 4 * lh;
-            f32x4_t ov = {dv_acc[db][4 * g], dv_acc[db][4 * g + 1], dv_acc[db][4 * g + 2], dv_acc[db][4 * g + 3]};
-            f32x4_t ok = {dk_acc[db][4 * g] * scale, dk_acc[db][4 * g + 1] * scale, dk_acc[db][4 * g + 2] * scale,
-                          dk_acc[db][4 * g + 3] * scale};
-            *(f32x4_t*)(dv + at + d) = ov;
-            *(f32x4_t*)(dk + at + d) = ok;
+            for (int db = 0; db < 4; ++db) {
+              __builtin_nontemporal_store(dv_acc[db][r], dv + at + 32 * db);
+              __builtin_nontemporal_store(dk_acc[db][r] * scale, dk + at + 32 * db);
+            }
           }
+        }
       }
       pa = npa;
       pb = npb;
