@@ -346,10 +346,9 @@ BwdPlan plan_bwd(const aurora_attn_desc* d) {
   p.lse_off = p.out_off + align_up(rows * d->head_dim * esz);
   p.delta_off = p.lse_off + align_up(rows * sizeof(float));
   p.pb_off = p.delta_off + align_up(rows * sizeof(float));
-  // matrix-core kernel: one partial dq (32 rows x 128 columns) per run of tiles
+  // matrix-core kernel: one partial dq (the pair's query rows x 128 columns) per run of tiles
   p.part_dq_off = p.pb_off + align_up(((size_t)d->batch + 1) * sizeof(int32_t));
-  const size_t runs = (size_t)attn_bwd_mfma_workgroups() + (size_t)d->batch * d->num_kv_heads;
-  p.bytes = p.part_dq_off + align_up(runs * 32 * 128 * sizeof(float));
+  p.bytes = p.part_dq_off + align_up(attn_bwd_mfma_partial_bytes(d->batch, d->num_kv_heads, d->num_q_heads / d->num_kv_heads * d->num_q));
   return p;
 }
 }  // namespace

@@ -25,19 +25,20 @@ constexpr int kBmThreads = 256;
 constexpr int kBmXtStride = 80;                       // bytes per token row of a transposed 32 x 32 bf16 tile
 constexpr int kBmXtBytes = 32 * kBmXtStride;          // 2560
 constexpr int kBmWaveBytes = 2 * kAtTileBytes + 2 * kBmXtBytes;
-constexpr int kBmLdsBytes = 4 * kAtTileBytes + 4 * kBmWaveBytes;  // Q, dO in two layouts each + four wavefronts
+constexpr int bm_lds_bytes(int rt) { return 2 * rt * kAtTileBytes + 4 * kBmWaveBytes; }  // Q and dO tiles + four wavefronts
 
-// S^T-type product: rows of `abuf` (V-tile layout: chunk ^ v_key(row)) against the rows of `btile` (query-tile
-// layout: chunk ^ (row & 15)), contraction over the 128 columns
+// S^T-type product: rows of `abuf` against the rows of `btile` (both in the V-tile layout, chunk ^ v_key(row):
+// v_key is a permutation of 0..15 over any 16 consecutive rows, so the 128-bit row reads are conflict-free as
+// well), contraction over the 128 columns
 __device__ __forceinline__ f32x16_t tile_scores_v(const char* abuf, const char* btile, int li, int lh) {
   f32x16_t acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-  const int ka_key = v_key(li), kb_key = li & 15;
+  const int key = v_key(li);
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
-    const bf16x8_t a = *(const bf16x8_t*)(abuf + li * kAtRowBytes + (((2 * s + lh) ^ ka_key) * 16));
-    const bf16x8_t b = *(const bf16x8_t*)(btile + li * kAtRowBytes + (((2 * s + lh) ^ kb_key) * 16));
+    const bf16x8_t a = *(const bf16x8_t*)(abuf + li * kAtRowBytes + (((2 * s + lh) ^ key) * 16));
+    const bf16x8_t b = *(const bf16x8_t*)(btile + li * kAtRowBytes + (((2 * s + lh) ^ key) * 16));
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
   }
   return acc;
@@ -101,6 +102,7 @@ __device__ __forceinline__ void read_transposed(const char* xt, bf16x8_t b[2], i
   }
 }
 
+template <int kRT /* 32-row tiles of query rows per KV head: 1, 2 or 4 */>
 __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ parents,
@@ -108,10 +110,9 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
     int32_t* __restrict__ PB, float* __restrict__ part_dq, float* __restrict__ dk, float* __restrict__ dv, int B, int Nq,
     int Hq, int Hkv, int page_shift, int max_pages, float scale) {
   extern __shared__ __attribute__((aligned(1024))) char bm_lds[];
-  char* qK = bm_lds;                       // query rows, layout read by tile_scores_v's B side
-  char* doK = bm_lds + kAtTileBytes;
-  char* qV = bm_lds + 2 * kAtTileBytes;    // the same rows in the V-tile layout, for the transposing reads
-  char* doV = bm_lds + 3 * kAtTileBytes;
+  char* qV = bm_lds;                          // the pair's query rows, kRT tiles in the V-tile layout
+  char* doV = bm_lds + kRT * kAtTileBytes;    // their upstream gradients
+  char* waves = bm_lds + 2 * kRT * kAtTileBytes;
   __shared__ int s_pb[kLocalPlanMax + 1];
   __shared__ int s_wsum[4];
   build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
@@ -128,16 +129,10 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 31, lh = lane >> 5;
-  char* wbase = bm_lds + 4 * kAtTileBytes + wv * kBmWaveBytes;
-  char* kbuf = wbase;
-  char* vbuf = wbase + kAtTileBytes;
-  char* pt = wbase + 2 * kAtTileBytes;
+  char* kbuf = waves + wv * kBmWaveBytes;
+  char* vbuf = kbuf + kAtTileBytes;
+  char* pt = kbuf + 2 * kAtTileBytes;
   char* dst = pt + kBmXtBytes;
-  const bool row_ok = li < R;
-  const int node = row_ok ? li / G : 0;
-  const int qs_row = tid >> 3;  // staging: 8 threads per query row, 32 bytes each
-  const bool qs_ok = qs_row < R;
-  const int qs_node = qs_ok ? qs_row / G : 0, qs_g = qs_ok ? qs_row % G : 0;
   const float scale_log2 = scale * kLog2e;
 
   int b = 0;
@@ -164,37 +159,46 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
     const int prefix = L - Nq;
     const int ntile = t1 - t0;
     const int32_t* bt = block_table + (size_t)b * max_pages;
-    {
-      // the pair's query rows and their upstream gradients, each in both LDS layouts
-      const size_t at = (((size_t)b * Nq + qs_node) * Hq + hk * G + qs_g) * kAtD;
+    // the pair's query rows and their upstream gradients: group row m = n * G + g <-> (node n, head hk * G + g);
+    // 8 threads per row, 32 bytes each, 32 rows per turn
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt) {
+      const int m = 32 * rt + (tid >> 3);
+      const bool ok = m < R;
+      const int n = ok ? m / G : 0, g = ok ? m % G : 0;
+      const size_t at = (((size_t)b * Nq + n) * Hq + hk * G + g) * kAtD;
       const u32x4_t* qp = (const u32x4_t*)(q + at);
       const u32x4_t* gp = (const u32x4_t*)(dout + at);
-      const int c0 = (tid & 7) * 2;
+      const int c0 = (tid & 7) * 2, row = tid >> 3;
       const u32x4_t z = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const u32x4_t qv = qs_ok ? qp[c0 + i] : z;
-        const u32x4_t gv = qs_ok ? gp[c0 + i] : z;
-        const int ck = ((c0 + i) ^ (qs_row & 15)) * 16, cv = ((c0 + i) ^ v_key(qs_row)) * 16;
-        *(u32x4_t*)(qK + qs_row * kAtRowBytes + ck) = qv;
-        *(u32x4_t*)(doK + qs_row * kAtRowBytes + ck) = gv;
-        *(u32x4_t*)(qV + qs_row * kAtRowBytes + cv) = qv;
-        *(u32x4_t*)(doV + qs_row * kAtRowBytes + cv) = gv;
+        const int cv = ((c0 + i) ^ v_key(row)) * 16;
+        *(u32x4_t*)(qV + rt * kAtTileBytes + row * kAtRowBytes + cv) = ok ? qp[c0 + i] : z;
+        *(u32x4_t*)(doV + rt * kAtTileBytes + row * kAtRowBytes + cv) = ok ? gp[c0 + i] : z;
       }
     }
-    // this lane's query row: logsumexp (log2 units) and delta; rows past the group see nothing
-    float lse2 = INFINITY, dlt = 0.f;
-    if (row_ok) {
-      const size_t row = ((size_t)b * Nq + node) * Hq + hk * G + li % G;
-      lse2 = lse[row] * kLog2e;
-      dlt = delta[row];
-    }
-    unsigned long long anc;
-    if (parents) {
-      anc = 0;
-      for (int a = node, hops = 0; a >= 0 && hops <= Nq; a = parents[(size_t)b * Nq + a], ++hops) anc |= 1ull << a;
-    } else {
-      anc = node == 63 ? ~0ull : ((1ull << (node + 1)) - 1);
+    // this lane's query row of every row tile: logsumexp (log2 units), delta and the set of tree nodes it sees;
+    // rows past the group see nothing
+    float lse2[kRT], dlt[kRT];
+    unsigned long long anc[kRT];
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt) {
+      const int m = 32 * rt + li;
+      lse2[rt] = INFINITY;
+      dlt[rt] = 0.f;
+      anc[rt] = 0;
+      if (m < R) {
+        const int node = m / G;
+        const size_t row = ((size_t)b * Nq + node) * Hq + hk * G + m % G;
+        lse2[rt] = lse[row] * kLog2e;
+        dlt[rt] = delta[row];
+        if (parents) {
+          for (int a = node, hops = 0; a >= 0 && hops <= Nq; a = parents[(size_t)b * Nq + a], ++hops) anc[rt] |= 1ull << a;
+        } else {
+          anc[rt] = node == 63 ? ~0ull : ((1ull << (node + 1)) - 1);
+        }
+      }
     }
 
     auto tile_pages = [&](int tt, int& pid_a, int& pid_b) {
@@ -208,11 +212,13 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
       for (int j = 0; j < 8; ++j) issue_rows<true>(pool, buf, j, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
     };
 
-    f32x16_t dq_acc[4];
+    f32x16_t dq_acc[kRT][4];
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int rt = 0; rt < kRT; ++rt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dq_acc[db][r] = 0.f;
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dq_acc[rt][db][r] = 0.f;
 
     __syncthreads();  // query rows staged
     int tt = wv;
@@ -228,38 +234,45 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
       if (more) tile_pages(tt + 4, npa, npb);
       WAIT_VMCNT(0);  // this tile's K and V have landed (and the previous tile's stores have left)
       const int j0 = start + tt * kAtTile;
-      const f32x16_t s_acc = tile_scores_v(kbuf, qK, li, lh);
-      const f32x16_t dp_acc = tile_scores_v(vbuf, doK, li, lh);
-      asm volatile("" ::: "memory");
-      if (more) issue_tile(vp, vbuf, tt + 4, npa, npb);  // V is not read again
-      float p[16], ds[16];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-        const bool seen = j < prefix || (j < L && ((anc >> (j - prefix)) & 1ull));
-        p[r] = seen ? __builtin_amdgcn_exp2f(fmaf(s_acc[r], scale_log2, -lse2)) : 0.f;
-        ds[r] = p[r] * (dp_acc[r] - dlt);
-      }
-      bf16x8_t p_b[2], ds_b[2];
-      pack_and_transpose(p, p_b, pt, li, lh);
-      pack_and_transpose(ds, ds_b, dst, li, lh);
-      tile_tmm(kbuf, ds_b, dq_acc, lane);  // dQ^T += K^T dS^T
-      asm volatile("" ::: "memory");
-      if (more) issue_tile(kp, kbuf, tt + 4, npa, npb);  // K is not read again
-      // dV = P^T dO and dK = dS^T Q
       f32x16_t dv_acc[4], dk_acc[4];
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dv_acc[db][r] = 0.f; dk_acc[db][r] = 0.f; }
-      bf16x8_t pt_b[2], dst_b[2];
-      read_transposed(pt, pt_b, li, lh);
-      read_transposed(dst, dst_b, li, lh);
-      // the transposed tile is the A operand: the output has one column per lane (32 db + li) and 16 tokens in the
-      // registers, so that a store instruction writes two whole 128-byte lines; the gradients are not read again
-      tile_tmm<true>(doV, pt_b, dv_acc, lane);
-      tile_tmm<true>(qV, dst_b, dk_acc, lane);
+#pragma unroll
+      for (int rt = 0; rt < kRT; ++rt) {
+        const f32x16_t s_acc = tile_scores_v(kbuf, qV + rt * kAtTileBytes, li, lh);
+        const f32x16_t dp_acc = tile_scores_v(vbuf, doV + rt * kAtTileBytes, li, lh);
+        if (rt == kRT - 1) {
+          asm volatile("" ::: "memory");
+          if (more) issue_tile(vp, vbuf, tt + 4, npa, npb);  // V is not read again
+        }
+        float p[16], ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          const bool seen = j < prefix || (j < L && ((anc[rt] >> (j - prefix)) & 1ull));
+          p[r] = seen ? __builtin_amdgcn_exp2f(fmaf(s_acc[r], scale_log2, -lse2[rt])) : 0.f;
+          ds[r] = p[r] * (dp_acc[r] - dlt[rt]);
+        }
+        bf16x8_t p_b[2], ds_b[2];
+        pack_and_transpose(p, p_b, pt, li, lh);
+        pack_and_transpose(ds, ds_b, dst, li, lh);
+        tile_tmm(kbuf, ds_b, dq_acc[rt], lane);  // dQ^T += K^T dS^T
+        if (rt == kRT - 1) {
+          asm volatile("" ::: "memory");
+          if (more) issue_tile(kp, kbuf, tt + 4, npa, npb);  // K is not read again
+        }
+        // dV += P^T dO and dK += dS^T Q over this row tile.  The transposed tile is the A operand: the output has
+        // one column per lane (32 db + li) and 16 tokens in the registers.
+        bf16x8_t pt_b[2], dst_b[2];
+        read_transposed(pt, pt_b, li, lh);
+        read_transposed(dst, dst_b, li, lh);
+        tile_tmm<true>(doV + rt * kAtTileBytes, pt_b, dv_acc, lane);
+        tile_tmm<true>(qV + rt * kAtTileBytes, dst_b, dk_acc, lane);
+      }
       {
+        // a store instruction writes two whole 128-byte lines; the gradients are not read again
         const int mask = (1 << page_shift) - 1;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -279,37 +292,40 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
       pb = npb;
     }
 
-    // ---- sum dQ^T over the four wavefronts and write the run's partial ---------------------------------------
+    // ---- sum dQ^T over the four wavefronts and write the run's partial, one row tile at a time ----------------
     WAIT_VMCNT(0);
     __syncthreads();  // every wavefront is done with its tiles
 #pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      float* obuf = (float*)(db < 2 ? kbuf : vbuf);
+    for (int rt = 0; rt < kRT; ++rt) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int dd = 32 * (db & 1) + 8 * g + 4 * lh;
-        f32x4_t o = {dq_acc[db][4 * g], dq_acc[db][4 * g + 1], dq_acc[db][4 * g + 2], dq_acc[db][4 * g + 3]};
-        *(f32x4_t*)(obuf + li * 64 + ((dd / 4 + li) & 15) * 4) = o;
-      }
-    }
-    __syncthreads();
-    {
-      const int db = wv;  // wavefront w sums and stores d-block w of all rows
-      const size_t prow = (size_t)slot * 32 + li;
+      for (int db = 0; db < 4; ++db) {
+        float* obuf = (float*)(db < 2 ? kbuf : vbuf);
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int dd = 32 * (db & 1) + 8 * g + 4 * lh;
-        f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const char* wb = bm_lds + 4 * kAtTileBytes + w * kBmWaveBytes;
-          const float* ob = (const float*)(db < 2 ? wb : wb + kAtTileBytes);
-          sum += *(const f32x4_t*)(ob + li * 64 + ((dd / 4 + li) & 15) * 4);
+        for (int g = 0; g < 4; ++g) {
+          const int dd = 32 * (db & 1) + 8 * g + 4 * lh;
+          f32x4_t o = {dq_acc[rt][db][4 * g], dq_acc[rt][db][4 * g + 1], dq_acc[rt][db][4 * g + 2], dq_acc[rt][db][4 * g + 3]};
+          *(f32x4_t*)(obuf + li * 64 + ((dd / 4 + li) & 15) * 4) = o;
         }
-        if (row_ok) *(f32x4_t*)(part_dq + prow * kAtD + 32 * db + 8 * g + 4 * lh) = sum;
       }
+      __syncthreads();
+      {
+        const int db = wv;  // wavefront w sums and stores d-block w of all rows
+        const size_t prow = ((size_t)slot * kRT + rt) * 32 + li;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int dd = 32 * (db & 1) + 8 * g + 4 * lh;
+          f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const char* wb = waves + w * kBmWaveBytes;
+            const float* ob = (const float*)(db < 2 ? wb : wb + kAtTileBytes);
+            sum += *(const f32x4_t*)(ob + li * 64 + ((dd / 4 + li) & 15) * 4);
+          }
+          if (32 * rt + li < R) *(f32x4_t*)(part_dq + prow * kAtD + 32 * db + 8 * g + 4 * lh) = sum;
+        }
+      }
+      __syncthreads();  // the tiles are about to be overwritten (next row tile, or the next run's K and V)
     }
-    __syncthreads();  // the tiles are about to be refilled for the next run
   }
 }
 
@@ -317,7 +333,7 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
 __global__ __launch_bounds__(256) void attn_bwd_dq_combine(const float* __restrict__ part_dq,
                                                            const int32_t* __restrict__ seq_lens,
                                                            const int32_t* __restrict__ PB, float* __restrict__ dq, int B,
-                                                           int Nq, int Hq, int Hkv, int wgs, unsigned n_rows, float scale) {
+                                                           int Nq, int Hq, int Hkv, int wgs, int row_tiles, unsigned n_rows, float scale) {
   const size_t row = (size_t)blockIdx.x * 8 + (threadIdx.x >> 5);
   if (row >= n_rows) return;
   const int hq = (int)(row % Hq);
@@ -332,30 +348,45 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_combine(const float* __restri
   const int pair = b * Hkv + hk;
   const int d4 = threadIdx.x & 31;
   f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-  for (int w = w0; w <= w1; ++w) acc += *(const f32x4_t*)(part_dq + ((size_t)(w + pair) * 32 + mrow) * kAtD + 4 * d4);
+  for (int w = w0; w <= w1; ++w) acc += *(const f32x4_t*)(part_dq + ((size_t)(w + pair) * 32 * row_tiles + mrow) * kAtD + 4 * d4);
   *(f32x4_t*)(dq + row * kAtD + 4 * d4) = acc * scale;
 }
 
 bool attn_bwd_mfma_supported(const AttnBwdLaunch& a) {
-  return a.bf16 && a.D == kAtD && a.page >= 16 && (a.page & (a.page - 1)) == 0 && a.Hq / a.Hkv * a.Nq <= 32 &&
+  return a.bf16 && a.D == kAtD && a.page >= 16 && (a.page & (a.page - 1)) == 0 && a.Hq / a.Hkv * a.Nq <= 128 &&
          a.B <= kLocalPlanMax;
 }
 
 int attn_bwd_mfma_workgroups() { return 256; }
 
+// row tiles the kernel is instantiated for: 1, 2 or 4
+static int bwd_row_tiles(const AttnBwdLaunch& a) {
+  const int R = a.Hq / a.Hkv * a.Nq;
+  return R <= 32 ? 1 : R <= 64 ? 2 : 4;
+}
+size_t attn_bwd_mfma_partial_bytes(int batch, int kv_heads, int rows_per_group) {
+  const int rt = rows_per_group <= 32 ? 1 : rows_per_group <= 64 ? 2 : 4;
+  return ((size_t)attn_bwd_mfma_workgroups() + (size_t)batch * kv_heads) * 32 * rt * kAtD * sizeof(float);
+}
+
+template <int kRT>
+static hipError_t launch_bwd_mfma_t(const AttnBwdLaunch& a, hipStream_t st) {
+  static LdsAttrOnce attr;
+  if (hipError_t e = attr.ensure((const void*)attn_bwd_mfma_kernel<kRT>, bm_lds_bytes(kRT)); e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_bwd_mfma_kernel<kRT>, dim3(attn_bwd_mfma_workgroups()), dim3(kBmThreads), bm_lds_bytes(kRT), st,
+                     (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
+                     (const bf16_t*)a.dout, a.lse, a.delta, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv,
+                     __builtin_ctz(a.page), a.max_pages, a.scale);
+  return hipGetLastError();
+}
+
 hipError_t launch_attn_backward_mfma(const AttnBwdLaunch& a, hipStream_t st) {
   const int rows = a.B * a.Nq * a.Hq;
-  static LdsAttrOnce attr;
-  if (hipError_t e = attr.ensure((const void*)attn_bwd_mfma_kernel, kBmLdsBytes); e != hipSuccess) return e;
-  const int wgs = attn_bwd_mfma_workgroups();
-  hipLaunchKernelGGL(attn_bwd_mfma_kernel, dim3(wgs), dim3(kBmThreads), kBmLdsBytes, st, (const bf16_t*)a.q,
-                     (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents, (const bf16_t*)a.dout,
-                     a.lse, a.delta, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv, __builtin_ctz(a.page),
-                     a.max_pages, a.scale);
-  hipError_t e = hipGetLastError();
+  const int rt = bwd_row_tiles(a);
+  hipError_t e = rt == 1 ? launch_bwd_mfma_t<1>(a, st) : rt == 2 ? launch_bwd_mfma_t<2>(a, st) : launch_bwd_mfma_t<4>(a, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_bwd_dq_combine, dim3((rows + 7) / 8), dim3(256), 0, st, a.part_dq, a.seq_lens, a.plan_pb, a.dq,
-                     a.B, a.Nq, a.Hq, a.Hkv, wgs, (unsigned)rows, a.scale);
+                     a.B, a.Nq, a.Hq, a.Hkv, attn_bwd_mfma_workgroups(), rt, (unsigned)rows, a.scale);
   return hipGetLastError();
 }
 

@@ -86,6 +86,7 @@ hipError_t launch_attn_backward(const AttnBwdLaunch& a, hipStream_t st);
 // matrix-core kernel (attn_bwd_mfma.hip): shapes it takes, its resident workgroups, and its launch (delta is ready)
 bool attn_bwd_mfma_supported(const AttnBwdLaunch& a);
 int attn_bwd_mfma_workgroups();
+size_t attn_bwd_mfma_partial_bytes(int batch, int kv_heads, int rows_per_group);
 hipError_t launch_attn_backward_mfma(const AttnBwdLaunch& a, hipStream_t st);
 
 // packing of trace records (see pack.hip)

@@ -64,6 +64,13 @@ def test_tree_bf16_many_query_rows(gpu_lib):
     _check(gen.llama_tree(132, batch=3, num_q=16, context=150, vocab=64, hidden_size=64, num_q_heads=8, num_kv_heads=2), 2)
 
 
+def test_tree_bf16_128_query_rows(gpu_lib):
+    """A 32-node tree with four query heads per KV head (the tree workload's shape): four row tiles per pair, a ragged last
+    tile, several runs of tiles per pair; then 24 rows (one tile) as a tree."""
+    _check(gen.llama_tree(138, batch=5, num_q=32, context=700, vocab=64, hidden_size=64, num_q_heads=8, num_kv_heads=2), 7)
+    _check(gen.llama_tree(139, batch=2, num_q=24, context=90, vocab=64, hidden_size=64, num_q_heads=4, num_kv_heads=1), 8)
+
+
 def test_fp32_head_dim_64_and_large_pages(gpu_lib):
     _check(gen.tiny_chain(133), 3)
     _check(gen.llama_chain(134, batch=2, len_lo=30, len_hi=200, vocab=64, hidden_size=64, page_size=24, head_dim=64,
