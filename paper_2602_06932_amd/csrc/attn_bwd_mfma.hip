@@ -329,6 +329,227 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
   }
 }
 
+// ---- 65 .. 128 query rows per KV head: one row tile per wavefront, K / V tiles shared by the workgroup -----------
+// Four dq accumulator sets per wavefront do not fit the register file next to the dK / dV accumulators, so the
+// work of a tile is cut the other way: the workgroup walks the tiles of its run together (K / V tile loaded once,
+// double-buffered, each wavefront issuing a quarter of the loads); wavefront w forms S^T, dP^T, P, dS and dQ for
+// row tile w, and publishes its transposed P and dS tiles; after a barrier it contracts over ALL row tiles for
+// column block w of dV and dK (16 accumulator registers each) and stores those columns.  The K / V loads of the
+// next tile are requested before this tile's products, and this tile's stores are still in flight when the next
+// tile starts: the wait at its top only covers the loads, which are older than the 32 stores.
+constexpr int kBsKvBytes = 2 * kAtTileBytes;   // K tile, then V tile
+constexpr int kBsXtBytes = 2 * kBmXtBytes;     // transposed P, then dS, of one wavefront
+constexpr int kBsLdsBytes = 8 * kAtTileBytes + 2 * kBsKvBytes + 2 * 4 * kBsXtBytes;
+
+// block db of tile_tmm<true>: acc += B^T A[:, 32 db .. 32 db + 31]
+__device__ __forceinline__ void tile_tmm_block(const char* abuf, const bf16x8_t b[2], f32x16_t& acc, int lane, int db) {
+  const int lh = lane >> 5, k = lane & 15, kq = k >> 2;
+  const int g1 = (lane >> 4) & 1;
+  const int lo0 = ((2 * g1 + ((k & 3) >> 1)) ^ (lh & 3)) * 16;
+  const int lo1 = ((2 * g1 + ((k & 3) >> 1)) ^ ((2 + lh) & 3)) * 16;
+  const int common = lh * 1024 + kq * 256 + (k & 1) * 8 + kq * 64;
+  const int base0 = (common + lo0) ^ (db * 64);
+  const int base1 = (common + lo1 + 2048) ^ (db * 64);
+#pragma unroll
+  for (int uu = 0; uu < 2; ++uu) {
+    typedef __attribute__((address_space(3))) s16x4_t* lds_v4;
+    const s16x4_t r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(abuf + uu * 4096 + base0));
+    const s16x4_t r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(abuf + uu * 4096 + base1));
+    const u16x8_t va = {(unsigned short)r0[0], (unsigned short)r0[1], (unsigned short)r0[2], (unsigned short)r0[3],
+                        (unsigned short)r1[0], (unsigned short)r1[1], (unsigned short)r1[2], (unsigned short)r1[3]};
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[uu], __builtin_bit_cast(bf16x8_t, va), acc, 0, 0, 0);
+  }
+}
+
+__global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_shared_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
+    const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ parents,
+    const bf16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    int32_t* __restrict__ PB, float* __restrict__ part_dq, float* __restrict__ dk, float* __restrict__ dv, int B, int Nq,
+    int Hq, int Hkv, int page_shift, int max_pages, float scale) {
+  extern __shared__ __attribute__((aligned(1024))) char bm_lds[];
+  char* qV = bm_lds;                        // four row tiles of the pair's query rows (V-tile layout)
+  char* doV = bm_lds + 4 * kAtTileBytes;    // their upstream gradients
+  char* kv = bm_lds + 8 * kAtTileBytes;     // two K / V tile pairs
+  char* xt = kv + 2 * kBsKvBytes;           // two sets of four transposed (P, dS) tiles
+  __shared__ int s_pb[kLocalPlanMax + 1];
+  __shared__ int s_wsum[4];
+  build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
+  if (blockIdx.x == 0)
+    for (int i = threadIdx.x; i <= B; i += kBmThreads) PB[i] = s_pb[i];
+
+  const int U = s_pb[B];
+  const int c = units_per_wg(U, gridDim.x);
+  int u = blockIdx.x * c;
+  const int u_end = min(U, u + c);
+  if (u >= u_end) return;
+
+  const int G = Hq / Hkv, R = G * Nq;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 31, lh = lane >> 5;
+  const float scale_log2 = scale * kLog2e;
+  const int mask = (1 << page_shift) - 1;
+
+  int b = 0;
+  {
+    int lo = 0, hi = B - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (s_pb[mid] <= u) lo = mid; else hi = mid - 1;
+    }
+    b = lo;
+  }
+
+  while (u < u_end) {
+    while (s_pb[b + 1] <= u) ++b;
+    const int L = seq_lens[b];
+    const int n_b = (L + kAtTile - 1) / kAtTile;
+    const int rel = u - s_pb[b];
+    const int hk = __builtin_amdgcn_readfirstlane(rel / n_b);
+    const int t0 = rel - hk * n_b;
+    const int t1 = min(n_b, t0 + (u_end - u));
+    const int slot = blockIdx.x + b * Hkv + hk;
+    u += t1 - t0;
+    const int start = t0 * kAtTile;
+    const int prefix = L - Nq;
+    const int ntile = t1 - t0;
+    const int32_t* bt = block_table + (size_t)b * max_pages;
+    // the pair's query rows and upstream gradients: 8 threads per row, 32 bytes each, 32 rows per turn
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt) {
+      const int m = 32 * rt + (tid >> 3);
+      const bool ok = m < R;
+      const int n = ok ? m / G : 0, g = ok ? m % G : 0;
+      const size_t at = (((size_t)b * Nq + n) * Hq + hk * G + g) * kAtD;
+      const u32x4_t* qp = (const u32x4_t*)(q + at);
+      const u32x4_t* gp = (const u32x4_t*)(dout + at);
+      const int c0 = (tid & 7) * 2, row = tid >> 3;
+      const u32x4_t z = {0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int cv = ((c0 + i) ^ v_key(row)) * 16;
+        *(u32x4_t*)(qV + rt * kAtTileBytes + row * kAtRowBytes + cv) = ok ? qp[c0 + i] : z;
+        *(u32x4_t*)(doV + rt * kAtTileBytes + row * kAtRowBytes + cv) = ok ? gp[c0 + i] : z;
+      }
+    }
+    // this lane's query row (row tile = wavefront): logsumexp in log2 units, delta, visible tree nodes
+    const int m_row = 32 * wv + li;
+    float lse2 = INFINITY, dlt = 0.f;
+    unsigned long long anc = 0;
+    if (m_row < R) {
+      const int node = m_row / G;
+      const size_t row = ((size_t)b * Nq + node) * Hq + hk * G + m_row % G;
+      lse2 = lse[row] * kLog2e;
+      dlt = delta[row];
+      if (parents) {
+        for (int a = node, hops = 0; a >= 0 && hops <= Nq; a = parents[(size_t)b * Nq + a], ++hops) anc |= 1ull << a;
+      } else {
+        anc = node == 63 ? ~0ull : ((1ull << (node + 1)) - 1);
+      }
+    }
+
+    auto tile_pages = [&](int tt, int& pid_a, int& pid_b) {
+      const int j0 = start + tt * kAtTile;
+      pid_a = bt[j0 >> page_shift];
+      pid_b = bt[min(j0 + 16, L - 1) >> page_shift];
+    };
+    // this wavefront's quarter of a tile pair's loads: two instructions (eight token rows) of K, two of V
+    auto issue_quarter = [&](int tt, int pid_a, int pid_b) {
+      const int j0 = start + tt * kAtTile;
+      char* kb = kv + (tt & 1) * kBsKvBytes;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        issue_rows<true>(kp, kb, 2 * wv + i, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
+        issue_rows<true>(vp, kb + kAtTileBytes, 2 * wv + i, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
+      }
+    };
+
+    f32x16_t dq_acc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dq_acc[db][r] = 0.f;
+
+    __syncthreads();  // query rows staged; the previous run is done with every buffer
+    int pa, pb;
+    tile_pages(0, pa, pb);
+    issue_quarter(0, pa, pb);
+    for (int tt = 0; tt < ntile; ++tt) {
+      const bool more = tt + 1 < ntile;
+      int npa = 0, npb = 0;
+      if (more) tile_pages(tt + 1, npa, npb);
+      // this tile's loads have landed; from the second tile on they are older than the previous tile's 32 stores
+      // (a tile that is followed by another one is never ragged, so all of its stores were issued)
+      if (tt == 0) WAIT_VMCNT(0); else WAIT_VMCNT(32);
+      __builtin_amdgcn_s_barrier();  // ... from all four wavefronts; everyone is also done with the tile before
+      asm volatile("" ::: "memory");
+      if (more) issue_quarter(tt + 1, npa, npb);  // into the pair the tile before last used
+      const char* kb = kv + (tt & 1) * kBsKvBytes;
+      const char* vb = kb + kAtTileBytes;
+      char* xts = xt + (tt & 1) * 4 * kBsXtBytes;
+      const int j0 = start + tt * kAtTile;
+      {
+        const f32x16_t s_acc = tile_scores_v(kb, qV + wv * kAtTileBytes, li, lh);
+        const f32x16_t dp_acc = tile_scores_v(vb, doV + wv * kAtTileBytes, li, lh);
+        float p[16], ds[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          const bool seen = j < prefix || (j < L && ((anc >> (j - prefix)) & 1ull));
+          p[r] = seen ? __builtin_amdgcn_exp2f(fmaf(s_acc[r], scale_log2, -lse2)) : 0.f;
+          ds[r] = p[r] * (dp_acc[r] - dlt);
+        }
+        bf16x8_t p_b[2], ds_b[2];
+        pack_and_transpose(p, p_b, xts + wv * kBsXtBytes, li, lh);
+        pack_and_transpose(ds, ds_b, xts + wv * kBsXtBytes + kBmXtBytes, li, lh);
+        tile_tmm(kb, ds_b, dq_acc, lane);  // dQ^T += K^T dS^T for this wavefront's row tile
+      }
+      __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0): the transposed tiles are written
+      __builtin_amdgcn_s_barrier();                            // ... by all four wavefronts
+      asm volatile("" ::: "memory");
+      {
+        // columns 32 wv .. 32 wv + 31 of dV = P^T dO and dK = dS^T Q, contraction over all four row tiles
+        f32x16_t dv_acc, dk_acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { dv_acc[r] = 0.f; dk_acc[r] = 0.f; }
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+          bf16x8_t pt_b[2], dst_b[2];
+          read_transposed(xts + rt * kBsXtBytes, pt_b, li, lh);
+          read_transposed(xts + rt * kBsXtBytes + kBmXtBytes, dst_b, li, lh);
+          tile_tmm_block(doV + rt * kAtTileBytes, pt_b, dv_acc, lane, wv);
+          tile_tmm_block(qV + rt * kAtTileBytes, dst_b, dk_acc, lane, wv);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int tok = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          if (tok < L) {
+            const int pid = r < 8 ? pa : pb;
+            const size_t at = ((((size_t)pid * Hkv + hk) << page_shift) + (tok & mask)) * kAtD + 32 * wv + li;
+            __builtin_nontemporal_store(dv_acc[r], dv + at);
+            __builtin_nontemporal_store(dk_acc[r] * scale, dk + at);
+          }
+        }
+      }
+      pa = npa;
+      pb = npb;
+    }
+    // the run's partial dq of this wavefront's row tile
+    if (m_row < R) {
+      const size_t prow = (size_t)slot * 128 + m_row;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4_t o = {dq_acc[db][4 * g], dq_acc[db][4 * g + 1], dq_acc[db][4 * g + 2], dq_acc[db][4 * g + 3]};
+          *(f32x4_t*)(part_dq + prow * kAtD + 32 * db + 8 * g + 4 * lh) = o;
+        }
+    }
+    __syncthreads();  // slower wavefronts still read the query tiles, which the next run overwrites
+  }
+}
+
 // dq of one output row = scale * sum of the partials of the runs that met its (request, KV head) pair
 __global__ __launch_bounds__(256) void attn_bwd_dq_combine(const float* __restrict__ part_dq,
                                                            const int32_t* __restrict__ seq_lens,
@@ -380,10 +601,20 @@ static hipError_t launch_bwd_mfma_t(const AttnBwdLaunch& a, hipStream_t st) {
   return hipGetLastError();
 }
 
+static hipError_t launch_bwd_mfma_shared(const AttnBwdLaunch& a, hipStream_t st) {
+  static LdsAttrOnce attr;
+  if (hipError_t e = attr.ensure((const void*)attn_bwd_mfma_shared_kernel, kBsLdsBytes); e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_bwd_mfma_shared_kernel, dim3(attn_bwd_mfma_workgroups()), dim3(kBmThreads), kBsLdsBytes, st,
+                     (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
+                     (const bf16_t*)a.dout, a.lse, a.delta, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv,
+                     __builtin_ctz(a.page), a.max_pages, a.scale);
+  return hipGetLastError();
+}
+
 hipError_t launch_attn_backward_mfma(const AttnBwdLaunch& a, hipStream_t st) {
   const int rows = a.B * a.Nq * a.Hq;
   const int rt = bwd_row_tiles(a);
-  hipError_t e = rt == 1 ? launch_bwd_mfma_t<1>(a, st) : rt == 2 ? launch_bwd_mfma_t<2>(a, st) : launch_bwd_mfma_t<4>(a, st);
+  hipError_t e = rt == 1 ? launch_bwd_mfma_t<1>(a, st) : rt == 2 ? launch_bwd_mfma_t<2>(a, st) : launch_bwd_mfma_shared(a, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_bwd_dq_combine, dim3((rows + 7) / 8), dim3(256), 0, st, a.part_dq, a.seq_lens, a.plan_pb, a.dq,
                      a.B, a.Nq, a.Hq, a.Hkv, attn_bwd_mfma_workgroups(), rt, (unsigned)rows, a.scale);
