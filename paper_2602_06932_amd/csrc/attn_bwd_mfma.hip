@@ -102,7 +102,27 @@ __device__ __forceinline__ void read_transposed(const char* xt, bf16x8_t b[2], i
   }
 }
 
-template <int kRT /* 32-row tiles of query rows per KV head: 1, 2 or 4 */>
+// P^T and dS^T of a tile for this lane's query row (register r <-> token j0 + 8(r/4) + 4 lh + r%4).  Only tiles
+// that reach into the draft positions need the mask (a wavefront-uniform test); masked scores become -inf, and a
+// row past the group has lse = +inf, so both give p = 0 without a select.
+__device__ __forceinline__ void tile_p_ds(f32x16_t s_acc, const f32x16_t dp_acc, float p[16], float ds[16], float scale_log2,
+                                          float lse2, float dlt, unsigned long long anc, int j0, int prefix, int L, int lh) {
+  if (j0 + kAtTile > prefix) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+      const bool seen = j < prefix || (j < L && ((anc >> (j - prefix)) & 1ull));
+      s_acc[r] = seen ? s_acc[r] : -INFINITY;
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    p[r] = __builtin_amdgcn_exp2f(fmaf(s_acc[r], scale_log2, -lse2));
+    ds[r] = p[r] * (dp_acc[r] - dlt);
+  }
+}
+
+template <int kRT /* 32-row tiles of query rows per KV head: 1 or 2 */>
 __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ parents,
@@ -248,13 +268,7 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
           if (more) issue_tile(vp, vbuf, tt + 4, npa, npb);  // V is not read again
         }
         float p[16], ds[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-          const bool seen = j < prefix || (j < L && ((anc[rt] >> (j - prefix)) & 1ull));
-          p[r] = seen ? __builtin_amdgcn_exp2f(fmaf(s_acc[r], scale_log2, -lse2[rt])) : 0.f;
-          ds[r] = p[r] * (dp_acc[r] - dlt[rt]);
-        }
+        tile_p_ds(s_acc, dp_acc, p, ds, scale_log2, lse2[rt], dlt[rt], anc[rt], j0, prefix, L, lh);
         bf16x8_t p_b[2], ds_b[2];
         pack_and_transpose(p, p_b, pt, li, lh);
         pack_and_transpose(ds, ds_b, dst, li, lh);
@@ -493,13 +507,7 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_shared_kernel(
         const f32x16_t s_acc = tile_scores_v(kb, qV + wv * kAtTileBytes, li, lh);
         const f32x16_t dp_acc = tile_scores_v(vb, doV + wv * kAtTileBytes, li, lh);
         float p[16], ds[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = j0 + 8 * (r >> 2) + 4 * lh + (r & 3);
-          const bool seen = j < prefix || (j < L && ((anc >> (j - prefix)) & 1ull));
-          p[r] = seen ? __builtin_amdgcn_exp2f(fmaf(s_acc[r], scale_log2, -lse2)) : 0.f;
-          ds[r] = p[r] * (dp_acc[r] - dlt);
-        }
+        tile_p_ds(s_acc, dp_acc, p, ds, scale_log2, lse2, dlt, anc, j0, prefix, L, lh);
         bf16x8_t p_b[2], ds_b[2];
         pack_and_transpose(p, p_b, xts + wv * kBsXtBytes, li, lh);
         pack_and_transpose(ds, ds_b, xts + wv * kBsXtBytes + kBmXtBytes, li, lh);
@@ -580,7 +588,7 @@ bool attn_bwd_mfma_supported(const AttnBwdLaunch& a) {
 
 int attn_bwd_mfma_workgroups() { return 256; }
 
-// row tiles the kernel is instantiated for: 1, 2 or 4
+// row tiles of the pair: 1 or 2 (wavefront-private tiles), 4 (shared tiles)
 static int bwd_row_tiles(const AttnBwdLaunch& a) {
   const int R = a.Hq / a.Hkv * a.Nq;
   return R <= 32 ? 1 : R <= 64 ? 2 : 4;
