@@ -133,6 +133,15 @@ def main():
         torch.cuda.synchronize()
         ms = event_time_ms(fn, args.steps, torch)
         ms_fwd = event_time_ms(dv.attn, args.steps, torch)
+        # the same backward on an output and logsumexp kept from aurora_attn_forward (no recomputation)
+        out_s = torch.empty_like(dv.q)
+        lse_s = torch.empty(dv.q.shape[:3], dtype=torch.float32, device="cuda")
+        av.aurora_attn_forward(dv.attn_desc, dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.seq_lens, dv.parents,
+                               out_s, lse_s, wsb)
+        fn_saved = lambda: av.aurora_attn_backward_saved(dv.attn_desc, dv.q, dv.k_pages, dv.v_pages, dv.block_table,
+                                                         dv.seq_lens, dv.parents, out_s, lse_s, dout, dq, dk, dvp, wsb)
+        fn_saved()
+        ms_saved = event_time_ms(fn_saved, args.steps, torch)
         tok = int(w.seq_lens.astype(np.int64).sum())
         esz = 2 if w.dtype == "bf16" else 4
         kv_elems = tok * w.num_kv_heads * w.head_dim
@@ -140,6 +149,7 @@ def main():
         rows = w.num_q * w.num_q_heads // w.num_kv_heads
         flops = 2.0 * rows * w.head_dim * tok * w.num_kv_heads * (2 + 5)
         print(json.dumps({"stage": "attn_bwd", "steps": args.steps, "avg_ms": ms, "forward_alone_ms": ms_fwd,
+                          "backward_from_saved_ms": ms_saved,
                           "workload": w.name, "algorithmic_bytes": alg, "flops": flops,
                           "roofline": {"bound": "hbm", "achieved": alg / (ms * 1e-3) / 1e9, "peak": 8000.0,
                                        "unit": "GB/s", "frac": alg / (ms * 1e-3) / 1e9 / 8000.0,

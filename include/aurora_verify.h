@@ -298,18 +298,34 @@ const char* aurora_status_string(int status);
  *   dq_i = sm_scale sum_j dS_ij k_j      dk_j = sm_scale sum_i dS_ij q_i      dv_j = sum_i p_ij dout_i
  *
  * (dk_j, dv_j sum over every node and every query head of the KV head's group that sees position j: the cached
- * prefix receives gradient as well).  The call runs the forward pass itself (into the workspace), so `out` is
- * not an argument.  dq is float32 [B, Nq, Hq, D]; dk_pages / dv_pages are float32 pools in the layout of
- * k_pages / v_pages - the positions the batch's block tables address are written, every other element is
- * left as it is.  dout has the type of q.  All sums run in a fixed order: bit-reproducible.
- * This first version of the kernel is plain fp32 vector code (no matrix cores).  An 8-bit KV cache is not
- * supported (AURORA_ERR_UNSUPPORTED).  Workspace: aurora_attn_backward_workspace_bytes().
+ * prefix receives gradient as well).  dq is float32 [B, Nq, Hq, D]; dk_pages / dv_pages are float32 pools in the
+ * layout of k_pages / v_pages - the positions the batch's block tables address are written, every other element
+ * is left as it is.  dout has the type of q.  All sums run in a fixed order: bit-reproducible.
+ * bf16 caches with head_dim 128, power-of-two pages >= 16, at most 128 query rows per KV head and at most 1024
+ * requests run on the matrix cores (P and dS rounded to bf16 for the products, fp32 accumulation); every other
+ * shape takes a plain fp32 vector kernel.  An 8-bit KV cache is not supported (AURORA_ERR_UNSUPPORTED).
+ *
+ *   aurora_attn_backward        runs the forward pass itself (into the workspace): nothing is kept from a forward call
+ *   aurora_attn_forward         aurora_verify_attn that also writes lse [B, Nq, Hq] float32, the natural logarithm of
+ *                               each row's softmax denominator sum_j exp(sm_scale <q_i, k_j>) - what a training
+ *                               step keeps for the backward pass.  Workspace as for aurora_verify_attn
+ *                               (aurora_verify_workspace_bytes(desc, NULL)); 8-bit KV caches are accepted.
+ *   aurora_attn_backward_saved  the backward pass on `out` (type of q) and `lse` saved from aurora_attn_forward
+ *                               with the same inputs; results are bit-identical to aurora_attn_backward.
+ * Workspace of both backward calls: aurora_attn_backward_workspace_bytes().
  */
 int aurora_attn_backward_workspace_bytes(const aurora_attn_desc* desc, size_t* out_bytes);
 int aurora_attn_backward(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
                          const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents,
                          const void* dout, float* dq, float* dk_pages, float* dv_pages,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
+int aurora_attn_forward(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                        const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents, void* out,
+                        float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+int aurora_attn_backward_saved(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                               const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents,
+                               const void* out, const float* lse, const void* dout, float* dq, float* dk_pages,
+                               float* dv_pages, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Packing of the trace records that are shipped to the training side (appendix A.1, eq. 4: a record is

@@ -309,6 +309,12 @@ def trace_pack(*args, **kw):
     return _impl(*args, **kw)
 
 
+def attn_lse(*args, **kw):
+    """Logsumexp of every attention row (see oracle/attn_bwd_oracle.py)."""
+    from .attn_bwd_oracle import attn_lse as _impl
+    return _impl(*args, **kw)
+
+
 def attn_backward(*args, **kw):
     """Backward pass of the chunk / tree attention (see oracle/attn_bwd_oracle.py)."""
     from .attn_bwd_oracle import attn_backward as _impl

@@ -66,3 +66,31 @@ def attn_backward(q, k_pages, v_pages, block_table, seq_lens, parents, dout, sm_
                     dk[pg, hk, off] += scale * dS[t] * q[b, n, hq]
                     dv[pg, hk, off] += p[t] * g
     return out, dq, dk, dv
+
+
+def attn_lse(q, k_pages, block_table, seq_lens, parents, sm_scale=0.0):
+    """Natural logarithm of every row's softmax denominator, lse[b, n, hq] = log sum_j exp(scale * <q, k_j>) over the
+    positions j the row sees - the quantity a training step keeps from the forward pass.  float64 [B, Nq, Hq]."""
+    q = np.asarray(q, np.float64)
+    kp = np.asarray(k_pages, np.float64)
+    B, Nq, Hq, D = q.shape
+    P, Hkv, page, _ = kp.shape
+    G = Hq // Hkv
+    scale = sm_scale if sm_scale > 0 else 1.0 / np.sqrt(D)
+    lse = np.zeros((B, Nq, Hq))
+    for b in range(B):
+        L = int(seq_lens[b])
+        prefix = L - Nq
+        for n in range(Nq):
+            js = list(range(prefix))
+            chain = []
+            a = n
+            while a >= 0:
+                chain.append(prefix + a)
+                a = int(parents[b, a]) if parents is not None else a - 1
+            js += sorted(chain)
+            for hq in range(Hq):
+                s = np.array([scale * float(kp[int(block_table[b, j // page]), hq // G, j % page] @ q[b, n, hq]) for j in js])
+                top = s.max()
+                lse[b, n, hq] = top + np.log(np.exp(s - top).sum())
+    return lse

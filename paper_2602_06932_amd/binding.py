@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_v
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
            "aurora_verify_lmhead", "aurora_verify_accept_logits", "aurora_trace_emit",
            "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack", "aurora_attn_backward",
-           "aurora_attn_backward_workspace_bytes")
+           "aurora_attn_backward_workspace_bytes", "aurora_attn_forward", "aurora_attn_backward_saved")
 
 
 class aurora_attn_desc(C.Structure):
@@ -97,6 +97,11 @@ def load():
     lib.aurora_attn_backward_workspace_bytes.restype = C.c_int
     lib.aurora_attn_backward.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, f32p, f32p, f32p, vp, C.c_size_t, vp]
     lib.aurora_attn_backward.restype = C.c_int
+    lib.aurora_attn_forward.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, f32p, vp, C.c_size_t, vp]
+    lib.aurora_attn_forward.restype = C.c_int
+    lib.aurora_attn_backward_saved.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, f32p, vp, f32p, f32p, f32p, vp,
+                                               C.c_size_t, vp]
+    lib.aurora_attn_backward_saved.restype = C.c_int
     lib.aurora_trace_pack.argtypes = [C.POINTER(aurora_pack_desc)] + [vp] * 15
     lib.aurora_trace_pack.restype = C.c_int
     lib.aurora_draft_loss.argtypes = [C.POINTER(aurora_loss_desc), f32p, i32p, vp, vp, f32p, f32p, f32p, vp]
@@ -223,8 +228,7 @@ def aurora_verify_check_inputs(attn_desc, accept_desc, block_table, seq_lens, pa
                                            _ptr(parents), _ptr(draft_tokens), _ptr(uniforms), _ptr(flags),
                                            _stream(stream))
     if check and st != AURORA_OK:
-        raise AuroraError(st, "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack", "aurora_attn_backward",
-           "aurora_attn_backward_workspace_bytes")
+        raise AuroraError(st, "aurora_verify_check_inputs")
     return st
 
 
@@ -270,3 +274,24 @@ def aurora_draft_loss(desc, draft_logits, topk_ids, topk_logits, traj, row_kl, l
 def aurora_verify_logits_ptr(attn_desc, accept_desc, workspace) -> int:
     p = load().aurora_verify_logits_ptr(_ref(attn_desc), _ref(accept_desc), _ptr(workspace))
     return int(p or 0)
+
+
+def aurora_attn_forward(desc, q, k_pages, v_pages, block_table, seq_lens, parents, out, lse, workspace, stream=None,
+                        check=True) -> int:
+    wb = workspace.numel() * workspace.element_size()
+    st = load().aurora_attn_forward(_ref(desc), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table), _ptr(seq_lens),
+                                    _ptr(parents), _ptr(out), _ptr(lse), _ptr(workspace), wb, _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_attn_forward")
+    return st
+
+
+def aurora_attn_backward_saved(desc, q, k_pages, v_pages, block_table, seq_lens, parents, out, lse, dout, dq, dk_pages,
+                               dv_pages, workspace, stream=None, check=True) -> int:
+    wb = workspace.numel() * workspace.element_size()
+    st = load().aurora_attn_backward_saved(_ref(desc), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                           _ptr(seq_lens), _ptr(parents), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq),
+                                           _ptr(dk_pages), _ptr(dv_pages), _ptr(workspace), wb, _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_attn_backward_saved")
+    return st

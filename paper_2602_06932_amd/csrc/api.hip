@@ -362,6 +362,31 @@ int aurora_attn_backward_workspace_bytes(const aurora_attn_desc* desc, size_t* o
   return AURORA_OK;
 }
 
+namespace {
+// delta, the backward kernel and the dq merge on a forward output and logsumexp that are already there
+int run_attn_bwd(const aurora_attn_desc* desc, const BwdPlan& bp, const void* q, const void* k_pages, const void* v_pages,
+                 const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents, const void* out,
+                 const float* lse, const void* dout, float* dq, float* dk_pages, float* dv_pages, char* ws, hipStream_t st) {
+  AttnBwdLaunch a = {};
+  a.B = desc->batch; a.Nq = desc->num_q; a.Hq = desc->num_q_heads; a.Hkv = desc->num_kv_heads; a.D = desc->head_dim;
+  a.page = desc->page_size; a.max_pages = desc->max_pages_per_seq; a.bf16 = desc->dtype == AURORA_BF16;
+  a.scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->head_dim);
+  a.q = q; a.k = k_pages; a.v = v_pages; a.out = out; a.dout = dout;
+  a.block_table = block_table; a.seq_lens = seq_lens; a.parents = parents;
+  a.lse = lse; a.delta = (float*)(ws + bp.delta_off); a.dq = dq; a.dk = dk_pages; a.dv = dv_pages;
+  a.plan_pb = (int32_t*)(ws + bp.pb_off); a.part_dq = (float*)(ws + bp.part_dq_off);
+  return launch_attn_backward(a, st) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
+}
+
+int check_bwd_args(const aurora_attn_desc* desc, const void* dout, const float* dq, const float* dk_pages,
+                   const float* dv_pages, const void* workspace, size_t workspace_bytes, const BwdPlan& bp) {
+  if (!dout || !dq || !dk_pages || !dv_pages) return AURORA_ERR_INVALID_ARG;
+  if (((uintptr_t)dout | (uintptr_t)dq | (uintptr_t)dk_pages | (uintptr_t)dv_pages) & 15) return AURORA_ERR_INVALID_ARG;
+  if (!workspace || misaligned(workspace) || workspace_bytes < bp.bytes) return AURORA_ERR_WORKSPACE;
+  return AURORA_OK;
+}
+}  // namespace
+
 int aurora_attn_backward(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
                          const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents,
                          const void* dout, float* dq, float* dk_pages, float* dv_pages,
@@ -370,25 +395,47 @@ int aurora_attn_backward(const aurora_attn_desc* desc, const void* q, const void
   if (rc != AURORA_OK) return rc;
   if (desc->kv_fp8) return AURORA_ERR_UNSUPPORTED;
   if (desc->batch == 0) return AURORA_OK;
-  if (!dout || !dq || !dk_pages || !dv_pages) return AURORA_ERR_INVALID_ARG;
-  if (((uintptr_t)dout | (uintptr_t)dq | (uintptr_t)dk_pages | (uintptr_t)dv_pages) & 15) return AURORA_ERR_INVALID_ARG;
   const BwdPlan bp = plan_bwd(desc);
-  if (!workspace || misaligned(workspace) || workspace_bytes < bp.bytes) return AURORA_ERR_WORKSPACE;
+  rc = check_bwd_args(desc, dout, dq, dk_pages, dv_pages, workspace, workspace_bytes, bp);
+  if (rc != AURORA_OK) return rc;
+  if (!have_device()) return AURORA_ERR_HIP;
   char* ws = (char*)workspace;
   hipStream_t st = (hipStream_t)hip_stream;
   // forward pass into the workspace: out and the rows' logsumexp
   float* lse = (float*)(ws + bp.lse_off);
   rc = run_attn(desc, q, k_pages, v_pages, block_table, seq_lens, parents, ws + bp.out_off, workspace, bp.fwd_bytes, st, lse);
   if (rc != AURORA_OK) return rc;
-  AttnBwdLaunch a = {};
-  a.B = desc->batch; a.Nq = desc->num_q; a.Hq = desc->num_q_heads; a.Hkv = desc->num_kv_heads; a.D = desc->head_dim;
-  a.page = desc->page_size; a.max_pages = desc->max_pages_per_seq; a.bf16 = desc->dtype == AURORA_BF16;
-  a.scale = desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->head_dim);
-  a.q = q; a.k = k_pages; a.v = v_pages; a.out = ws + bp.out_off; a.dout = dout;
-  a.block_table = block_table; a.seq_lens = seq_lens; a.parents = parents;
-  a.lse = lse; a.delta = (float*)(ws + bp.delta_off); a.dq = dq; a.dk = dk_pages; a.dv = dv_pages;
-  a.plan_pb = (int32_t*)(ws + bp.pb_off); a.part_dq = (float*)(ws + bp.part_dq_off);
-  return launch_attn_backward(a, st) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
+  return run_attn_bwd(desc, bp, q, k_pages, v_pages, block_table, seq_lens, parents, ws + bp.out_off, lse, dout, dq,
+                      dk_pages, dv_pages, ws, st);
+}
+
+int aurora_attn_forward(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                        const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents, void* out,
+                        float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_attn_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (desc->batch > 0 && (!lse || ((uintptr_t)lse & 3))) return AURORA_ERR_INVALID_ARG;
+  if (!have_device()) return AURORA_ERR_HIP;
+  return run_attn(desc, q, k_pages, v_pages, block_table, seq_lens, parents, out, workspace, workspace_bytes,
+                  (hipStream_t)hip_stream, lse);
+}
+
+int aurora_attn_backward_saved(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                               const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents,
+                               const void* out, const float* lse, const void* dout, float* dq, float* dk_pages,
+                               float* dv_pages, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_attn_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  if (desc->kv_fp8) return AURORA_ERR_UNSUPPORTED;
+  if (desc->batch == 0) return AURORA_OK;
+  if (!q || !k_pages || !v_pages || !block_table || !seq_lens || !out || !lse) return AURORA_ERR_INVALID_ARG;
+  if (((uintptr_t)q | (uintptr_t)k_pages | (uintptr_t)v_pages | (uintptr_t)out) & 15) return AURORA_ERR_INVALID_ARG;
+  const BwdPlan bp = plan_bwd(desc);
+  rc = check_bwd_args(desc, dout, dq, dk_pages, dv_pages, workspace, workspace_bytes, bp);
+  if (rc != AURORA_OK) return rc;
+  if (!have_device()) return AURORA_ERR_HIP;
+  return run_attn_bwd(desc, bp, q, k_pages, v_pages, block_table, seq_lens, parents, out, lse, dout, dq, dk_pages,
+                      dv_pages, (char*)workspace, (hipStream_t)hip_stream);
 }
 
 int aurora_trace_pack(const aurora_pack_desc* d, const int8_t* traj, const void* h, const int32_t* topk_ids,

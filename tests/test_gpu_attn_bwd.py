@@ -102,3 +102,62 @@ def test_unused_pool_positions_are_left_alone_and_host_errors(gpu_lib):
     with pytest.raises(av.AuroraError) as e:
         av.aurora_attn_backward_workspace_bytes(d8.attn_desc)
     assert e.value.status == av.AURORA_ERR_UNSUPPORTED
+
+
+def _forward_lse(w):
+    import paper_2602_06932_amd as av
+    from paper_2602_06932_amd.device import DeviceVerify
+    dv = DeviceVerify(w)
+    out = torch.empty_like(dv.q)
+    lse = torch.full(w.q.shape[:3], float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(av.aurora_verify_workspace_bytes(dv.attn_desc, None), dtype=torch.uint8, device="cuda")
+    av.aurora_attn_forward(dv.attn_desc, dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.seq_lens, dv.parents, out, lse, ws)
+    torch.cuda.synchronize()
+    return dv, out, lse
+
+
+def test_forward_with_logsumexp(gpu_lib):
+    """aurora_attn_forward: the output is the verify step's, lse against the float64 oracle.  bf16 inputs are exact in
+    the products and the sums run in fp32 over at most a few thousand terms of either path: absolute 1e-3 (lse is of
+    order log L); fp32 storage 2e-5."""
+    from parity_util import check_attention
+    cases = [gen.llama_chain(140, batch=3, len_lo=40, len_hi=600, vocab=64, hidden_size=64),
+             gen.llama_tree(141, batch=2, num_q=32, context=300, vocab=64, hidden_size=64, num_q_heads=8, num_kv_heads=2),
+             gen.tiny_chain(142),
+             gen.llama_chain(143, batch=2, len_lo=40, len_hi=300, vocab=64, hidden_size=64, kv_fp8=True)]
+    for w in cases:
+        print(f"[case] {w.name} {w.dtype} kv={w.kv_dtype}", flush=True)
+        dv, out, lse = _forward_lse(w)
+        check_attention(out.float().cpu().numpy(), oracle.attn_workload(w), w.dtype)
+        if w.kv_dtype == "fp8":
+            kf = gen.e4m3_rows_to_f32(w.k_pages.reshape(-1, w.head_dim), np.ones(1, np.float32)).reshape(w.k_pages.shape)
+            kf = kf * w.k_scale[None, :, None, None]
+        else:
+            kf = gen.as_f32(w.k_pages, w.dtype)
+        ref = oracle.attn_lse(gen.as_f32(w.q, w.dtype), kf, w.host_block_table(), w.seq_lens, w.parents)
+        got = lse.cpu().numpy()
+        assert np.isfinite(got).all()
+        assert np.abs(got - ref).max() <= (2e-5 if w.dtype == "f32" else 1e-3), np.abs(got - ref).max()
+
+
+def test_backward_from_saved_forward_is_bit_identical(gpu_lib):
+    import paper_2602_06932_amd as av
+    from paper_2602_06932_amd.device import _to_dev
+    for w, seed in ((gen.llama_chain(144, batch=3, len_lo=40, len_hi=400, vocab=64, hidden_size=64), 9),
+                    (gen.llama_tree(145, batch=2, num_q=32, context=200, vocab=64, hidden_size=64, num_q_heads=8,
+                                    num_kv_heads=2), 10),
+                    (gen.tiny_chain(146), 11)):
+        rng = np.random.default_rng(seed)
+        g32 = rng.standard_normal(w.q.shape).astype(np.float32)
+        dout = (g32.view(np.uint32) >> 16).astype(np.uint16) if w.dtype == "bf16" else g32
+        ref = _run(w, dout)
+        dv, out, lse = _forward_lse(w)
+        dq = torch.full(w.q.shape, float("nan"), dtype=torch.float32, device="cuda")
+        dk = torch.zeros(dv.k_pages.shape, dtype=torch.float32, device="cuda")
+        dvp = torch.zeros(dv.v_pages.shape, dtype=torch.float32, device="cuda")
+        ws = torch.empty(av.aurora_attn_backward_workspace_bytes(dv.attn_desc), dtype=torch.uint8, device="cuda")
+        av.aurora_attn_backward_saved(dv.attn_desc, dv.q, dv.k_pages, dv.v_pages, dv.block_table, dv.seq_lens, dv.parents,
+                                      out, lse, _to_dev(dout, w.dtype), dq, dk, dvp, ws)
+        torch.cuda.synchronize()
+        for x, y in zip(ref, (dq.cpu().numpy(), dk.cpu().numpy(), dvp.cpu().numpy())):
+            assert np.array_equal(x, y)

@@ -107,3 +107,26 @@ def test_central_differences_of_the_forward_oracle():
         am[idx] -= h
         fd = (loss(**{name: ap}) - loss(**{name: am})) / (float(ap[idx]) - float(am[idx]))
         assert abs(fd - grad[idx]) < 1e-4 * max(1.0, abs(grad[idx])), name
+
+
+def test_lse_against_library_logsumexp_and_the_attention_oracle():
+    """The logsumexp oracle against torch.logsumexp on dense masked scores, and tied to the (separately pinned)
+    attention oracle: softmax weights rebuilt from it reproduce that oracle's output."""
+    for w in (gen.llama_tree(9, batch=2, num_q=7, context=25, vocab=32, hidden_size=16, num_q_heads=4, num_kv_heads=2,
+                             head_dim=16, page_size=8, dtype=gen.F32),
+              gen.llama_chain(10, batch=2, len_lo=9, len_hi=33, vocab=32, hidden_size=16, num_q_heads=6, num_kv_heads=2,
+                              head_dim=8, page_size=4, dtype=gen.F32)):
+        B, Nq, Hq, D = w.q.shape
+        G = Hq // w.num_kv_heads
+        lse = oracle.attn_lse(w.q, w.k_pages, w.block_table, w.seq_lens, w.parents)
+        fwd = oracle.attn_workload(w)
+        scale = 1.0 / np.sqrt(D)
+        for b, (K, V, mask) in enumerate(_dense_case(w)):
+            s = torch.einsum("nhd,hjd->hnj", torch.tensor(w.q[b].astype(np.float64)),
+                             torch.tensor(K).repeat_interleave(G, 0)) * scale
+            s = s.masked_fill(~torch.tensor(mask)[None], float("-inf"))
+            ref = torch.logsumexp(s, dim=-1).numpy().T                               # [Nq, Hq]
+            assert np.allclose(lse[b], ref, rtol=1e-12, atol=1e-12)
+            p = np.exp(s.numpy() - lse[b].T[:, :, None])                              # [Hq, Nq, L]
+            o = np.einsum("hnj,hjd->nhd", p, np.repeat(V, G, axis=0))
+            assert np.allclose(o, fwd[b], rtol=1e-9, atol=1e-11)
