@@ -23,7 +23,8 @@ import numpy as np
 
 def attn_backward(q, k_pages, v_pages, block_table, seq_lens, parents, dout, sm_scale=0.0):
     """q, dout [B,Nq,Hq,D]; pools [P,Hkv,page,D] (float arrays holding the stored values); returns
-    (out, dq, dk_pages, dv_pages), all float64."""
+    (out, dq, dk_pages, dv_pages), all float64.  Per (request, KV head) the request's K / V rows are gathered once
+    and the gradients of its positions are scattered back once; in between, one query row at a time."""
     q = np.asarray(q, np.float64)
     dout = np.asarray(dout, np.float64)
     kp = np.asarray(k_pages, np.float64)
@@ -39,32 +40,38 @@ def attn_backward(q, k_pages, v_pages, block_table, seq_lens, parents, dout, sm_
     for b in range(B):
         L = int(seq_lens[b])
         prefix = L - Nq
-        where = [(int(block_table[b, j // page]), j % page) for j in range(L)]
+        pos = np.arange(L)
+        pg = np.asarray(block_table[b], np.int64)[pos // page]
+        off = pos % page
+        seen = np.zeros((Nq, L), bool)
+        seen[:, :prefix] = True
         for n in range(Nq):
-            seen = np.zeros(L, bool)
-            seen[:prefix] = True
             a = n
             while a >= 0:
-                seen[prefix + a] = True
+                seen[n, prefix + a] = True
                 a = int(parents[b, a]) if parents is not None else a - 1
-            js = np.flatnonzero(seen)
-            for hq in range(Hq):
-                hk = hq // G
-                K = np.stack([kp[where[j][0], hk, where[j][1]] for j in js])
-                V = np.stack([vp[where[j][0], hk, where[j][1]] for j in js])
-                s = scale * (K @ q[b, n, hq])
-                p = np.exp(s - s.max())
-                p /= p.sum()
-                o = p @ V
-                out[b, n, hq] = o
-                g = dout[b, n, hq]
-                delta = float(g @ o)
-                dS = p * (V @ g - delta)
-                dq[b, n, hq] = scale * (dS @ K)
-                for t, j in enumerate(js):
-                    pg, off = where[j]
-                    dk[pg, hk, off] += scale * dS[t] * q[b, n, hq]
-                    dv[pg, hk, off] += p[t] * g
+        for hk in range(Hkv):
+            K = kp[pg, hk, off]                       # [L, D]: position j of this request
+            V = vp[pg, hk, off]
+            dK = np.zeros_like(K)
+            dV = np.zeros_like(V)
+            for n in range(Nq):
+                vis = seen[n]
+                for hq in range(hk * G, (hk + 1) * G):
+                    s = scale * (K @ q[b, n, hq])
+                    p = np.exp(np.where(vis, s - s[vis].max(), -np.inf))
+                    p /= p.sum()
+                    o = p @ V
+                    out[b, n, hq] = o
+                    g = dout[b, n, hq]
+                    delta = float(g @ o)
+                    dS = p * (V @ g - delta)
+                    dq[b, n, hq] = scale * (dS @ K)
+                    dK += scale * np.outer(dS, q[b, n, hq])
+                    dV += np.outer(p, g)
+            # a request's positions are distinct (page, offset) pairs: plain indexed accumulation
+            dk[pg, hk, off] += dK
+            dv[pg, hk, off] += dV
     return out, dq, dk, dv
 
 

@@ -161,3 +161,40 @@ def test_backward_from_saved_forward_is_bit_identical(gpu_lib):
         torch.cuda.synchronize()
         for x, y in zip(ref, (dq.cpu().numpy(), dk.cpu().numpy(), dvp.cpu().numpy())):
             assert np.array_equal(x, y)
+
+
+def _sampled_check(w, sample, seed):
+    """The whole batch runs on the GPU; the oracle differentiates the requests in `sample` one by one (pages are not
+    shared between requests, so their dK / dV rows depend on nothing else)."""
+    print(f"[case] full size {w.name} B={w.batch} Nq={w.num_q} L={int(w.seq_lens.min())}..{int(w.seq_lens.max())} "
+          f"sample={list(sample)}", flush=True)
+    rng = np.random.default_rng(seed)
+    g32 = rng.standard_normal(w.q.shape).astype(np.float32)
+    dout = (g32.view(np.uint32) >> 16).astype(np.uint16)
+    g = (dout.astype(np.uint32) << 16).view(np.float32)
+    dq, dk, dv = _run(w, dout)
+    kf, vf = gen.as_f32(w.k_pages, w.dtype), gen.as_f32(w.v_pages, w.dtype)
+    bt = w.host_block_table()
+    for b in sample:
+        ws = w.take_requests([b])
+        _, rq, rk, rv = oracle.attn_backward(gen.as_f32(ws.q, w.dtype), kf, vf, bt[b:b + 1], ws.seq_lens, ws.parents,
+                                             g[b:b + 1])
+        L = int(w.seq_lens[b])
+        pos = np.arange(L)
+        pg, off = bt[b][pos // w.page_size], pos % w.page_size
+        for name, got, ref in (("dq", dq[b], rq[0]), ("dk", dk[pg, :, off], rk[pg, :, off]),
+                               ("dv", dv[pg, :, off], rv[pg, :, off])):
+            assert np.isfinite(got).all(), (name, b)
+            err = np.abs(got - ref)
+            assert err.max() <= 2e-2 * np.abs(ref).max(), f"{name} request {b}: abs err {err.max()} vs max {np.abs(ref).max()}"
+            assert np.sqrt((err ** 2).mean()) <= 1e-2 * np.sqrt((ref ** 2).mean()), (name, b)
+
+
+@pytest.mark.timeout(300)
+def test_full_size_chain_and_tree_sampled(gpu_lib):
+    """The two shapes bench.py --stage attn_bwd times (config 2's chain batch, config 4's tree batch), whole batch on
+    the GPU, sampled requests against the oracle."""
+    w = gen.llama_chain(1, vocab=64, hidden_size=64)
+    order = np.argsort(w.seq_lens, kind="stable")
+    _sampled_check(w, [int(order[0]), int(order[len(order) // 2]), int(order[-1])], 12)
+    _sampled_check(gen.llama_tree(1, vocab=64, hidden_size=64), [0, 11], 13)
