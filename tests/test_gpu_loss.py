@@ -53,6 +53,13 @@ def test_loss_and_gradient_match_the_oracle(gpu_lib, rows, vd, k, dk):
     _check(z, ids, bits, traj, 0.5, dk or None)
 
 
+@pytest.mark.timeout(300)
+def test_full_size_loss_batch(gpu_lib):
+    """The batch bench.py --stage loss times: 4096 rows, draft vocabulary 32000, 1024 kept logits, filter 64; every
+    row against the oracle."""
+    _check(*gen.loss_inputs(1, 4096, 32000, top_k=1024), 0.5, 64)
+
+
 def test_classes_missing_and_single_rows(gpu_lib):
     z, ids, bits, traj = gen.loss_inputs(3, 6, 3000, top_k=128)
     for t in ([1] * 6, [2] * 6, [0] * 6, [1, 0, 0, 0, 0, 2]):
