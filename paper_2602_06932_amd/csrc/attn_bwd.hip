@@ -4,13 +4,14 @@
 //   p_ij = exp(scale <q_i, k_j> - lse_i),  delta_i = <dO_i, O_i>,  dP_ij = <dO_i, v_j>,  dS_ij = p_ij (dP_ij - delta_i)
 //   dq_i = scale sum_j dS_ij k_j      dk_j = scale sum_i dS_ij q_i      dv_j = sum_i p_ij dO_i
 //
-// The forward pass is run first (the library's own kernels; its merge kernel also writes lse).  Then one
+// The forward pass comes first (the library's own kernels; its merge kernel also writes lse), or its saved
+// output and lse are handed in.  Then one
 // workgroup per (request, KV head) pair walks the pair's KV positions in blocks of 64 with fp32 vector
 // arithmetic: in the token-major half a thread owns a quarter of one token's K and V row, forms the scores and
 // dP against the group's query rows (kept in LDS, 32 at a time), and accumulates its share of dk_j and dv_j over
 // the rows; dS goes to LDS, and in the row-major half a thread owns 16 columns of one query row and adds the
 // block's dS_ij k_j to dq_i.  Every K / V element is read once per 32 query rows; all sums run in a fixed order.
-// This is the plain first version of the kernel: vector fp32, no matrix cores.
+// This is the kernel for the shapes the matrix-core kernels (attn_bwd_mfma.hip) do not take: vector fp32 arithmetic.
 #include "launch.hpp"
 
 namespace aurora {

@@ -345,15 +345,12 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
 
 // ---- 65 .. 128 query rows per KV head: one row tile per wavefront, K / V tiles shared by the workgroup -----------
 // Four dq accumulator sets per wavefront do not fit the register file next to the dK / dV accumulators, so the
-// work of a tile is cut the other way: the workgroup walks the tiles of its run together (K / V tile loaded once,
-// double-buffered, each wavefront issuing a quarter of the loads); wavefront w forms S^T, dP^T, P, dS and dQ for
-// row tile w, and publishes its transposed P and dS tiles; after a barrier it contracts over ALL row tiles for
-// column block w of dV and dK (16 accumulator registers each) and stores those columns.  The K / V loads of the
-// next tile are requested before this tile's products, and this tile's stores are still in flight when the next
-// tile starts: the wait at its top only covers the loads, which are older than the 32 stores.
+// work of a tile is cut the other way.  The workgroup walks the tiles of its run together (a K / V tile pair is
+// loaded once for everybody); wavefront w of a group of four forms S^T, dP^T, P, dS and dQ for row tile w and
+// publishes its transposed P and dS tiles; after a barrier it contracts over ALL row tiles for column block w of
+// dV and dK (16 accumulator registers each) and stores those columns.
 constexpr int kBsKvBytes = 2 * kAtTileBytes;   // K tile, then V tile
 constexpr int kBsXtBytes = 2 * kBmXtBytes;     // transposed P, then dS, of one wavefront
-constexpr int kBsLdsBytes = 8 * kAtTileBytes + 2 * kBsKvBytes + 2 * 4 * kBsXtBytes;
 
 // block db of tile_tmm<true>: acc += B^T A[:, 32 db .. 32 db + 31]
 __device__ __forceinline__ void tile_tmm_block(const char* abuf, const bf16x8_t b[2], f32x16_t& acc, int lane, int db) {
@@ -375,7 +372,20 @@ __device__ __forceinline__ void tile_tmm_block(const char* abuf, const bf16x8_t 
   }
 }
 
-__global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_shared_kernel(
+// Eight wavefronts: two groups of four, half a tile apart.  Group g = wavefront / 4 takes the tiles of the run
+// with parity g.  The workgroup advances in steps separated by one barrier: in step s group s % 2 does the first half of tile s (S^T, dP^T, P, dS, dQ for row tile w, transposed
+// tiles published to the group's own buffer) while the other group does the second half of tile s - 1 (column
+// block w of dV and dK over all row tiles, stores).  Each SIMD thus holds one wavefront that mostly multiplies
+// and one that mostly moves data, and there is one barrier per tile instead of two.  K / V tile pairs rotate
+// through three buffers: tile s + 2 is requested at the top of step s (every wavefront issues one row group of K
+// and one of V), into the buffer that tile s - 1 left at the end of step s - 1.  The requests are issued for
+// clamped tile numbers up to the last step, so that every wavefront's queue of outstanding memory operations looks
+// the same at every step top: [loads of tile s] [2 loads, 32 stores in either order] - hence vmcnt(34), and
+// vmcnt(2) in the first three steps, where the stores are not there yet.
+constexpr int kB8Threads = 512;
+constexpr int kB8LdsBytes = 8 * kAtTileBytes + 3 * kBsKvBytes + 2 * 4 * kBsXtBytes;
+
+__global__ __launch_bounds__(kB8Threads, 1) void attn_bwd_mfma_shared_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ parents,
     const bf16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
@@ -384,13 +394,13 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_shared_kernel(
   extern __shared__ __attribute__((aligned(1024))) char bm_lds[];
   char* qV = bm_lds;                        // four row tiles of the pair's query rows (V-tile layout)
   char* doV = bm_lds + 4 * kAtTileBytes;    // their upstream gradients
-  char* kv = bm_lds + 8 * kAtTileBytes;     // two K / V tile pairs
-  char* xt = kv + 2 * kBsKvBytes;           // two sets of four transposed (P, dS) tiles
+  char* kv = bm_lds + 8 * kAtTileBytes;     // three K / V tile pairs
+  char* xt = kv + 3 * kBsKvBytes;           // per group: four transposed (P, dS) tiles
   __shared__ int s_pb[kLocalPlanMax + 1];
-  __shared__ int s_wsum[4];
+  __shared__ int s_wsum[8];
   build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
   if (blockIdx.x == 0)
-    for (int i = threadIdx.x; i <= B; i += kBmThreads) PB[i] = s_pb[i];
+    for (int i = threadIdx.x; i <= B; i += kB8Threads) PB[i] = s_pb[i];
 
   const int U = s_pb[B];
   const int c = units_per_wg(U, gridDim.x);
@@ -400,10 +410,12 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_shared_kernel(
 
   const int G = Hq / Hkv, R = G * Nq;
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wv8 = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wv8 >> 2, wv = wv8 & 3;  // group; row tile and column block within the group
   const int li = lane & 31, lh = lane >> 5;
   const float scale_log2 = scale * kLog2e;
   const int mask = (1 << page_shift) - 1;
+  char* xts = xt + grp * 4 * kBsXtBytes;
 
   int b = 0;
   {
@@ -429,16 +441,16 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_shared_kernel(
     const int prefix = L - Nq;
     const int ntile = t1 - t0;
     const int32_t* bt = block_table + (size_t)b * max_pages;
-    // the pair's query rows and upstream gradients: 8 threads per row, 32 bytes each, 32 rows per turn
+    // the pair's query rows and upstream gradients: 8 threads per row, 32 bytes each, 64 rows per turn
 #pragma unroll
-    for (int rt = 0; rt < 4; ++rt) {
-      const int m = 32 * rt + (tid >> 3);
+    for (int turn = 0; turn < 2; ++turn) {
+      const int m = 64 * turn + (tid >> 3);
       const bool ok = m < R;
       const int n = ok ? m / G : 0, g = ok ? m % G : 0;
       const size_t at = (((size_t)b * Nq + n) * Hq + hk * G + g) * kAtD;
       const u32x4_t* qp = (const u32x4_t*)(q + at);
       const u32x4_t* gp = (const u32x4_t*)(dout + at);
-      const int c0 = (tid & 7) * 2, row = tid >> 3;
+      const int c0 = (tid & 7) * 2, row = m & 31, rt = m >> 5;
       const u32x4_t z = {0u, 0u, 0u, 0u};
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
@@ -447,7 +459,7 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_shared_kernel(
         *(u32x4_t*)(doV + rt * kAtTileBytes + row * kAtRowBytes + cv) = ok ? gp[c0 + i] : z;
       }
     }
-    // this lane's query row (row tile = wavefront): logsumexp in log2 units, delta, visible tree nodes
+    // this lane's query row (row tile = wavefront within the group)
     const int m_row = 32 * wv + li;
     float lse2 = INFINITY, dlt = 0.f;
     unsigned long long anc = 0;
@@ -463,20 +475,15 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_shared_kernel(
       }
     }
 
-    auto tile_pages = [&](int tt, int& pid_a, int& pid_b) {
-      const int j0 = start + tt * kAtTile;
-      pid_a = bt[j0 >> page_shift];
-      pid_b = bt[min(j0 + 16, L - 1) >> page_shift];
-    };
-    // this wavefront's quarter of a tile pair's loads: two instructions (eight token rows) of K, two of V
-    auto issue_quarter = [&](int tt, int pid_a, int pid_b) {
-      const int j0 = start + tt * kAtTile;
-      char* kb = kv + (tt & 1) * kBsKvBytes;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        issue_rows<true>(kp, kb, 2 * wv + i, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
-        issue_rows<true>(vp, kb + kAtTileBytes, 2 * wv + i, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
-      }
+    // this wavefront's eighth of a tile pair's loads: one row group (four token rows) of K and one of V
+    auto issue_eighth = [&](int tt) {
+      const int tl = min(tt, ntile - 1);
+      const int j0 = start + tl * kAtTile;
+      const int pid_a = bt[j0 >> page_shift];
+      const int pid_b = bt[min(j0 + 16, L - 1) >> page_shift];
+      char* kb = kv + (tt % 3) * kBsKvBytes;
+      issue_rows<true>(kp, kb, wv8, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
+      issue_rows<true>(vp, kb + kAtTileBytes, wv8, j0, L, page_shift, Hkv, hk, pid_a, pid_b, lane);
     };
 
     f32x16_t dq_acc[4];
@@ -486,38 +493,33 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_shared_kernel(
       for (int r = 0; r < 16; ++r) dq_acc[db][r] = 0.f;
 
     __syncthreads();  // query rows staged; the previous run is done with every buffer
-    int pa, pb;
-    tile_pages(0, pa, pb);
-    issue_quarter(0, pa, pb);
-    for (int tt = 0; tt < ntile; ++tt) {
-      const bool more = tt + 1 < ntile;
-      int npa = 0, npb = 0;
-      if (more) tile_pages(tt + 1, npa, npb);
-      // this tile's loads have landed; from the second tile on they are older than the previous tile's 32 stores
-      // (a tile that is followed by another one is never ragged, so all of its stores were issued)
-      if (tt == 0) WAIT_VMCNT(0); else WAIT_VMCNT(32);
-      __builtin_amdgcn_s_barrier();  // ... from all four wavefronts; everyone is also done with the tile before
+    issue_eighth(0);
+    issue_eighth(1);
+    for (int s = 0; s <= ntile; ++s) {
+      if (s <= 2) WAIT_VMCNT(2); else WAIT_VMCNT(34);            // tile s has landed (this wavefront's part)
+      __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);      // lgkmcnt(0): LDS reads and writes of the last step
+      __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      if (more) issue_quarter(tt + 1, npa, npb);  // into the pair the tile before last used
-      const char* kb = kv + (tt & 1) * kBsKvBytes;
-      const char* vb = kb + kAtTileBytes;
-      char* xts = xt + (tt & 1) * 4 * kBsXtBytes;
-      const int j0 = start + tt * kAtTile;
-      {
-        const f32x16_t s_acc = tile_scores_v(kb, qV + wv * kAtTileBytes, li, lh);
-        const f32x16_t dp_acc = tile_scores_v(vb, doV + wv * kAtTileBytes, li, lh);
-        float p[16], ds[16];
-        tile_p_ds(s_acc, dp_acc, p, ds, scale_log2, lse2, dlt, anc, j0, prefix, L, lh);
-        bf16x8_t p_b[2], ds_b[2];
-        pack_and_transpose(p, p_b, xts + wv * kBsXtBytes, li, lh);
-        pack_and_transpose(ds, ds_b, xts + wv * kBsXtBytes + kBmXtBytes, li, lh);
-        tile_tmm(kb, ds_b, dq_acc, lane);  // dQ^T += K^T dS^T for this wavefront's row tile
-      }
-      __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0): the transposed tiles are written
-      __builtin_amdgcn_s_barrier();                            // ... by all four wavefronts
-      asm volatile("" ::: "memory");
-      {
-        // columns 32 wv .. 32 wv + 31 of dV = P^T dO and dK = dS^T Q, contraction over all four row tiles
+      issue_eighth(s + 2);  // into the buffer tile s - 1 used
+      if ((s & 1) == grp) {
+        if (s < ntile) {
+          const char* kb = kv + (s % 3) * kBsKvBytes;
+          const char* vb = kb + kAtTileBytes;
+          const int j0 = start + s * kAtTile;
+          const f32x16_t s_acc = tile_scores_v(kb, qV + wv * kAtTileBytes, li, lh);
+          const f32x16_t dp_acc = tile_scores_v(vb, doV + wv * kAtTileBytes, li, lh);
+          float p[16], ds[16];
+          tile_p_ds(s_acc, dp_acc, p, ds, scale_log2, lse2, dlt, anc, j0, prefix, L, lh);
+          bf16x8_t p_b[2], ds_b[2];
+          pack_and_transpose(p, p_b, xts + wv * kBsXtBytes, li, lh);
+          pack_and_transpose(ds, ds_b, xts + wv * kBsXtBytes + kBmXtBytes, li, lh);
+          tile_tmm(kb, ds_b, dq_acc, lane);  // dQ^T += K^T dS^T for this wavefront's row tile
+        }
+      } else if (s >= 1) {
+        // columns 32 wv .. 32 wv + 31 of dV = P^T dO and dK = dS^T Q of tile s - 1, contraction over all four row tiles
+        const int j0 = start + (s - 1) * kAtTile;
+        const int pa = bt[j0 >> page_shift];
+        const int pb = bt[min(j0 + 16, L - 1) >> page_shift];
         f32x16_t dv_acc, dk_acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dv_acc[r] = 0.f; dk_acc[r] = 0.f; }
@@ -540,21 +542,31 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_shared_kernel(
           }
         }
       }
-      pa = npa;
-      pb = npb;
     }
-    // the run's partial dq of this wavefront's row tile
-    if (m_row < R) {
+    // ---- the two groups' dq of a row tile are summed through LDS; group 0 writes the run's partial -----------
+    WAIT_VMCNT(0);  // the clamped requests of the last steps have landed: the tile buffers can be reused
+    __syncthreads();
+    float* park = (float*)kv + wv * (64 * 64);  // 16 KB per row tile, inside the K / V and transposed-tile buffers
+    if (grp == 1) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) park[(db * 16 + r) * 64 + lane] = dq_acc[db][r];
+    }
+    __syncthreads();
+    if (grp == 0 && m_row < R) {
       const size_t prow = (size_t)slot * 128 + m_row;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          f32x4_t o = {dq_acc[db][4 * g], dq_acc[db][4 * g + 1], dq_acc[db][4 * g + 2], dq_acc[db][4 * g + 3]};
+          f32x4_t o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = dq_acc[db][4 * g + e] + park[(db * 16 + 4 * g + e) * 64 + lane];
           *(f32x4_t*)(part_dq + prow * kAtD + 32 * db + 8 * g + 4 * lh) = o;
         }
     }
-    __syncthreads();  // slower wavefronts still read the query tiles, which the next run overwrites
+    __syncthreads();  // the query tiles and the parked sums are overwritten by the next run
   }
 }
 
@@ -611,8 +623,8 @@ static hipError_t launch_bwd_mfma_t(const AttnBwdLaunch& a, hipStream_t st) {
 
 static hipError_t launch_bwd_mfma_shared(const AttnBwdLaunch& a, hipStream_t st) {
   static LdsAttrOnce attr;
-  if (hipError_t e = attr.ensure((const void*)attn_bwd_mfma_shared_kernel, kBsLdsBytes); e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_mfma_shared_kernel, dim3(attn_bwd_mfma_workgroups()), dim3(kBmThreads), kBsLdsBytes, st,
+  if (hipError_t e = attr.ensure((const void*)attn_bwd_mfma_shared_kernel, kB8LdsBytes); e != hipSuccess) return e;
+  hipLaunchKernelGGL(attn_bwd_mfma_shared_kernel, dim3(attn_bwd_mfma_workgroups()), dim3(kB8Threads), kB8LdsBytes, st,
                      (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
                      (const bf16_t*)a.dout, a.lse, a.delta, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv,
                      __builtin_ctz(a.page), a.max_pages, a.scale);
