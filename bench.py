@@ -39,6 +39,8 @@ def make_workload(name, seed):
         return gen.llama_chain(seed, kv_fp8=True, head_fp8=True)
     if name == "llama_draft32k":
         return gen.llama_chain(seed, draft_vocab=32000, draft_noise=0.5)
+    if name == "llama_k10":
+        return gen.llama_chain(seed, num_q=11)   # lookahead 10 (paper section 5, the discard-token experiment)
     if name == "tiny":
         return gen.tiny_chain(seed)
     if name == "qwen_greedy":
@@ -71,7 +73,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_fp8kv", "llama_fp8", "llama_draft32k", "tiny", "qwen_greedy", "tree", "tree_fp8kv", "stress"])
+    ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_fp8kv", "llama_fp8", "llama_draft32k", "llama_k10", "tiny", "qwen_greedy", "tree", "tree_fp8kv", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
     ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy", "loss", "attn_bwd"],

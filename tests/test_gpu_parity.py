@@ -230,6 +230,13 @@ def test_full_size_stress_sparse_pool(gpu_lib):
     _, a = _full_check(gpu_lib, w, sample=_spread_sample(w, 4))
 
 
+def test_lookahead_10_chain(gpu_lib):
+    """Eleven query positions per request (lookahead 10, the paper's discard-token experiment of section 5) with the
+    headline configuration's heads: 44 query rows per KV head; sampling and greedy."""
+    _full_check(gpu_lib, gen.llama_chain(61, batch=6, num_q=11, len_lo=60, len_hi=900, vocab=3000, hidden_size=256))
+    _full_check(gpu_lib, gen.qwen_greedy_chain(62, batch=4, num_q=11, len_lo=60, len_hi=500, vocab=3000, hidden_size=256))
+
+
 def test_many_short_requests(gpu_lib):
     """More requests than the attention kernel plans for in shared memory (separate planning kernel),
     many (request, head) pairs per workgroup, every sequence shorter than one tile run."""
