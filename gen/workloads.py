@@ -201,6 +201,8 @@ class Workload:
     v_scale: Optional[np.ndarray] = None
     # one temperature per request (float32 [B]; 0 = that request is verified greedily), or None: `temperature`
     temperatures: Optional[np.ndarray] = None
+    # tree drafts whose siblings were drawn one after the other without replacement
+    tree_without_replacement: bool = False
 
     def target_to_draft(self) -> Optional[np.ndarray]:
         """Inverse of draft_to_target over the target vocabulary, -1 where the draft model has no entry."""
@@ -331,7 +333,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
                   tree: bool = False, greedy_hit: float = 0.7,
                   shuffle_pages: bool = True, pool_pages: Optional[int] = None,
                   distinct_siblings: bool = False, draft_vocab: Optional[int] = None,
-                  head_fp8: bool = False, kv_fp8: bool = False, temperatures=None, recipe: str = "") -> Workload:
+                  head_fp8: bool = False, kv_fp8: bool = False, temperatures=None,
+                  siblings_without_replacement: bool = False, recipe: str = "") -> Workload:
     """Build one workload.
 
     draft = "independent": draft logits ~ N(0,1), draft tokens uniform over the vocab.
@@ -341,6 +344,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
             probability `greedy_hit`, else uniform; draft_probs/uniforms are None.
     draft_vocab (with "noisy_target"): the draft model's vocabulary is a random subset of that many
             target ids; draft_probs is over the subset, tokens are drawn from it and stored as target ids.
+    siblings_without_replacement (trees with "noisy_target"): the children of a node are drawn one after the
+            other, each from the parent's row with the earlier siblings' tokens removed and renormalised.
     head_fp8: hidden and lm_head are drawn as float32 with the same recipe, then stored as E4M3 codes
             with one scale per row; the stand-in target logits use the values the codes stand for.
     kv_fp8: the K/V pools are stored as E4M3 codes with one scale per KV head (see make_kv).
@@ -403,9 +408,19 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
         noise = rng.standard_normal(t.shape, dtype=np.float32) * np.float32(draft_noise)
         draft_probs = _softmax_rows_f32((t + noise) / T).reshape(B, Nq, t.shape[1])
         del t, noise
+        drawn = np.full((B, Nq), -1, dtype=np.int64)   # index within the draft vocabulary of node n's token
         for n in range(1, Nq):
             rows = draft_probs[np.arange(B), par[:, n]]
+            if siblings_without_replacement:
+                # the drafter draws the children of a node one after the other, each from q with the earlier
+                # siblings' tokens removed and the rest renormalised
+                rows = rows.copy()
+                for m in range(1, n):
+                    same = np.flatnonzero(par[:, m] == par[:, n])
+                    rows[same, drawn[same, m]] = 0.0
+                rows /= rows.sum(axis=1, keepdims=True, dtype=np.float64).astype(np.float32)
             idx = _draw_from_rows(rng, rows)
+            drawn[:, n] = idx
             draft_tokens[:, n] = d2t[idx] if draft_vocab else idx
         uniforms = _uniform24(rng, (B, Nq, 2))
     elif draft == "greedy_mix":
@@ -435,7 +450,8 @@ def make_workload(*, name: str, seed: int, dtype: str, batch: int, num_q: int,
                  draft_vocab=int(draft_vocab or 0), draft_to_target=d2t,
                  head_dtype="fp8" if head_fp8 else "", hidden_scale=hidden_scale, lm_head_scale=lm_head_scale,
                  kv_dtype="fp8" if kv_fp8 else "", k_scale=k_scale, v_scale=v_scale,
-                 temperatures=None if temperatures is None else np.asarray(temperatures, dtype=np.float32))
+                 temperatures=None if temperatures is None else np.asarray(temperatures, dtype=np.float32),
+                 tree_without_replacement=bool(siblings_without_replacement and tree))
     return w
 
 

@@ -23,7 +23,7 @@ def lib():
     global _lib
     if _lib is None:
         _lib = C.CDLL(_build.build(force=False))
-        for name in ("oracle_attn", "oracle_logits", "oracle_accept_logits", "oracle_accept",
+        for name in ("oracle_attn", "oracle_logits", "oracle_accept_logits", "oracle_accept", "oracle_accept_logits_ex",
                      "oracle_num_threads", "oracle_trace_topk", "oracle_trace_records", "oracle_logits_fp8",
                      "oracle_decode_e4m3", "oracle_attn_fp8kv"):
             getattr(_lib, name).restype = C.c_int
@@ -166,7 +166,9 @@ def _dense_draft_probs(draft_probs, draft_to_target, V):
 
 
 def accept_from_logits(*, logits, draft_tokens, draft_probs=None, uniforms=None, parents=None,
-                       temperature, want_cdf=False, draft_to_target=None) -> AcceptResult:
+                       temperature, want_cdf=False, draft_to_target=None, without_replacement=False) -> AcceptResult:
+    """Acceptance on given float64 logits [B, Nq, V].  without_replacement: the children of a tree node were drawn
+    one after the other without replacement (see oracle_accept_logits_ex in aurora_oracle.c)."""
     lg = _chk(logits, np.float64)
     B, Nq, V = lg.shape
     draft_probs = _dense_draft_probs(draft_probs, draft_to_target, V)
@@ -175,11 +177,12 @@ def accept_from_logits(*, logits, draft_tokens, draft_probs=None, uniforms=None,
     uniforms = _chk(uniforms, np.float32, (B, Nq, 2))
     parents = _chk(parents, np.int32, (B, Nq))
     r = _alloc_results(B, Nq, V, want_cdf and temperature > 0)
-    st = lib().oracle_accept_logits(
+    st = lib().oracle_accept_logits_ex(
         C.c_int(B), C.c_int(Nq), C.c_int(V), C.c_double(float(np.float32(temperature))), _p(lg),
         _p(draft_tokens), _p(draft_probs), _p(uniforms), _p(parents), _p(r["accept_len"]),
         _p(r["next_token"]), _p(r["accept_mask"]), _p(r["p_at_draft"]), _p(r["row_lse"]),
-        _p(r["test_margin"]), _p(r["top_gap"]), _p(r["stop_node"]), _p(r["final_cdf"]))
+        _p(r["test_margin"]), _p(r["top_gap"]), _p(r["stop_node"]), _p(r["final_cdf"]),
+        C.c_int(1 if without_replacement else 0))
     if st != 0:
         raise ValueError(f"oracle_accept_logits status {st}")
     return AcceptResult(logits=None, **r)
@@ -251,12 +254,16 @@ def accept_workload(w, want_cdf=False, want_logits=False) -> AcceptResult:
                 return None
             return np.concatenate(vals, axis=0)
         return AcceptResult(**{f.name: cat(f.name) for f in dataclasses.fields(AcceptResult)})
-    if getattr(w, "head_dtype", "") == "fp8":
-        lg = logits_fp8(hidden=w.hidden, hidden_scale=w.hidden_scale, lm_head=w.lm_head,
-                        lm_head_scale=w.lm_head_scale)
+    wor = bool(getattr(w, "tree_without_replacement", False))
+    if getattr(w, "head_dtype", "") == "fp8" or wor:
+        if getattr(w, "head_dtype", "") == "fp8":
+            lg = logits_fp8(hidden=w.hidden, hidden_scale=w.hidden_scale, lm_head=w.lm_head,
+                            lm_head_scale=w.lm_head_scale)
+        else:
+            lg = logits(hidden=w.hidden, lm_head=w.lm_head, dtype=w.dtype)
         a = accept_from_logits(logits=lg, draft_tokens=w.draft_tokens, draft_probs=w.draft_probs,
                                uniforms=w.uniforms, parents=w.parents, temperature=w.temperature, want_cdf=want_cdf,
-                               draft_to_target=getattr(w, "draft_to_target", None))
+                               draft_to_target=getattr(w, "draft_to_target", None), without_replacement=wor)
         if want_logits:
             a.logits = lg
         return a

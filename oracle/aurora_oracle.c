@@ -428,6 +428,11 @@ static int accept_chain(int num_q, int vocab, double T, const double *lg, const 
  *       accepted: mark c, cur = c, p = p_c, continue with c's children
  *       rejected: p <- max(0, p - q_cur) / sum max(0, p - q_cur)   (q_cur unchanged:
  *                 siblings are independent draws from q_cur); if that sum is 0, p is kept
+ *   siblings_without_replacement != 0 (oracle_accept_logits_ex): the children of a node were drawn one after
+ *   the other, each from q_cur with the tokens of the earlier siblings removed.  Then the test and the residual
+ *   of a child use q' = that distribution, q'(v) = 0 for v in X, else q_cur(v) / (1 - sum_{x in X} q_cur(x)),
+ *   X = the set of tokens rejected at this node so far (the row q_cur is taken to sum to 1; a remaining mass
+ *   <= 0 makes q' identically 0).
  *   no child left: next_token ~ p by inverse CDF with uniforms[b, cur, 1].
  * T == 0: accept c iff tok_c == argmax_cur; next_token = argmax_cur.
  *
@@ -446,12 +451,13 @@ static int accept_chain(int num_q, int vocab, double T, const double *lg, const 
  *   final_cdf  [B, V]   normalised running sums of the distribution next_token was drawn from
  *                       (T == 0: not written)
  * ---------------------------------------------------------------------- */
-int oracle_accept_logits(int batch, int num_q, int vocab, double temperature,
-                         const double *logits, const int32_t *draft_tokens,
-                         const float *draft_probs, const float *uniforms, const int32_t *parents,
-                         int32_t *accept_len, int32_t *next_token, uint8_t *accept_mask,
-                         double *p_at_draft, double *row_lse,
-                         double *test_margin, double *top_gap, int32_t *stop_node, double *final_cdf)
+int oracle_accept_logits_ex(int batch, int num_q, int vocab, double temperature,
+                            const double *logits, const int32_t *draft_tokens,
+                            const float *draft_probs, const float *uniforms, const int32_t *parents,
+                            int32_t *accept_len, int32_t *next_token, uint8_t *accept_mask,
+                            double *p_at_draft, double *row_lse,
+                            double *test_margin, double *top_gap, int32_t *stop_node, double *final_cdf,
+                            int siblings_without_replacement)
 {
     if (batch < 0 || num_q < 1 || vocab < 1 || temperature < 0.0) return ORACLE_BAD_ARG;
     const int greedy = temperature == 0.0;
@@ -541,13 +547,27 @@ int oracle_accept_logits(int batch, int num_q, int vocab, double temperature,
             }
         } else {
             row_softmax(lg + (int64_t)cur * vocab, vocab, temperature, p);
+            /* removed[v] != 0: token v was rejected at the current node (only used without replacement) */
+            unsigned char *removed = siblings_without_replacement ? (unsigned char *)calloc((size_t)vocab, 1) : NULL;
+            if (siblings_without_replacement && !removed) {
+#pragma omp atomic write
+                status = ORACLE_NOMEM;
+                free(p);
+                free(r);
+                continue;
+            }
             for (;;) {
                 const float *qrow = draft_probs + (b * (int64_t)num_q + cur) * vocab;
+                double removed_mass = 0.0; /* sum of q_cur over the removed tokens */
+                if (removed) memset(removed, 0, (size_t)vocab);
                 int moved = 0;
                 for (int c = cur + 1; c < num_q && !moved; ++c) {
                     if (parent_of(parents, b, num_q, c) != cur) continue;
                     const double u = (double)uniforms[(b * (int64_t)num_q + c) * 2 + 0];
-                    const double qc = (double)qrow[tok[c]];
+                    /* the distribution this sibling was drawn from: q_cur, or q_cur without the removed tokens */
+                    const double left = 1.0 - removed_mass;
+                    const double qscale = !removed ? 1.0 : (left > 0.0 ? 1.0 / left : 0.0);
+                    const double qc = removed && removed[tok[c]] ? 0.0 : (double)qrow[tok[c]] * qscale;
                     const double pc = p[tok[c]];
                     if (test_margin)
                         test_margin[b * num_q + c] = qc > 0.0 ? fabs(pc / qc - u) : INFINITY;
@@ -560,16 +580,22 @@ int oracle_accept_logits(int batch, int num_q, int vocab, double temperature,
                     } else {
                         double Z = 0.0;
                         for (int v = 0; v < vocab; ++v) {
-                            const double d = p[v] - (double)qrow[v];
+                            const double qv = removed && removed[v] ? 0.0 : (double)qrow[v] * qscale;
+                            const double d = p[v] - qv;
                             r[v] = d > 0.0 ? d : 0.0;
                             Z += r[v];
                         }
                         if (Z > 0.0)
                             for (int v = 0; v < vocab; ++v) p[v] = r[v] / Z;
+                        if (removed && !removed[tok[c]]) {
+                            removed[tok[c]] = 1;
+                            removed_mass += (double)qrow[tok[c]];
+                        }
                     }
                 }
                 if (!moved) break;
             }
+            free(removed);
             const double us = (double)uniforms[(b * (int64_t)num_q + cur) * 2 + 1];
             const int t = draw_inverse_cdf(p, vocab, us, final_cdf ? final_cdf + b * (int64_t)vocab : NULL);
             if (next_token) next_token[b] = t;
@@ -580,6 +606,18 @@ int oracle_accept_logits(int batch, int num_q, int vocab, double temperature,
         free(r);
     }
     return status;
+}
+
+int oracle_accept_logits(int batch, int num_q, int vocab, double temperature,
+                         const double *logits, const int32_t *draft_tokens,
+                         const float *draft_probs, const float *uniforms, const int32_t *parents,
+                         int32_t *accept_len, int32_t *next_token, uint8_t *accept_mask,
+                         double *p_at_draft, double *row_lse,
+                         double *test_margin, double *top_gap, int32_t *stop_node, double *final_cdf)
+{
+    return oracle_accept_logits_ex(batch, num_q, vocab, temperature, logits, draft_tokens, draft_probs, uniforms,
+                                   parents, accept_len, next_token, accept_mask, p_at_draft, row_lse, test_margin,
+                                   top_gap, stop_node, final_cdf, 0);
 }
 
 /* LM head, then acceptance.  logits_out (optional) receives double [B*Nq, V]. */

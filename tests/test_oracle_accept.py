@@ -314,6 +314,98 @@ def test_monte_carlo_tree_emits_target_distribution():
     assert (r.accept_len == 0).mean() < first_only
 
 
+# ------------------------------------------------------------------ siblings drawn without replacement
+def _draw_siblings_without_replacement(rng, q, par, B):
+    """Tokens [B, Nq]: the children of a node are drawn in node order, each from the parent's row with the earlier
+    siblings' tokens removed and the rest renormalised (inverse-CDF draws, written here independently)."""
+    Nq, V = q.shape
+    toks = np.zeros((B, Nq), np.int32)
+    for n in range(1, Nq):
+        rows = np.broadcast_to(q[par[n]].astype(np.float64), (B, V)).copy()
+        for m in range(1, n):
+            if par[m] == par[n]:
+                rows[np.arange(B), toks[:, m]] = 0.0
+        rows /= rows.sum(1, keepdims=True)
+        cdf = np.cumsum(rows, axis=1)
+        u = rng.random(B)
+        toks[:, n] = np.minimum((cdf <= u[:, None]).sum(1), V - 1)
+    return toks
+
+
+def test_monte_carlo_tree_without_replacement_emits_target_distribution():
+    """Three distinct candidates per node: the emitted token is distributed as the target's p at every node reached
+    often enough - and it is NOT when the with-replacement rule is applied to the same drafts (the check has teeth)."""
+    rng = np.random.default_rng(14)
+    B, V = 250_000, 16
+    par = np.array([-1, 0, 0, 0, 1, 1, 2, 4, 3], np.int32)
+    Nq = len(par)
+    lrow = rng.standard_normal((Nq, V)) * 1.5
+    p = _softmax64(lrow)
+    q = _softmax64(lrow + rng.standard_normal((Nq, V)) * 1.2).astype(np.float32)
+    toks = _draw_siblings_without_replacement(rng, q, par, B)
+    for a, b in ((1, 2), (1, 3), (2, 3), (4, 5)):
+        assert (toks[:, a] != toks[:, b]).all()
+    un = gen.workloads._uniform24(rng, (B, Nq, 2))
+    kw = dict(logits=np.broadcast_to(lrow, (B, Nq, V)).copy(), draft_tokens=toks,
+              draft_probs=np.broadcast_to(q, (B, Nq, V)).copy(), uniforms=un,
+              parents=np.broadcast_to(par, (B, Nq)).copy(), temperature=1.0)
+
+    def root_freq(r):
+        mask = r.accept_mask.astype(bool)
+        emitted = r.next_token.copy()
+        for m in (1, 2, 3):
+            emitted[mask[:, m]] = toks[mask[:, m], m]
+        return np.bincount(emitted, minlength=V) / B
+
+    r = oracle.accept_from_logits(without_replacement=True, **kw)
+    mask = r.accept_mask.astype(bool)
+    for c in range(Nq):
+        sel = mask[:, c]
+        n = int(sel.sum())
+        if n < 2000:
+            continue
+        emitted = r.next_token[sel].copy()
+        for m in [m for m in range(Nq) if par[m] == c]:
+            took = mask[sel, m]
+            emitted[took] = toks[sel, m][took]
+        assert _within(np.bincount(emitted, minlength=V) / n, p[c], n), (c, n)
+    assert _within(root_freq(r), p[0], B)
+    assert not _within(root_freq(oracle.accept_from_logits(**kw)), p[0], B)
+
+
+def test_without_replacement_hand_worked_step():
+    """Vocabulary {0, 1, 2}, p = (0.5, 0.3, 0.2), q = (0.2, 0.5, 0.3), two candidates 1 then 2 under the root.
+    Candidate 1: p/q = 0.6, rejected by u = 0.7.  Residual max(p - q, 0) = (0.3, 0, 0) -> p' = (1, 0, 0).
+    Without replacement the second candidate was drawn from q' = (0.2, 0, 0.3) / 0.5 = (0.4, 0, 0.6):
+    p'(2) / q'(2) = 0 -> rejected for any u, and the next token is drawn from max(p' - q', 0) = (0.6, 0, 0) -> token 0.
+    A candidate 0 in second place: p'(0) / q'(0) = 1 / 0.4 > 1 -> accepted for every u < 1 (with replacement the
+    ratio 1 / 0.2 gives the same decision; the two rules differ in q', checked through test_margin = |p'/q' - u|)."""
+    lg = np.log(np.array([0.5, 0.3, 0.2]))[None, None, :].repeat(3, axis=1)
+    q = np.array([0.2, 0.5, 0.3], np.float32)[None, None, :].repeat(3, axis=1)
+    par = np.array([[-1, 0, 0]], np.int32)
+    un = np.array([[[0, 0.3], [0.7, 0.5], [0.9, 0.5]]], np.float32)
+    r = oracle.accept_from_logits(logits=lg, draft_tokens=np.array([[0, 1, 2]], np.int32), draft_probs=q, uniforms=un,
+                                  parents=par, temperature=1.0, without_replacement=True)
+    assert r.accept_len[0] == 0 and r.next_token[0] == 0 and not r.accept_mask[0, 1:].any()
+    assert abs(r.test_margin[0, 1] - abs(0.6 - np.float32(0.7))) < 1e-6 and abs(r.test_margin[0, 2] - np.float32(0.9)) < 1e-6
+    for wor, ratio in ((True, 1 / 0.4), (False, 1 / 0.2)):
+        r = oracle.accept_from_logits(logits=lg, draft_tokens=np.array([[0, 1, 0]], np.int32), draft_probs=q, uniforms=un,
+                                      parents=par, temperature=1.0, without_replacement=wor)
+        assert r.accept_len[0] == 1 and r.accept_mask[0, 2] == 1 and r.stop_node[0] == 2
+        assert abs(r.test_margin[0, 2] - (ratio - np.float32(0.9))) < 1e-5
+
+
+def test_without_replacement_changes_nothing_on_chains_and_single_children():
+    w = gen.llama_chain(71, batch=6, len_lo=8, len_hi=20, vocab=64, hidden_size=32, num_q_heads=2, num_kv_heads=1,
+                        head_dim=8, page_size=4, dtype=gen.F32)
+    lg = oracle.logits(hidden=w.hidden, lm_head=w.lm_head, dtype=w.dtype)
+    kw = dict(logits=lg, draft_tokens=w.draft_tokens, draft_probs=w.draft_probs, uniforms=w.uniforms,
+              parents=gen.chain_parents(w.batch, w.num_q), temperature=w.temperature)
+    a, b = oracle.accept_from_logits(**kw), oracle.accept_from_logits(without_replacement=True, **kw)
+    for f in ("accept_len", "next_token", "accept_mask", "stop_node"):
+        assert np.array_equal(getattr(a, f), getattr(b, f))
+
+
 # ------------------------------------------------------------------ draft model with a smaller vocabulary
 def test_monte_carlo_subvocabulary_draft_still_emits_target_distribution():
     """q lives on 6 of the 16 target ids (ids the draft model cannot emit have q = 0).  Speculative
