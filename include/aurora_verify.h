@@ -101,6 +101,12 @@ typedef struct {
    * draft_probs / uniforms rows are then not read, row_lse is that of the raw logits and p_at_draft is
    * 1 / 0 as in a greedy call).  draft_probs and uniforms must be given. */
   const float* temperatures;
+  /* Tree drafts at a temperature > 0: how the children of a node were drawn (the paper's tree verification does
+   * not say).  0: independently from the parent's draft distribution q - after a rejection q stays as it is.
+   * Non-zero: one after the other without replacement - a rejected child's token is removed from q (set to 0,
+   * the rest divided by the mass that is left, the row being taken to sum to 1) for the tests and residuals of
+   * its later siblings.  Ignored for chains and greedy requests. */
+  int32_t tree_without_replacement;
 } aurora_accept_desc;
 
 /* Bytes of workspace needed by aurora_verify / _attn / _accept for these descriptors.

@@ -38,7 +38,7 @@ class aurora_accept_desc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("hidden", C.c_int32), ("vocab", C.c_int32),
                 ("dtype", C.c_int32), ("temperature", C.c_float), ("draft_vocab", C.c_int32),
                 ("target_to_draft", C.c_void_p), ("hidden_scale", C.c_void_p), ("lm_head_scale", C.c_void_p),
-                ("temperatures", C.c_void_p)]
+                ("temperatures", C.c_void_p), ("tree_without_replacement", C.c_int32)]
 
 
 class aurora_trace_desc(C.Structure):

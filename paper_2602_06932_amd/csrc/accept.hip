@@ -58,6 +58,40 @@ __device__ __forceinline__ double sweep_weight(float l, float qv, double lse, do
   return x;
 }
 
+// Siblings drawn without replacement: the children of a node were drawn one after the other, each from the
+// parent's q with the earlier siblings' tokens removed.  The draft distribution that residual level s was formed
+// with is then q with the tokens rej[0 .. len[s]) set to zero, times fac[s] = 1 / (1 - their mass).
+struct QLevels {
+  const int* rej;
+  const int* len;
+  const double* fac;
+};
+__device__ __forceinline__ bool in_list(int v, const int* list, int n) {
+  bool hit = false;
+  for (int i = 0; i < n; ++i) hit |= list[i] == v;
+  return hit;
+}
+__device__ __forceinline__ double node_weight_wor(float l, float qv, int v, double lse, double T, int nres, const double* Zs,
+                                                  const QLevels& ql) {
+  double x = exp((double)l / T - lse);
+  for (int s = 0; s < nres; ++s) {
+    const double qs = in_list(v, ql.rej, ql.len[s]) ? 0.0 : (double)qv * ql.fac[s];
+    x = fmax(0.0, x - qs) / Zs[s];
+  }
+  return x;
+}
+__device__ __forceinline__ double sweep_weight_wor(float l, float qv, int v, double lse, double inv_t, int nres,
+                                                   const double* invZs, bool skip_last, const QLevels& ql) {
+  const double a = ((double)l * inv_t - lse) * 1.4426950408889634;
+  double x = (double)__builtin_amdgcn_exp2f((float)a);
+  for (int s = 0; s < nres; ++s) {
+    const double qs = in_list(v, ql.rej, ql.len[s]) ? 0.0 : (double)qv * ql.fac[s];
+    x = fmax(0.0, x - qs);
+    if (!(skip_last && s == nres - 1)) x *= invZs[s];
+  }
+  return x;
+}
+
 __device__ __forceinline__ double wave_incl_scan(double x, int lane) {
 #pragma unroll
   for (int o = 1; o < kWave; o <<= 1) {
@@ -96,6 +130,7 @@ struct AcceptParams {
   int tree_slices;
   int32_t* tree_bar;
   const float* temps;  // [B] one temperature per request (0 = that request is verified greedily), or NULL
+  int wor;             // tree walk: siblings were drawn without replacement
 };
 
 // the temperature of request b: its own, or the call's
@@ -214,6 +249,13 @@ __device__ __forceinline__ void lane_weights(const Lane4& r, int v0, int V, doub
 #pragma unroll
   for (int e = 0; e < 4; ++e)
     x[e] = v0 + e < V ? sweep_weight(r.l[e], r.q[e], lse, inv_t, nres, invZs, skip_last) : 0.0;
+}
+
+__device__ __forceinline__ void lane_weights_wor(const Lane4& r, int v0, int V, double lse, double inv_t, int nres,
+                                                 double x[4], const double* invZs, bool skip_last, const QLevels& ql) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    x[e] = v0 + e < V ? sweep_weight_wor(r.l[e], r.q[e], v0 + e, lse, inv_t, nres, invZs, skip_last, ql) : 0.0;
 }
 
 // Kernel 1: S workgroups per request.  Every workgroup repeats the (cheap) walk - merge the tile
@@ -481,6 +523,10 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   __shared__ int s_par[kMaxNq], s_tok[kMaxNq];
   __shared__ float s_u0[kMaxNq], s_u1[kMaxNq];
   __shared__ float s_ltok[kMaxNq], s_qtok[kMaxNq];  // logit and draft probability of node n's token in its parent's row
+  // siblings without replacement: tokens rejected at the current node, the draft distribution each residual level
+  // was formed with (see QLevels), and the one the next sibling was drawn from
+  __shared__ int s_rej[kMaxNq], s_qlen[kMaxNq], s_cur_len;
+  __shared__ double s_qfac[kMaxNq], s_cur_fac, s_rej_mass;
 
   const int b = blockIdx.y;
   const int S = (int)gridDim.x, slice = blockIdx.x;  // S > 1 only for sampling walks
@@ -563,8 +609,11 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   const int g_lo = slice * per_slice;
   const int g_hi = min(ngroups, g_lo + per_slice);
   int sweeps = 0;  // sweeps done so far: the same in every workgroup of the request
+  const bool wor = P.wor != 0;
+  const QLevels ql = {s_rej, s_qlen, s_qfac};
   if (tid == 0) {
     s_cur = 0; s_depth = 0; s_nres = 0; s_last_child = 0; s_have_gsum = 0; s_fail = 0;
+    s_cur_len = 0; s_cur_fac = 1.0; s_rej_mass = 0.0;
   }
   enum { ST_DONE = 0, ST_ACCEPTED = 1, ST_REJECTED = 2 };
   for (;;) {
@@ -579,17 +628,25 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       } else {
         const float l = s_ltok[c];
         const float qv = s_qtok[c];
-        const double p = node_weight(l, qv, s_lse[cur], T, s_nres, s_Z);
+        const int tk = s_tok[c];
+        const double p = wor ? node_weight_wor(l, qv, tk, s_lse[cur], T, s_nres, s_Z, ql)
+                             : node_weight(l, qv, s_lse[cur], T, s_nres, s_Z);
+        // the probability this sibling was drawn with
+        const double qd = !wor ? (double)qv : in_list(tk, s_rej, s_cur_len) ? 0.0 : (double)qv * s_cur_fac;
         const double u = (double)s_u0[c];
         s_last_child = c;
-        if (u * (double)qv < p) {
+        if (u * qd < p) {
           s_cur = c;
           s_depth = s_depth + 1;
           s_nres = 0;
           s_have_gsum = 0;
+          s_cur_len = 0; s_cur_fac = 1.0; s_rej_mass = 0.0;
           if (writer) P.accept_mask[row0 + c] = 1;
           s_state = ST_ACCEPTED;
         } else {
+          // the residual level that the sweep below forms subtracts the distribution this sibling was drawn from
+          s_qlen[s_nres] = s_cur_len;
+          s_qfac[s_nres] = s_cur_fac;
           s_state = ST_REJECTED;
         }
       }
@@ -624,7 +681,8 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
           if (gi < g_hi) {  // wave-uniform
             const int v0 = gi * kGroup + lane * 4;
             double x[4];
-            lane_weights(r[i], v0, V, lse, inv_t, nres, x, s_invZ, skip_last);
+            if (wor) lane_weights_wor(r[i], v0, V, lse, inv_t, nres, x, s_invZ, skip_last, ql);
+            else lane_weights(r[i], v0, V, lse, inv_t, nres, x, s_invZ, skip_last);
 #pragma unroll
             for (int e = 0; e < 4; ++e)
               if (x[e] > 0.0) lastpos = max(lastpos, v0 + e);
@@ -695,6 +753,17 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
         } else {
           s_have_gsum = 0;  // residual vanished: the distribution is left as it was
         }
+        if (wor) {
+          // the rejected token leaves the distribution the later siblings were drawn from
+          const int c = s_last_child, tk = s_tok[c];
+          if (!in_list(tk, s_rej, s_cur_len)) {
+            s_rej[s_cur_len] = tk;
+            s_cur_len = s_cur_len + 1;
+            s_rej_mass = s_rej_mass + (double)s_qtok[c];
+            const double left = 1.0 - s_rej_mass;
+            s_cur_fac = left > 0.0 ? 1.0 / left : 0.0;
+          }
+        }
       }
       continue;
     }
@@ -731,7 +800,8 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
         const int nres = s_nres;
         const int v0 = pick * kGroup + lane * 4;
         double x[4];
-        lane_weights(lane_load(lrow, qrow, v0, V, vec_ok), v0, V, lse, inv_t, nres, x, s_invZ, have);
+        if (wor) lane_weights_wor(lane_load(lrow, qrow, v0, V, vec_ok), v0, V, lse, inv_t, nres, x, s_invZ, have, ql);
+        else lane_weights(lane_load(lrow, qrow, v0, V, vec_ok), v0, V, lse, inv_t, nres, x, s_invZ, have);
         const double lane_tot = (x[0] + x[1]) + (x[2] + x[3]);
         const double lane_incl = wave_incl_scan(lane_tot, lane) + s_pick_prefix;
         const unsigned long long hit = __ballot(lane_incl > thr);
@@ -807,6 +877,7 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st) {
   P.st_lse = a.st_lse; P.st_row = a.st_row; P.st_rej = a.st_rej; P.gsum = a.gsum; P.lastpos = a.lastpos;
   P.tree_bar = a.tree_bar;
   P.temps = a.temps;
+  P.wor = a.wor;
   const bool sampling = a.temperature > 0.f || a.temps != nullptr;  // per-request temperatures: the sampling kernels
   const bool chain_sampling = sampling && a.parents == nullptr;
   if (!chain_sampling) {

@@ -89,6 +89,7 @@ AcceptLaunch accept_launch_from(const aurora_accept_desc* d) {
   a.hidden_scale = d->hidden_scale; a.lm_scale = d->lm_head_scale;
   a.temperature = d->temperature;
   a.temps = d->temperatures;
+  a.wor = d->tree_without_replacement;
   if (d->draft_vocab > 0 && (d->temperature > 0.f || d->temperatures)) { a.Vd = d->draft_vocab; a.target_to_draft = d->target_to_draft; }
   return a;
 }

@@ -28,6 +28,7 @@ struct AcceptLaunch {
   const float *hidden_scale, *lm_scale;  // [B*Nq], [V] when fp8
   float temperature;
   const float* temps;  // [B] one temperature per request (0 = greedy request), or NULL: `temperature` for all
+  int wor;             // tree siblings were drawn without replacement
   const void *hidden, *lm_head;
   const int32_t *draft_tokens, *parents;
   const float *draft_probs, *uniforms;

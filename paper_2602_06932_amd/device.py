@@ -76,7 +76,8 @@ class DeviceVerify:
             target_to_draft=None if t2d is None else self.target_to_draft.data_ptr(),
             hidden_scale=self.hidden_scale.data_ptr() if head_fp8 else None,
             lm_head_scale=self.lm_head_scale.data_ptr() if head_fp8 else None,
-            temperatures=None if temps is None else self.temperatures.data_ptr())
+            temperatures=None if temps is None else self.temperatures.data_ptr(),
+            tree_without_replacement=1 if getattr(w, "tree_without_replacement", False) else 0)
         self.ws_bytes = B.aurora_verify_workspace_bytes(self.attn_desc, self.accept_desc)
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device="cuda")
         assert self.workspace.data_ptr() % 256 == 0

@@ -230,6 +230,34 @@ def test_full_size_stress_sparse_pool(gpu_lib):
     _, a = _full_check(gpu_lib, w, sample=_spread_sample(w, 4))
 
 
+def _rules_differ(w):
+    """Requests on which the with-replacement rule would decide differently (oracle against oracle)."""
+    import dataclasses
+    a = oracle.accept_workload(w)
+    b = oracle.accept_workload(dataclasses.replace(w, tree_without_replacement=False))
+    return int(((a.next_token != b.next_token) | (a.accept_len != b.accept_len)).sum())
+
+
+@pytest.mark.parametrize("vocab,noise,temperature,min_diff", [(700, 2.0, 0.3, 6), (20011, 2.0, 0.3, 5), (20011, 0.5, 1.0, 0)])
+def test_tree_siblings_without_replacement(gpu_lib, vocab, noise, temperature, min_diff):
+    """Trees whose siblings were drawn one after the other without replacement (the other reading of the
+    multi-candidate rule): one workgroup per request (small vocabulary) and several.  Peaked, noisy drafters reject
+    most siblings (walks reach the third and fourth residual level) and make the two rules disagree on many
+    requests, so a kernel that ignored the option would fail; the third case walks deep accepted paths."""
+    w = gen.llama_tree(70, batch=24, num_q=16, vocab=vocab, hidden_size=128, context=48, num_q_heads=4,
+                       num_kv_heads=2, siblings_without_replacement=True, draft_noise=noise, temperature=temperature)
+    assert w.tree_without_replacement and _rules_differ(w) >= min_diff
+    _full_check(gpu_lib, w)
+
+
+def test_tree_without_replacement_with_draft_vocabulary_and_request_temperatures(gpu_lib):
+    temps = np.array([0.3, 0.0, 0.3, 0.35, 0.0, 0.25, 0.3, 0.4], np.float32)
+    w = gen.llama_tree(75, batch=8, num_q=14, vocab=9000, hidden_size=128, context=60, num_q_heads=4, num_kv_heads=2,
+                       siblings_without_replacement=True, draft_vocab=3000, draft_noise=2.0, temperatures=temps)
+    assert _rules_differ(w) >= 2
+    _full_check(gpu_lib, w)
+
+
 def test_lookahead_10_chain(gpu_lib):
     """Eleven query positions per request (lookahead 10, the paper's discard-token experiment of section 5) with the
     headline configuration's heads: 44 query rows per KV head; sampling and greedy."""
