@@ -71,6 +71,21 @@ def test_tree_bf16_128_query_rows(gpu_lib):
     _check(gen.llama_tree(139, batch=2, num_q=24, context=90, vocab=64, hidden_size=64, num_q_heads=4, num_kv_heads=1), 8)
 
 
+@pytest.mark.parametrize("num_q,context", [(18, 33), (25, 40), (25, 257), (32, 32), (20, 700)])
+def test_tree_bf16_partly_filled_row_tiles_and_short_runs(gpu_lib, num_q, context):
+    """65 .. 128 query rows per KV head with a last row tile that is partly or wholly empty, on sequences of one or
+    two tiles (runs shorter than the tile pipeline), a one-token last tile, and a prefix of zero length."""
+    _check(gen.llama_tree(150 + num_q, batch=3, num_q=num_q, context=context, vocab=64, hidden_size=64, num_q_heads=8,
+                          num_kv_heads=2), 20 + num_q)
+
+
+def test_more_requests_than_the_matrix_core_kernel_plans_for(gpu_lib):
+    """1030 short requests: past the 1024 requests whose tile prefix the matrix-core kernels build in LDS, the call
+    takes the vector kernel."""
+    _check(gen.llama_chain(160, batch=1030, num_q=3, num_q_heads=4, num_kv_heads=2, len_lo=3, len_hi=40, vocab=64,
+                           hidden_size=64), 30)
+
+
 def test_fp32_head_dim_64_and_large_pages(gpu_lib):
     _check(gen.tiny_chain(133), 3)
     _check(gen.llama_chain(134, batch=2, len_lo=30, len_hi=200, vocab=64, hidden_size=64, page_size=24, head_dim=64,
