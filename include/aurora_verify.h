@@ -307,8 +307,8 @@ const char* aurora_status_string(int status);
  * prefix receives gradient as well).  dq is float32 [B, Nq, Hq, D]; dk_pages / dv_pages are float32 pools in the
  * layout of k_pages / v_pages - the positions the batch's block tables address are written, every other element
  * is left as it is.  dout has the type of q.  All sums run in a fixed order: bit-reproducible.
- * bf16 caches with head_dim 128, power-of-two pages >= 16, at most 128 query rows per KV head and at most 1024
- * requests run on the matrix cores (P and dS rounded to bf16 for the products, fp32 accumulation); every other
+ * bf16 caches with head_dim 128, power-of-two pages >= 16 and at most 128 query rows per KV head run on the
+ * matrix cores (P and dS rounded to bf16 for the products, fp32 accumulation); every other
  * shape takes a plain fp32 vector kernel.  An 8-bit KV cache is not supported (AURORA_ERR_UNSUPPORTED).
  *
  *   aurora_attn_backward        runs the forward pass itself (into the workspace): nothing is kept from a forward call

@@ -122,7 +122,9 @@ __device__ __forceinline__ void tile_p_ds(f32x16_t s_acc, const f32x16_t dp_acc,
   }
 }
 
-template <int kRT /* 32-row tiles of query rows per KV head: 1 or 2 */>
+// kLocalPlan: every workgroup builds the tile prefix per request in LDS (up to kLocalPlanMax requests; workgroup 0
+// also writes it to PB for the dq merge); otherwise PB was filled by the planning kernel and is read from memory.
+template <int kRT /* 32-row tiles of query rows per KV head: 1 or 2 */, bool kLocalPlan>
 __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ parents,
@@ -133,13 +135,16 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
   char* qV = bm_lds;                          // the pair's query rows, kRT tiles in the V-tile layout
   char* doV = bm_lds + kRT * kAtTileBytes;    // their upstream gradients
   char* waves = bm_lds + 2 * kRT * kAtTileBytes;
-  __shared__ int s_pb[kLocalPlanMax + 1];
+  __shared__ int s_pb[kLocalPlan ? kLocalPlanMax + 1 : 1];
   __shared__ int s_wsum[4];
-  build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
-  if (blockIdx.x == 0)
-    for (int i = threadIdx.x; i <= B; i += kBmThreads) PB[i] = s_pb[i];
+  if (kLocalPlan) {
+    build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
+    if (blockIdx.x == 0)
+      for (int i = threadIdx.x; i <= B; i += kBmThreads) PB[i] = s_pb[i];
+  }
+  auto pbv = [&](int i) -> int { return kLocalPlan ? s_pb[i] : PB[i]; };
 
-  const int U = s_pb[B];
+  const int U = pbv(B);
   const int c = units_per_wg(U, gridDim.x);
   int u = blockIdx.x * c;
   const int u_end = min(U, u + c);
@@ -160,16 +165,16 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
     int lo = 0, hi = B - 1;
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
-      if (s_pb[mid] <= u) lo = mid; else hi = mid - 1;
+      if (pbv(mid) <= u) lo = mid; else hi = mid - 1;
     }
     b = lo;
   }
 
   while (u < u_end) {
-    while (s_pb[b + 1] <= u) ++b;
+    while (pbv(b + 1) <= u) ++b;
     const int L = seq_lens[b];
     const int n_b = (L + kAtTile - 1) / kAtTile;
-    const int rel = u - s_pb[b];
+    const int rel = u - pbv(b);
     const int hk = __builtin_amdgcn_readfirstlane(rel / n_b);
     const int t0 = rel - hk * n_b;
     const int t1 = min(n_b, t0 + (u_end - u));
@@ -385,6 +390,7 @@ __device__ __forceinline__ void tile_tmm_block(const char* abuf, const bf16x8_t 
 constexpr int kB8Threads = 512;
 constexpr int kB8LdsBytes = 8 * kAtTileBytes + 3 * kBsKvBytes + 2 * 4 * kBsXtBytes;
 
+template <bool kLocalPlan>
 __global__ __launch_bounds__(kB8Threads, 1) void attn_bwd_mfma_shared_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ parents,
@@ -396,13 +402,16 @@ __global__ __launch_bounds__(kB8Threads, 1) void attn_bwd_mfma_shared_kernel(
   char* doV = bm_lds + 4 * kAtTileBytes;    // their upstream gradients
   char* kv = bm_lds + 8 * kAtTileBytes;     // three K / V tile pairs
   char* xt = kv + 3 * kBsKvBytes;           // per group: four transposed (P, dS) tiles
-  __shared__ int s_pb[kLocalPlanMax + 1];
+  __shared__ int s_pb[kLocalPlan ? kLocalPlanMax + 1 : 1];
   __shared__ int s_wsum[8];
-  build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
-  if (blockIdx.x == 0)
-    for (int i = threadIdx.x; i <= B; i += kB8Threads) PB[i] = s_pb[i];
+  if (kLocalPlan) {
+    build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
+    if (blockIdx.x == 0)
+      for (int i = threadIdx.x; i <= B; i += kB8Threads) PB[i] = s_pb[i];
+  }
+  auto pbv = [&](int i) -> int { return kLocalPlan ? s_pb[i] : PB[i]; };
 
-  const int U = s_pb[B];
+  const int U = pbv(B);
   const int c = units_per_wg(U, gridDim.x);
   int u = blockIdx.x * c;
   const int u_end = min(U, u + c);
@@ -422,16 +431,16 @@ __global__ __launch_bounds__(kB8Threads, 1) void attn_bwd_mfma_shared_kernel(
     int lo = 0, hi = B - 1;
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
-      if (s_pb[mid] <= u) lo = mid; else hi = mid - 1;
+      if (pbv(mid) <= u) lo = mid; else hi = mid - 1;
     }
     b = lo;
   }
 
   while (u < u_end) {
-    while (s_pb[b + 1] <= u) ++b;
+    while (pbv(b + 1) <= u) ++b;
     const int L = seq_lens[b];
     const int n_b = (L + kAtTile - 1) / kAtTile;
-    const int rel = u - s_pb[b];
+    const int rel = u - pbv(b);
     const int hk = __builtin_amdgcn_readfirstlane(rel / n_b);
     const int t0 = rel - hk * n_b;
     const int t1 = min(n_b, t0 + (u_end - u));
@@ -594,8 +603,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_combine(const float* __restri
 }
 
 bool attn_bwd_mfma_supported(const AttnBwdLaunch& a) {
-  return a.bf16 && a.D == kAtD && a.page >= 16 && (a.page & (a.page - 1)) == 0 && a.Hq / a.Hkv * a.Nq <= 128 &&
-         a.B <= kLocalPlanMax;
+  return a.bf16 && a.D == kAtD && a.page >= 16 && (a.page & (a.page - 1)) == 0 && a.Hq / a.Hkv * a.Nq <= 128;
 }
 
 int attn_bwd_mfma_workgroups() { return 256; }
@@ -610,21 +618,24 @@ size_t attn_bwd_mfma_partial_bytes(int batch, int kv_heads, int rows_per_group) 
   return ((size_t)attn_bwd_mfma_workgroups() + (size_t)batch * kv_heads) * 32 * rt * kAtD * sizeof(float);
 }
 
-template <int kRT>
+template <int kRT, bool kLocalPlan>
 static hipError_t launch_bwd_mfma_t(const AttnBwdLaunch& a, hipStream_t st) {
   static LdsAttrOnce attr;
-  if (hipError_t e = attr.ensure((const void*)attn_bwd_mfma_kernel<kRT>, bm_lds_bytes(kRT)); e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_mfma_kernel<kRT>, dim3(attn_bwd_mfma_workgroups()), dim3(kBmThreads), bm_lds_bytes(kRT), st,
+  if (hipError_t e = attr.ensure((const void*)attn_bwd_mfma_kernel<kRT, kLocalPlan>, bm_lds_bytes(kRT)); e != hipSuccess)
+    return e;
+  hipLaunchKernelGGL((attn_bwd_mfma_kernel<kRT, kLocalPlan>), dim3(attn_bwd_mfma_workgroups()), dim3(kBmThreads), bm_lds_bytes(kRT), st,
                      (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
                      (const bf16_t*)a.dout, a.lse, a.delta, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv,
                      __builtin_ctz(a.page), a.max_pages, a.scale);
   return hipGetLastError();
 }
 
+template <bool kLocalPlan>
 static hipError_t launch_bwd_mfma_shared(const AttnBwdLaunch& a, hipStream_t st) {
   static LdsAttrOnce attr;
-  if (hipError_t e = attr.ensure((const void*)attn_bwd_mfma_shared_kernel, kB8LdsBytes); e != hipSuccess) return e;
-  hipLaunchKernelGGL(attn_bwd_mfma_shared_kernel, dim3(attn_bwd_mfma_workgroups()), dim3(kB8Threads), kB8LdsBytes, st,
+  if (hipError_t e = attr.ensure((const void*)attn_bwd_mfma_shared_kernel<kLocalPlan>, kB8LdsBytes); e != hipSuccess)
+    return e;
+  hipLaunchKernelGGL(attn_bwd_mfma_shared_kernel<kLocalPlan>, dim3(attn_bwd_mfma_workgroups()), dim3(kB8Threads), kB8LdsBytes, st,
                      (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
                      (const bf16_t*)a.dout, a.lse, a.delta, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv,
                      __builtin_ctz(a.page), a.max_pages, a.scale);
@@ -634,7 +645,16 @@ static hipError_t launch_bwd_mfma_shared(const AttnBwdLaunch& a, hipStream_t st)
 hipError_t launch_attn_backward_mfma(const AttnBwdLaunch& a, hipStream_t st) {
   const int rows = a.B * a.Nq * a.Hq;
   const int rt = bwd_row_tiles(a);
-  hipError_t e = rt == 1 ? launch_bwd_mfma_t<1>(a, st) : rt == 2 ? launch_bwd_mfma_t<2>(a, st) : launch_bwd_mfma_shared(a, st);
+  hipError_t e = hipSuccess;
+  if (a.B <= kLocalPlanMax) {
+    e = rt == 1 ? launch_bwd_mfma_t<1, true>(a, st) : rt == 2 ? launch_bwd_mfma_t<2, true>(a, st)
+                                                              : launch_bwd_mfma_shared<true>(a, st);
+  } else {
+    e = launch_attn_plan(a.seq_lens, a.B, a.Hkv, a.plan_pb, st);
+    if (e != hipSuccess) return e;
+    e = rt == 1 ? launch_bwd_mfma_t<1, false>(a, st) : rt == 2 ? launch_bwd_mfma_t<2, false>(a, st)
+                                                               : launch_bwd_mfma_shared<false>(a, st);
+  }
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attn_bwd_dq_combine, dim3((rows + 7) / 8), dim3(256), 0, st, a.part_dq, a.seq_lens, a.plan_pb, a.dq,
                      a.B, a.Nq, a.Hq, a.Hkv, attn_bwd_mfma_workgroups(), rt, (unsigned)rows, a.scale);

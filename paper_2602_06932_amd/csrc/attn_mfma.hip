@@ -53,6 +53,11 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restric
   }
 }
 
+hipError_t launch_attn_plan(const int32_t* seq_lens, int B, int Hkv, int32_t* PB, hipStream_t st) {
+  hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, st, seq_lens, B, Hkv, PB);
+  return hipGetLastError();
+}
+
 // kFp8KV: kp_ / vp_ hold E4M3 codes and k_scale / v_scale [Hkv] their per-head scales (see Tile8 above);
 // otherwise bf16 pools, loaded straight into LDS.
 template <bool kLocalPlan, bool kFp8KV>
@@ -620,8 +625,7 @@ hipError_t launch_attn_mfma(const AttnLaunch& a, hipStream_t st) {
   const bool local_plan = a.B <= kLocalPlanMax;
   hipError_t e;
   if (!local_plan) {
-    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, st, a.seq_lens, a.B, a.Hkv, a.plan_pb);
-    e = hipGetLastError();
+    e = launch_attn_plan(a.seq_lens, a.B, a.Hkv, a.plan_pb, st);
     if (e != hipSuccess) return e;
   }
   const int shift = __builtin_ctz(a.page);

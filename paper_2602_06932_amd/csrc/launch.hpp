@@ -85,6 +85,8 @@ struct AttnBwdLaunch {
 };
 hipError_t launch_attn_backward(const AttnBwdLaunch& a, hipStream_t st);
 // matrix-core kernel (attn_bwd_mfma.hip): shapes it takes, its resident workgroups, and its launch (delta is ready)
+// tile prefix per request, PB[0 .. B], by one workgroup (attn_mfma.hip): for batches past the in-LDS plan
+hipError_t launch_attn_plan(const int32_t* seq_lens, int B, int Hkv, int32_t* PB, hipStream_t st);
 bool attn_bwd_mfma_supported(const AttnBwdLaunch& a);
 int attn_bwd_mfma_workgroups();
 size_t attn_bwd_mfma_partial_bytes(int batch, int kv_heads, int rows_per_group);

@@ -79,11 +79,13 @@ def test_tree_bf16_partly_filled_row_tiles_and_short_runs(gpu_lib, num_q, contex
                           num_kv_heads=2), 20 + num_q)
 
 
-def test_more_requests_than_the_matrix_core_kernel_plans_for(gpu_lib):
-    """1030 short requests: past the 1024 requests whose tile prefix the matrix-core kernels build in LDS, the call
-    takes the vector kernel."""
+def test_more_requests_than_the_in_lds_plan_holds(gpu_lib):
+    """1030 short requests: past the 1024 requests whose tile prefix the kernels build in LDS, a planning kernel
+    writes it to memory (one row tile; then a 70-row tree batch through the shared-tile kernel)."""
     _check(gen.llama_chain(160, batch=1030, num_q=3, num_q_heads=4, num_kv_heads=2, len_lo=3, len_hi=40, vocab=64,
                            hidden_size=64), 30)
+    _check(gen.llama_tree(161, batch=1027, num_q=35, context=36, vocab=64, hidden_size=64, num_q_heads=2, num_kv_heads=1),
+           31)
 
 
 def test_fp32_head_dim_64_and_large_pages(gpu_lib):
