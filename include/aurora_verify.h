@@ -151,6 +151,11 @@ int aurora_verify_attn(const aurora_attn_desc* desc,
  *           A chain is the one-child case: the first rejection ends the walk.
  *   T == 0: a child is accepted iff its token equals the arg-max (lowest index on ties) of the
  *           current row; next_token is the arg-max of the row the walk stops at.
+ *
+ * Tree walks at T > 0 over large vocabularies are split over several workgroups per request that wait for each
+ * other between vocabulary sweeps.  They fit the device together when nothing else occupies it; the wait is
+ * bounded all the same, and a request whose workgroups did not meet in time gets accept_len = next_token = -1
+ * (its other outputs are then unspecified): run the call again.  Chains and greedy calls never wait.
  */
 int aurora_verify_accept(const aurora_accept_desc* desc,
                          const void* hidden,          /* [B, Nq, H]                           */
@@ -290,6 +295,11 @@ int aurora_trace_emit(const aurora_trace_desc* desc,
                       int32_t* y_out,              /* [B, Nq]                                  */
                       int8_t* traj,                /* [B, Nq]                                  */
                       void* hip_stream);
+
+/* For tests of the bounded wait described at aurora_verify_accept: the number of polls of the arrival counter a
+ * workgroup of a split tree walk makes before it gives up (process-wide, applies to later calls; negative restores
+ * the default of 2^21, about a second).  0 makes every wait fail at once unless the others have already arrived. */
+void aurora_debug_set_tree_spin_limit(int polls);
 
 /* Human-readable name of a status code; never NULL. */
 const char* aurora_status_string(int status);

@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_v
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
            "aurora_verify_lmhead", "aurora_verify_accept_logits", "aurora_trace_emit",
            "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack", "aurora_attn_backward",
-           "aurora_attn_backward_workspace_bytes", "aurora_attn_forward", "aurora_attn_backward_saved")
+           "aurora_attn_backward_workspace_bytes", "aurora_attn_forward", "aurora_attn_backward_saved", "aurora_debug_set_tree_spin_limit")
 
 
 class aurora_attn_desc(C.Structure):
@@ -97,6 +97,8 @@ def load():
     lib.aurora_attn_backward_workspace_bytes.restype = C.c_int
     lib.aurora_attn_backward.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, f32p, f32p, f32p, vp, C.c_size_t, vp]
     lib.aurora_attn_backward.restype = C.c_int
+    lib.aurora_debug_set_tree_spin_limit.argtypes = [C.c_int]
+    lib.aurora_debug_set_tree_spin_limit.restype = None
     lib.aurora_attn_forward.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, f32p, vp, C.c_size_t, vp]
     lib.aurora_attn_forward.restype = C.c_int
     lib.aurora_attn_backward_saved.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, f32p, vp, f32p, f32p, f32p, vp,
@@ -295,3 +297,7 @@ def aurora_attn_backward_saved(desc, q, k_pages, v_pages, block_table, seq_lens,
     if check and st != AURORA_OK:
         raise AuroraError(st, "aurora_attn_backward_saved")
     return st
+
+
+def aurora_debug_set_tree_spin_limit(polls: int) -> None:
+    load().aurora_debug_set_tree_spin_limit(int(polls))

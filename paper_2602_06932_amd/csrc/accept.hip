@@ -131,6 +131,7 @@ struct AcceptParams {
   int32_t* tree_bar;
   const float* temps;  // [B] one temperature per request (0 = that request is verified greedily), or NULL
   int wor;             // tree walk: siblings were drawn without replacement
+  int spin_limit;      // tree walk with several workgroups: polls of the arrival counter before giving up
 };
 
 // the temperature of request b: its own, or the call's
@@ -485,7 +486,7 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams 
 // so all workgroups of a request are resident together; the wait on the counter is bounded all the same.
 // ============================================================================================
 constexpr int kTreeMaxSlices = 16;
-constexpr int kSpinLimit = 1 << 21;  // polls of the arrival counter (about a second) before giving up
+constexpr int kSpinLimit = 1 << 21;  // default number of polls of the arrival counter (about a second) before giving up
 
 // The values exchanged between the workgroups of a request are written and read with device-scope
 // atomic accesses: on this multi-die part they go past the die-local L2 to the point all dies see, so the
@@ -710,11 +711,18 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
           int polls = 0;
           while (load_agent(&P.tree_bar[b]) < target) {
             __builtin_amdgcn_s_sleep(4);
-            if (++polls > kSpinLimit) { s_fail = 1; break; }
+            if (++polls > P.spin_limit) { s_fail = 1; break; }
           }
         }
         __syncthreads();
-        if (s_fail) return;  // a workgroup of the request never arrived: give up rather than wait for ever
+        if (s_fail) {
+          // a workgroup of the request never arrived: give up rather than wait for ever, and say so
+          if (writer && tid == 0) {
+            P.accept_len[b] = -1;
+            P.next_token[b] = -1;
+          }
+          return;
+        }
         // loads that bypass this compute unit's L1, which may still hold the copy of two sweeps ago
         for (int g = tid; g < ngroups; g += kAccThreads) s_gsum[g] = load_agent(&gs_out[g]);
         if (tid < S) atomicMax(&s_lastpos, load_agent(&lp[tid]));
@@ -848,6 +856,10 @@ void accept_chain_geometry(int batch, int vocab, int* slices, int* gmul, int* ng
   *ngroups = ng;
 }
 
+// polls before a workgroup of a split tree walk gives up waiting for the others (host-side setting, see the header)
+static int g_tree_spin_limit = kSpinLimit;
+void set_tree_spin_limit(int polls) { g_tree_spin_limit = polls < 0 ? kSpinLimit : polls; }
+
 __global__ void zero_i32_kernel(int32_t* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
@@ -878,6 +890,7 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st) {
   P.tree_bar = a.tree_bar;
   P.temps = a.temps;
   P.wor = a.wor;
+  P.spin_limit = g_tree_spin_limit;
   const bool sampling = a.temperature > 0.f || a.temps != nullptr;  // per-request temperatures: the sampling kernels
   const bool chain_sampling = sampling && a.parents == nullptr;
   if (!chain_sampling) {

@@ -410,6 +410,8 @@ int aurora_attn_backward(const aurora_attn_desc* desc, const void* q, const void
                       dk_pages, dv_pages, ws, st);
 }
 
+void aurora_debug_set_tree_spin_limit(int polls) { set_tree_spin_limit(polls); }
+
 int aurora_attn_forward(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
                         const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents, void* out,
                         float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {

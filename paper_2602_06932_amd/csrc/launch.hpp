@@ -85,6 +85,7 @@ struct AttnBwdLaunch {
 };
 hipError_t launch_attn_backward(const AttnBwdLaunch& a, hipStream_t st);
 // matrix-core kernel (attn_bwd_mfma.hip): shapes it takes, its resident workgroups, and its launch (delta is ready)
+void set_tree_spin_limit(int polls);  // accept.hip: bounded wait of the split tree walk (negative: default)
 // tile prefix per request, PB[0 .. B], by one workgroup (attn_mfma.hip): for batches past the in-LDS plan
 hipError_t launch_attn_plan(const int32_t* seq_lens, int B, int Hkv, int32_t* PB, hipStream_t st);
 bool attn_bwd_mfma_supported(const AttnBwdLaunch& a);
