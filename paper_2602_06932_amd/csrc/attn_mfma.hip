@@ -454,11 +454,13 @@ __global__ __launch_bounds__(kWideThreads, 1) void attn_mfma_wide_kernel(
     SoftmaxState st;
     softmax_state_reset(st);
     __syncthreads();  // query tiles staged; the ring is idle
+    QFrags qf;  // this wavefront's query tile as MFMA operand fragments, for the whole run
+    load_q_frags(qf, qtile, li, lh);
     auto compute_step = [&](int sidx) {
       const int tt = 2 * sidx + grp;
       if (rt_ok && tt < ntile) {
         const char* kb = ring + (sidx % kWideStages) * kWideStageBytes + grp * (2 * kAtTileBytes);
-        const f32x16_t s_acc = tile_scores(kb, qtile, li, lh);
+        const f32x16_t s_acc = tile_scores_qreg(kb, qf, li, lh);
         bf16x8_t pb2[2];
         tile_softmax(s_acc, st, pb2, scale_log2, start + tt * kAtTile, prefix, L, anc, lh);
         tile_pv(kb + kAtTileBytes, pb2, st, lane);
