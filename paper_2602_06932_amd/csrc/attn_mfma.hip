@@ -529,6 +529,7 @@ __global__ __launch_bounds__(kWideThreads, 1) void attn_mfma_wide_kernel(
       }
     }
 
+    pin_accumulators(st);
     // each wavefront writes the partial of its own query tile and tile parity
     const float l_row = st.l_half + __shfl_xor(st.l_half, 32, kWave);
     if (row_ok) {
