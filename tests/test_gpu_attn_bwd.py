@@ -215,3 +215,45 @@ def test_full_size_chain_and_tree_sampled(gpu_lib):
     order = np.argsort(w.seq_lens, kind="stable")
     _sampled_check(w, [int(order[0]), int(order[len(order) // 2]), int(order[-1])], 12)
     _sampled_check(gen.llama_tree(1, vocab=64, hidden_size=64), [0, 11], 13)
+
+
+@pytest.mark.parametrize("tree", [False, True])
+def test_backward_replays_from_a_captured_graph(gpu_lib, tree):
+    """The backward call (forward recomputed, delta, backward kernel, dq merge) is plain kernel launches on the caller's
+    stream - no allocation, no memset: captured once and replayed, with eager work on the same workspace between
+    the replays, it gives the eager call's bits every time."""
+    import paper_2602_06932_amd as av
+    from paper_2602_06932_amd.device import DeviceVerify, _to_dev
+    if tree:
+        w = gen.llama_tree(170, batch=3, num_q=32, context=300, vocab=64, hidden_size=64, num_q_heads=8, num_kv_heads=2)
+    else:
+        w = gen.llama_chain(171, batch=4, len_lo=40, len_hi=500, vocab=64, hidden_size=64)
+    rng = np.random.default_rng(40)
+    dout = (rng.standard_normal(w.q.shape).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    ref = _run(w, dout)
+    dv = DeviceVerify(w)
+    d_dout = _to_dev(dout, w.dtype)
+    dq = torch.zeros(w.q.shape, dtype=torch.float32, device="cuda")
+    dk = torch.zeros(dv.k_pages.shape, dtype=torch.float32, device="cuda")
+    dvp = torch.zeros(dv.v_pages.shape, dtype=torch.float32, device="cuda")
+    ws = torch.empty(av.aurora_attn_backward_workspace_bytes(dv.attn_desc), dtype=torch.uint8, device="cuda")
+    call = lambda stream=None: av.aurora_attn_backward(dv.attn_desc, dv.q, dv.k_pages, dv.v_pages, dv.block_table,
+                                                       dv.seq_lens, dv.parents, d_dout, dq, dk, dvp, ws, stream=stream)
+    call()  # the first call of a kernel also sets its LDS attribute: not part of the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for i in range(3):
+        dq.fill_(float("nan"))
+        dk.zero_()
+        dvp.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, x, y in zip(("dq", "dk", "dv"), ref, (dq, dk, dvp)):
+            assert np.array_equal(x, y.cpu().numpy()), (i, name)
+        ws.fill_(0xff)  # eager work on the workspace between the replays
+        torch.cuda.synchronize()
