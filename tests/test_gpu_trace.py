@@ -131,3 +131,58 @@ def test_verify_then_emit(gpu_lib):
         diff = np.setxor1d(gid[m], rid[m])
         assert np.all(np.abs(ref[m, diff] - kth) <= 2 * tol), (m, diff[:5])
     assert len(np.setxor1d(gid, rid)) < 0.01 * gid.size
+
+
+def test_verify_emit_pack_loss_replay_from_one_captured_graph(gpu_lib):
+    """The serving-side sequence verify -> emit -> pack and the training-side loss on the emitted rows, captured as
+    ONE graph (none of the calls allocates or records a memset) and replayed with eager work in between: every
+    replay gives the eager sequence's bits."""
+    from paper_2602_06932_amd.device import DeviceVerify
+    av = gpu_lib
+    w = gen.llama_chain(26, batch=6, len_lo=30, len_hi=90, vocab=20011, hidden_size=256)
+    dv = DeviceVerify(w)
+    B, Nq, V, K = w.batch, w.num_q, w.vocab, 256
+    M = B * Nq
+    td = av.aurora_trace_desc(batch=B, num_q=Nq, vocab=V, top_k=K)
+    pd = av.aurora_pack_desc(rows=M, top_k=K, h_row_bytes=0)
+    ld = av.aurora_loss_desc(rows=M, draft_vocab=V, top_k=K, discard_top_k=16, lambda_discard=0.5)
+    lp = av.aurora_verify_logits_ptr(dv.attn_desc, dv.accept_desc, dv.workspace)
+    dev = lambda shape, dt: torch.zeros(shape, dtype=dt, device="cuda")
+    ids, vals, y, r = dev((M, K), torch.int32), dev((M, K), torch.int16), dev((B, Nq), torch.int32), dev((B, Nq), torch.int8)
+    n_out, row_index = dev((1,), torch.int32), dev((M,), torch.int32)
+    ids_p, vals_p, y_p, r_p = dev((M, K), torch.int32), dev((M, K), torch.int16), dev((M,), torch.int32), dev((M,), torch.int8)
+    z = torch.randn((M, V), device="cuda", generator=torch.Generator(device="cuda").manual_seed(5))
+    row_kl, loss, grad = dev((M,), torch.float32), dev((5,), torch.float32), dev((M, V), torch.float32)
+    outs = (ids, vals, y, r, n_out, row_index, ids_p, vals_p, y_p, r_p, row_kl, loss, grad)
+
+    def sequence(stream=None):
+        dv.verify(stream=stream)
+        av.aurora_trace_emit(td, lp, dv.draft_tokens, dv.parents, dv.next_token, dv.accept_mask, ids, vals, y, r, stream=stream)
+        av.aurora_trace_pack(pd, r.view(-1), None, ids, vals, None, y.view(-1), n_out, row_index, None, ids_p, vals_p, None, y_p,
+                             r_p, stream=stream)
+        av.aurora_draft_loss(ld, z, ids, vals, r.view(-1), row_kl, loss, grad, stream=stream)
+
+    sequence()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs]
+    assert 0 < int(n_out.item()) <= M and torch.isfinite(loss).all()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sequence(stream=torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for i in range(3):
+        for t in outs:
+            t.fill_(1)
+        graph.replay()
+        torch.cuda.synchronize()
+        n = int(n_out.item())
+        for k, (a, b) in enumerate(zip(ref, outs)):
+            if k in (6, 7, 8, 9):   # packed arrays: positions from n on are not written
+                a, b = a[:n], b[:n]
+            elif k == 5:
+                a, b = a[:n], b[:n]
+            assert torch.equal(a, b), (i, k)
+        dv.accept()  # eager work on the verify workspace between replays
+        torch.cuda.synchronize()
