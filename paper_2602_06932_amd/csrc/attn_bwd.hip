@@ -166,12 +166,12 @@ __global__ __launch_bounds__(kBwThreads) void attn_bwd_kernel(
 
 template <typename T>
 static hipError_t launch_bwd_t(const AttnBwdLaunch& a, hipStream_t st) {
+  if (attn_bwd_mfma_supported(a)) return launch_attn_backward_mfma(a, st);  // forms delta itself
   const int rows = a.B * a.Nq * a.Hq;
   hipLaunchKernelGGL(attn_bwd_delta_kernel<T>, dim3((rows + 3) / 4), dim3(256), 0, st, (const T*)a.out, (const T*)a.dout,
                      a.delta, rows, a.D);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (attn_bwd_mfma_supported(a)) return launch_attn_backward_mfma(a, st);
   dim3 grid(a.B * a.Hkv);
   const int lds = (int)sizeof(float) * (2 * kBwRows * a.D + kBwTok * (a.D + 4) + kBwRows * (kBwTok + 1));
   static LdsAttrOnce attr128, attr64;

@@ -14,8 +14,9 @@
 //                                                      128-byte lines of the fp32 pools (partial lines cost 2.5x)
 // K and V tiles come in by direct global->LDS loads in the layout of the forward kernel's V tiles (it serves
 // the 128-bit row reads and the transposing reads alike); the next tile's V is requested once dP is formed,
-// its K once dQ is updated.  dq is summed over the wavefronts at the end of a run and over the runs of a pair
-// by a second kernel; dK / dV tiles are written once, by the wavefront that owns the tile.
+// its K once dQ is updated.  delta = <dO, O> of a row is formed by the threads that stage the row.  dq is summed
+// over the wavefronts at the end of a run and over the runs of a pair by a second kernel; dK / dV tiles are written
+// once, by the wavefront that owns the tile.
 #include "launch.hpp"
 #include "attn_tile.hpp"
 
@@ -102,6 +103,16 @@ __device__ __forceinline__ void read_transposed(const char* xt, bf16x8_t b[2], i
   }
 }
 
+// <a, b> over eight bf16 pairs held as four 32-bit words each, accumulated in fp32
+__device__ __forceinline__ float dot8_bf16(const u32x4_t a, const u32x4_t b, float acc) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    acc = fmaf(__uint_as_float(a[w] << 16), __uint_as_float(b[w] << 16), acc);
+    acc = fmaf(__uint_as_float(a[w] & 0xffff0000u), __uint_as_float(b[w] & 0xffff0000u), acc);
+  }
+  return acc;
+}
+
 // P^T and dS^T of a tile for this lane's query row (register r <-> token j0 + 8(r/4) + 4 lh + r%4).  Only tiles
 // that reach into the draft positions need the mask (a wavefront-uniform test); masked scores become -inf, and a
 // row past the group has lse = +inf, so both give p = 0 without a select.
@@ -128,7 +139,7 @@ template <int kRT /* 32-row tiles of query rows per KV head: 1 or 2 */, bool kLo
 __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ parents,
-    const bf16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    const bf16_t* __restrict__ dout, const float* __restrict__ lse, const bf16_t* __restrict__ out,
     int32_t* __restrict__ PB, float* __restrict__ part_dq, float* __restrict__ dk, float* __restrict__ dv, int B, int Nq,
     int Hq, int Hkv, int page_shift, int max_pages, float scale) {
   extern __shared__ __attribute__((aligned(1024))) char bm_lds[];
@@ -137,6 +148,7 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
   char* waves = bm_lds + 2 * kRT * kAtTileBytes;
   __shared__ int s_pb[kLocalPlan ? kLocalPlanMax + 1 : 1];
   __shared__ int s_wsum[4];
+  __shared__ float s_delta[32 * kRT];  // delta_i = <dO_i, O_i> of the pair's query rows, formed while they are staged
   if (kLocalPlan) {
     build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
     if (blockIdx.x == 0)
@@ -194,14 +206,22 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
       const size_t at = (((size_t)b * Nq + n) * Hq + hk * G + g) * kAtD;
       const u32x4_t* qp = (const u32x4_t*)(q + at);
       const u32x4_t* gp = (const u32x4_t*)(dout + at);
+      const u32x4_t* op = (const u32x4_t*)(out + at);
       const int c0 = (tid & 7) * 2, row = tid >> 3;
       const u32x4_t z = {0u, 0u, 0u, 0u};
+      float dpart = 0.f;  // this thread's share of delta = <dO, O> of the row
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int cv = ((c0 + i) ^ v_key(row)) * 16;
+        const u32x4_t gv = ok ? gp[c0 + i] : z;
         *(u32x4_t*)(qV + rt * kAtTileBytes + row * kAtRowBytes + cv) = ok ? qp[c0 + i] : z;
-        *(u32x4_t*)(doV + rt * kAtTileBytes + row * kAtRowBytes + cv) = ok ? gp[c0 + i] : z;
+        *(u32x4_t*)(doV + rt * kAtTileBytes + row * kAtRowBytes + cv) = gv;
+        dpart = dot8_bf16(gv, ok ? op[c0 + i] : z, dpart);
       }
+      dpart += __shfl_xor(dpart, 1, kWave);
+      dpart += __shfl_xor(dpart, 2, kWave);
+      dpart += __shfl_xor(dpart, 4, kWave);
+      if ((tid & 7) == 0) s_delta[32 * rt + row] = dpart;
     }
     // this lane's query row of every row tile: logsumexp (log2 units), delta and the set of tree nodes it sees;
     // rows past the group see nothing
@@ -217,7 +237,6 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
         const int node = m / G;
         const size_t row = ((size_t)b * Nq + node) * Hq + hk * G + m % G;
         lse2[rt] = lse[row] * kLog2e;
-        dlt[rt] = delta[row];
         if (parents) {
           for (int a = node, hops = 0; a >= 0 && hops <= Nq; a = parents[(size_t)b * Nq + a], ++hops) anc[rt] |= 1ull << a;
         } else {
@@ -246,6 +265,8 @@ __global__ __launch_bounds__(kBmThreads, 1) void attn_bwd_mfma_kernel(
         for (int r = 0; r < 16; ++r) dq_acc[rt][db][r] = 0.f;
 
     __syncthreads();  // query rows staged
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt) dlt[rt] = 32 * rt + li < R ? s_delta[32 * rt + li] : 0.f;
     int tt = wv;
     int pa = 0, pb = 0;
     if (tt < ntile) {
@@ -394,7 +415,7 @@ template <bool kLocalPlan>
 __global__ __launch_bounds__(kB8Threads, 1) void attn_bwd_mfma_shared_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kp, const bf16_t* __restrict__ vp,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ parents,
-    const bf16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ delta,
+    const bf16_t* __restrict__ dout, const float* __restrict__ lse, const bf16_t* __restrict__ out,
     int32_t* __restrict__ PB, float* __restrict__ part_dq, float* __restrict__ dk, float* __restrict__ dv, int B, int Nq,
     int Hq, int Hkv, int page_shift, int max_pages, float scale) {
   extern __shared__ __attribute__((aligned(1024))) char bm_lds[];
@@ -404,6 +425,7 @@ __global__ __launch_bounds__(kB8Threads, 1) void attn_bwd_mfma_shared_kernel(
   char* xt = kv + 3 * kBsKvBytes;           // per group: four transposed (P, dS) tiles
   __shared__ int s_pb[kLocalPlan ? kLocalPlanMax + 1 : 1];
   __shared__ int s_wsum[8];
+  __shared__ float s_delta[128];  // delta_i = <dO_i, O_i> of the pair's query rows, formed while they are staged
   if (kLocalPlan) {
     build_prefix(seq_lens, B, Hkv, s_pb, s_wsum);
     if (blockIdx.x == 0)
@@ -459,14 +481,22 @@ __global__ __launch_bounds__(kB8Threads, 1) void attn_bwd_mfma_shared_kernel(
       const size_t at = (((size_t)b * Nq + n) * Hq + hk * G + g) * kAtD;
       const u32x4_t* qp = (const u32x4_t*)(q + at);
       const u32x4_t* gp = (const u32x4_t*)(dout + at);
+      const u32x4_t* op = (const u32x4_t*)(out + at);
       const int c0 = (tid & 7) * 2, row = m & 31, rt = m >> 5;
       const u32x4_t z = {0u, 0u, 0u, 0u};
+      float dpart = 0.f;  // this thread's share of delta = <dO, O> of the row
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int cv = ((c0 + i) ^ v_key(row)) * 16;
+        const u32x4_t gv = ok ? gp[c0 + i] : z;
         *(u32x4_t*)(qV + rt * kAtTileBytes + row * kAtRowBytes + cv) = ok ? qp[c0 + i] : z;
-        *(u32x4_t*)(doV + rt * kAtTileBytes + row * kAtRowBytes + cv) = ok ? gp[c0 + i] : z;
+        *(u32x4_t*)(doV + rt * kAtTileBytes + row * kAtRowBytes + cv) = gv;
+        dpart = dot8_bf16(gv, ok ? op[c0 + i] : z, dpart);
       }
+      dpart += __shfl_xor(dpart, 1, kWave);
+      dpart += __shfl_xor(dpart, 2, kWave);
+      dpart += __shfl_xor(dpart, 4, kWave);
+      if ((tid & 7) == 0) s_delta[m] = dpart;
     }
     // this lane's query row (row tile = wavefront within the group)
     const int m_row = 32 * wv + li;
@@ -476,7 +506,6 @@ __global__ __launch_bounds__(kB8Threads, 1) void attn_bwd_mfma_shared_kernel(
       const int node = m_row / G;
       const size_t row = ((size_t)b * Nq + node) * Hq + hk * G + m_row % G;
       lse2 = lse[row] * kLog2e;
-      dlt = delta[row];
       if (parents) {
         for (int a = node, hops = 0; a >= 0 && hops <= Nq; a = parents[(size_t)b * Nq + a], ++hops) anc |= 1ull << a;
       } else {
@@ -502,6 +531,7 @@ __global__ __launch_bounds__(kB8Threads, 1) void attn_bwd_mfma_shared_kernel(
       for (int r = 0; r < 16; ++r) dq_acc[db][r] = 0.f;
 
     __syncthreads();  // query rows staged; the previous run is done with every buffer
+    dlt = m_row < R ? s_delta[m_row] : 0.f;
     issue_eighth(0);
     issue_eighth(1);
     for (int s = 0; s <= ntile; ++s) {
@@ -625,7 +655,7 @@ static hipError_t launch_bwd_mfma_t(const AttnBwdLaunch& a, hipStream_t st) {
     return e;
   hipLaunchKernelGGL((attn_bwd_mfma_kernel<kRT, kLocalPlan>), dim3(attn_bwd_mfma_workgroups()), dim3(kBmThreads), bm_lds_bytes(kRT), st,
                      (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
-                     (const bf16_t*)a.dout, a.lse, a.delta, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv,
+                     (const bf16_t*)a.dout, a.lse, (const bf16_t*)a.out, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv,
                      __builtin_ctz(a.page), a.max_pages, a.scale);
   return hipGetLastError();
 }
@@ -637,7 +667,7 @@ static hipError_t launch_bwd_mfma_shared(const AttnBwdLaunch& a, hipStream_t st)
     return e;
   hipLaunchKernelGGL(attn_bwd_mfma_shared_kernel<kLocalPlan>, dim3(attn_bwd_mfma_workgroups()), dim3(kB8Threads), kB8LdsBytes, st,
                      (const bf16_t*)a.q, (const bf16_t*)a.k, (const bf16_t*)a.v, a.block_table, a.seq_lens, a.parents,
-                     (const bf16_t*)a.dout, a.lse, a.delta, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv,
+                     (const bf16_t*)a.dout, a.lse, (const bf16_t*)a.out, a.plan_pb, a.part_dq, a.dk, a.dv, a.B, a.Nq, a.Hq, a.Hkv,
                      __builtin_ctz(a.page), a.max_pages, a.scale);
   return hipGetLastError();
 }
