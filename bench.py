@@ -49,6 +49,8 @@ def make_workload(name, seed):
         return gen.llama_tree(seed)
     if name == "tree_fp8kv":
         return gen.llama_tree(seed, kv_fp8=True)
+    if name == "tree_fp8":
+        return gen.llama_tree(seed, kv_fp8=True, head_fp8=True)
     if name == "stress":
         import torch
         pool_bytes = int(0.40 * torch.cuda.get_device_properties(0).total_memory)
@@ -73,7 +75,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_fp8kv", "llama_fp8", "llama_draft32k", "llama_k10", "tiny", "qwen_greedy", "tree", "tree_fp8kv", "stress"])
+    ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_fp8kv", "llama_fp8", "llama_draft32k", "llama_k10", "tiny", "qwen_greedy", "tree", "tree_fp8kv", "tree_fp8", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
     ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy", "loss", "attn_bwd"],
