@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--workload", default="llama", choices=["llama", "llama_fp8head", "llama_fp8kv", "llama_fp8", "llama_draft32k", "llama_k10", "tiny", "qwen_greedy", "tree", "tree_fp8kv", "tree_fp8", "stress"])
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-sample", type=int, default=32, help="requests given to the CPU oracle (0 = skip)")
+    ap.add_argument("--steps-only", action="store_true",
+                    help="skip the back-to-back stage timings: every kernel launch of the run then belongs to a step "
+                         "sequence (for kernel traces whose averages should be the in-step durations)")
     ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy", "loss", "attn_bwd"],
                     help="profiling aid: launch only this stage --steps times (after --warmup) and exit; "
                          "'copy' runs a plain device-to-device copy of 1 GiB for counter calibration")
@@ -184,11 +187,13 @@ def main():
     it = 20
     dv.verify()
     torch.cuda.synchronize()
-    ms_attn_b2b = event_time_ms(dv.attn, it, torch)
-    ms_lmhead_b2b = event_time_ms(dv.lmhead, it, torch)
-    ms_accept_half = event_time_ms(dv.accept, it, torch)
-    ms_verify_ev = event_time_ms(dv.verify, it, torch)
-    ms_trace = event_time_ms(dv.trace, it, torch)  # not part of a step: the emission that follows a verify
+    ms_attn_b2b = ms_lmhead_b2b = ms_accept_half = ms_verify_ev = ms_trace = None
+    if not args.steps_only:
+        ms_attn_b2b = event_time_ms(dv.attn, it, torch)
+        ms_lmhead_b2b = event_time_ms(dv.lmhead, it, torch)
+        ms_accept_half = event_time_ms(dv.accept, it, torch)
+        ms_verify_ev = event_time_ms(dv.verify, it, torch)
+        ms_trace = event_time_ms(dv.trace, it, torch)  # not part of a step: the emission that follows a verify
 
     # ---- timed region: K whole verify steps (one aurora_verify call each) ---------------------------
     for _ in range(args.warmup):
