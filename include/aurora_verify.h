@@ -10,7 +10,8 @@
  *     Descriptors are host structs, read during the call and not retained.
  *     q, k_pages, v_pages, out, hidden and lm_head must be 16-byte aligned
  *     (AURORA_ERR_INVALID_ARG otherwise).
- *   - The library allocates nothing and keeps no state.  All scratch lives in the
+ *   - The library allocates nothing and keeps no state between calls (the one process-wide
+ *     setting is the test knob aurora_debug_set_tree_spin_limit).  All scratch lives in the
  *     caller's `workspace` (device memory, 256-byte aligned, at least
  *     aurora_verify_workspace_bytes() bytes).  No pointer is retained after the
  *     enqueued work completes.  Calls with distinct workspaces may overlap.
