@@ -75,6 +75,43 @@ def test_host_validation_without_device():
     assert av.status_string(12345) == "unknown status"
 
 
+def test_training_side_entry_points_validate_on_the_host():
+    """aurora_attn_forward / aurora_attn_backward / aurora_attn_backward_saved: descriptor, pointer, alignment and
+    workspace checks come before any device is touched (addresses below are never dereferenced)."""
+    import torch
+    import paper_2602_06932_amd as av
+    ad = av.aurora_attn_desc(batch=2, num_q=5, num_q_heads=8, num_kv_heads=2, head_dim=128, page_size=16,
+                             max_pages_per_seq=4, num_pages=8, dtype=av.AURORA_BF16, sm_scale=0.0)
+    n = av.aurora_attn_backward_workspace_bytes(ad)
+    assert n % 256 == 0 and n > av.aurora_verify_workspace_bytes(ad, None)
+    big = av.aurora_attn_desc.from_buffer_copy(ad)
+    big.batch = 64
+    assert av.aurora_attn_backward_workspace_bytes(big) > n
+    f8 = av.aurora_attn_desc.from_buffer_copy(ad)
+    f8.kv_fp8, f8.k_scale, f8.v_scale = 1, 256, 512
+    with pytest.raises(av.AuroraError) as e:
+        av.aurora_attn_backward_workspace_bytes(f8)
+    assert e.value.status == av.AURORA_ERR_UNSUPPORTED
+    ws = torch.empty(n + 256, dtype=torch.uint8)
+    ws = ws[(-ws.data_ptr()) % 256:][:n]                       # a 256-byte aligned host buffer standing in for the workspace
+    P = 4096                                                    # any 16-byte aligned address
+    args = (P, P, P, P, P, None)                                # q, k, v, block_table, seq_lens, parents
+    assert av.aurora_attn_forward(ad, *args, P, None, ws, stream=0, check=False) == av.AURORA_ERR_INVALID_ARG      # no lse
+    assert av.aurora_attn_forward(ad, *args, P, P + 2, ws, stream=0, check=False) == av.AURORA_ERR_INVALID_ARG     # lse misaligned
+    bw = lambda **k: av.aurora_attn_backward_saved(ad, *args, k.get("out", P), k.get("lse", P), k.get("dout", P), k.get("dq", P),
+                                                   P, P, k.get("ws", ws), stream=0, check=False)
+    assert bw(out=None) == av.AURORA_ERR_INVALID_ARG
+    assert bw(lse=None) == av.AURORA_ERR_INVALID_ARG
+    assert bw(dout=P + 8) == av.AURORA_ERR_INVALID_ARG                                                                # misaligned
+    assert bw(dq=None) == av.AURORA_ERR_INVALID_ARG
+    assert bw(ws=ws[:n - 256]) == av.AURORA_ERR_WORKSPACE
+    assert av.aurora_attn_backward(ad, *args, P, None, P, P, ws, stream=0, check=False) == av.AURORA_ERR_INVALID_ARG  # no dq
+    assert av.aurora_attn_backward(f8, *args, P, P, P, P, ws, stream=0, check=False) == av.AURORA_ERR_UNSUPPORTED
+    empty = av.aurora_attn_desc.from_buffer_copy(ad)
+    empty.batch = 0
+    assert av.aurora_attn_backward_saved(empty, *args, P, P, P, P, P, P, ws, stream=0, check=False) == av.AURORA_OK
+
+
 def test_product_package_does_not_touch_the_oracle():
     """The product path must not import, read or call anything under oracle/."""
     pkg = os.path.join(ROOT, "paper_2602_06932_amd")
