@@ -33,9 +33,9 @@ constexpr int kCpolNT = 2;
 #define WAIT_VMCNT(n) LM_WAIT_VMCNT(n)
 
 // kFp8: operands are OCP E4M3 codes (1 byte) with one float32 scale per token row and per vocabulary
-// row; the products run on v_mfma_f32_32x32x16_fp8_fp8, whose operand layout is the bf16 one with
-// bytes for halfwords, and the scales are applied to the fp32 accumulators in the epilogue.  A stage
-// then holds 128 hidden elements per row instead of 64 - the same 128 bytes.
+// row; the products run on v_mfma_scale_f32_32x32x64_f8f6f4 (K = 64: twice the products per cycle of the
+// K = 16 fp8 form, which runs at the bf16 rate), and the scales are applied to the fp32 accumulators in the
+// epilogue.  A stage then holds 128 hidden elements per row instead of 64 - the same 128 bytes.
 template <int NT, bool kFp8>
 __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     const char* __restrict__ hidden, const char* __restrict__ w, const float* __restrict__ h_scale,
@@ -132,9 +132,8 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
   const int sw = (li >> 1) & 7;
 
   // A stage is walked in four steps of one 16-byte chunk pair per row: lane half lh takes chunk 2s + lh.
-  // For bf16 that is one MFMA step (k = 16); for fp8 the 16 bytes feed two MFMA steps (low and high 8
-  // bytes) - which hidden elements meet in which step does not matter as long as both operands are read
-  // the same way.  The operands of step s+1 are read from LDS while the MFMAs of step s run (fragments
+  // For bf16 that is one MFMA step (k = 16); the 8-bit path further down joins two steps into one K = 64
+  // MFMA.  The operands of step s+1 are read from LDS while the MFMAs of step s run (fragments
   // double-buffered in registers), and the barrier that opens the next stage sits before the last step
   // of the current one, so that the matrix pipe never waits for LDS latency or for the barrier.
   typedef __attribute__((ext_vector_type(2))) long i64x2_t;
@@ -147,25 +146,15 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
 #pragma unroll
     for (int t = 0; t < NT; ++t) f.h[t] = *(const i64x2_t*)(base + hrow_off + t * 32 * kLmRowBytes + coff);
   };
-  auto multiply = [&](const Frag& f) {
-    if constexpr (!kFp8) {
+  auto multiply = [&](const Frag& f) {  // bf16 operands
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
-          acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, f.w[a]),
-                                                              __builtin_bit_cast(bf16x8_t, f.h[t]), acc[a][t], 0, 0, 0);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 2; ++e)
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-            acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(f.w[a][e], f.h[t][e], acc[a][t], 0, 0, 0);
-    }
+      for (int t = 0; t < NT; ++t)
+        acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, f.w[a]),
+                                                            __builtin_bit_cast(bf16x8_t, f.h[t]), acc[a][t], 0, 0, 0);
   };
-  constexpr int kMfmaPerStep = (kFp8 ? 2 : 1) * 2 * NT;
+  constexpr int kMfmaPerStep = 2 * NT;
   // pins "this step's LDS reads, then the previous step's MFMAs" against the compiler's own ordering
 #define LM_STEP_ORDER()                                                 \
   do {                                                                  \
@@ -174,6 +163,66 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     __builtin_amdgcn_sched_barrier(0);                                  \
   } while (0)
 
+  if constexpr (kFp8) {
+    // 8-bit operands: the K = 16 fp8 MFMA runs at the bf16 rate; the K = 64 form (v_mfma_scale_f32_32x32x64_f8f6f4,
+    // both formats E4M3, unit scales) delivers twice the products per cycle.  It takes 32 bytes per lane and operand:
+    // the lane's 16-byte chunks of two consecutive steps (which hidden elements meet in which MFMA does not matter
+    // as long as both operands are read the same way).  A stage is two such double steps.
+    typedef __attribute__((ext_vector_type(8))) int i32x8_t;
+    typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+    struct Frag64 { i32x8_t w[2], h[NT]; };
+    auto load_frag64 = [&](int stg, int s2, Frag64& f) {
+      const char* base = lds + stg * kStageBytes;
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int coff = ((2 * (2 * s2 + e) + lh) ^ sw) * 16;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+          const i32x4_t v = *(const i32x4_t*)(base + wrow_off + a * 32 * kLmRowBytes + coff);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) f.w[a][4 * e + i] = v[i];
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const i32x4_t v = *(const i32x4_t*)(base + hrow_off + t * 32 * kLmRowBytes + coff);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) f.h[t][4 * e + i] = v[i];
+        }
+      }
+    };
+    auto multiply64 = [&](const Frag64& f) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          acc[a][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.w[a], f.h[t], acc[a][t], 0, 0, 0, 127, 0, 127);
+    };
+    // an empty statement that "uses" every accumulator and clobbers memory: the MFMAs before it cannot sink below
+    // it, the LDS reads after it cannot rise above it
+    auto pin_acc = [&]() {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) asm volatile("" : "+v"(acc[0][t]), "+v"(acc[1][t])::"memory");
+    };
+    __builtin_amdgcn_s_barrier();  // stage 0 visible
+    asm volatile("" ::: "memory");
+    int stg = 0;
+    Frag64 g;
+    for (int ks = 0; ks < nk; ++ks) {
+      load_frag64(stg, 0, g);
+      multiply64(g);
+      pin_acc();  // one fragment set in registers at a time: these MFMAs come before the next LDS reads
+      load_frag64(stg, 1, g);
+      if (ks + 1 < nk) {
+        // every LDS read of this stage has returned before the producers are told its buffer may be refilled
+        __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0) only
+        __builtin_amdgcn_s_barrier();  // stage ks+1 visible
+        asm volatile("" ::: "memory");
+        stg = stg + 1 == kLmStages ? 0 : stg + 1;
+      }
+      multiply64(g);
+      pin_acc();
+    }
+  } else {
   Frag f0, f1;
   __builtin_amdgcn_s_barrier();  // stage 0 visible
   asm volatile("" ::: "memory");
@@ -199,6 +248,7 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     }
     multiply(f1);
     LM_STEP_ORDER();
+  }
   }
 #undef LM_STEP_ORDER
 
