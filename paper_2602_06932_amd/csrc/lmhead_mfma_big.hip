@@ -11,14 +11,16 @@
 // stage sits before the last step of the current one, so the matrix pipe never waits on it.
 // The eight 16-byte chunks of a row segment are XOR-swizzled by (row / 2) mod 8 on the way in, which
 // makes the 128-bit operand reads conflict free on the 64-bank LDS.
+// kFp8: operands are E4M3 codes with one float32 scale per token row and per vocabulary row (as in the small-M
+// kernel): a stage of 128 bytes per row is then 128 hidden elements, multiplied by two K = 64 MFMAs per accumulator
+// tile (v_mfma_scale_f32_32x32x64_f8f6f4, unit scales); the scales are applied to the accumulators in the epilogue.
 #include "launch.hpp"
 #include "lmhead_tile.hpp"
 
 namespace aurora {
 
 constexpr int kBgThreads = 512;
-constexpr int kBgBK = 64;                       // hidden elements per stage
-constexpr int kBgRowBytes = kBgBK * 2;          // 128
+constexpr int kBgRowBytes = 128;                // bytes of a row segment per stage: 64 bf16 or 128 fp8 elements
 constexpr int kBgVTile = 256;                   // vocab rows per workgroup (= statistics tile)
 constexpr int kBgMTile = 256;                   // token rows per workgroup, at most
 constexpr int kBgWBytes = kBgVTile * kBgRowBytes;  // 32 KB: one stage of W rows
@@ -37,8 +39,10 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
 }
 
+template <bool kFp8>
 __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
-    const bf16_t* __restrict__ hidden, const bf16_t* __restrict__ w, float* __restrict__ logits,
+    const char* __restrict__ hidden, const char* __restrict__ w, const float* __restrict__ h_scale,
+    const float* __restrict__ w_scale, float* __restrict__ logits,
     float* __restrict__ pmax, float* __restrict__ psum, int32_t* __restrict__ parg, int M, int H, int V, int n_tiles,
     int m_tiles, float exp_scale /* log2(e) / T */, const float* __restrict__ temps /* per-request T, or NULL */,
     int Nq) {
@@ -59,7 +63,8 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
   const int vbase = vt * kBgVTile;
   const int m0 = mt * kBgMTile;
   const int tb0 = wm * 4;  // first 32-token tile of this wavefront; rows past M are loaded clamped and never stored
-  const int nk = H / kBgBK;
+  constexpr int kEsz = kFp8 ? 1 : 2;  // bytes per operand element
+  const int nk = H * kEsz / kBgRowBytes;
   const unsigned lds0 = (unsigned)(uintptr_t)lds;  // LDS pointers are 32-bit offsets
 
   // ---- loader role: 64 rows of one operand per wavefront and stage.  A wavefront's vmcnt queue holds one
@@ -67,7 +72,7 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
   const bool w_loader = wave < 4;
   const int depth = w_loader ? kBgWStages : kBgHStages;
   const int lrow = lane >> 3, lslot = lane & 7;
-  const bf16_t* src[8];
+  const char* src[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int r = 64 * (wave & 3) + 8 * j + lrow;
@@ -76,12 +81,12 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
     vrow = vrow < V ? vrow : V - 1;
     int hrow = m0 + r;
     hrow = hrow < M ? hrow : M - 1;
-    src[j] = w_loader ? w + (size_t)vrow * H + chunk * 8 : hidden + (size_t)hrow * H + chunk * 8;
+    src[j] = w_loader ? w + ((size_t)vrow * H * kEsz + chunk * 16) : hidden + ((size_t)hrow * H * kEsz + chunk * 16);
   }
   const unsigned ring0 = lds0 + (w_loader ? 0 : kBgWRing) + 64 * (wave & 3) * kBgRowBytes;
   auto issue = [&](int ks, int slot) {
     const unsigned base = ring0 + slot * kBgWBytes;
-    const int koff = ks * kBgBK;
+    const int koff = ks * kBgRowBytes;
 #pragma unroll
     for (int j = 0; j < 8; ++j) dma16(src[j] + koff, base + 8 * j * kBgRowBytes);
   };
@@ -135,10 +140,64 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
   wait_younger(nk - 1 < depth - 1 ? nk - 1 : depth - 1);
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  bf16x8_t wa0[2], hb0[4], wa1[2], hb1[4];
-  load_frag(0, 0, 0, wa0, hb0);
   int wslot = 0, hslot = 0;  // ring slots of the stage being multiplied
   int myslot = 0;            // the same for this wavefront's loader ring
+  if constexpr (kFp8) {
+    // a double step = the lane's 16-byte chunks of two consecutive steps = 32 bytes per operand = one K = 64 MFMA per
+    // accumulator tile; one fragment set at a time (a second set spills into the main loop: five times slower)
+    typedef __attribute__((ext_vector_type(8))) int i32x8_t;
+    typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+    i32x8_t wa[2], hb[4];
+    auto load64 = [&](int s2) {
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int coff = ((2 * (2 * s2 + e) + lh) ^ sw) * 16;
+        const char* wb = lds + wslot * kBgWBytes + wrow_off + coff;
+        const char* hbp = lds + hslot * kBgHBytes + hrow_off + coff;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+          const i32x4_t v = *(const i32x4_t*)(wb + a * 32 * kBgRowBytes);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) wa[a][4 * e + i] = v[i];
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const i32x4_t v = *(const i32x4_t*)(hbp + t * 32 * kBgRowBytes);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) hb[t][4 * e + i] = v[i];
+        }
+      }
+    };
+    auto multiply64 = [&]() {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+          acc[a][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wa[a], hb[t], acc[a][t], 0, 0, 0, 127, 0, 127);
+      // the MFMAs above cannot sink below this point, the LDS reads after it cannot rise above it
+#pragma unroll
+      for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(acc[0][t]), "+v"(acc[1][t])::"memory");
+    };
+    for (int ks = 0; ks < nk; ++ks) {
+      load64(0);
+      multiply64();
+      load64(1);
+      if (ks + 1 < nk) {
+        // every read of stage ks by this wavefront has returned before it says so to the others
+        __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0) only
+        wait_younger(nk - 2 - ks < depth - 2 ? nk - 2 - ks : depth - 2);
+        __builtin_amdgcn_s_barrier();  // stage ks+1 visible to all; nobody reads stage ks's slots again
+        asm volatile("" ::: "memory");
+        if (ks + depth < nk) issue(ks + depth, myslot);
+        myslot = myslot + 1 == depth ? 0 : myslot + 1;
+        wslot = wslot + 1 == kBgWStages ? 0 : wslot + 1;
+        hslot = hslot + 1 == kBgHStages ? 0 : hslot + 1;
+      }
+      multiply64();
+    }
+  } else {
+  bf16x8_t wa0[2], hb0[4], wa1[2], hb1[4];
+  load_frag(0, 0, 0, wa0, hb0);
   for (int ks = 0; ks + 1 < nk; ++ks) {
     load_frag(wslot, hslot, 1, wa1, hb1);
     multiply(wa0, hb0);
@@ -169,6 +228,7 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
   load_frag(wslot, hslot, 3, wa1, hb1);
   multiply(wa0, hb0);
   multiply(wa1, hb1);
+  }
 #undef BG_STEP_ORDER
   __syncthreads();  // every wavefront is done with the ring; it becomes epilogue scratch
 
@@ -180,6 +240,29 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
   int* st_arg = (int*)(st_sum + 4 * kBgMTile);
   const int vrow0 = vbase + wvv * 64;
   const bool vec_ok = (V & 3) == 0;
+  if constexpr (kFp8) {
+    // dequantise: accumulator (vocab row v, token m) times w_scale[v] * h_scale[m]
+    float hs[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int m = m0 + (tb0 + t) * 32 + li;
+      hs[t] = h_scale[m < M ? m : M - 1];
+    }
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        // four consecutive vocabulary rows: 8(r/4) + 4 lh + r%4 for r = 4g .. 4g+3
+        const int v = vrow0 + 32 * a + 8 * g + 4 * lh;
+        float wsc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) wsc[e] = w_scale[v + e < V ? v + e : V - 1];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[a][t][4 * g + e] *= wsc[e] * hs[t];
+      }
+  }
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     const int col0 = (tb0 + t) * 32;
@@ -211,21 +294,28 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
 }
 
 bool lmhead_mfma_big_supported(const AcceptLaunch& a) {
-  return a.bf16 && a.H % kBgBK == 0 && a.H >= kBgBK && a.V >= 1 && a.plan.stat_tile == kBgVTile;
+  const int esz = a.fp8 ? 1 : 2;
+  return (a.bf16 || a.fp8) && (a.H * esz) % kBgRowBytes == 0 && a.H * esz >= kBgRowBytes && a.V >= 1 &&
+         a.plan.stat_tile == kBgVTile;
 }
 
-hipError_t launch_lmhead_mfma_big(const AcceptLaunch& a, hipStream_t st) {
+template <bool kFp8>
+static hipError_t launch_big_t(const AcceptLaunch& a, hipStream_t st) {
   static LdsAttrOnce attr;
-  if (hipError_t e = attr.ensure((const void*)lmhead_mfma_big_kernel, kBgLdsBytes); e != hipSuccess) return e;
+  if (hipError_t e = attr.ensure((const void*)lmhead_mfma_big_kernel<kFp8>, kBgLdsBytes); e != hipSuccess) return e;
   const int M = (int)a.plan.rows;
   const int m_tiles = (M + kBgMTile - 1) / kBgMTile;
   const float exp_scale = 1.4426950408889634f / (a.temperature > 0.f ? a.temperature : 1.f);
   const int v_tiles = (a.V + kBgVTile - 1) / kBgVTile;
   dim3 grid((v_tiles + 7) / 8 * 8 * m_tiles);
-  hipLaunchKernelGGL(lmhead_mfma_big_kernel, grid, dim3(kBgThreads), kBgLdsBytes, st, (const bf16_t*)a.hidden,
-                     (const bf16_t*)a.lm_head, a.logits, a.pmax, a.psum, a.parg, M, a.H, a.V, a.plan.n_tiles, m_tiles,
-                     exp_scale, a.temps, a.Nq);
+  hipLaunchKernelGGL(lmhead_mfma_big_kernel<kFp8>, grid, dim3(kBgThreads), kBgLdsBytes, st, (const char*)a.hidden,
+                     (const char*)a.lm_head, a.hidden_scale, a.lm_scale, a.logits, a.pmax, a.psum, a.parg, M, a.H, a.V,
+                     a.plan.n_tiles, m_tiles, exp_scale, a.temps, a.Nq);
   return hipGetLastError();
+}
+
+hipError_t launch_lmhead_mfma_big(const AcceptLaunch& a, hipStream_t st) {
+  return a.fp8 ? launch_big_t<true>(a, st) : launch_big_t<false>(a, st);
 }
 
 }  // namespace aurora

@@ -388,6 +388,28 @@ def test_fp8_lm_head_tree_and_draft_subvocabulary(gpu_lib):
     _full_check(gpu_lib, w)
 
 
+@pytest.mark.parametrize("batch,vocab,hidden", [(96, 3001, 384), (52, 777, 1024)])
+def test_fp8_lm_head_many_token_rows(gpu_lib, batch, vocab, hidden):
+    """Enough token rows (480, 260) for the 256 x 256-tile kernel with 8-bit operands: K = 64 MFMAs, scales in the
+    epilogue; a vocabulary that ends inside a tile, one to eight stages of the hidden dimension."""
+    w = gen.llama_chain(32, batch=batch, len_lo=20, len_hi=60, vocab=vocab, hidden_size=hidden, head_fp8=True,
+                        draft_noise=0.5)
+    _, a = _full_check(gpu_lib, w)
+    assert a.accept_len.max() > 0
+
+
+def test_fp8_lm_head_tree_many_token_rows(gpu_lib):
+    w = gen.llama_tree(33, batch=8, num_q=32, vocab=20011, hidden_size=256, context=64, num_q_heads=4, num_kv_heads=2,
+                       head_fp8=True, kv_fp8=True, draft_noise=0.5)
+    _full_check(gpu_lib, w)
+
+
+def test_full_size_tree_with_fp8_head_and_cache(gpu_lib):
+    """Config 4's shapes with LM head and KV cache in 8 bits (bench.py --workload tree_fp8)."""
+    w = gen.llama_tree(1, kv_fp8=True, head_fp8=True)
+    _full_check(gpu_lib, w, sample=[0, 9])
+
+
 def test_fp8_lm_head_rejects_unsupported_hidden_size(gpu_lib):
     av = gpu_lib
     d = av.aurora_accept_desc(batch=1, num_q=2, hidden=192, vocab=100, dtype=av.AURORA_FP8_E4M3, temperature=1.0,
