@@ -97,6 +97,116 @@ def test_greedy_lowest_index_on_exact_tie():
     assert r.accept_len[0] == 0 and r.next_token[0] == 2
 
 
+# ------------------------------------------------------------------ P1 on branching trees (hand-worked)
+GOLDEN_TREE = os.path.join(os.path.dirname(__file__), "golden", "greedy_tree_hand_worked.txt")
+
+
+def _parse_golden_tree():
+    cases = []
+    for line in open(GOLDEN_TREE):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        lhs, rhs = line.split("->")
+        name, par, toks, best = lhs.split()
+        ints = lambda s: [int(x) for x in s.split(",")]
+        alen, nxt, mask, stop = rhs.split()
+        cases.append(dict(name=name, par=ints(par), toks=ints(toks), best=ints(best), accept_len=int(alen),
+                          next_token=int(nxt), mask=ints(mask), stop=int(stop)))
+    return cases
+
+
+def _logits_with_best(best, V, rng):
+    """A row per node whose largest entry is at best[n]; the other entries are a scrambled descending ramp."""
+    lg = np.empty((len(best), V))
+    for n, t in enumerate(best):
+        lg[n] = rng.permutation(np.linspace(-3.0, 1.0, V))
+        lg[n, t] = 2.5
+    return lg
+
+
+@pytest.mark.parametrize("case", _parse_golden_tree(), ids=lambda c: c["name"])
+def test_greedy_walk_on_hand_worked_branching_trees(case):
+    V = 16
+    Nq = len(case["par"])
+    lg = _logits_with_best(case["best"], V, np.random.default_rng(Nq))
+    # two copies of the request in one batch: the second one checks the per-request offsets of parents / tokens
+    r = oracle.accept_from_logits(logits=np.stack([lg, lg]), draft_tokens=np.array([case["toks"]] * 2, np.int32),
+                                  parents=np.array([case["par"]] * 2, np.int32), temperature=0.0)
+    for b in range(2):
+        assert int(r.accept_len[b]) == case["accept_len"]
+        assert int(r.next_token[b]) == case["next_token"]
+        assert r.accept_mask[b].tolist() == case["mask"]
+        assert int(r.stop_node[b]) == case["stop"]
+    # p_at_draft at T = 0: 1 where the node's token is its PARENT's arg-max, else 0
+    want = [0.0] + [1.0 if case["toks"][n] == case["best"][case["par"][n]] else 0.0 for n in range(1, Nq)]
+    assert r.p_at_draft[0].tolist() == want
+
+
+def test_greedy_tree_walk_agrees_with_a_recursive_search_on_random_trees():
+    """Independent statement of the same rule: the accepted path is the root plus, recursively, the path from the
+    lowest-numbered child carrying the current arg-max.  Random trees with up to 4 children per node and many
+    duplicated tokens, so that wrong-parent and duplicate-sibling situations occur all the time."""
+    rng = np.random.default_rng(77)
+    B, Nq, V = 400, 12, 5
+    logits = rng.standard_normal((B, Nq, V))
+    top = logits.argmax(-1)
+    par = np.full((B, Nq), -1, np.int32)
+    for n in range(1, Nq):
+        par[:, n] = rng.integers(0, n, B)
+    toks = rng.integers(0, V, (B, Nq)).astype(np.int32)
+    r = oracle.accept_from_logits(logits=logits, draft_tokens=toks, parents=par, temperature=0.0)
+
+    def path_from(b, n):
+        kids = [c for c in range(n + 1, Nq) if par[b, c] == n and toks[b, c] == top[b, n]]
+        return [n] + (path_from(b, min(kids)) if kids else [])
+
+    depths = []
+    for b in range(B):
+        path = path_from(b, 0)
+        mask = np.zeros(Nq, np.uint8)
+        mask[path] = 1
+        assert r.accept_len[b] == len(path) - 1 and r.stop_node[b] == path[-1]
+        assert r.next_token[b] == top[b, path[-1]]
+        assert np.array_equal(r.accept_mask[b], mask)
+        depths.append(len(path) - 1)
+    assert max(depths) >= 3 and min(depths) == 0
+
+
+def test_p_at_draft_and_row_lse_on_a_branching_tree_against_library_softmax():
+    """p_at_draft[n] = softmax(l[parent(n)] / T)[tok_n] gathered through non-chain parents (a chain-only gather
+    `row n-1` fails here), and row_lse = logsumexp(l / T); at T = 0 the reading is logsumexp of the raw logits."""
+    from scipy.special import logsumexp, softmax
+    rng = np.random.default_rng(78)
+    B, V = 7, 33
+    par = np.array([-1, 0, 0, 1, 0, 2, 2, 4, 1, 7], np.int32)
+    Nq = len(par)
+    assert (par[1:] != np.arange(Nq - 1)).sum() >= 6
+    logits = rng.standard_normal((B, Nq, V)) * 2.0
+    toks = rng.integers(0, V, (B, Nq)).astype(np.int32)
+    q = _rand_dist(rng, (B, Nq, V)).astype(np.float32)
+    un = gen.workloads._uniform24(rng, (B, Nq, 2))
+    parents = np.broadcast_to(par, (B, Nq)).copy()
+    for T in (1.0, 0.6):
+        Tf = float(np.float32(T))
+        r = oracle.accept_from_logits(logits=logits, draft_tokens=toks, draft_probs=q, uniforms=un, parents=parents,
+                                      temperature=T)
+        p = softmax(logits / Tf, axis=-1)
+        want = p[np.arange(B)[:, None], par[None, 1:], toks[:, 1:]]
+        np.testing.assert_allclose(r.p_at_draft[:, 1:], want, rtol=1e-11)
+        assert (r.p_at_draft[:, 0] == 0).all()
+        np.testing.assert_allclose(r.row_lse, logsumexp(logits / Tf, axis=-1), rtol=1e-13)
+    r0 = oracle.accept_from_logits(logits=logits, draft_tokens=toks, parents=parents, temperature=0.0)
+    np.testing.assert_allclose(r0.row_lse, logsumexp(logits, axis=-1), rtol=1e-13)
+    top = logits.argmax(-1)
+    want0 = (toks[:, 1:] == top[np.arange(B)[:, None], par[None, 1:]]).astype(np.float64)
+    assert np.array_equal(r0.p_at_draft[:, 1:], want0)
+    # chain form at T = 0 as well
+    rc = oracle.accept_from_logits(logits=logits, draft_tokens=toks, temperature=0.0)
+    np.testing.assert_allclose(rc.row_lse, logsumexp(logits, axis=-1), rtol=1e-13)
+    assert np.array_equal(rc.p_at_draft[:, 1:], (toks[:, 1:] == top[:, :-1]).astype(np.float64))
+
+
 # ------------------------------------------------------------------ P2 q == p
 @pytest.mark.parametrize("T", [1.0, 0.7])
 def test_q_equal_p_accepts_everything(T):
