@@ -155,8 +155,10 @@ int aurora_verify_attn(const aurora_attn_desc* desc,
  *
  * Tree walks at T > 0 over large vocabularies are split over several workgroups per request that wait for each
  * other between vocabulary sweeps.  They fit the device together when nothing else occupies it; the wait is
- * bounded all the same, and a request whose workgroups did not meet in time gets accept_len = next_token = -1
- * (its other outputs are then unspecified): run the call again.  Chains and greedy calls never wait.
+ * bounded all the same: when the workgroups of a request do not meet in time (a GPU shared with other work), one
+ * of them finishes the request alone inside the same call, with the same result bit for bit, only later.  The
+ * outputs are therefore always complete and valid once the stream is synchronised.  Chains and greedy calls
+ * never wait.
  */
 int aurora_verify_accept(const aurora_accept_desc* desc,
                          const void* hidden,          /* [B, Nq, H]                           */
@@ -298,8 +300,9 @@ int aurora_trace_emit(const aurora_trace_desc* desc,
                       void* hip_stream);
 
 /* For tests of the bounded wait described at aurora_verify_accept: the number of polls of the arrival counter a
- * workgroup of a split tree walk makes before it gives up (process-wide, applies to later calls; negative restores
- * the default of 2^21, about a second).  0 makes every wait fail at once unless the others have already arrived. */
+ * workgroup of a split tree walk makes before it stops waiting (process-wide, applies to later calls; negative
+ * restores the default of 2^15, some tens of milliseconds).  0 makes every wait fail at once unless the others have
+ * already arrived, which forces the finish-alone path; results do not depend on the setting. */
 void aurora_debug_set_tree_spin_limit(int polls);
 
 /* Human-readable name of a status code; never NULL. */

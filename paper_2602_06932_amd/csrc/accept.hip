@@ -486,7 +486,7 @@ __global__ __launch_bounds__(kSmallThreads) void accept_chain_pick(AcceptParams 
 // so all workgroups of a request are resident together; the wait on the counter is bounded all the same.
 // ============================================================================================
 constexpr int kTreeMaxSlices = 16;
-constexpr int kSpinLimit = 1 << 21;  // default number of polls of the arrival counter (about a second) before giving up
+constexpr int kSpinLimit = 1 << 15;  // default number of polls of the arrival counter (tens of milliseconds) before a workgroup stops waiting
 
 // The values exchanged between the workgroups of a request are written and read with device-scope
 // atomic accesses: on this multi-die part they go past the die-local L2 to the point all dies see, so the
@@ -607,9 +607,10 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
   const int ngroups = (V + kGroup - 1) / kGroup;  // <= kMaxGroups (checked by the launcher)
   const bool vec_ok = rows_vec_ok(P);
   const int per_slice = (ngroups + S - 1) / S;
-  const int g_lo = slice * per_slice;
-  const int g_hi = min(ngroups, g_lo + per_slice);
-  int sweeps = 0;  // sweeps done so far: the same in every workgroup of the request
+  int g_lo = slice * per_slice;
+  int g_hi = min(ngroups, g_lo + per_slice);
+  bool split = S > 1;  // false once the writer has stopped waiting for the others and carries on alone
+  int sweeps = 0;      // sweeps done so far: the same in every workgroup of the request
   const bool wor = P.wor != 0;
   const QLevels ql = {s_rej, s_qlen, s_qfac};
   if (tid == 0) {
@@ -668,7 +669,8 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       const bool skip_last = state == ST_REJECTED;
       int lastpos = -1;
       constexpr int kBatch = 5;  // groups whose loads a wavefront keeps in flight together (160 KB per workgroup)
-      double* gs_out = P.gsum + ((size_t)b * 2 + (sweeps & 1)) * ngroups;  // used when S > 1
+      double* gs_out = P.gsum + ((size_t)b * 2 + (sweeps & 1)) * ngroups;  // used while split
+    sweep_again:
       for (int g = g_lo + wv; g < g_hi; g += kBatch * kAccWaves) {
         Lane4 r[kBatch];
 #pragma unroll
@@ -689,7 +691,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
               if (x[e] > 0.0) lastpos = max(lastpos, v0 + e);
             const double sg = wave_sum((x[0] + x[1]) + (x[2] + x[3]));
             if (lane == 0) {
-              if (S > 1) store_agent(&gs_out[gi], sg); else s_gsum[gi] = sg;
+              if (split) store_agent(&gs_out[gi], sg); else s_gsum[gi] = sg;
             }
           }
         }
@@ -698,7 +700,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
       if (tid == 0) s_lastpos = -1;
       __syncthreads();
       if (lane == 0) atomicMax(&s_lastpos, lastpos);
-      if (S > 1) {
+      if (split) {
         // ---- exchange with the request's other workgroups ----------------------------------------
         wait_stores_acknowledged();  // this thread's group sums, before the arrival is counted
         __syncthreads();
@@ -706,22 +708,30 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
         if (tid == 0) {
           store_agent(&lp[slice], s_lastpos);
           wait_stores_acknowledged();
-          atomicAdd(&P.tree_bar[b], 1);
+          // release: everything this workgroup stored (ordered before this thread by the barrier above) is
+          // visible device-wide before the arrival is
+          __hip_atomic_fetch_add(&P.tree_bar[b], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
           const int target = S * (sweeps + 1);
           int polls = 0;
           while (load_agent(&P.tree_bar[b]) < target) {
-            __builtin_amdgcn_s_sleep(4);
             if (++polls > P.spin_limit) { s_fail = 1; break; }
+            __builtin_amdgcn_s_sleep(4);
           }
+          // acquire: pairs with the release of every arrival counted above
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
         __syncthreads();
         if (s_fail) {
-          // a workgroup of the request never arrived: give up rather than wait for ever, and say so
-          if (writer && tid == 0) {
-            P.accept_len[b] = -1;
-            P.next_token[b] = -1;
-          }
-          return;
+          // A workgroup of the request has not arrived within the bound (the GPU is shared and they are not all
+          // resident, or one of them gave up earlier).  The others leave; the writer, which holds the whole walk
+          // state like every workgroup, repeats this sweep over the entire vocabulary by itself and finishes the
+          // request as the one-workgroup form would: same sums in the same order, so the same result.
+          if (!writer) return;
+          split = false;
+          g_lo = 0;
+          g_hi = ngroups;
+          lastpos = -1;
+          goto sweep_again;
         }
         // loads that bypass this compute unit's L1, which may still hold the copy of two sweeps ago
         for (int g = tid; g < ngroups; g += kAccThreads) s_gsum[g] = load_agent(&gs_out[g]);
