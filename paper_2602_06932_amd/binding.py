@@ -72,6 +72,13 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2602_06932_amd.build` "
                           "(or __graft_entry__.build()) first")
+    # One HIP runtime per process: PyTorch ships its own copy of the runtime library, and device pointers and
+    # streams made by one copy mean nothing to another.  Importing torch first makes the loader resolve this
+    # library's dependency to the copy torch has already mapped, whatever order the caller imports things in.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     vp, i32p, f32p, u8p = C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p
     ad, cd = C.POINTER(aurora_attn_desc), C.POINTER(aurora_accept_desc)
