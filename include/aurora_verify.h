@@ -42,8 +42,12 @@ enum {
   AURORA_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, Hq % Hkv != 0, ...      */
   AURORA_ERR_UNSUPPORTED = -2, /* well-formed but outside what the kernels cover           */
   AURORA_ERR_WORKSPACE = -3,   /* workspace null, misaligned or too small                  */
-  AURORA_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed               */
+  AURORA_ERR_HIP = -4,         /* a HIP runtime call or kernel launch failed               */
+  AURORA_ERR_TOO_LARGE = -5    /* aurora_verify_attn_static: needs more than AURORA_STATIC_SCRATCH_BYTES */
 };
+
+/* Size of the fixed scratch array behind aurora_verify_attn_static (bytes, per GPU the library runs on). */
+#define AURORA_STATIC_SCRATCH_BYTES (16u << 20)
 
 enum { AURORA_F32 = 0, AURORA_BF16 = 1, AURORA_FP8_E4M3 = 2 /* LM-head operands only, see aurora_accept_desc */ };
 
@@ -137,6 +141,22 @@ int aurora_verify_attn(const aurora_attn_desc* desc,
                        const int32_t* parents,     /* [B, Nq], parents[b,0] = -1, parents[b,n] < n; or NULL */
                        void* out,                  /* [B, Nq, Hq, D], same dtype as q         */
                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * aurora_verify_attn for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * `out`; the partial results the kernels exchange live in a fixed array of AURORA_STATIC_SCRATCH_BYTES (16 MiB)
+ * inside the library instead of a caller's workspace - one copy per GPU, held until the process ends.  The call
+ * allocates and frees nothing (the array's device address is looked up once per device, on the first call there).
+ *   - Returns AURORA_ERR_TOO_LARGE, with nothing enqueued, when aurora_verify_workspace_bytes(desc, NULL) exceeds
+ *     AURORA_STATIC_SCRATCH_BYTES (the headline shape - 32 requests, 8 KV heads, 20 query rows per KV head - needs
+ *     12.6 MiB; 32-node trees of 16 requests do not fit).
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race.
+ *     Calls on one stream, or otherwise ordered, are safe; nothing of a previous call's contents is relied upon.
+ */
+int aurora_verify_attn_static(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                              const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents, void* out,
+                              void* hip_stream);
 
 /*
  * LM head + softmax + acceptance (sections 2.1, 3.1, 3.3; appendix A.1).

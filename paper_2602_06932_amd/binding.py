@@ -15,6 +15,8 @@ AURORA_ERR_INVALID_ARG = -1
 AURORA_ERR_UNSUPPORTED = -2
 AURORA_ERR_WORKSPACE = -3
 AURORA_ERR_HIP = -4
+AURORA_ERR_TOO_LARGE = -5
+AURORA_STATIC_SCRATCH_BYTES = 16 << 20
 AURORA_F32 = 0
 AURORA_BF16 = 1
 AURORA_FP8_E4M3 = 2
@@ -24,7 +26,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_v
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
            "aurora_verify_lmhead", "aurora_verify_accept_logits", "aurora_trace_emit",
            "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack", "aurora_attn_backward",
-           "aurora_attn_backward_workspace_bytes", "aurora_attn_forward", "aurora_attn_backward_saved", "aurora_debug_set_tree_spin_limit")
+           "aurora_attn_backward_workspace_bytes", "aurora_attn_forward", "aurora_attn_backward_saved", "aurora_debug_set_tree_spin_limit", "aurora_verify_attn_static")
 
 
 class aurora_attn_desc(C.Structure):
@@ -86,6 +88,8 @@ def load():
     lib.aurora_verify_workspace_bytes.restype = C.c_int
     lib.aurora_verify_attn.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, vp, C.c_size_t, vp]
     lib.aurora_verify_attn.restype = C.c_int
+    lib.aurora_verify_attn_static.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, vp]
+    lib.aurora_verify_attn_static.restype = C.c_int
     lib.aurora_verify_accept.argtypes = [cd, vp, vp, i32p, f32p, f32p, i32p, i32p, i32p, u8p, f32p, f32p, vp,
                                          C.c_size_t, vp]
     lib.aurora_verify_accept.restype = C.c_int
@@ -166,6 +170,15 @@ def aurora_verify_attn(desc, q, k_pages, v_pages, block_table, seq_lens, parents
                                    _ptr(seq_lens), _ptr(parents), _ptr(out), _ptr(workspace), wb, _stream(stream))
     if check and st != AURORA_OK:
         raise AuroraError(st, "aurora_verify_attn")
+    return st
+
+
+def aurora_verify_attn_static(desc, q, k_pages, v_pages, block_table, seq_lens, parents, out, stream=None,
+                              check=True) -> int:
+    st = load().aurora_verify_attn_static(_ref(desc), _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                          _ptr(seq_lens), _ptr(parents), _ptr(out), _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_verify_attn_static")
     return st
 
 

@@ -3,6 +3,8 @@
 #include "common.hpp"
 #include "launch.hpp"
 
+#include <mutex>
+
 using namespace aurora;
 
 namespace {
@@ -202,6 +204,30 @@ int run_lmhead(const aurora_accept_desc* desc, const void* hidden, const void* l
   return e == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
 }
 
+// ---- the allocation-free attention entry point's scratch -------------------------------------------------
+// One array per GPU the library is loaded on, held until the process ends.  In host code the name `scratch` is
+// only a handle for the symbol: the device address is looked up once per device and kept in g_scratch_ptr.
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[AURORA_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up on the first call per device).
+hipError_t static_scratch(void** out) {
+  int dev = -1;
+  if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 bool have_device() {
   static int cached = -1;  // the answer does not change during a process's life
   if (cached < 0) {
@@ -239,6 +265,21 @@ int aurora_verify_attn(const aurora_attn_desc* desc, const void* q, const void* 
   if (rc != AURORA_OK) return rc;
   if (!have_device()) return AURORA_ERR_HIP;
   return run_attn(desc, q, k_pages, v_pages, block_table, seq_lens, parents, out, workspace, workspace_bytes,
+                  (hipStream_t)hip_stream);
+}
+
+int aurora_verify_attn_static(const aurora_attn_desc* desc, const void* q, const void* k_pages, const void* v_pages,
+                              const int32_t* block_table, const int32_t* seq_lens, const int32_t* parents, void* out,
+                              void* hip_stream) {
+  int rc = check_attn_desc(desc);
+  if (rc != AURORA_OK) return rc;
+  const size_t need = plan_attn(desc).bytes;
+  if (need > (size_t)AURORA_STATIC_SCRATCH_BYTES) return AURORA_ERR_TOO_LARGE;
+  if (!have_device()) return AURORA_ERR_HIP;
+  void* ws = nullptr;
+  if (static_scratch(&ws) != hipSuccess) return AURORA_ERR_HIP;
+  // the kernels write every partial they later read, so nothing of the previous call's contents needs clearing
+  return run_attn(desc, q, k_pages, v_pages, block_table, seq_lens, parents, out, ws, AURORA_STATIC_SCRATCH_BYTES,
                   (hipStream_t)hip_stream);
 }
 
@@ -514,6 +555,9 @@ const char* aurora_status_string(int status) {
     case AURORA_ERR_UNSUPPORTED: return "unsupported configuration";
     case AURORA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case AURORA_ERR_HIP: return "HIP runtime error or no device";
+    case AURORA_ERR_TOO_LARGE:
+      return "problem needs more scratch than the allocation-free entry point's fixed array (AURORA_STATIC_SCRATCH_BYTES) "
+             "holds; use the entry point that takes a workspace";
     default: return "unknown status";
   }
 }
