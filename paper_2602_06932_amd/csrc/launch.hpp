@@ -53,6 +53,7 @@ hipError_t launch_attn_combine(const AttnLaunch& a, hipStream_t st);
 bool lmhead_mfma_supported(const AcceptLaunch& a);
 int lmhead_mfma_stat_tile();
 hipError_t launch_lmhead_mfma(const AcceptLaunch& a, hipStream_t st);  // picks the small- or large-M kernel
+constexpr int kLmBigFromRows = 384;  // token rows from which the tiled many-row kernel takes the LM head
 bool lmhead_mfma_big_supported(const AcceptLaunch& a);
 hipError_t launch_lmhead_mfma_big(const AcceptLaunch& a, hipStream_t st);
 hipError_t launch_lmhead_generic(const AcceptLaunch& a, hipStream_t st);

@@ -2,8 +2,11 @@
 // contraction is bound by the matrix cores rather than by the sweep over W (appendix A.1, eq. 4 of the
 // paper: target logits l in R^{T x V}; softmax statistics fused as in the small-M kernel).
 //
-// One workgroup of 8 wavefronts owns 256 vocabulary rows x up to 256 token rows; wavefront (v, m) owns
-// 64 vocab rows x up to 128 tokens (2 x 4 accumulator tiles of v_mfma_f32_32x32x16_bf16).  Every
+// One workgroup of 8 wavefronts owns 256 vocabulary rows x 64 NT token rows (NT = 1..4); wavefront (v, m) owns
+// 64 vocab rows x 32 NT tokens (2 x NT accumulator tiles of v_mfma_f32_32x32x16_bf16).  The token rows of a call
+// are cut into pairs of 32-row tiles and the pairs dealt evenly to the fewest workgroup columns, so a launch uses
+// at most two values of NT, one apart (448 rows: 7 pairs = 4 + 3), and no matrix-core work is spent on padding
+// beyond the last pair.  Every
 // wavefront multiplies; wavefronts 0-3 also load W and 4-7 the token rows, each operand into its own
 // LDS ring (W: 3 stages of 32 KB, it comes from HBM; token rows: 2 stages, they come from L2), by direct
 // global->LDS loads of 128-byte row segments.  A stage is 64 hidden elements = 4 MFMA steps; operand
@@ -39,43 +42,54 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
 }
 
-template <bool kFp8>
-__global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
-    const char* __restrict__ hidden, const char* __restrict__ w, const float* __restrict__ h_scale,
-    const float* __restrict__ w_scale, float* __restrict__ logits,
-    float* __restrict__ pmax, float* __restrict__ psum, int32_t* __restrict__ parg, int M, int H, int V, int n_tiles,
-    int m_tiles, float exp_scale /* log2(e) / T */, const float* __restrict__ temps /* per-request T, or NULL */,
-    int Nq) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
+struct BgArgs {
+  const char* hidden;
+  const char* w;
+  const float* h_scale;
+  const float* w_scale;
+  float* logits;
+  float* pmax;
+  float* psum;
+  int32_t* parg;
+  int M, H, V, n_tiles;
+  float exp_scale;     // log2(e) / T
+  const float* temps;  // per-request T, or NULL
+  int Nq;
+};
+
+// One workgroup's tile: vocabulary tile vt, token rows m0 .. m0 + 64 NT.
+template <bool kFp8, int NT>
+__device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int m0) {
+  const char* __restrict__ hidden = A.hidden;
+  const char* __restrict__ w = A.w;
+  const float* __restrict__ h_scale = A.h_scale;
+  const float* __restrict__ w_scale = A.w_scale;
+  float* __restrict__ logits = A.logits;
+  const int M = A.M, H = A.H, V = A.V, n_tiles = A.n_tiles, Nq = A.Nq;
+  const float exp_scale = A.exp_scale;
+  const float* __restrict__ temps = A.temps;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wvv = wave & 3;   // vocab slice of 64 rows
   const int wm = wave >> 2;   // token half
-  // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  The m_tiles token tiles
-  // of one vocab tile get ids 8 apart: same XCD, launched together - the W tile comes from HBM once and
-  // from L2 for the others.  Every workgroup walks the hidden dimension in the same order: the
-  // workgroups resident on one XCD then want the same slices of the token tiles at about the same time
-  // and its L2 serves all but the first.
-  const int wg = blockIdx.x;
-  const int vt = (wg / (8 * m_tiles)) * 8 + (wg & 7);
-  const int mt = (wg >> 3) % m_tiles;
-  if (vt >= n_tiles) return;
   const int vbase = vt * kBgVTile;
-  const int m0 = mt * kBgMTile;
-  const int tb0 = wm * 4;  // first 32-token tile of this wavefront; rows past M are loaded clamped and never stored
+  const int tb0 = wm * NT;  // first 32-token tile of this wavefront; rows past M are loaded clamped and never stored
   constexpr int kEsz = kFp8 ? 1 : 2;  // bytes per operand element
   const int nk = H * kEsz / kBgRowBytes;
   const unsigned lds0 = (unsigned)(uintptr_t)lds;  // LDS pointers are 32-bit offsets
 
   // ---- loader role: 64 rows of one operand per wavefront and stage.  A wavefront's vmcnt queue holds one
   // operand only, so the deeper W ring is not held up behind token-row loads.
+  // A W loader brings 64 vocabulary rows per stage (8 instructions), a token-row loader 16 NT rows (2 NT).
   const bool w_loader = wave < 4;
   const int depth = w_loader ? kBgWStages : kBgHStages;
+  constexpr int kHLoads = 2 * NT;
   const int lrow = lane >> 3, lslot = lane & 7;
+  const int row0 = (w_loader ? 64 : 8 * kHLoads) * (wave & 3);  // first row of the wavefront's share, within the tile
   const char* src[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const int r = 64 * (wave & 3) + 8 * j + lrow;
+    const int r = row0 + 8 * j + lrow;
     const int chunk = lslot ^ ((r >> 1) & 7);
     int vrow = vbase + r;
     vrow = vrow < V ? vrow : V - 1;
@@ -83,19 +97,24 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
     hrow = hrow < M ? hrow : M - 1;
     src[j] = w_loader ? w + ((size_t)vrow * H * kEsz + chunk * 16) : hidden + ((size_t)hrow * H * kEsz + chunk * 16);
   }
-  const unsigned ring0 = lds0 + (w_loader ? 0 : kBgWRing) + 64 * (wave & 3) * kBgRowBytes;
+  const unsigned ring0 = lds0 + (w_loader ? 0 : kBgWRing) + row0 * kBgRowBytes;
   auto issue = [&](int ks, int slot) {
     const unsigned base = ring0 + slot * kBgWBytes;
     const int koff = ks * kBgRowBytes;
+    if (w_loader) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) dma16(src[j] + koff, base + 8 * j * kBgRowBytes);
+      for (int j = 0; j < kBgLoads; ++j) dma16(src[j] + koff, base + 8 * j * kBgRowBytes);
+    } else {
+#pragma unroll
+      for (int j = 0; j < kHLoads; ++j) dma16(src[j] + koff, base + 8 * j * kBgRowBytes);
+    }
   };
 
-  f32x16_t acc[2][4];
+  f32x16_t acc[2][NT];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
 
@@ -104,19 +123,19 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
   const int wrow_off = (wvv * 64 + li) * kBgRowBytes;
   const int hrow_off = kBgWRing + (tb0 * 32 + li) * kBgRowBytes;
 
-  auto load_frag = [&](int wslot, int hslot, int s, bf16x8_t (&wa)[2], bf16x8_t (&hb)[4]) {
+  auto load_frag = [&](int wslot, int hslot, int s, bf16x8_t (&wa)[2], bf16x8_t (&hb)[NT]) {
     const int coff = ((2 * s + lh) ^ sw) * 16;
     const char* wb = lds + wslot * kBgWBytes + wrow_off + coff;
     const char* hbp = lds + hslot * kBgHBytes + hrow_off + coff;
 #pragma unroll
     for (int a = 0; a < 2; ++a) wa[a] = *(const bf16x8_t*)(wb + a * 32 * kBgRowBytes);
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < NT; ++t)
       hb[t] = *(const bf16x8_t*)(hbp + t * 32 * kBgRowBytes);
   };
-  auto multiply = [&](const bf16x8_t (&wa)[2], const bf16x8_t (&hb)[4]) {
+  auto multiply = [&](const bf16x8_t (&wa)[2], const bf16x8_t (&hb)[NT]) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int a = 0; a < 2; ++a)
         acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[t], acc[a][t], 0, 0, 0);
@@ -125,14 +144,17 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
 #define BG_STEP_ORDER()                                  \
   do {                                                   \
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   \
-    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);   \
-    __builtin_amdgcn_sched_group_barrier(0x008, 7, 0);   \
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 + NT, 0);   \
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * NT - 1, 0);   \
     __builtin_amdgcn_sched_barrier(0);                   \
   } while (0)
   auto wait_younger = [&](int groups) {  // wait until at most `groups` stages' loads of this wavefront are outstanding
-    if (groups >= 2) LM_WAIT_VMCNT(2 * kBgLoads);
-    else if (groups == 1) LM_WAIT_VMCNT(kBgLoads);
-    else LM_WAIT_VMCNT(0);
+    if (groups <= 0) LM_WAIT_VMCNT(0);
+    else if (w_loader) {
+      if (groups >= 2) LM_WAIT_VMCNT(2 * kBgLoads); else LM_WAIT_VMCNT(kBgLoads);
+    } else {
+      if (groups >= 2) LM_WAIT_VMCNT(2 * kHLoads); else LM_WAIT_VMCNT(kHLoads);
+    }
   };
   static_assert(kBgWStages <= 3 && kBgHStages <= 3, "wait_younger covers at most 2 younger stages");
 
@@ -147,7 +169,7 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
     // accumulator tile; one fragment set at a time (a second set spills into the main loop: five times slower)
     typedef __attribute__((ext_vector_type(8))) int i32x8_t;
     typedef __attribute__((ext_vector_type(4))) int i32x4_t;
-    i32x8_t wa[2], hb[4];
+    i32x8_t wa[2], hb[NT];
     auto load64 = [&](int s2) {
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
@@ -161,7 +183,7 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
           for (int i = 0; i < 4; ++i) wa[a][4 * e + i] = v[i];
         }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < NT; ++t) {
           const i32x4_t v = *(const i32x4_t*)(hbp + t * 32 * kBgRowBytes);
 #pragma unroll
           for (int i = 0; i < 4; ++i) hb[t][4 * e + i] = v[i];
@@ -170,13 +192,13 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
     };
     auto multiply64 = [&]() {
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
+      for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int a = 0; a < 2; ++a)
           acc[a][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wa[a], hb[t], acc[a][t], 0, 0, 0, 127, 0, 127);
       // the MFMAs above cannot sink below this point, the LDS reads after it cannot rise above it
 #pragma unroll
-      for (int t = 0; t < 4; ++t) asm volatile("" : "+v"(acc[0][t]), "+v"(acc[1][t])::"memory");
+      for (int t = 0; t < NT; ++t) asm volatile("" : "+v"(acc[0][t]), "+v"(acc[1][t])::"memory");
     };
     for (int ks = 0; ks < nk; ++ks) {
       load64(0);
@@ -196,7 +218,7 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
       multiply64();
     }
   } else {
-  bf16x8_t wa0[2], hb0[4], wa1[2], hb1[4];
+  bf16x8_t wa0[2], hb0[NT], wa1[2], hb1[NT];
   load_frag(0, 0, 0, wa0, hb0);
   for (int ks = 0; ks + 1 < nk; ++ks) {
     load_frag(wslot, hslot, 1, wa1, hb1);
@@ -242,9 +264,9 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
   const bool vec_ok = (V & 3) == 0;
   if constexpr (kFp8) {
     // dequantise: accumulator (vocab row v, token m) times w_scale[v] * h_scale[m]
-    float hs[4];
+    float hs[NT];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < NT; ++t) {
       const int m = m0 + (tb0 + t) * 32 + li;
       hs[t] = h_scale[m < M ? m : M - 1];
     }
@@ -258,13 +280,13 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
 #pragma unroll
         for (int e = 0; e < 4; ++e) wsc[e] = w_scale[v + e < V ? v + e : V - 1];
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
           for (int e = 0; e < 4; ++e) acc[a][t][4 * g + e] *= wsc[e] * hs[t];
       }
   }
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < NT; ++t) {
     const int col0 = (tb0 + t) * 32;
     if (m0 + col0 < M) {  // tiles wholly past the last token row hold nothing
       float mx, sum;
@@ -279,43 +301,90 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(
     }
   }
   __syncthreads();
-  if (tid < kBgMTile) {
+  if (tid < 64 * NT) {
     const int m = m0 + tid;
     if (m < M) {
       float mx, sum;
       int arg;
       lm_merge_waves(st_max, st_sum, st_arg, kBgMTile, tid, lm_row_scale(exp_scale, temps, Nq, m, M), mx, sum, arg);
       const size_t o = (size_t)m * n_tiles + vt;
-      pmax[o] = mx;
-      psum[o] = sum;
-      parg[o] = arg;
+      A.pmax[o] = mx;
+      A.psum[o] = sum;
+      A.parg[o] = arg;
     }
+  }
+}
+
+// Workgroup columns [0, n_a) hold 64 NTA token rows each, the others 64 NTB (NTB = NTA or NTA - 1).
+template <bool kFp8, int NTA, int NTB>
+__global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(BgArgs A, int m_tiles, int n_a) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  The m_tiles token tiles
+  // of one vocab tile get ids 8 apart: same XCD, launched together - the W tile comes from HBM once and
+  // from L2 for the others.  Every workgroup walks the hidden dimension in the same order: the
+  // workgroups resident on one XCD then want the same slices of the token tiles at about the same time
+  // and its L2 serves all but the first.
+  const int wg = blockIdx.x;
+  const int vt = (wg / (8 * m_tiles)) * 8 + (wg & 7);
+  const int mt = (wg >> 3) % m_tiles;
+  if (vt >= A.n_tiles) return;
+  if constexpr (NTA == NTB) {
+    bg_tile<kFp8, NTA>(A, lds, vt, mt * 64 * NTA);
+  } else {
+    if (mt < n_a) bg_tile<kFp8, NTA>(A, lds, vt, mt * 64 * NTA);
+    else bg_tile<kFp8, NTB>(A, lds, vt, n_a * 64 * NTA + (mt - n_a) * 64 * NTB);
   }
 }
 
 bool lmhead_mfma_big_supported(const AcceptLaunch& a) {
   const int esz = a.fp8 ? 1 : 2;
-  return (a.bf16 || a.fp8) && (a.H * esz) % kBgRowBytes == 0 && a.H * esz >= kBgRowBytes && a.V >= 1 &&
+  return a.plan.rows >= kLmBigFromRows && (a.bf16 || a.fp8) && (a.H * esz) % kBgRowBytes == 0 && a.H * esz >= kBgRowBytes && a.V >= 1 &&
          a.plan.stat_tile == kBgVTile;
 }
 
-template <bool kFp8>
-static hipError_t launch_big_t(const AcceptLaunch& a, hipStream_t st) {
+template <bool kFp8, int NTA, int NTB>
+static hipError_t launch_big_t(const AcceptLaunch& a, hipStream_t st, int m_tiles, int n_a) {
   static LdsAttrOnce attr;
-  if (hipError_t e = attr.ensure((const void*)lmhead_mfma_big_kernel<kFp8>, kBgLdsBytes); e != hipSuccess) return e;
-  const int M = (int)a.plan.rows;
-  const int m_tiles = (M + kBgMTile - 1) / kBgMTile;
-  const float exp_scale = 1.4426950408889634f / (a.temperature > 0.f ? a.temperature : 1.f);
+  if (hipError_t e = attr.ensure((const void*)lmhead_mfma_big_kernel<kFp8, NTA, NTB>, kBgLdsBytes); e != hipSuccess)
+    return e;
+  BgArgs A = {};
+  A.hidden = (const char*)a.hidden; A.w = (const char*)a.lm_head; A.h_scale = a.hidden_scale; A.w_scale = a.lm_scale;
+  A.logits = a.logits; A.pmax = a.pmax; A.psum = a.psum; A.parg = a.parg;
+  A.M = (int)a.plan.rows; A.H = a.H; A.V = a.V; A.n_tiles = a.plan.n_tiles;
+  A.exp_scale = 1.4426950408889634f / (a.temperature > 0.f ? a.temperature : 1.f);
+  A.temps = a.temps; A.Nq = a.Nq;
   const int v_tiles = (a.V + kBgVTile - 1) / kBgVTile;
   dim3 grid((v_tiles + 7) / 8 * 8 * m_tiles);
-  hipLaunchKernelGGL(lmhead_mfma_big_kernel<kFp8>, grid, dim3(kBgThreads), kBgLdsBytes, st, (const char*)a.hidden,
-                     (const char*)a.lm_head, a.hidden_scale, a.lm_scale, a.logits, a.pmax, a.psum, a.parg, M, a.H, a.V,
-                     a.plan.n_tiles, m_tiles, exp_scale, a.temps, a.Nq);
+  hipLaunchKernelGGL((lmhead_mfma_big_kernel<kFp8, NTA, NTB>), grid, dim3(kBgThreads), kBgLdsBytes, st, A, m_tiles, n_a);
   return hipGetLastError();
 }
 
+// Pairs of 32-row tiles dealt evenly to the fewest workgroup columns of at most four pairs.
+void lmhead_mfma_big_geometry(int M, int* m_tiles, int* nt_a, int* nt_b, int* n_a) {
+  const int pairs = (M + 63) / 64;
+  const int cols = (pairs + 3) / 4;
+  const int base = pairs / cols, rem = pairs % cols;
+  *m_tiles = cols;
+  *nt_a = rem ? base + 1 : base;
+  *nt_b = base;
+  *n_a = rem ? rem : cols;
+}
+
+template <bool kFp8>
+static hipError_t launch_big_dt(const AcceptLaunch& a, hipStream_t st) {
+  int m_tiles, nta, ntb, n_a;
+  lmhead_mfma_big_geometry((int)a.plan.rows, &m_tiles, &nta, &ntb, &n_a);
+  // from kLmBigFromRows (six pairs) on, every column holds three or four pairs
+  switch (nta * 10 + ntb) {
+    case 44: return launch_big_t<kFp8, 4, 4>(a, st, m_tiles, n_a);
+    case 43: return launch_big_t<kFp8, 4, 3>(a, st, m_tiles, n_a);
+    case 33: return launch_big_t<kFp8, 3, 3>(a, st, m_tiles, n_a);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 hipError_t launch_lmhead_mfma_big(const AcceptLaunch& a, hipStream_t st) {
-  return a.fp8 ? launch_big_t<true>(a, st) : launch_big_t<false>(a, st);
+  return a.fp8 ? launch_big_dt<true>(a, st) : launch_big_dt<false>(a, st);
 }
 
 }  // namespace aurora

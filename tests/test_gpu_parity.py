@@ -301,11 +301,14 @@ def test_lmhead_stage_alone_matches_oracle_logits(gpu_lib):
     check_logits(dv.logits_host(after="accept"), ref, w.dtype)
 
 
-@pytest.mark.parametrize("batch,num_q,vocab,hidden", [(33, 7, 5003, 256), (52, 5, 2304, 128), (101, 5, 1100, 192)])
+@pytest.mark.parametrize("batch,num_q,vocab,hidden", [(33, 7, 5003, 256), (52, 5, 2304, 128), (101, 5, 1100, 192),
+                                                       (64, 6, 1100, 192), (64, 7, 2304, 128), (115, 5, 777, 128),
+                                                       (100, 7, 1500, 128), (55, 7, 1100, 64)])
 def test_lmhead_many_token_rows(gpu_lib, batch, num_q, vocab, hidden):
-    """More than 160 token rows: the 256 x 256-tile LM-head kernel (231 rows: one token tile with clamped
-    rows and whole 32-row tiles past the end; 260 rows would not fill it and stays on the small-M kernel;
-    505 rows: two token tiles), ragged vocabulary tail, statistics checked through row_lse / accept."""
+    """More than 160 token rows.  231 and 260 rows: several passes of the W-streaming kernel.  From 384 rows the
+    tiled kernel, whose workgroup columns hold three or four pairs of 32-row tiles: 384 rows = 3 + 3 pairs, 385 and
+    448 = 4 + 3 (the last pair half empty for 385), 505 = 4 + 4, 575 = 3 + 3 + 3, 700 = 4 + 4 + 3; ragged vocabulary
+    tail, statistics checked through row_lse / accept."""
     from paper_2602_06932_amd.device import DeviceVerify
     w = gen.llama_chain(18, batch=batch, num_q=num_q, len_lo=20, len_hi=40, vocab=vocab, hidden_size=hidden,
                         num_q_heads=4, num_kv_heads=2)
@@ -388,9 +391,10 @@ def test_fp8_lm_head_tree_and_draft_subvocabulary(gpu_lib):
     _full_check(gpu_lib, w)
 
 
-@pytest.mark.parametrize("batch,vocab,hidden", [(96, 3001, 384), (52, 777, 1024)])
+@pytest.mark.parametrize("batch,vocab,hidden", [(96, 3001, 384), (52, 777, 1024), (88, 1500, 256), (115, 777, 128)])
 def test_fp8_lm_head_many_token_rows(gpu_lib, batch, vocab, hidden):
-    """Enough token rows (480, 260) for the 256 x 256-tile kernel with 8-bit operands: K = 64 MFMAs, scales in the
+    """Many token rows with 8-bit operands (480, 440, 575 rows: the tiled kernel with 4 + 4, 4 + 3 and 3 + 3 + 3 pairs
+    of row tiles per workgroup column; 260: passes of the W-streaming kernel): K = 64 MFMAs, scales in the
     epilogue; a vocabulary that ends inside a tile, one to eight stages of the hidden dimension."""
     w = gen.llama_chain(32, batch=batch, len_lo=20, len_hi=60, vocab=vocab, hidden_size=hidden, head_fp8=True,
                         draft_noise=0.5)
