@@ -11,8 +11,8 @@ Integer outputs are bit-exact, except that
     that test on (it is compared up to that test, reported, and not counted);
   - a next_token mismatch is excused when the uniform lies within 1e-6 of the oracle's normalised
     CDF interval of the GPU's token (the draw sat on a knot of the CDF);
-  - greedy rows whose top-1/top-2 logit gap is below 1e-4 are exempt.
-Exempt requests are counted and must stay rare.
+  - a greedy request is exempt when a row on the oracle's accepted path has a top-1/top-2 logit gap below 1e-4.
+Exempt requests are printed and counted: at most 5 % of a batch of 20 or more requests, none of a smaller one.
 """
 import numpy as np
 
@@ -32,6 +32,12 @@ def check_attention(out, ref, dtype):
         assert rel_rms <= 1e-2, f"attention relative rms {rel_rms}"
     else:
         scale = np.abs(ref).max(axis=-1, keepdims=True)
+        # the elementwise relative error, for the record: it is unbounded in principle (an entry that cancels to
+        # ~0 has no meaningful relative error in any fp32 summation order), so the bar is relative to the row
+        big = np.abs(ref) > 1e-3 * scale
+        print(f"[fp32 attention] max |d|/max|row| = {(err / scale).max():.2e}; elementwise max |d|/|ref| = "
+              f"{(err / np.maximum(np.abs(ref), 1e-300)).max():.2e} (over entries above 1e-3 of their row: "
+              f"{(err[big] / np.abs(ref[big])).max():.2e})", flush=True)
         assert (err <= 1e-5 * scale + 1e-30).all(), f"attention rel err {(err / scale).max()}"
     return float(err.max())
 
@@ -39,6 +45,9 @@ def check_attention(out, ref, dtype):
 def check_logits(got, ref, dtype):
     err = np.abs(np.asarray(got, np.float64) - ref)
     bar = 1e-3 if dtype == "bf16" else 1e-5 * np.abs(ref).max()
+    if dtype != "bf16":
+        print(f"[fp32 logits] max |d| = {err.max():.2e} (bar {bar:.2e}); elementwise max |d|/|ref| = "
+              f"{(err / np.maximum(np.abs(ref), 1e-300)).max():.2e}", flush=True)
     assert err.max() <= bar, f"logits err {err.max()} > {bar}"
     return float(err.max())
 
@@ -49,8 +58,10 @@ def _ancestors_in_eval_order(orc, b, parents, Nq):
     return [n for n in range(1, Nq) if not np.isnan(orc.test_margin[b, n])]
 
 
-def check_accept(res, orc, w, max_exempt_frac=0.05):
-    """res: dict of host arrays from the HIP path; orc: oracle.AcceptResult (with final_cdf when T > 0)."""
+def check_accept(res, orc, w, max_exempt_frac=0.05, small_batch_exempt=0):
+    """res: dict of host arrays from the HIP path; orc: oracle.AcceptResult (with final_cdf when T > 0).
+    At most int(max_exempt_frac * B) requests may be exempt when B >= 20; smaller batches get none unless the
+    caller passes small_batch_exempt and says why where it does."""
     B, Nq = w.batch, w.num_q
     temps = getattr(w, "temperatures", None)   # one temperature per request, or None
     greedy_b = np.full(B, not (w.temperature > 0)) if temps is None else (np.asarray(temps) == 0)
@@ -62,8 +73,9 @@ def check_accept(res, orc, w, max_exempt_frac=0.05):
         if same_walk and same_tok:
             continue
         if greedy_b[b]:
-            # rows on the oracle's path decide; any near-tie row exempts the request
-            if (orc.top_gap[b] < GREEDY_TIE).any():
+            # only the rows the oracle's walk consulted (the nodes on its accepted path) can excuse a difference
+            on_path = orc.accept_mask[b].astype(bool)
+            if (orc.top_gap[b][on_path] < GREEDY_TIE).any():
                 exempt.append((b, "greedy near-tie"))
                 continue
             mism.append((b, "greedy"))
@@ -91,7 +103,8 @@ def check_accept(res, orc, w, max_exempt_frac=0.05):
         else:
             mism.append((b, f"token {vg} vs {int(orc.next_token[b])}, u={u}, interval=({lo},{hi})"))
     assert not mism, f"{len(mism)} mismatching requests: {mism[:5]}"
-    assert len(exempt) <= max(1, int(max_exempt_frac * B)), f"too many exempt requests: {exempt}"
+    budget = int(max_exempt_frac * B) if B >= 20 else small_batch_exempt
+    assert len(exempt) <= budget, f"too many exempt requests ({len(exempt)} > {budget} of {B}): {exempt}"
 
     # per-node outputs
     lse_err = np.abs(res["row_lse"].astype(np.float64) - orc.row_lse).max()
