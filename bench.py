@@ -61,6 +61,7 @@ def make_workload(name, seed):
 def event_time_ms(fn, iters, torch):
     """Average duration of fn() over `iters` back-to-back launches, by HIP events on the launch stream."""
     st = torch.cuda.current_stream()
+    fn()  # untimed: the first call of a stage may set up its buffers
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(st)
     for _ in range(iters):
@@ -187,13 +188,18 @@ def main():
     it = 20
     dv.verify()
     torch.cuda.synchronize()
-    ms_attn_b2b = ms_lmhead_b2b = ms_accept_half = ms_verify_ev = ms_trace = None
+    ms_attn_b2b = ms_lmhead_b2b = ms_accept_half = ms_verify_ev = ms_trace = ms_step_emit = None
     if not args.steps_only:
         ms_attn_b2b = event_time_ms(dv.attn, it, torch)
         ms_lmhead_b2b = event_time_ms(dv.lmhead, it, torch)
         ms_accept_half = event_time_ms(dv.accept, it, torch)
         ms_verify_ev = event_time_ms(dv.verify, it, torch)
         ms_trace = event_time_ms(dv.trace, it, torch)  # not part of a step: the emission that follows a verify
+        # ... and as it runs in serving, once after every step (the logits are then cold): step + emission, minus the step
+        def step_and_emit():
+            dv.verify()
+            dv.trace()
+        ms_step_emit = event_time_ms(step_and_emit, it, torch)
 
     # ---- timed region: K whole verify steps (one aurora_verify call each) ---------------------------
     for _ in range(args.warmup):
@@ -278,7 +284,8 @@ def main():
         "stage_ms": {"attn_in_step": ms_attn, "lmhead_in_step": ms_lmhead, "step_as_three_calls": ms_step_split,
                      "attn_back_to_back": ms_attn_b2b, "lmhead_back_to_back": ms_lmhead_b2b,
                      "accept_half(lmhead+walk)": ms_accept_half, "verify_by_events": ms_verify_ev,
-                     "trace_emit_after_verify(top-1024)": ms_trace},
+                     "trace_emit_after_verify(top-1024)": ms_trace,
+                     "verify_step_plus_trace_emit": ms_step_emit},
         "roofline": {"kernel": "lmhead (LM-head GEMM + softmax statistics)", "bound": "hbm",
                      "achieved": lm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": lm_gbs / HBM_PEAK_GBS,
                      "traffic": (tr_lm["read_bytes"] + tr_lm["write_bytes"]) if tr_lm else None,

@@ -239,6 +239,15 @@ int aurora_verify(const aurora_attn_desc* attn_desc, const aurora_accept_desc* a
 const float* aurora_verify_logits_ptr(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,
                                       const void* workspace);
 
+/* After aurora_verify_accept / aurora_verify_lmhead / aurora_verify has been enqueued with `workspace`: the largest
+ * logit of every 32 consecutive vocabulary ids of every token row, float32 [B*Nq, *n_groups] (group g = ids 32 g ..
+ * 32 g + 31; -inf for groups past the vocabulary), valid like the logits above - what aurora_trace_desc.group_max
+ * takes.  Host only.  Returns NULL and *n_groups = 0 for
+ * configurations whose LM head runs outside the matrix-core kernels (float32 operands, hidden sizes they do not
+ * take), which write none. */
+const float* aurora_verify_group_max_ptr(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,
+                                         const void* workspace, int32_t* n_groups);
+
 /*
  * Debug check of the device-resident inputs of a verify step.  The calls above validate descriptors and
  * pointers on the host only; what the device arrays hold is trusted, and a page id, length, parent or
@@ -305,6 +314,16 @@ typedef struct {
    * ids, distinct); topk_ids then hold draft indices j, ties by ascending j, padding when Vd < K. */
   int32_t draft_vocab;
   const int32_t* draft_to_target;
+  /* Optional, from the vocabulary sweep of the verify step (appendix A.2 reduces 256 KB of logits per token to
+   * 2 KB; with this the reduction reads only the 128-byte groups that can hold a kept logit, about a quarter of the
+   * row, instead of sampling and then streaming all of it).  n_groups = 0: not given.  Otherwise group_max is a
+   * DEVICE pointer to float32 [B*Nq, n_groups] and entry (m, g) MUST be the largest of logits[m, 32 g .. 32 g + 31]
+   * (ids below V) for every g < ceil(V / 32); further entries of a row are ignored.  aurora_verify_group_max_ptr()
+   * hands out what the LM head wrote.  Used when K <= ceil(V / 32) <= 8192, V > 4096 and draft_vocab = 0, ignored
+   * otherwise.  An entry larger than the true maximum only costs time; a smaller one may hide that group's logits
+   * from the selection. */
+  int32_t n_groups;
+  const float* group_max;
 } aurora_trace_desc;
 
 int aurora_trace_emit(const aurora_trace_desc* desc,

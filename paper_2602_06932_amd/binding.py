@@ -26,7 +26,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libaurora_v
 EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify_accept", "aurora_verify",
            "aurora_verify_lmhead", "aurora_verify_accept_logits", "aurora_trace_emit",
            "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack", "aurora_attn_backward",
-           "aurora_attn_backward_workspace_bytes", "aurora_attn_forward", "aurora_attn_backward_saved", "aurora_debug_set_tree_spin_limit", "aurora_verify_attn_static")
+           "aurora_attn_backward_workspace_bytes", "aurora_attn_forward", "aurora_attn_backward_saved", "aurora_debug_set_tree_spin_limit", "aurora_verify_attn_static",
+           "aurora_verify_group_max_ptr")
 
 
 class aurora_attn_desc(C.Structure):
@@ -45,7 +46,8 @@ class aurora_accept_desc(C.Structure):
 
 class aurora_trace_desc(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_q", C.c_int32), ("vocab", C.c_int32), ("top_k", C.c_int32),
-                ("draft_vocab", C.c_int32), ("draft_to_target", C.c_void_p)]
+                ("draft_vocab", C.c_int32), ("draft_to_target", C.c_void_p), ("n_groups", C.c_int32),
+                ("group_max", C.c_void_p)]
 
 
 class aurora_pack_desc(C.Structure):
@@ -88,6 +90,8 @@ def load():
     lib.aurora_verify_workspace_bytes.restype = C.c_int
     lib.aurora_verify_attn.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, vp, C.c_size_t, vp]
     lib.aurora_verify_attn.restype = C.c_int
+    lib.aurora_verify_group_max_ptr.argtypes = [ad, cd, vp, C.POINTER(C.c_int32)]
+    lib.aurora_verify_group_max_ptr.restype = C.c_void_p
     lib.aurora_verify_attn_static.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, vp]
     lib.aurora_verify_attn_static.restype = C.c_int
     lib.aurora_verify_accept.argtypes = [cd, vp, vp, i32p, f32p, f32p, i32p, i32p, i32p, u8p, f32p, f32p, vp,
@@ -296,6 +300,13 @@ def aurora_draft_loss(desc, draft_logits, topk_ids, topk_logits, traj, row_kl, l
 def aurora_verify_logits_ptr(attn_desc, accept_desc, workspace) -> int:
     p = load().aurora_verify_logits_ptr(_ref(attn_desc), _ref(accept_desc), _ptr(workspace))
     return int(p or 0)
+
+
+def aurora_verify_group_max_ptr(attn_desc, accept_desc, workspace):
+    """(device address, n_groups) of the group maxima the LM head left in the workspace; (0, 0) when it wrote none."""
+    n = C.c_int32(0)
+    p = load().aurora_verify_group_max_ptr(_ref(attn_desc), _ref(accept_desc), _ptr(workspace), C.byref(n))
+    return int(p or 0), int(n.value)
 
 
 def aurora_attn_forward(desc, q, k_pages, v_pages, block_table, seq_lens, parents, out, lse, workspace, stream=None,

@@ -109,7 +109,10 @@ AcceptPlan plan_accept(const aurora_accept_desc* d) {
   p.parg_off = p.psum_off + align_up(rows * p.n_tiles * sizeof(float));
   accept_chain_geometry(d->batch, d->vocab, &p.slices, &p.gmul, &p.ngroups);
   const size_t B = (size_t)d->batch;
-  p.st_lse_off = p.parg_off + align_up(rows * p.n_tiles * sizeof(int32_t));
+  // maxima of groups of 32 vocabulary entries, written by the matrix-core LM-head kernels for the top-K emission
+  p.n_half = lmhead_mfma_supported(probe) ? p.n_tiles * kLmHalfPerTile : 0;
+  p.hmax_off = p.parg_off + align_up(rows * p.n_tiles * sizeof(int32_t));
+  p.st_lse_off = p.hmax_off + align_up(rows * p.n_half * sizeof(float));
   p.st_row_off = p.st_lse_off + align_up(B * sizeof(double));
   p.st_rej_off = p.st_row_off + align_up(B * sizeof(int32_t));
   p.gsum_off = p.st_rej_off + align_up(B * sizeof(int32_t));
@@ -169,6 +172,7 @@ int run_accept(const aurora_accept_desc* desc, const void* hidden, const void* l
   a.pmax = (float*)(ws + plan.pmax_off);
   a.psum = (float*)(ws + plan.psum_off);
   a.parg = (int32_t*)(ws + plan.parg_off);
+  a.hmax = (float*)(ws + plan.hmax_off);
   a.st_lse = (double*)(ws + plan.st_lse_off);
   a.st_row = (int32_t*)(ws + plan.st_row_off);
   a.st_rej = (int32_t*)(ws + plan.st_rej_off);
@@ -199,6 +203,7 @@ int run_lmhead(const aurora_accept_desc* desc, const void* hidden, const void* l
   a.pmax = (float*)(ws + plan.pmax_off);
   a.psum = (float*)(ws + plan.psum_off);
   a.parg = (int32_t*)(ws + plan.parg_off);
+  a.hmax = (float*)(ws + plan.hmax_off);
   a.plan = plan;
   hipError_t e = lmhead_mfma_supported(a) ? launch_lmhead_mfma(a, st) : launch_lmhead_generic(a, st);
   return e == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
@@ -353,6 +358,21 @@ const float* aurora_verify_logits_ptr(const aurora_attn_desc* attn_desc, const a
     off = plan_attn(attn_desc).bytes;
   }
   return (const float*)((const char*)workspace + off + plan_accept(accept_desc).logits_off);
+}
+
+const float* aurora_verify_group_max_ptr(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,
+                                         const void* workspace, int32_t* n_groups) {
+  if (n_groups) *n_groups = 0;
+  if (!workspace || !n_groups || check_accept_desc(accept_desc) != AURORA_OK) return nullptr;
+  size_t off = 0;
+  if (attn_desc) {
+    if (check_attn_desc(attn_desc) != AURORA_OK) return nullptr;
+    off = plan_attn(attn_desc).bytes;
+  }
+  const AcceptPlan plan = plan_accept(accept_desc);
+  if (plan.n_half == 0) return nullptr;
+  *n_groups = plan.n_half;
+  return (const float*)((const char*)workspace + off + plan.hmax_off);
 }
 
 int aurora_verify_check_inputs(const aurora_attn_desc* attn_desc, const aurora_accept_desc* accept_desc,
@@ -529,6 +549,7 @@ int aurora_trace_emit(const aurora_trace_desc* d, const float* logits, const int
   if (!d || d->batch < 0 || d->num_q < 1 || d->vocab < 1 || d->top_k < 1) return AURORA_ERR_INVALID_ARG;
   if (d->draft_vocab < 0 || d->draft_vocab > d->vocab || (d->draft_vocab > 0 && !d->draft_to_target))
     return AURORA_ERR_INVALID_ARG;
+  if (d->n_groups < 0 || (d->n_groups > 0 && !d->group_max)) return AURORA_ERR_INVALID_ARG;
   if (d->num_q > kMaxNq || d->top_k > trace_max_k()) return AURORA_ERR_UNSUPPORTED;
   const bool want_topk = topk_ids || topk_logits, want_rec = y_out || traj;
   if (!want_topk && !want_rec) return AURORA_ERR_INVALID_ARG;
@@ -537,14 +558,21 @@ int aurora_trace_emit(const aurora_trace_desc* d, const float* logits, const int
   if (!have_device()) return AURORA_ERR_HIP;
   if (d->batch == 0) return AURORA_OK;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (want_topk &&
-      launch_trace_topk(logits, (int64_t)d->batch * d->num_q, d->vocab, d->top_k,
-                        d->draft_vocab > 0 ? d->draft_to_target : nullptr, d->draft_vocab, topk_ids, topk_logits,
-                        st) != hipSuccess)
+  RecArgs rec = {};
+  if (want_rec) {
+    rec.B = d->batch; rec.Nq = d->num_q; rec.draft_tokens = draft_tokens; rec.parents = parents;
+    rec.next_token = next_token; rec.accept_mask = accept_mask; rec.y_out = y_out; rec.traj = traj;
+  }
+  if (want_topk) {
+    // the records ride in the same launch as the top-K rows
+    if (launch_trace_topk(logits, (int64_t)d->batch * d->num_q, d->vocab, d->top_k,
+                          d->draft_vocab > 0 ? d->draft_to_target : nullptr, d->draft_vocab,
+                          d->n_groups > 0 ? d->group_max : nullptr, d->n_groups, topk_ids, topk_logits,
+                          want_rec ? &rec : nullptr, st) != hipSuccess)
+      return AURORA_ERR_HIP;
+  } else if (launch_trace_records(rec, st) != hipSuccess) {
     return AURORA_ERR_HIP;
-  if (want_rec && launch_trace_records(d->batch, d->num_q, draft_tokens, parents, next_token, accept_mask, y_out, traj,
-                                       st) != hipSuccess)
-    return AURORA_ERR_HIP;
+  }
   return AURORA_OK;
 }
 

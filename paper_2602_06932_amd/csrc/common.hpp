@@ -85,6 +85,8 @@ struct AcceptPlan {
   int slices;       // chain draw: workgroups per request in the vocabulary sweep
   int gmul;         // chain draw: a group is 64 * gmul consecutive tokens
   int ngroups;      // chain draw: ceil(V / (64 * gmul))
+  int n_half;       // group maxima per row kept for the top-K emission (0: the LM-head kernel in use writes none)
+  size_t hmax_off;
   size_t logits_off, pmax_off, psum_off, parg_off, st_lse_off, st_row_off, st_rej_off, gsum_off, lastpos_off, tree_bar_off, bytes;
 };
 

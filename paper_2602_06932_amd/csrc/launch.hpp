@@ -37,6 +37,7 @@ struct AcceptLaunch {
   float *p_at_draft, *row_lse;
   float *logits, *pmax, *psum;
   int32_t* parg;
+  float* hmax;  // [rows, n_tiles * kLmHalfPerTile] maxima of groups of 32 vocabulary entries (matrix-core LM head only)
   double *st_lse, *gsum;
   int32_t *st_row, *st_rej, *lastpos;
   int32_t* tree_bar;  // [B] arrival counters of the several-workgroups-per-request tree walk
@@ -53,6 +54,7 @@ hipError_t launch_attn_combine(const AttnLaunch& a, hipStream_t st);
 bool lmhead_mfma_supported(const AcceptLaunch& a);
 int lmhead_mfma_stat_tile();
 hipError_t launch_lmhead_mfma(const AcceptLaunch& a, hipStream_t st);  // picks the small- or large-M kernel
+constexpr int kLmHalfPerTile = 8;     // groups of 32 vocabulary rows per 256-row statistics tile
 constexpr int kLmBigFromRows = 384;  // token rows from which the tiled many-row kernel takes the LM head
 bool lmhead_mfma_big_supported(const AcceptLaunch& a);
 hipError_t launch_lmhead_mfma_big(const AcceptLaunch& a, hipStream_t st);
@@ -65,11 +67,20 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st);
 
 // trace emission: top-K target logits per token row, y_out and rejection trajectory
 int trace_max_k();
+// records of the acceptance outcome (y_out, rejection trajectory); B = 0: none wanted
+struct RecArgs {
+  int B, Nq;  // B = 0: no records wanted
+  const int32_t* draft_tokens;
+  const int32_t* parents;
+  const int32_t* next_token;
+  const uint8_t* accept_mask;
+  int32_t* y_out;
+  int8_t* traj;
+};
 hipError_t launch_trace_topk(const float* logits, int64_t rows, int V, int K, const int32_t* map, int n_map,
-                             int32_t* ids, uint16_t* vals, hipStream_t st);
-hipError_t launch_trace_records(int B, int Nq, const int32_t* draft_tokens, const int32_t* parents,
-                                const int32_t* next_token, const uint8_t* accept_mask, int32_t* y_out, int8_t* traj,
-                                hipStream_t st);
+                             const float* group_max, int n_groups, int32_t* ids, uint16_t* vals, const RecArgs* rec,
+                             hipStream_t st);
+hipError_t launch_trace_records(const RecArgs& R, hipStream_t st);
 
 // backward pass of the chunk / tree attention (see attn_bwd.hip); out / lse come from the forward kernels
 struct AttnBwdLaunch {

@@ -40,7 +40,8 @@ template <int NT, bool kFp8>
 __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     const char* __restrict__ hidden, const char* __restrict__ w, const float* __restrict__ h_scale,
     const float* __restrict__ w_scale, float* __restrict__ logits, float* __restrict__ pmax,
-    float* __restrict__ psum, int32_t* __restrict__ parg, int M, int H, int V, int n_tiles, int m_tiles,
+    float* __restrict__ psum, int32_t* __restrict__ parg, float* __restrict__ hmax, int M, int H, int V, int n_tiles,
+    int m_tiles,
     float exp_scale /* log2(e) / T */, const float* __restrict__ temps /* per-request T, or NULL */, int Nq) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   constexpr int kEsz = kFp8 ? 1 : 2;             // bytes per operand element
@@ -259,6 +260,7 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
   float* st_max = (float*)(lds + (nk % kLmStages) * kStageBytes + kLmWBytes);  // hidden part of an idle stage
   float* st_sum = st_max + 4 * NT * 32;
   int* st_arg = (int*)(st_sum + 4 * NT * 32);
+  float* st_half = (float*)(st_arg + 4 * NT * 32);  // [8][NT * 32]: maxima of the eight groups of 32 vocab rows
   const int vrow0 = vbase + wv * kLmWaveV;
   const bool vec_ok = (V & 3) == 0;
   char* tb = lds + wv * (kLmWaveV * kLmRowBytes);
@@ -287,15 +289,16 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
   }
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
-    float mx, sum;
+    float mx, sum, half;
     int arg;
     lm_tile_out(acc[0][t], acc[1][t], vrow0, V, m0 + 32 * t, M, lm_row_scale(exp_scale, temps, Nq, m0 + 32 * t + li, M), tb,
-                logits, vec_ok, lane, mx, sum, arg);
+                logits, vec_ok, lane, mx, sum, arg, half);
     if (lh == 0) {
       st_max[wv * NT * 32 + t * 32 + li] = mx;
       st_sum[wv * NT * 32 + t * 32 + li] = sum;
       st_arg[wv * NT * 32 + t * 32 + li] = arg;
     }
+    st_half[(2 * wv + lh) * NT * 32 + t * 32 + li] = half;
   }
   __syncthreads();  // the producers' last barrier pairs with this one
   if (tid < NT * 32) {
@@ -308,6 +311,16 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
       pmax[o] = mx;
       psum[o] = sum;
       parg[o] = arg;
+      // the eight group maxima of this tile, 32 contiguous bytes per token row
+      f32x4_t h0, h1;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        h0[j] = st_half[j * NT * 32 + tid];
+        h1[j] = st_half[(4 + j) * NT * 32 + tid];
+      }
+      f32x4_t* hd = (f32x4_t*)(hmax + ((size_t)m * n_tiles + vt) * kLmHalfPerTile);
+      hd[0] = h0;
+      hd[1] = h1;
     }
   }
 }
@@ -328,7 +341,7 @@ static hipError_t launch_nt_t(const AcceptLaunch& a, hipStream_t st, int m_tiles
   const int v_tiles = (a.V + kLmVTile - 1) / kLmVTile;
   dim3 grid((v_tiles + 7) / 8 * 8 * m_tiles);
   hipLaunchKernelGGL((lmhead_mfma_kernel<NT, kFp8>), grid, dim3(kLmThreads), lds_bytes, st, (const char*)a.hidden,
-                     (const char*)a.lm_head, a.hidden_scale, a.lm_scale, a.logits, a.pmax, a.psum, a.parg,
+                     (const char*)a.lm_head, a.hidden_scale, a.lm_scale, a.logits, a.pmax, a.psum, a.parg, a.hmax,
                      (int)a.plan.rows, a.H, a.V, a.plan.n_tiles, m_tiles, exp_scale, a.temps, a.Nq);
   return hipGetLastError();
 }

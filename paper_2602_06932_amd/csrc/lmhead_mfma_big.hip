@@ -51,6 +51,7 @@ struct BgArgs {
   float* pmax;
   float* psum;
   int32_t* parg;
+  float* hmax;
   int M, H, V, n_tiles;
   float exp_scale;     // log2(e) / T
   const float* temps;  // per-request T, or NULL
@@ -260,6 +261,7 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
   float* st_max = (float*)(lds + 8 * 8192);
   float* st_sum = st_max + 4 * kBgMTile;
   int* st_arg = (int*)(st_sum + 4 * kBgMTile);
+  float* st_half = (float*)(st_arg + 4 * kBgMTile);  // [8][256]: maxima of the eight groups of 32 vocab rows
   const int vrow0 = vbase + wvv * 64;
   const bool vec_ok = (V & 3) == 0;
   if constexpr (kFp8) {
@@ -289,15 +291,16 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
   for (int t = 0; t < NT; ++t) {
     const int col0 = (tb0 + t) * 32;
     if (m0 + col0 < M) {  // tiles wholly past the last token row hold nothing
-      float mx, sum;
+      float mx, sum, half;
       int arg;
       lm_tile_out(acc[0][t], acc[1][t], vrow0, V, m0 + col0, M, lm_row_scale(exp_scale, temps, Nq, m0 + col0 + li, M), tb,
-                  logits, vec_ok, lane, mx, sum, arg);
+                  logits, vec_ok, lane, mx, sum, arg, half);
       if (lh == 0) {
         st_max[wvv * kBgMTile + col0 + li] = mx;
         st_sum[wvv * kBgMTile + col0 + li] = sum;
         st_arg[wvv * kBgMTile + col0 + li] = arg;
       }
+      st_half[(2 * wvv + lh) * kBgMTile + col0 + li] = half;
     }
   }
   __syncthreads();
@@ -311,6 +314,16 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
       A.pmax[o] = mx;
       A.psum[o] = sum;
       A.parg[o] = arg;
+      // the eight group maxima of this tile, 32 contiguous bytes per token row
+      f32x4_t h0, h1;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        h0[j] = st_half[j * kBgMTile + tid];
+        h1[j] = st_half[(4 + j) * kBgMTile + tid];
+      }
+      f32x4_t* hd = (f32x4_t*)(A.hmax + o * kLmHalfPerTile);
+      hd[0] = h0;
+      hd[1] = h1;
     }
   }
 }
@@ -349,7 +362,7 @@ static hipError_t launch_big_t(const AcceptLaunch& a, hipStream_t st, int m_tile
     return e;
   BgArgs A = {};
   A.hidden = (const char*)a.hidden; A.w = (const char*)a.lm_head; A.h_scale = a.hidden_scale; A.w_scale = a.lm_scale;
-  A.logits = a.logits; A.pmax = a.pmax; A.psum = a.psum; A.parg = a.parg;
+  A.logits = a.logits; A.pmax = a.pmax; A.psum = a.psum; A.parg = a.parg; A.hmax = a.hmax;
   A.M = (int)a.plan.rows; A.H = a.H; A.V = a.V; A.n_tiles = a.plan.n_tiles;
   A.exp_scale = 1.4426950408889634f / (a.temperature > 0.f ? a.temperature : 1.f);
   A.temps = a.temps; A.Nq = a.Nq;

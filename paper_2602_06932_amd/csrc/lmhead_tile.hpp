@@ -23,15 +23,16 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 // Accumulator register r of a 32x32 MFMA tile holds row 8(r/4) + 4(lane/32) + r%4, column lane%32.
 // a0 / a1 are the tiles of vocab rows vrow0.. and vrow0+32.. for the 32 tokens mrow0.. (column = token).
 // Entries past the vocabulary are set to -inf in place.  Returns this token's (max, arg-max, sum of
-// exp2((x - max) * exp_scale)) over the 64 vocab rows in every lane of the token's lane pair, and
+// exp2((x - max) * exp_scale)) over the 64 vocab rows in every lane of the token's lane pair, in half_max_out the
+// largest of the 32 consecutive vocab rows vrow0 + 32 (lane / 32) .., and
 // writes the 64 x 32 logits through `tb`, 8 KB of LDS private to the calling wavefront, so that each
 // store instruction covers four token rows of 256 contiguous bytes.  LDS operations of one wavefront
 // execute in order, so consecutive calls may reuse `tb` without a barrier.
 __device__ __forceinline__ void lm_tile_out(f32x16_t& a0, f32x16_t& a1, int vrow0, int V, int mrow0, int M,
                                             float exp_scale, char* tb, float* __restrict__ logits, bool vec_ok, int lane,
-                                            float& mx_out, float& sum_out, int& arg_out) {
+                                            float& mx_out, float& sum_out, int& arg_out, float& half_max_out) {
   const int li = lane & 31, lh = lane >> 5;
-  float mx = -INFINITY;
+  float m01[2] = {-INFINITY, -INFINITY};  // this lane's largest entry among vocab rows vrow0 .. +31 and vrow0 + 32 .. +63
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -39,8 +40,15 @@ __device__ __forceinline__ void lm_tile_out(f32x16_t& a0, f32x16_t& a1, int vrow
       f32x16_t& acc = a ? a1 : a0;
       const int v = vrow0 + 32 * a + 8 * (r >> 2) + 4 * lh + (r & 3);
       if (v >= V) acc[r] = -INFINITY;
-      mx = fmaxf(mx, acc[r]);
+      m01[a] = fmaxf(m01[a], acc[r]);
     }
+  float mx = fmaxf(m01[0], m01[1]);
+  // largest of 32 consecutive vocab rows (the two lane halves hold interleaved runs of four): lane half 0 keeps the
+  // group vrow0 .. +31, lane half 1 the group vrow0 + 32 .. +63
+  {
+    const float o0 = __shfl_xor(m01[0], 32, kWave), o1 = __shfl_xor(m01[1], 32, kWave);
+    half_max_out = lh ? fmaxf(m01[1], o1) : fmaxf(m01[0], o0);
+  }
   int arg = 0x7fffffff;
 #pragma unroll
   for (int a = 1; a >= 0; --a)

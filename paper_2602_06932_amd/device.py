@@ -141,22 +141,33 @@ class DeviceVerify:
         torch.cuda.synchronize()
         return flags.cpu().numpy()
 
-    def trace(self, top_k=1024, after="verify", stream=None):
-        """Trace emission from the logits and acceptance outputs the last verify / accept call left."""
+    def trace(self, top_k=1024, after="verify", stream=None, group_max=True):
+        """Trace emission from the logits and acceptance outputs the last verify / accept call left (with the group
+        maxima of the same call's LM head, unless group_max is False or the call wrote none)."""
         w = self.w
-        if getattr(self, "_trace_k", None) != (top_k, after):
+        if getattr(self, "_trace_k", None) != (top_k, after, group_max):
             rows = w.batch * w.num_q
-            self.trace_desc = B.aurora_trace_desc(batch=w.batch, num_q=w.num_q, vocab=w.vocab, top_k=top_k)
+            gptr, ng = B.aurora_verify_group_max_ptr(self.attn_desc if after == "verify" else None, self.accept_desc,
+                                                     self.workspace) if group_max else (0, 0)
+            self.trace_desc = B.aurora_trace_desc(batch=w.batch, num_q=w.num_q, vocab=w.vocab, top_k=top_k,
+                                                  n_groups=ng, group_max=gptr or None)
             self.topk_ids = torch.empty((rows, top_k), dtype=torch.int32, device="cuda")
             self.topk_logits = torch.empty((rows, top_k), dtype=torch.int16, device="cuda")
             self.y_out = torch.empty((w.batch, w.num_q), dtype=torch.int32, device="cuda")
             self.traj = torch.empty((w.batch, w.num_q), dtype=torch.int8, device="cuda")
             self._trace_logits = B.aurora_verify_logits_ptr(self.attn_desc if after == "verify" else None,
                                                             self.accept_desc, self.workspace)
-            self._trace_k = (top_k, after)
-        return B.aurora_trace_emit(self.trace_desc, self._trace_logits, self.draft_tokens, self.parents,
-                                   self.next_token, self.accept_mask, self.topk_ids, self.topk_logits, self.y_out,
-                                   self.traj, stream)
+            self._trace_k = (top_k, after, group_max)
+            import ctypes as C
+            P = B._ptr
+            # marshalled once, like the verify calls: the buffers never move
+            self._trace_args = (C.byref(self.trace_desc), self._trace_logits, P(self.draft_tokens), P(self.parents),
+                                P(self.next_token), P(self.accept_mask), P(self.topk_ids), P(self.topk_logits),
+                                P(self.y_out), P(self.traj))
+        st = B.load().aurora_trace_emit(*self._trace_args, B._stream(stream))
+        if st != B.AURORA_OK:
+            raise B.AuroraError(st, "aurora_trace_emit")
+        return st
 
     def attn_via_binding(self, stream=None):
         return B.aurora_verify_attn(self.attn_desc, self.q, self.k_pages, self.v_pages, self.block_table,

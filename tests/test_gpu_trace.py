@@ -66,6 +66,69 @@ def test_topk_over_the_draft_vocabulary(gpu_lib, vocab, draft_vocab, k):
     _check_topk(gpu_lib, gen.trace_logits(26, 3, vocab, "normal"), k, rng.permutation(d2t).astype(np.int32))
 
 
+def _group_max(logits, group=32, pad_groups=0):
+    """Maxima of consecutive groups of `group` entries per row (numpy; -inf pads the last group and `pad_groups`
+    further ones, as the LM head pads its rows to whole tiles)."""
+    rows, V = logits.shape
+    n = (V + group - 1) // group
+    x = np.full((rows, (n + pad_groups) * group), -np.inf, np.float32)
+    x[:, :V] = logits
+    return np.ascontiguousarray(x.reshape(rows, n + pad_groups, group).max(-1))
+
+
+def _emit_topk_with_groups(av, logits, k, gmax):
+    rows, V = logits.shape
+    dg = torch.from_numpy(gmax).cuda()
+    d = av.aurora_trace_desc(batch=rows, num_q=1, vocab=V, top_k=k, n_groups=gmax.shape[1], group_max=dg.data_ptr())
+    dl = torch.from_numpy(logits).cuda()
+    ids = torch.full((rows, k), -9, dtype=torch.int32, device="cuda")
+    vals = torch.full((rows, k), 0x1234, dtype=torch.int16, device="cuda")
+    av.aurora_trace_emit(d, dl, None, None, None, None, ids, vals, None, None)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), vals.cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("kind", gen.TRACE_KINDS)
+@pytest.mark.parametrize("vocab,k,pad", [(128256, 1024, 0), (50001, 1000, 5), (151936, 1024, 0), (40000, 300, 2),
+                                         (32768, 1024, 0), (32737, 1024, 0), (262144, 1024, 0), (262145, 1024, 0),
+                                         (20000, 1024, 0)])
+def test_topk_with_group_maxima(gpu_lib, kind, vocab, k, pad):
+    """The route that takes its cut-off from the maxima of groups of 32 consecutive ids (made here with numpy from the
+    same seeded rows) and gathers only the groups that reach it.  All value kinds (ties and constant rows overflow
+    the list and fall back to the whole-row route), rows that are not 16-byte aligned and end inside a group, exactly
+    K groups (32768 / 32 and the ragged 32737), the largest vocabulary the route takes (8192 groups) and the first
+    it does not, fewer groups than K (ignored), rows of maxima padded with -inf as the LM head pads them."""
+    x = gen.trace_logits(31, 5, vocab, kind)
+    print(f"[case] top-k with group maxima rows=5 V={vocab} K={k} pad={pad} kind={kind}", flush=True)
+    ids, vals = _emit_topk_with_groups(gpu_lib, x, k, _group_max(x, 32, pad))
+    rid, rvals = oracle.trace_topk(x, k)
+    assert np.array_equal(ids, rid), f"first mismatch at {np.argwhere(ids != rid)[:3].tolist()}"
+    assert np.array_equal(vals, rvals)
+
+
+def test_topk_with_group_maxima_full_size(gpu_lib):
+    """The benchmark's shape (160 rows x 128256, K = 1024), and 600 rows (two workgroups per compute unit)."""
+    x = gen.trace_logits(2, 600, 50016, "normal")
+    ids, vals = _emit_topk_with_groups(gpu_lib, x, 1024, _group_max(x))
+    rid, rvals = oracle.trace_topk(x, 1024)
+    assert np.array_equal(ids, rid) and np.array_equal(vals, rvals)
+    x = gen.trace_logits(1, 160, 128256, "normal")
+    ids, vals = _emit_topk_with_groups(gpu_lib, x, 1024, _group_max(x))
+    rid, rvals = oracle.trace_topk(x, 1024)
+    assert np.array_equal(ids, rid) and np.array_equal(vals, rvals)
+
+
+@pytest.mark.parametrize("fill", [np.inf, -np.inf, 0.0, 1e30])
+def test_topk_survives_group_maxima_that_are_uniformly_wrong(gpu_lib, fill):
+    """The same wrong value in every group (a buffer that was never filled): too high a cut-off leaves the list
+    short, too low a one overflows it, and both take the whole-row route - the result is still exact."""
+    x = gen.trace_logits(32, 4, 50001, "normal")
+    g = np.full((4, (50001 + 31) // 32), fill, np.float32)
+    ids, vals = _emit_topk_with_groups(gpu_lib, x, 1024, g)
+    rid, rvals = oracle.trace_topk(x, 1024)
+    assert np.array_equal(ids, rid) and np.array_equal(vals, rvals)
+
+
 def test_topk_qwen_vocab_with_ties(gpu_lib):
     _check_topk(gpu_lib, gen.trace_logits(2, 8, 151936, "ties"), 1024)
 
@@ -131,6 +194,42 @@ def test_verify_then_emit(gpu_lib):
         diff = np.setxor1d(gid[m], rid[m])
         assert np.all(np.abs(ref[m, diff] - kth) <= 2 * tol), (m, diff[:5])
     assert len(np.setxor1d(gid, rid)) < 0.01 * gid.size
+
+
+@pytest.mark.parametrize("case", ["chain", "tree", "fp8", "many_rows"])
+def test_group_maxima_from_the_lm_head_give_the_same_records(gpu_lib, case):
+    """verify -> emit with the group maxima the LM head left in the workspace against verify -> emit without them
+    (the sampling route): identical ids and values, and the maxima themselves equal the largest fp32 logit of every
+    32 consecutive ids (chain: the W-streaming kernel; tree / many rows: the tiled kernel; 8-bit head)."""
+    from paper_2602_06932_amd.device import DeviceVerify
+    av = gpu_lib
+    if case == "chain":
+        w = gen.llama_chain(27, batch=6, len_lo=30, len_hi=90, vocab=50011, hidden_size=256)
+    elif case == "tree":
+        w = gen.llama_tree(27, batch=14, num_q=32, vocab=40003, hidden_size=128, context=48, num_q_heads=4, num_kv_heads=2)
+    elif case == "fp8":
+        w = gen.llama_chain(27, batch=6, len_lo=30, len_hi=90, vocab=50011, hidden_size=256, head_fp8=True)
+    else:
+        w = gen.llama_chain(27, batch=90, len_lo=20, len_hi=40, vocab=40003, hidden_size=128, num_q_heads=4, num_kv_heads=2)
+    dv = DeviceVerify(w)
+    dv.verify()
+    torch.cuda.synchronize()
+    gptr, ng = av.aurora_verify_group_max_ptr(dv.attn_desc, dv.accept_desc, dv.workspace)
+    assert gptr and ng == (w.vocab + 255) // 256 * 8
+    rows = w.batch * w.num_q
+    lg = dv.logits_host().reshape(rows, w.vocab)
+    off = gptr - dv.workspace.data_ptr()
+    gm = dv.workspace[off:off + 4 * rows * ng].view(torch.float32).view(rows, ng).cpu().numpy()
+    want = _group_max(lg)
+    assert np.array_equal(gm[:, :want.shape[1]], want) and np.all(gm[:, want.shape[1]:] == -np.inf)
+    dv.trace(group_max=True)
+    torch.cuda.synchronize()
+    a = (dv.topk_ids.cpu().numpy().copy(), dv.topk_logits.cpu().numpy().copy())
+    dv.topk_ids.fill_(-5)
+    dv.trace(group_max=False)
+    torch.cuda.synchronize()
+    b = (dv.topk_ids.cpu().numpy(), dv.topk_logits.cpu().numpy())
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
 
 
 def test_verify_emit_pack_loss_replay_from_one_captured_graph(gpu_lib):
