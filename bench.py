@@ -82,9 +82,12 @@ def main():
     ap.add_argument("--steps-only", action="store_true",
                     help="skip the back-to-back stage timings: every kernel launch of the run then belongs to a step "
                          "sequence (for kernel traces whose averages should be the in-step durations)")
-    ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy", "loss", "attn_bwd"],
+    ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy", "loss", "attn_bwd",
+                                                      "vendor_gemm"],
                     help="profiling aid: launch only this stage --steps times (after --warmup) and exit; "
-                         "'copy' runs a plain device-to-device copy of 1 GiB for counter calibration")
+                         "'copy' runs a plain device-to-device copy of 1 GiB for counter calibration; 'vendor_gemm' times "
+                         "the vendor GEMM library (torch.matmul, bf16, product only) on the workload's LM-head shape and "
+                         "on a large square, as a reference for what dense bf16 contraction reaches on this box")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding of the "
@@ -165,6 +168,21 @@ def main():
                                                "when the shape allows, fp32 gradients written once"},
                           "mfma_TFLOPs": flops / (ms * 1e-3) / 1e12,
                           "hbm_GBps": alg / (ms * 1e-3) / 1e9}))
+        return
+
+    if args.stage == "vendor_gemm":
+        res = []
+        for (m, n, k) in [(w.batch * w.num_q, w.vocab, w.hidden_size), (8192, 8192, 8192)]:
+            a_ = torch.randn(m, k, device="cuda").to(torch.bfloat16)
+            b_ = (torch.randn(n, k, device="cuda") * 0.02).to(torch.bfloat16)
+            fn = lambda: torch.matmul(a_, b_.T)
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            ms = event_time_ms(fn, args.steps, torch)
+            res.append({"M": m, "N": n, "K": k, "avg_ms": ms, "TFLOPs": 2.0 * m * n * k / (ms * 1e-3) / 1e12})
+            del a_, b_
+        print(json.dumps({"stage": "vendor_gemm", "workload": w.name, "dtype": "bf16 in, bf16 out", "results": res}))
         return
 
     if args.stage:
