@@ -83,11 +83,13 @@ def main():
                     help="skip the back-to-back stage timings: every kernel launch of the run then belongs to a step "
                          "sequence (for kernel traces whose averages should be the in-step durations)")
     ap.add_argument("--stage", default=None, choices=["attn", "lmhead", "accept", "verify", "trace", "copy", "loss", "attn_bwd",
-                                                      "vendor_gemm"],
+                                                      "vendor_gemm", "ceiling"],
                     help="profiling aid: launch only this stage --steps times (after --warmup) and exit; "
                          "'copy' runs a plain device-to-device copy of 1 GiB for counter calibration; 'vendor_gemm' times "
                          "the vendor GEMM library (torch.matmul, bf16, product only) on the workload's LM-head shape and "
-                         "on a large square, as a reference for what dense bf16 contraction reaches on this box")
+                         "on a large square, as a reference for what dense bf16 contraction reaches on this box; "
+                         "'ceiling' runs the library's calibration probe (matrix cores alone, + operand reads from LDS, "
+                         "+ LDS-direct loads from L2, loads alone) on random and on zero operands")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding of the "
@@ -100,6 +102,30 @@ def main():
     import paper_2602_06932_amd as av
     from paper_2602_06932_amd.device import DeviceVerify
     av.load()
+
+    if args.stage == "ceiling":
+        # what a dense bf16 contraction reaches on this device, part by part, and how much the values matter
+        g = torch.Generator(device="cuda").manual_seed(args.seed)
+        rows = torch.randn((4, 512, 4096), device="cuda", generator=g)
+        rows[:, :256] *= 0.02                      # the first 256 rows of a tile stand for LM-head rows, the rest for tokens
+        data = {"random (LM-head-like values)": rows.to(torch.bfloat16).contiguous(), "zeros": torch.zeros((4, 512, 4096), dtype=torch.bfloat16, device="cuda")}
+        sink = torch.zeros(1, device="cuda")
+        wgs, stages = 1024, 96
+        names = ["matrix cores only", "+ operand reads from LDS", "+ LDS-direct loads from L2", "LDS-direct loads alone"]
+        res = []
+        for dname, buf in data.items():
+            for mode in range(4):
+                fn = lambda: av.aurora_probe_contraction(mode, buf, wgs, stages, sink)
+                for _ in range(args.warmup):
+                    fn()
+                torch.cuda.synchronize()
+                ms = event_time_ms(fn, args.steps, torch)
+                flops = 0.0 if mode == 3 else 2.0 * wgs * stages * 256 * 256 * 64
+                loaded = wgs * stages * 65536.0 if mode >= 2 else 0.0
+                res.append({"operands": dname, "mode": names[mode], "avg_ms": ms, "TFLOPs": flops / (ms * 1e-3) / 1e12,
+                            "TBps_into_LDS": loaded / (ms * 1e-3) / 1e12})
+        print(json.dumps({"stage": "ceiling", "workgroups": wgs, "stages": stages, "results": res}))
+        return
 
     if args.stage == "loss":
         # the training side's first kernel on a batch of trace rows: 32K-entry draft vocabulary, 1024 kept target

@@ -344,6 +344,20 @@ int aurora_trace_emit(const aurora_trace_desc* desc,
  * already arrived, which forces the finish-alone path; results do not depend on the setting. */
 void aurora_debug_set_tree_spin_limit(int polls);
 
+/*
+ * Calibration probe for the roofline of the LM head (appendix A.1's projection is a dense contraction): the inner
+ * structure of the many-row LM-head kernel with its parts switched on one at a time, on operands the caller provides,
+ * so that a benchmark can say what a bf16 contraction reaches on the device at hand - and how much that depends on
+ * the values multiplied.  mode 0: matrix cores only (operands in registers); 1: + operand reads from LDS; 2: + the
+ * LDS-direct global loads that refill a stage (L2 resident, no HBM traffic); 3: those loads alone.  `operands`:
+ * DEVICE memory, 16-byte aligned, at least 16 MiB (operand_bytes says how much there is), read as bf16 - fill it with
+ * values like the workload's, or zeros.  `workgroups` x `stages` is the amount of work (a stage is 256 x 256 x 64
+ * multiply-adds per workgroup and 64 KB loaded); results are discarded; `sink` is one DEVICE float that is never
+ * written in practice.  Asynchronous on hip_stream; the caller times it.  Not part of the verify step.
+ */
+int aurora_probe_contraction(int mode, const void* operands, size_t operand_bytes, int workgroups, int stages,
+                             float* sink, void* hip_stream);
+
 /* Human-readable name of a status code; never NULL. */
 const char* aurora_status_string(int status);
 

@@ -10,5 +10,5 @@ from .binding import (AURORA_BF16, AURORA_FP8_E4M3, AURORA_ERR_HIP, AURORA_ERR_I
                       aurora_accept_desc, aurora_attn_desc, aurora_trace_desc, aurora_trace_emit, aurora_verify,
                       aurora_verify_accept, aurora_verify_accept_logits,
                       aurora_verify_attn, aurora_verify_lmhead, aurora_verify_logits_ptr, aurora_verify_workspace_bytes, load,
-                      status_string, aurora_verify_check_inputs, aurora_draft_loss, aurora_loss_desc, aurora_trace_pack, aurora_pack_desc, aurora_attn_backward, aurora_attn_backward_workspace_bytes, aurora_attn_forward, aurora_attn_backward_saved, aurora_debug_set_tree_spin_limit, aurora_verify_attn_static, aurora_verify_group_max_ptr, AURORA_ERR_TOO_LARGE, AURORA_STATIC_SCRATCH_BYTES, AURORA_CHECK_SEQ_LEN, AURORA_CHECK_PAGE_ID,
+                      status_string, aurora_verify_check_inputs, aurora_draft_loss, aurora_loss_desc, aurora_trace_pack, aurora_pack_desc, aurora_attn_backward, aurora_attn_backward_workspace_bytes, aurora_attn_forward, aurora_attn_backward_saved, aurora_debug_set_tree_spin_limit, aurora_verify_attn_static, aurora_verify_group_max_ptr, aurora_probe_contraction, AURORA_ERR_TOO_LARGE, AURORA_STATIC_SCRATCH_BYTES, AURORA_CHECK_SEQ_LEN, AURORA_CHECK_PAGE_ID,
                       AURORA_CHECK_PARENT, AURORA_CHECK_TOKEN, AURORA_CHECK_UNIFORM)

@@ -27,7 +27,7 @@ EXPORTS = ("aurora_verify_workspace_bytes", "aurora_verify_attn", "aurora_verify
            "aurora_verify_lmhead", "aurora_verify_accept_logits", "aurora_trace_emit",
            "aurora_verify_logits_ptr", "aurora_status_string", "aurora_verify_check_inputs", "aurora_draft_loss", "aurora_trace_pack", "aurora_attn_backward",
            "aurora_attn_backward_workspace_bytes", "aurora_attn_forward", "aurora_attn_backward_saved", "aurora_debug_set_tree_spin_limit", "aurora_verify_attn_static",
-           "aurora_verify_group_max_ptr")
+           "aurora_verify_group_max_ptr", "aurora_probe_contraction")
 
 
 class aurora_attn_desc(C.Structure):
@@ -90,6 +90,8 @@ def load():
     lib.aurora_verify_workspace_bytes.restype = C.c_int
     lib.aurora_verify_attn.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, vp, C.c_size_t, vp]
     lib.aurora_verify_attn.restype = C.c_int
+    lib.aurora_probe_contraction.argtypes = [C.c_int, vp, C.c_size_t, C.c_int, C.c_int, vp, vp]
+    lib.aurora_probe_contraction.restype = C.c_int
     lib.aurora_verify_group_max_ptr.argtypes = [ad, cd, vp, C.POINTER(C.c_int32)]
     lib.aurora_verify_group_max_ptr.restype = C.c_void_p
     lib.aurora_verify_attn_static.argtypes = [ad, vp, vp, vp, i32p, i32p, i32p, vp, vp]
@@ -300,6 +302,14 @@ def aurora_draft_loss(desc, draft_logits, topk_ids, topk_logits, traj, row_kl, l
 def aurora_verify_logits_ptr(attn_desc, accept_desc, workspace) -> int:
     p = load().aurora_verify_logits_ptr(_ref(attn_desc), _ref(accept_desc), _ptr(workspace))
     return int(p or 0)
+
+
+def aurora_probe_contraction(mode, operands, workgroups, stages, sink, stream=None, check=True) -> int:
+    st = load().aurora_probe_contraction(int(mode), _ptr(operands), operands.numel() * operands.element_size(),
+                                         int(workgroups), int(stages), _ptr(sink), _stream(stream))
+    if check and st != AURORA_OK:
+        raise AuroraError(st, "aurora_probe_contraction")
+    return st
 
 
 def aurora_verify_group_max_ptr(attn_desc, accept_desc, workspace):

@@ -576,6 +576,15 @@ int aurora_trace_emit(const aurora_trace_desc* d, const float* logits, const int
   return AURORA_OK;
 }
 
+int aurora_probe_contraction(int mode, const void* operands, size_t operand_bytes, int workgroups, int stages,
+                             float* sink, void* hip_stream) {
+  if (mode < 0 || mode > 3 || !operands || !sink || workgroups < 1 || stages < 1) return AURORA_ERR_INVALID_ARG;
+  if (operand_bytes < probe_operand_bytes() || ((uintptr_t)operands & 15)) return AURORA_ERR_INVALID_ARG;
+  if (!have_device()) return AURORA_ERR_HIP;
+  return launch_probe(mode, operands, workgroups, stages, sink, (hipStream_t)hip_stream) == hipSuccess ? AURORA_OK
+                                                                                                          : AURORA_ERR_HIP;
+}
+
 const char* aurora_status_string(int status) {
   switch (status) {
     case AURORA_OK: return "ok";

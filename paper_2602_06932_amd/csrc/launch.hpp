@@ -67,6 +67,10 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st);
 
 // trace emission: top-K target logits per token row, y_out and rejection trajectory
 int trace_max_k();
+// calibration probe (see probe.hip)
+size_t probe_operand_bytes();
+hipError_t launch_probe(int mode, const void* operands, int workgroups, int stages, float* sink, hipStream_t st);
+
 // records of the acceptance outcome (y_out, rejection trajectory); B = 0: none wanted
 struct RecArgs {
   int B, Nq;  // B = 0: no records wanted

@@ -1,0 +1,112 @@
+// Calibration probe: what a dense bf16 contraction can reach on this device, stripped of everything specific to
+// the LM head.  One workgroup per compute unit slot runs the many-row LM-head kernel's inner structure - eight
+// wavefronts, 2 x 4 accumulator tiles of v_mfma_f32_32x32x16_bf16 each, four steps per stage, 64 KB of operands per
+// stage - with its parts switched on one at a time:
+//   mode 0  matrix cores only, operands fixed in registers
+//   mode 1  + the operand reads from LDS (six 16-byte reads per lane and step, the LM head's swizzled layout)
+//   mode 2  + the LDS-direct global loads that refill the stage (row slivers of 128 bytes at an 8 KB pitch, L2
+//             resident: no HBM traffic), issued by the multiplying wavefronts
+//   mode 3  the loads alone
+// Nothing waits for data and the results are discarded: the probe measures rates, and how they depend on the VALUES
+// multiplied (the caller fills `operands`: random LM-head-like values, or zeros).  The time of a matrix-core
+// kernel on this part depends on them - the signature of a power limit - and the numbers this gives are the
+// ceiling the LM-head kernels are priced against beside the published peak.
+#include "launch.hpp"
+#include "lmhead_tile.hpp"
+
+namespace aurora {
+
+constexpr int kPrThreads = 512;
+constexpr int kPrLds = 65536;
+constexpr size_t kPrOperandBytes = (size_t)4 * 512 * 8192;  // four tiles of 512 rows at an 8 KB pitch
+
+__device__ __forceinline__ void probe_dma16(const void* g, unsigned l) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(g) : "memory");
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kPrThreads, 1) void probe_kernel(const char* __restrict__ base, int stages, float* __restrict__ sink) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const unsigned lds0 = (unsigned)(uintptr_t)lds;
+  const char* tile = base + (size_t)(blockIdx.x & 3) * (512 * 8192);
+  f32x16_t acc[2][4];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][t][r] = 0.f;
+  bf16x8_t wa[2], hb[4];
+  // register operands of mode 0: the first bytes of the caller's buffer, so that they are random or zero with it
+  {
+    const bf16x8_t* p = (const bf16x8_t*)(base + (size_t)lane * 128);
+    wa[0] = p[0]; wa[1] = p[1];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) hb[t] = p[2 + t];
+  }
+  if (MODE >= 1) {
+    // fill the LDS stage once (plain stores), so that mode 1 multiplies the caller's values too
+    for (int i = threadIdx.x; i < kPrLds / 16; i += kPrThreads)
+      ((f32x4_t*)lds)[i] = ((const f32x4_t*)tile)[i];
+    __syncthreads();
+  }
+  const int li = lane & 31, lh = lane >> 5;
+  for (int s = 0; s < stages; ++s) {
+    if (MODE != 3) {
+#pragma unroll
+      for (int st = 0; st < 4; ++st) {
+        if (MODE >= 1) {
+          const int chunk = ((2 * st + lh) ^ ((li >> 1) & 7)) * 16;
+#pragma unroll
+          for (int a = 0; a < 2; ++a) wa[a] = *(const bf16x8_t*)(lds + ((wave & 3) * 64 + a * 32 + li) * 128 + chunk);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) hb[t] = *(const bf16x8_t*)(lds + 32768 + (((wave >> 2) * 4 + t) * 32 + li) * 128 + chunk);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+          for (int a = 0; a < 2; ++a) acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[t], acc[a][t], 0, 0, 0);
+      }
+    }
+    if (MODE >= 2) {
+      LM_WAIT_VMCNT(8);  // at most one stage's loads of this wavefront in flight
+      // wavefront w, instruction j: rows 64 w + 8 j .. + 7 of the 512-row tile, 128 bytes at k offset s
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        probe_dma16(tile + (size_t)(wave * 64 + j * 8 + (lane >> 3)) * 8192 + (s & 63) * 128 + (lane & 7) * 16,
+                    lds0 + wave * 8192 + j * 1024);
+    }
+    __builtin_amdgcn_s_barrier();
+  }
+  LM_WAIT_VMCNT(0);  // every load has landed before the workgroup's LDS is given back
+  float x = 0.f;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) x += acc[a][t][r];
+  if (x == 12345.678f) sink[0] = x;  // keeps the products alive; practically never true
+}
+
+size_t probe_operand_bytes() { return kPrOperandBytes; }
+
+hipError_t launch_probe(int mode, const void* operands, int workgroups, int stages, float* sink, hipStream_t st) {
+  static LdsAttrOnce attr[4];
+  const void* fn[4] = {(const void*)probe_kernel<0>, (const void*)probe_kernel<1>, (const void*)probe_kernel<2>,
+                       (const void*)probe_kernel<3>};
+  if (mode < 0 || mode > 3) return hipErrorInvalidValue;
+  if (hipError_t e = attr[mode].ensure(fn[mode], kPrLds); e != hipSuccess) return e;
+  const char* b = (const char*)operands;
+  switch (mode) {
+    case 0: hipLaunchKernelGGL(probe_kernel<0>, dim3(workgroups), dim3(kPrThreads), kPrLds, st, b, stages, sink); break;
+    case 1: hipLaunchKernelGGL(probe_kernel<1>, dim3(workgroups), dim3(kPrThreads), kPrLds, st, b, stages, sink); break;
+    case 2: hipLaunchKernelGGL(probe_kernel<2>, dim3(workgroups), dim3(kPrThreads), kPrLds, st, b, stages, sink); break;
+    default: hipLaunchKernelGGL(probe_kernel<3>, dim3(workgroups), dim3(kPrThreads), kPrLds, st, b, stages, sink); break;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace aurora

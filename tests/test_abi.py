@@ -120,3 +120,17 @@ def test_product_package_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+
+
+def test_probe_rejects_bad_arguments_on_the_host():
+    """The calibration probe validates on the host before anything is enqueued (no GPU needed for this)."""
+    import ctypes as C
+    import paper_2602_06932_amd as av
+    lib = av.load()
+    buf = (C.c_char * 64)()
+    one = (C.c_float * 1)()
+    assert lib.aurora_probe_contraction(4, buf, 1 << 24, 8, 8, one, None) == av.AURORA_ERR_INVALID_ARG    # mode
+    assert lib.aurora_probe_contraction(0, None, 1 << 24, 8, 8, one, None) == av.AURORA_ERR_INVALID_ARG   # operands
+    assert lib.aurora_probe_contraction(0, buf, 1 << 20, 8, 8, one, None) == av.AURORA_ERR_INVALID_ARG    # too small
+    assert lib.aurora_probe_contraction(0, buf, 1 << 24, 0, 8, one, None) == av.AURORA_ERR_INVALID_ARG    # no work
+    assert lib.aurora_probe_contraction(0, buf, 1 << 24, 8, 8, None, None) == av.AURORA_ERR_INVALID_ARG   # sink
