@@ -124,6 +124,15 @@ def main():
                 loaded = wgs * stages * 65536.0 if mode >= 2 else 0.0
                 res.append({"operands": dname, "mode": names[mode], "avg_ms": ms, "TFLOPs": flops / (ms * 1e-3) / 1e12,
                             "TBps_into_LDS": loaded / (ms * 1e-3) / 1e12})
+        # the vocabulary sweep alone: 1 GiB streamed once from HBM in the LM head's tile shape
+        big = torch.empty((1 << 30) // 2, dtype=torch.bfloat16, device="cuda").normal_(0, 0.02, generator=g)
+        fn = lambda: av.aurora_probe_contraction(4, big, 1, 1, sink)
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        ms = event_time_ms(fn, args.steps, torch)
+        res.append({"operands": "1 GiB", "mode": "vocabulary sweep alone (HBM -> LDS, LM-head tile shape)", "avg_ms": ms,
+                    "TFLOPs": 0.0, "TBps_into_LDS": (1 << 30) / (ms * 1e-3) / 1e12})
         print(json.dumps({"stage": "ceiling", "workgroups": wgs, "stages": stages, "results": res}))
         return
 

@@ -578,9 +578,11 @@ int aurora_trace_emit(const aurora_trace_desc* d, const float* logits, const int
 
 int aurora_probe_contraction(int mode, const void* operands, size_t operand_bytes, int workgroups, int stages,
                              float* sink, void* hip_stream) {
-  if (mode < 0 || mode > 3 || !operands || !sink || workgroups < 1 || stages < 1) return AURORA_ERR_INVALID_ARG;
+  if (mode < 0 || mode > 4 || !operands || !sink || workgroups < 1 || stages < 1) return AURORA_ERR_INVALID_ARG;
   if (operand_bytes < probe_operand_bytes() || ((uintptr_t)operands & 15)) return AURORA_ERR_INVALID_ARG;
   if (!have_device()) return AURORA_ERR_HIP;
+  if (mode == 4)
+    return launch_probe_stream(operands, operand_bytes, (hipStream_t)hip_stream) == hipSuccess ? AURORA_OK : AURORA_ERR_HIP;
   return launch_probe(mode, operands, workgroups, stages, sink, (hipStream_t)hip_stream) == hipSuccess ? AURORA_OK
                                                                                                           : AURORA_ERR_HIP;
 }

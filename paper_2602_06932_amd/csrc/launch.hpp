@@ -69,6 +69,7 @@ hipError_t launch_accept(const AcceptLaunch& a, hipStream_t st);
 int trace_max_k();
 // calibration probe (see probe.hip)
 size_t probe_operand_bytes();
+hipError_t launch_probe_stream(const void* operands, size_t operand_bytes, hipStream_t st);
 hipError_t launch_probe(int mode, const void* operands, int workgroups, int stages, float* sink, hipStream_t st);
 
 // records of the acceptance outcome (y_out, rejection trajectory); B = 0: none wanted

@@ -7,6 +7,9 @@
 //   mode 2  + the LDS-direct global loads that refill the stage (row slivers of 128 bytes at an 8 KB pitch, L2
 //             resident: no HBM traffic), issued by the multiplying wavefronts
 //   mode 3  the loads alone
+//   mode 4  the W sweep alone: every workgroup streams its own 256 rows x 8 KB of `operands` once from HBM through a
+//           three-stage LDS ring in the LM head's tile shape (row slivers of 128 bytes per stage), four loading
+//           wavefronts, nothing multiplied - the ceiling of the vocabulary sweep's access pattern
 // Nothing waits for data and the results are discarded: the probe measures rates, and how they depend on the VALUES
 // multiplied (the caller fills `operands`: random LM-head-like values, or zeros).  The time of a matrix-core
 // kernel on this part depends on them - the signature of a power limit - and the numbers this gives are the
@@ -91,7 +94,44 @@ __global__ __launch_bounds__(kPrThreads, 1) void probe_kernel(const char* __rest
   if (x == 12345.678f) sink[0] = x;  // keeps the products alive; practically never true
 }
 
+// mode 4: workgroup i streams rows 256 i .. 256 i + 255 (8 KB each); the walk over k starts at a staggered offset
+__global__ __launch_bounds__(256, 1) void probe_stream_kernel(const char* __restrict__ base, int n_tiles) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const unsigned lds0 = (unsigned)(uintptr_t)lds;
+  const int vt = blockIdx.x;
+  if (vt >= n_tiles) return;
+  constexpr int nk = 64;
+  const int k0 = (vt * 13) % nk;
+  const char* src[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    src[j] = base + ((size_t)vt * 256 + wave * 64 + j * 8 + (lane >> 3)) * 8192 + (lane & 7) * 16;
+  auto issue = [&](int s) {
+    const int k = (k0 + s) % nk;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) probe_dma16(src[j] + k * 128, lds0 + (s % 3) * 32768 + wave * 8192 + j * 1024);
+  };
+  issue(0); issue(1); issue(2);
+  for (int s = 0; s < nk; ++s) {
+    const int rem = nk - 1 - s;  // stages after this one
+    if (rem >= 2) LM_WAIT_VMCNT(16); else if (rem == 1) LM_WAIT_VMCNT(8); else LM_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();  // stage s has landed for every wavefront; its slot may be refilled
+    if (s + 3 < nk) issue(s + 3);
+  }
+}
+
 size_t probe_operand_bytes() { return kPrOperandBytes; }
+
+hipError_t launch_probe_stream(const void* operands, size_t operand_bytes, hipStream_t st) {
+  static LdsAttrOnce attr;
+  if (hipError_t e = attr.ensure((const void*)probe_stream_kernel, 3 * 32768); e != hipSuccess) return e;
+  const int n_tiles = (int)(operand_bytes / ((size_t)256 * 8192));
+  if (n_tiles < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(probe_stream_kernel, dim3(n_tiles), dim3(256), 3 * 32768, st, (const char*)operands, n_tiles);
+  return hipGetLastError();
+}
 
 hipError_t launch_probe(int mode, const void* operands, int workgroups, int stages, float* sink, hipStream_t st) {
   static LdsAttrOnce attr[4];

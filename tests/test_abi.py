@@ -129,7 +129,7 @@ def test_probe_rejects_bad_arguments_on_the_host():
     lib = av.load()
     buf = (C.c_char * 64)()
     one = (C.c_float * 1)()
-    assert lib.aurora_probe_contraction(4, buf, 1 << 24, 8, 8, one, None) == av.AURORA_ERR_INVALID_ARG    # mode
+    assert lib.aurora_probe_contraction(5, buf, 1 << 24, 8, 8, one, None) == av.AURORA_ERR_INVALID_ARG    # mode
     assert lib.aurora_probe_contraction(0, None, 1 << 24, 8, 8, one, None) == av.AURORA_ERR_INVALID_ARG   # operands
     assert lib.aurora_probe_contraction(0, buf, 1 << 20, 8, 8, one, None) == av.AURORA_ERR_INVALID_ARG    # too small
     assert lib.aurora_probe_contraction(0, buf, 1 << 24, 0, 8, one, None) == av.AURORA_ERR_INVALID_ARG    # no work

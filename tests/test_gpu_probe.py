@@ -6,7 +6,7 @@ import torch
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4])
 def test_probe_modes_run(gpu_lib, mode):
     av = gpu_lib
     g = torch.Generator(device="cuda").manual_seed(1)
