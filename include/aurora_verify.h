@@ -10,8 +10,10 @@
  *     Descriptors are host structs, read during the call and not retained.
  *     q, k_pages, v_pages, out, hidden and lm_head must be 16-byte aligned
  *     (AURORA_ERR_INVALID_ARG otherwise).
- *   - The library allocates nothing and keeps no state between calls (the one process-wide
- *     setting is the test knob aurora_debug_set_tree_spin_limit).  All scratch lives in the
+ *   - The library allocates nothing and keeps no state that changes results between calls.  What it does keep,
+ *     per process: the test knob aurora_debug_set_tree_spin_limit, per-device facts looked up once (compute-unit
+ *     count, "large LDS enabled for this kernel"), and the fixed scratch array of aurora_verify_attn_static.
+ *     All other scratch lives in the
  *     caller's `workspace` (device memory, 256-byte aligned, at least
  *     aurora_verify_workspace_bytes() bytes).  No pointer is retained after the
  *     enqueued work completes.  Calls with distinct workspaces may overlap.
@@ -376,7 +378,10 @@ const char* aurora_status_string(int status);
  * (dk_j, dv_j sum over every node and every query head of the KV head's group that sees position j: the cached
  * prefix receives gradient as well).  dq is float32 [B, Nq, Hq, D]; dk_pages / dv_pages are float32 pools in the
  * layout of k_pages / v_pages - the positions the batch's block tables address are written, every other element
- * is left as it is.  dout has the type of q.  All sums run in a fixed order: bit-reproducible.
+ * is left as it is.  A page must belong to ONE request of the batch: dk / dv of a position are written, not
+ * accumulated, per block-table entry, so a page that two requests share (a common prefix) would keep the gradient
+ * of whichever wrote last - give such requests their own copies, or add the per-request results outside.
+ * dout has the type of q.  All sums run in a fixed order: bit-reproducible.
  * bf16 caches with head_dim 128, power-of-two pages >= 16 and at most 128 query rows per KV head run on the
  * matrix cores (P and dS rounded to bf16 for the products, fp32 accumulation); every other
  * shape takes a plain fp32 vector kernel.  An 8-bit KV cache is not supported (AURORA_ERR_UNSUPPORTED).

@@ -63,9 +63,7 @@ __device__ __forceinline__ void softmax_state_reset(SoftmaxState& st) {
 // registers for the later piecewise reads and refreshes it after the MFMAs of EVERY tile (64 moves per tile,
 // and 36 more registers).
 __device__ __forceinline__ void pin_accumulators(SoftmaxState& st) {
-#ifndef NO_ACC_PIN
   asm volatile("" : "+v"(st.o[0]), "+v"(st.o[1]), "+v"(st.o[2]), "+v"(st.o[3]));
-#endif
 }
 
 // S^T = K Q^T for one 32-token tile: tokens are MFMA rows, the 32 query rows MFMA columns
@@ -93,21 +91,6 @@ __device__ __forceinline__ void load_q_frags(QFrags& qf, const char* qtile, int 
   for (int s = 0; s < 8; ++s) qf.f[s] = *(const bf16x8_t*)(qtile + li * kAtRowBytes + (((2 * s + lh) ^ sw) * 16));
 }
 __device__ __forceinline__ f32x16_t tile_scores_qreg(const char* kbuf, const QFrags& qf, int li, int lh) {
-#ifdef SCORES_2ACC
-  // two accumulators, so that consecutive MFMAs do not depend on each other
-  f32x16_t a0, a1;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) { a0[r] = 0.f; a1[r] = 0.f; }
-  const int sw = li & 15;
-#pragma unroll
-  for (int s = 0; s < 8; s += 2) {
-    const bf16x8_t k0 = *(const bf16x8_t*)(kbuf + li * kAtRowBytes + (((2 * s + lh) ^ sw) * 16));
-    const bf16x8_t k1 = *(const bf16x8_t*)(kbuf + li * kAtRowBytes + (((2 * s + 2 + lh) ^ sw) * 16));
-    a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf.f[s], a0, 0, 0, 0);
-    a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf.f[s + 1], a1, 0, 0, 0);
-  }
-  return a0 + a1;
-#else
   f32x16_t s_acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) s_acc[r] = 0.f;
@@ -118,7 +101,6 @@ __device__ __forceinline__ f32x16_t tile_scores_qreg(const char* kbuf, const QFr
     s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf.f[s], s_acc, 0, 0, 0);
   }
   return s_acc;
-#endif
 }
 
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
