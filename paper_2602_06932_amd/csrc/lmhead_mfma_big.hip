@@ -9,7 +9,9 @@
 // beyond the last pair.  Every
 // wavefront multiplies; wavefronts 0-3 also load W and 4-7 the token rows, each operand into its own
 // LDS ring (W: 3 stages of 32 KB, it comes from HBM; token rows: 2 stages, they come from L2), by direct
-// global->LDS loads of 128-byte row segments.  A stage is 64 hidden elements = 4 MFMA steps; operand
+// global->LDS loads of 128-byte row segments through a buffer descriptor that covers exactly the tile's rows; a
+// stage's loads leave in four parts between the matrix-core steps rather than in one burst (a burst stalls the
+// matrix cores of the issuing wavefronts' SIMDs).  A stage is 64 hidden elements = 4 MFMA steps; operand
 // fragments are double-buffered in registers one step ahead, and the barrier that opens the next
 // stage sits before the last step of the current one, so the matrix pipe never waits on it.
 // The eight 16-byte chunks of a row segment are XOR-swizzled by (row / 2) mod 8 on the way in, which
@@ -34,12 +36,26 @@ constexpr int kBgWRing = kBgWStages * kBgWBytes;
 constexpr int kBgLdsBytes = kBgWRing + kBgHStages * kBgHBytes;  // 160 KB
 constexpr int kBgLoads = 8;                     // global->LDS instructions per wavefront per stage
 
-// Direct global->LDS load of 16 bytes per lane; lane i's data lands at lds_base + 16 i.  Written as
+// Direct global->LDS load of 16 bytes per lane through a buffer descriptor; lane i's data lands at lds_base + 16 i.
+// The address is descriptor base + voff (per lane, 32 bits) + soff (scalar); the hardware checks voff + soff against
+// the descriptor's byte count (out-of-range lanes read zero and touch nothing).  Written as
 // inline assembly so that the compiler does not order every later LDS read behind all such loads;
 // the explicit vmcnt waits below do the waiting.  m0 holds the LDS base; one wait state is required
 // between writing m0 and the load that reads it.
-__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+__device__ __forceinline__ void dma16(i32x4_t rsrc, unsigned voff, unsigned soff, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(lds_base), "v"(voff), "s"(rsrc), "s"(soff)
+               : "memory");
+}
+// Raw buffer descriptor (stride 0) over `bytes` bytes at p; the words are made wave-uniform.
+__device__ __forceinline__ i32x4_t bg_rsrc(const void* p, unsigned bytes) {
+  const uint64_t a = (uint64_t)(uintptr_t)p;
+  i32x4_t r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+  r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((a >> 32) & 0xffffu));
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;  // 32-bit data format, no swizzle, no index stride
+  return r;
 }
 
 struct BgArgs {
@@ -87,28 +103,36 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
   constexpr int kHLoads = 2 * NT;
   const int lrow = lane >> 3, lslot = lane & 7;
   const int row0 = (w_loader ? 64 : 8 * kHLoads) * (wave & 3);  // first row of the wavefront's share, within the tile
-  const char* src[8];
+  // the descriptor covers exactly the tile's rows that exist; rows past the end are loaded clamped and never stored
+  const int rows_here = w_loader ? (V - vbase < kBgVTile ? V - vbase : kBgVTile) : (M - m0 < 64 * NT ? M - m0 : 64 * NT);
+  const size_t row_bytes = (size_t)H * kEsz;
+  const i32x4_t rsrc = bg_rsrc(w_loader ? w + (size_t)vbase * row_bytes : hidden + (size_t)m0 * row_bytes,
+                               (unsigned)(rows_here * row_bytes));
+  unsigned voff[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const int r = row0 + 8 * j + lrow;
+    int r = row0 + 8 * j + lrow;
     const int chunk = lslot ^ ((r >> 1) & 7);
-    int vrow = vbase + r;
-    vrow = vrow < V ? vrow : V - 1;
-    int hrow = m0 + r;
-    hrow = hrow < M ? hrow : M - 1;
-    src[j] = w_loader ? w + ((size_t)vrow * H * kEsz + chunk * 16) : hidden + ((size_t)hrow * H * kEsz + chunk * 16);
+    r = r < rows_here ? r : rows_here - 1;
+    voff[j] = (unsigned)(r * row_bytes + chunk * 16);
   }
   const unsigned ring0 = lds0 + (w_loader ? 0 : kBgWRing) + row0 * kBgRowBytes;
-  auto issue = [&](int ks, int slot) {
+  // A stage's loads go out in four parts (a W loader: two instructions each; a token-row loader: NT each in the first two
+  // parts), so that they can be spread over the matrix-core work instead of leaving in one burst.
+  auto issue_part = [&](int ks, int slot, int part) {
     const unsigned base = ring0 + slot * kBgWBytes;
-    const int koff = ks * kBgRowBytes;
+    const unsigned koff = (unsigned)(ks * kBgRowBytes);
     if (w_loader) {
 #pragma unroll
-      for (int j = 0; j < kBgLoads; ++j) dma16(src[j] + koff, base + 8 * j * kBgRowBytes);
-    } else {
+      for (int j = 0; j < 2; ++j) dma16(rsrc, voff[2 * part + j], koff, base + 8 * (2 * part + j) * kBgRowBytes);
+    } else if (part < 2) {
 #pragma unroll
-      for (int j = 0; j < kHLoads; ++j) dma16(src[j] + koff, base + 8 * j * kBgRowBytes);
+      for (int j = 0; j < NT; ++j) dma16(rsrc, voff[NT * part + j], koff, base + 8 * (NT * part + j) * kBgRowBytes);
     }
+  };
+  auto issue = [&](int ks, int slot) {
+#pragma unroll
+    for (int part = 0; part < 4; ++part) issue_part(ks, slot, part);
   };
 
   f32x16_t acc[2][NT];
@@ -221,22 +245,36 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
   } else {
   bf16x8_t wa0[2], hb0[NT], wa1[2], hb1[NT];
   load_frag(0, 0, 0, wa0, hb0);
+  // The loads of stage ks + depth leave in four parts: one right after the barrier that frees their slot (below), the
+  // others between the first three steps of the next stage.  All of a stage's loads are out before the next vmcnt
+  // wait, so the counts waited for are the same as with one burst.
+  int pend = -1, pslot = 0;  // stage whose parts 1..3 are still to be issued, and its slot
+#define BG_PART(p)                                       \
+  do {                                                   \
+    if (pend >= 0) issue_part(pend, pslot, p);           \
+    __builtin_amdgcn_sched_barrier(0);                   \
+  } while (0)
   for (int ks = 0; ks + 1 < nk; ++ks) {
     load_frag(wslot, hslot, 1, wa1, hb1);
     multiply(wa0, hb0);
     BG_STEP_ORDER();
+    BG_PART(1);
     load_frag(wslot, hslot, 2, wa0, hb0);
     multiply(wa1, hb1);
     BG_STEP_ORDER();
+    BG_PART(2);
     load_frag(wslot, hslot, 3, wa1, hb1);
     multiply(wa0, hb0);
     BG_STEP_ORDER();
+    BG_PART(3);
     // every read of stage ks by this wavefront has returned before it says so to the others
     __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0) only
     wait_younger(nk - 2 - ks < depth - 2 ? nk - 2 - ks : depth - 2);
     __builtin_amdgcn_s_barrier();  // stage ks+1 visible to all; nobody reads stage ks's slots again
     asm volatile("" ::: "memory");
-    if (ks + depth < nk) issue(ks + depth, myslot);
+    pend = ks + depth < nk ? ks + depth : -1;
+    pslot = myslot;
+    BG_PART(0);
     myslot = myslot + 1 == depth ? 0 : myslot + 1;
     wslot = wslot + 1 == kBgWStages ? 0 : wslot + 1;
     hslot = hslot + 1 == kBgHStages ? 0 : hslot + 1;
@@ -244,6 +282,7 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
     multiply(wa1, hb1);
     BG_STEP_ORDER();
   }
+#undef BG_PART
   load_frag(wslot, hslot, 1, wa1, hb1);
   multiply(wa0, hb0);
   load_frag(wslot, hslot, 2, wa0, hb0);
@@ -351,7 +390,8 @@ __global__ __launch_bounds__(kBgThreads, 1) void lmhead_mfma_big_kernel(BgArgs A
 
 bool lmhead_mfma_big_supported(const AcceptLaunch& a) {
   const int esz = a.fp8 ? 1 : 2;
-  return a.plan.rows >= kLmBigFromRows && (a.bf16 || a.fp8) && (a.H * esz) % kBgRowBytes == 0 && a.H * esz >= kBgRowBytes && a.V >= 1 &&
+  return a.plan.rows >= kLmBigFromRows && (a.bf16 || a.fp8) && (a.H * esz) % kBgRowBytes == 0 && a.H * esz >= kBgRowBytes &&
+         a.H * esz <= (1 << 20) /* 256 rows of a tile within a 32-bit buffer offset */ && a.V >= 1 &&
          a.plan.stat_tile == kBgVTile;
 }
 
