@@ -225,9 +225,14 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
 #pragma unroll
       for (int t = 0; t < NT; ++t) asm volatile("" : "+v"(acc[0][t]), "+v"(acc[1][t])::"memory");
     };
+    int pend = -1, pslot = 0;  // stage whose second half of the loads is still to be issued, and its slot
     for (int ks = 0; ks < nk; ++ks) {
       load64(0);
       multiply64();
+      if (pend >= 0) {  // the second half of the loads of stage ks - 1 + depth, between the two double steps
+        issue_part(pend, pslot, 2);
+        issue_part(pend, pslot, 3);
+      }
       load64(1);
       if (ks + 1 < nk) {
         // every read of stage ks by this wavefront has returned before it says so to the others
@@ -235,7 +240,12 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
         wait_younger(nk - 2 - ks < depth - 2 ? nk - 2 - ks : depth - 2);
         __builtin_amdgcn_s_barrier();  // stage ks+1 visible to all; nobody reads stage ks's slots again
         asm volatile("" ::: "memory");
-        if (ks + depth < nk) issue(ks + depth, myslot);
+        pend = ks + depth < nk ? ks + depth : -1;
+        pslot = myslot;
+        if (pend >= 0) {
+          issue_part(pend, pslot, 0);
+          issue_part(pend, pslot, 1);
+        }
         myslot = myslot + 1 == depth ? 0 : myslot + 1;
         wslot = wslot + 1 == kBgWStages ? 0 : wslot + 1;
         hslot = hslot + 1 == kBgHStages ? 0 : hslot + 1;
