@@ -171,58 +171,97 @@ __global__ __launch_bounds__(kLmThreads, 1) void lmhead_mfma_kernel(
     // as long as both operands are read the same way).  A stage is two such double steps.
     typedef __attribute__((ext_vector_type(8))) int i32x8_t;
     typedef __attribute__((ext_vector_type(4))) int i32x4_t;
-    struct Frag64 { i32x8_t w[2], h[NT]; };
-    auto load_frag64 = [&](int stg, int s2, Frag64& f) {
-      const char* base = lds + stg * kStageBytes;
+    // Operands roll through the registers: the two W operands of the next double step are read into a second pair
+    // (16 registers), and a token-row operand is re-read for the next double step right after the two MFMAs that
+    // consumed it - so the LDS reads of a double step run under the MFMAs of the previous one without a second full
+    // fragment set (which would not fit beside the 32 NT accumulator registers).
+    auto ld_w = [&](int stg, int s2, i32x8_t (&wf)[2]) {
+      const char* base = lds + stg * kStageBytes + wrow_off;
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const int coff = ((2 * (2 * s2 + e) + lh) ^ sw) * 16;
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
-          const i32x4_t v = *(const i32x4_t*)(base + wrow_off + a * 32 * kLmRowBytes + coff);
+          const i32x4_t v = *(const i32x4_t*)(base + a * 32 * kLmRowBytes + coff);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) f.w[a][4 * e + i] = v[i];
-        }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const i32x4_t v = *(const i32x4_t*)(base + hrow_off + t * 32 * kLmRowBytes + coff);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) f.h[t][4 * e + i] = v[i];
+          for (int i = 0; i < 4; ++i) wf[a][4 * e + i] = v[i];
         }
       }
     };
-    auto multiply64 = [&](const Frag64& f) {
+    auto ld_h = [&](int stg, int s2, int t, i32x8_t& hf) {
+      const char* base = lds + stg * kStageBytes + hrow_off + t * 32 * kLmRowBytes;
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int coff = ((2 * (2 * s2 + e) + lh) ^ sw) * 16;
+        const i32x4_t v = *(const i32x4_t*)(base + coff);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) hf[4 * e + i] = v[i];
+      }
+    };
+    auto mul_t = [&](const i32x8_t (&wf)[2], const i32x8_t& hf, int t) {
 #pragma unroll
       for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-          acc[a][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.w[a], f.h[t], acc[a][t], 0, 0, 0, 127, 0, 127);
+        acc[a][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf[a], hf, acc[a][t], 0, 0, 0, 127, 0, 127);
     };
-    // an empty statement that "uses" every accumulator and clobbers memory: the MFMAs before it cannot sink below
-    // it, the LDS reads after it cannot rise above it
-    auto pin_acc = [&]() {
+    // First double step of a stage, rolling in its second.  Pinned order: two MFMAs; the next W pair's four reads, the two
+    // that refill the first token operand and the two of the last token operand of THIS double step (held back from
+    // the previous roll, so that a loop iteration ends on MFMAs and the wait at its head finds every read returned);
+    // then per further token tile two MFMAs and the two reads that refill its operand.
+    constexpr bool kDefer = NT >= 2;
+    i32x8_t wA[2], wB[2], hf[NT];
+    auto phase_a = [&](int stg_) {
+      ld_w(stg_, 1, wB);
+      if (kDefer) ld_h(stg_, 0, NT - 1, hf[NT - 1]);
 #pragma unroll
-      for (int t = 0; t < NT; ++t) asm volatile("" : "+v"(acc[0][t]), "+v"(acc[1][t])::"memory");
+      for (int t = 0; t < NT; ++t) {
+        mul_t(wA, hf[t], t);
+        ld_h(stg_, 1, t, hf[t]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, kDefer ? 8 : 6, 0);
+      for (int t_ = 1; t_ < NT; ++t_) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     };
     __builtin_amdgcn_s_barrier();  // stage 0 visible
     asm volatile("" ::: "memory");
     int stg = 0;
-    Frag64 g;
-    for (int ks = 0; ks < nk; ++ks) {
-      load_frag64(stg, 0, g);
-      multiply64(g);
-      pin_acc();  // one fragment set in registers at a time: these MFMAs come before the next LDS reads
-      load_frag64(stg, 1, g);
-      if (ks + 1 < nk) {
-        // every LDS read of this stage has returned before the producers are told its buffer may be refilled
-        __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0) only
-        __builtin_amdgcn_s_barrier();  // stage ks+1 visible
-        asm volatile("" ::: "memory");
-        stg = stg + 1 == kLmStages ? 0 : stg + 1;
+    ld_w(0, 0, wA);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) ld_h(0, 0, t, hf[t]);
+    for (int ks = 0; ks + 1 < nk; ++ks) {
+      phase_a(stg);
+      // second double step, rolling in the first of the next stage: the barrier that opens that stage comes after
+      // the first pair of MFMAs, which covers the return of this stage's last reads
+      mul_t(wB, hf[0], 0);
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0) only: every read of this stage is back
+      __builtin_amdgcn_s_barrier();  // stage ks+1 visible; this stage's buffer may be refilled
+      asm volatile("" ::: "memory");
+      stg = stg + 1 == kLmStages ? 0 : stg + 1;
+      ld_w(stg, 0, wA);
+      ld_h(stg, 0, 0, hf[0]);
+#pragma unroll
+      for (int t = 1; t < NT; ++t) {
+        mul_t(wB, hf[t], t);
+        if (!kDefer || t < NT - 1) ld_h(stg, 0, t, hf[t]);
       }
-      multiply64(g);
-      pin_acc();
+      __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+      for (int t_ = 1; t_ < NT; ++t_) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        if (!kDefer || t_ < NT - 1) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // the last stage: nothing left to roll in behind its second double step
+    phase_a(stg);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) mul_t(wB, hf[t], t);
+    // the epilogue's work stays behind the last MFMAs: mixed in with them it would need registers the operands still hold
+#pragma unroll
+    for (int t = 0; t < NT; ++t) asm volatile("" : "+v"(acc[0][t]), "+v"(acc[1][t])::"memory");
   } else {
   Frag f0, f1;
   __builtin_amdgcn_s_barrier();  // stage 0 visible

@@ -194,64 +194,113 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
     // accumulator tile; one fragment set at a time (a second set spills into the main loop: five times slower)
     typedef __attribute__((ext_vector_type(8))) int i32x8_t;
     typedef __attribute__((ext_vector_type(4))) int i32x4_t;
-    i32x8_t wa[2], hb[NT];
-    auto load64 = [&](int s2) {
+    // Operands roll through the registers as in the small-M kernel: a second pair of W operands, and a token-row operand
+    // is re-read for the next double step right after the two MFMAs that consumed it; the last one's refill is held back
+    // to the head of the next double step, so that a loop iteration ends on MFMAs.
+    i32x8_t wA[2], wB[2], hf[NT];
+    auto ld_w = [&](int slot, int s2, i32x8_t (&wf)[2]) {
+      const char* base = lds + slot * kBgWBytes + wrow_off;
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const int coff = ((2 * (2 * s2 + e) + lh) ^ sw) * 16;
-        const char* wb = lds + wslot * kBgWBytes + wrow_off + coff;
-        const char* hbp = lds + hslot * kBgHBytes + hrow_off + coff;
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
-          const i32x4_t v = *(const i32x4_t*)(wb + a * 32 * kBgRowBytes);
+          const i32x4_t v = *(const i32x4_t*)(base + a * 32 * kBgRowBytes + coff);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) wa[a][4 * e + i] = v[i];
-        }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const i32x4_t v = *(const i32x4_t*)(hbp + t * 32 * kBgRowBytes);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) hb[t][4 * e + i] = v[i];
+          for (int i = 0; i < 4; ++i) wf[a][4 * e + i] = v[i];
         }
       }
     };
-    auto multiply64 = [&]() {
+    auto ld_h = [&](int slot, int s2, int t, i32x8_t& f) {
+      const char* base = lds + slot * kBgHBytes + hrow_off + t * 32 * kBgRowBytes;
 #pragma unroll
-      for (int t = 0; t < NT; ++t)
+      for (int e = 0; e < 2; ++e) {
+        const int coff = ((2 * (2 * s2 + e) + lh) ^ sw) * 16;
+        const i32x4_t v = *(const i32x4_t*)(base + coff);
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
-          acc[a][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wa[a], hb[t], acc[a][t], 0, 0, 0, 127, 0, 127);
-      // the MFMAs above cannot sink below this point, the LDS reads after it cannot rise above it
+        for (int i = 0; i < 4; ++i) f[4 * e + i] = v[i];
+      }
+    };
+    auto mul_t = [&](const i32x8_t (&wf)[2], const i32x8_t& f, int t) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+        acc[a][t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf[a], f, acc[a][t], 0, 0, 0, 127, 0, 127);
+    };
+    // first double step of a stage, rolling in its second: two MFMAs; the next W pair's four reads, the two that refill the
+    // first token operand and the two held back for the last one of this double step; then two MFMAs and two reads per tile
+    auto phase_a = [&](int ws, int hs) {
+      ld_w(ws, 1, wB);
+      ld_h(hs, 0, NT - 1, hf[NT - 1]);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        mul_t(wA, hf[t], t);
+        ld_h(hs, 1, t, hf[t]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+      for (int t_ = 1; t_ < NT; ++t_) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // an empty statement that "uses" every accumulator and clobbers memory: the MFMAs before it cannot sink below it
+    // (into or past the conditional blocks of the loads), LDS reads cannot cross it
+    auto pin_acc = [&]() {
 #pragma unroll
       for (int t = 0; t < NT; ++t) asm volatile("" : "+v"(acc[0][t]), "+v"(acc[1][t])::"memory");
     };
+    ld_w(0, 0, wA);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) ld_h(0, 0, t, hf[t]);
     int pend = -1, pslot = 0;  // stage whose second half of the loads is still to be issued, and its slot
-    for (int ks = 0; ks < nk; ++ks) {
-      load64(0);
-      multiply64();
+    for (int ks = 0; ks + 1 < nk; ++ks) {
+      phase_a(wslot, hslot);
+      pin_acc();  // the MFMAs above stay above the branches below
       if (pend >= 0) {  // the second half of the loads of stage ks - 1 + depth, between the two double steps
         issue_part(pend, pslot, 2);
         issue_part(pend, pslot, 3);
       }
-      load64(1);
-      if (ks + 1 < nk) {
-        // every read of stage ks by this wavefront has returned before it says so to the others
-        __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0) only
-        wait_younger(nk - 2 - ks < depth - 2 ? nk - 2 - ks : depth - 2);
-        __builtin_amdgcn_s_barrier();  // stage ks+1 visible to all; nobody reads stage ks's slots again
-        asm volatile("" ::: "memory");
-        pend = ks + depth < nk ? ks + depth : -1;
-        pslot = myslot;
-        if (pend >= 0) {
-          issue_part(pend, pslot, 0);
-          issue_part(pend, pslot, 1);
-        }
-        myslot = myslot + 1 == depth ? 0 : myslot + 1;
-        wslot = wslot + 1 == kBgWStages ? 0 : wslot + 1;
-        hslot = hslot + 1 == kBgHStages ? 0 : hslot + 1;
+      __builtin_amdgcn_sched_barrier(0);
+      // second double step, rolling in the first of the next stage; the barrier that opens it comes after the first pair
+      // of MFMAs, which covers the return of this stage's last reads
+      mul_t(wB, hf[0], 0);
+      asm volatile("" : "+v"(acc[0][0]), "+v"(acc[1][0])::"memory");
+      __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0) only: every read of stage ks is back
+      wait_younger(nk - 2 - ks < depth - 2 ? nk - 2 - ks : depth - 2);
+      __builtin_amdgcn_s_barrier();  // stage ks+1 visible to all; nobody reads stage ks's slots again
+      asm volatile("" ::: "memory");
+      pend = ks + depth < nk ? ks + depth : -1;
+      pslot = myslot;
+      if (pend >= 0) {
+        issue_part(pend, pslot, 0);
+        issue_part(pend, pslot, 1);
       }
-      multiply64();
+      __builtin_amdgcn_sched_barrier(0);
+      myslot = myslot + 1 == depth ? 0 : myslot + 1;
+      wslot = wslot + 1 == kBgWStages ? 0 : wslot + 1;
+      hslot = hslot + 1 == kBgHStages ? 0 : hslot + 1;
+      ld_w(wslot, 0, wA);
+      ld_h(hslot, 0, 0, hf[0]);
+#pragma unroll
+      for (int t = 1; t < NT; ++t) {
+        mul_t(wB, hf[t], t);
+        if (t < NT - 1) ld_h(hslot, 0, t, hf[t]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+      for (int t_ = 1; t_ < NT; ++t_) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        if (t_ < NT - 1) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // the last stage: nothing left to roll in behind its second double step
+    phase_a(wslot, hslot);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) mul_t(wB, hf[t], t);
+    // the epilogue's work stays behind the last MFMAs
+#pragma unroll
+    for (int t = 0; t < NT; ++t) asm volatile("" : "+v"(acc[0][t]), "+v"(acc[1][t])::"memory");
   } else {
   bf16x8_t wa0[2], hb0[NT], wa1[2], hb1[NT];
   load_frag(0, 0, 0, wa0, hb0);
