@@ -147,7 +147,7 @@ __device__ __forceinline__ float request_temperature(const AcceptParams& P, int 
 // differs between the halves), so a workgroup gets through twice as many rows per round of loads.
 template <int kLanes = kWave>
 __device__ __forceinline__ void merge_row_stats(const AcceptParams& P, size_t row, double T, int lane, float* out_max,
-                                                double* out_lse, int* out_arg) {
+                                                double* out_lse, int* out_arg, bool want_arg = true) {
   const int nt = P.n_tiles;
   const float* pm = P.pmax + row * nt;
   const float* ps = P.psum + row * nt;
@@ -191,7 +191,8 @@ __device__ __forceinline__ void merge_row_stats(const AcceptParams& P, size_t ro
   }
   *out_max = m;
   *out_lse = (double)m / T + log(s);
-  *out_arg = P.parg[row * nt + mt];
+  // the arg-max id sits behind one more dependent load; only greedy verification reads it
+  *out_arg = want_arg ? P.parg[row * nt + mt] : 0;
 }
 
 // ============================================================================================
@@ -286,7 +287,7 @@ __global__ __launch_bounds__(kSweepThreads) void accept_chain_sweep(AcceptParams
   }
   for (int n = wv; n < Nq; n += kSweepThreads / kWave) {
     float mx; double lse; int arg;
-    merge_row_stats(P, row0 + n, T, lane, &mx, &lse, &arg);
+    merge_row_stats(P, row0 + n, T, lane, &mx, &lse, &arg, greedy);
     if (lane == 0) { s_lse[n] = lse; s_arg[n] = arg; }
   }
   __syncthreads();
@@ -552,7 +553,7 @@ __global__ __launch_bounds__(kAccThreads) void accept_tree_kernel(AcceptParams P
     const int n = n0 + 2 * wv + (lane >> 5);
     const int nc = n < Nq ? n : Nq - 1;  // idle halves repeat the last row (the shuffles need every lane)
     float mx; double lse; int arg;
-    merge_row_stats<32>(P, row0 + nc, T, lane, &mx, &lse, &arg);
+    merge_row_stats<32>(P, row0 + nc, T, lane, &mx, &lse, &arg, greedy);
     if ((lane & 31) == 0 && n < Nq) { s_lse[n] = lse; s_arg[n] = arg; }
   }
   __syncthreads();

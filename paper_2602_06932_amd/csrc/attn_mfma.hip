@@ -89,9 +89,8 @@ __global__ __launch_bounds__(kAtThreads, 2) void attn_mfma_kernel(
 
   const int rt = blockIdx.y, row_tiles = gridDim.y;
   const int U = pbv(B);
-  const int c = units_per_wg(U, gridDim.x);
-  int u = blockIdx.x * c;
-  const int u_end = min(U, u + c);
+  int u = unit_begin(U, gridDim.x, blockIdx.x);
+  const int u_end = unit_begin(U, gridDim.x, blockIdx.x + 1);
   if (u >= u_end) return;
 
   const int G = Hq / Hkv;
@@ -364,9 +363,8 @@ __global__ __launch_bounds__(kWideThreads, 1) void attn_mfma_wide_kernel(
   auto pbv = [&](int i) -> int { return kLocalPlan ? s_pb[i] : PB[i]; };
 
   const int U = pbv(B);
-  const int c = units_per_wg(U, gridDim.x);
-  int u = blockIdx.x * c;
-  const int u_end = min(U, u + c);
+  int u = unit_begin(U, gridDim.x, blockIdx.x);
+  const int u_end = unit_begin(U, gridDim.x, blockIdx.x + 1);
   if (u >= u_end) return;
 
   const int G = Hq / Hkv;
@@ -573,9 +571,9 @@ __global__ __launch_bounds__(32 * kCombineRows) void attn_mfma_combine(const flo
   const int mrow = n * G + hq % G;
   const int rt = mrow >> 5, li = mrow & 31;
   const int n_b = (seq_lens[b] + kAtTile - 1) / kAtTile;
-  const int c = units_per_wg(PB[B], wgs);
   const int u0 = PB[b] + hk * n_b, u1 = u0 + n_b;
-  const int w0 = u0 / c, w1 = (u1 - 1) / c;
+  // (a sequence of length 0 has no unit and no partial: w1 < w0, nothing is merged and the row comes out as zeros)
+  const int w0 = n_b > 0 ? unit_owner(PB[B], wgs, u0) : 0, w1 = n_b > 0 ? unit_owner(PB[B], wgs, u1 - 1) : -1;
   const int pair = b * Hkv + hk;
   const int d4 = threadIdx.x & 31;  // columns 4 d4 .. 4 d4 + 3
   // online merge, four partials' loads in flight at a time; partial p of the pair is segment

@@ -42,6 +42,19 @@ __device__ __forceinline__ int units_per_wg(int U, int wgs) {
   return (c + 3) & ~3;  // a multiple of four tiles: the four wavefronts of a workgroup stay balanced
 }
 
+// The forward sweeps deal the U units to the workgroups as evenly as they divide: contiguous runs of U / wgs units, one
+// more for the first U % wgs workgroups - every resident workgroup has work and no compute unit holds more than its share.
+__device__ __forceinline__ int unit_begin(int U, int wgs, int w) {
+  const int q = U / wgs, r = U % wgs;
+  return w * q + (w < r ? w : r);
+}
+// the workgroup whose run holds unit u (0 <= u < U)
+__device__ __forceinline__ int unit_owner(int U, int wgs, int u) {
+  const int q = U / wgs, r = U % wgs;
+  const int edge = r * (q + 1);  // units below it sit in runs of q + 1
+  return u < edge ? u / (q + 1) : r + (u - edge) / q;  // u >= edge implies q >= 1
+}
+
 // ---- pieces shared by the two sweep kernels -----------------------------------------------------------
 struct SoftmaxState {
   f32x16_t o[4];   // O^T accumulators: block db, register r <-> column 32 db + 8(r/4) + 4*lh + r%4
