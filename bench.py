@@ -24,22 +24,22 @@ MFMA_PEAK_TFLOPS = {4: 157.3, 2: 2500.0, 1: 5000.0}  # dense, by bytes per opera
 # names the file under profiles/ that holds the counters it was computed from (attention = sweep kernel + combine).
 # Constants of an earlier profiling run, not measured live: None for workloads and seeds that were not profiled.
 MEASURED_TRAFFIC = {
-    ("llama", 1, "lmhead"): {"read_bytes": 1061667997, "write_bytes": 91416796,
-                             "source": "profiles/lmhead_counters_llama3_8b_chain_k4.txt"},
-    ("llama", 1, "attn"): {"read_bytes": 314438568 + 7671525, "write_bytes": 7412137 + 1310720,
-                           "source": "profiles/attn_counters_llama3_8b_chain_k4.txt"},
-    ("qwen_greedy", 1, "lmhead"): {"read_bytes": 2062617916, "write_bytes": 306753619,
-                                   "source": "profiles/lmhead_counters_qwen3_8b_greedy_k6.txt"},
-    ("qwen_greedy", 1, "attn"): {"read_bytes": 1167430613 + 15060748, "write_bytes": 14680646 + 3670016,
-                                 "source": "profiles/attn_counters_qwen3_8b_greedy_k6.txt"},
-    ("tree", 1, "lmhead"): {"read_bytes": 1185191257, "write_bytes": 296134355,
-                            "source": "profiles/lmhead_counters_llama3_8b_tree32.txt"},
-    ("tree", 1, "attn"): {"read_bytes": 277111212 + 34707762, "write_bytes": 34078816 + 4194304,
-                          "source": "profiles/attn_counters_llama3_8b_tree32.txt"},
-    ("stress", 1, "lmhead"): {"read_bytes": 5769334082, "write_bytes": 1167900979,
-                              "source": "profiles/lmhead_counters_stress_b256.txt"},
-    ("stress", 1, "attn"): {"read_bytes": 8113351175 + 42048193, "write_bytes": 39984064 + 15728640,
-                            "source": "profiles/attn_counters_stress_b256.txt"},
+    ("llama", 1, "lmhead"): {"read_bytes": 1061787792, "write_bytes": 92673465,
+        "source": "profiles/lmhead_counters_llama3_8b_chain_k4.txt"},
+    ("llama", 1, "attn"): {"read_bytes": 314706446 + 8241264, "write_bytes": 7953420 + 1310720,
+        "source": "profiles/attn_counters_llama3_8b_chain_k4.txt"},
+    ("qwen_greedy", 1, "lmhead"): {"read_bytes": 1582910131, "write_bytes": 306656812,
+        "source": "profiles/lmhead_counters_qwen3_8b_greedy_k6.txt"},
+    ("qwen_greedy", 1, "attn"): {"read_bytes": 1167539001 + 15271195, "write_bytes": 14873830 + 3670016,
+        "source": "profiles/attn_counters_qwen3_8b_greedy_k6.txt"},
+    ("tree", 1, "lmhead"): {"read_bytes": 1185215020, "write_bytes": 296291315,
+        "source": "profiles/lmhead_counters_llama3_8b_tree32.txt"},
+    ("tree", 1, "attn"): {"read_bytes": 277109115 + 34725227, "write_bytes": 34078816 + 4194304,
+        "source": "profiles/attn_counters_llama3_8b_tree32.txt"},
+    ("stress", 1, "lmhead"): {"read_bytes": 9448627009, "write_bytes": 1161910137,
+        "source": "profiles/lmhead_counters_stress_b256.txt"},
+    ("stress", 1, "attn"): {"read_bytes": 8113377592 + 42115614, "write_bytes": 40029894 + 15728640,
+        "source": "profiles/attn_counters_stress_b256.txt"},
 }
 
 
