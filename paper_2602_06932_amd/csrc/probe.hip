@@ -4,8 +4,9 @@
 // stage - with its parts switched on one at a time:
 //   mode 0  matrix cores only, operands fixed in registers
 //   mode 1  + the operand reads from LDS (six 16-byte reads per lane and step, the LM head's swizzled layout)
-//   mode 2  + the LDS-direct global loads that refill the stage (row slivers of 128 bytes at an 8 KB pitch, L2
-//             resident: no HBM traffic), issued by the multiplying wavefronts
+//   mode 2  + the LDS-direct loads that refill the stage (row slivers of 128 bytes at an 8 KB pitch, L2
+//             resident: no HBM traffic), issued by the multiplying wavefronts as in that kernel: through a buffer
+//             descriptor, two after every step
 //   mode 3  the loads alone
 //   mode 4  the W sweep alone: every workgroup streams its own 256 rows x 8 KB of `operands` once from HBM through a
 //           three-stage LDS ring in the LM head's tile shape (row slivers of 128 bytes per stage), four loading
@@ -25,6 +26,11 @@ constexpr size_t kPrOperandBytes = (size_t)4 * 512 * 8192;  // four tiles of 512
 
 __device__ __forceinline__ void probe_dma16(const void* g, unsigned l) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(g) : "memory");
+}
+// the same through a buffer descriptor: descriptor base + 32-bit lane offset + scalar offset, range-checked by the hardware
+typedef __attribute__((ext_vector_type(4))) int probe_i32x4_t;
+__device__ __forceinline__ void probe_bdma16(probe_i32x4_t rsrc, unsigned voff, unsigned soff, unsigned l) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" ::"s"(l), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
 
 template <int MODE>
@@ -56,7 +62,21 @@ __global__ __launch_bounds__(kPrThreads, 1) void probe_kernel(const char* __rest
     __syncthreads();
   }
   const int li = lane & 31, lh = lane >> 5;
+  // descriptor over this workgroup's 512-row tile; wavefront w, instruction j: rows 64 w + 8 j .. + 7, 128 bytes at k offset s
+  probe_i32x4_t rsrc;
+  {
+    const uint64_t a = (uint64_t)(uintptr_t)tile;
+    rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    rsrc[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((a >> 32) & 0xffffu));
+    rsrc[2] = 512 * 8192;
+    rsrc[3] = 0x00020000;
+  }
+  const unsigned voff = (unsigned)((wave * 64 + (lane >> 3)) * 8192 + (lane & 7) * 16);
+  auto refill = [&](int s, int j) {
+    probe_bdma16(rsrc, voff, (unsigned)(j * 8 * 8192 + (s & 63) * 128), lds0 + wave * 8192 + j * 1024);
+  };
   for (int s = 0; s < stages; ++s) {
+    if (MODE == 2) LM_WAIT_VMCNT(8);  // at most one stage's loads of this wavefront in flight
     if (MODE != 3) {
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
@@ -71,15 +91,18 @@ __global__ __launch_bounds__(kPrThreads, 1) void probe_kernel(const char* __rest
         for (int t = 0; t < 4; ++t)
 #pragma unroll
           for (int a = 0; a < 2; ++a) acc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[t], acc[a][t], 0, 0, 0);
+        if (MODE == 2) {  // two of the stage's eight loads after every step
+          __builtin_amdgcn_sched_barrier(0);
+          refill(s, 2 * st);
+          refill(s, 2 * st + 1);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
-    if (MODE >= 2) {
-      LM_WAIT_VMCNT(8);  // at most one stage's loads of this wavefront in flight
-      // wavefront w, instruction j: rows 64 w + 8 j .. + 7 of the 512-row tile, 128 bytes at k offset s
+    if (MODE == 3) {
+      LM_WAIT_VMCNT(8);
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        probe_dma16(tile + (size_t)(wave * 64 + j * 8 + (lane >> 3)) * 8192 + (s & 63) * 128 + (lane & 7) * 16,
-                    lds0 + wave * 8192 + j * 1024);
+      for (int j = 0; j < 8; ++j) refill(s, j);
     }
     __builtin_amdgcn_s_barrier();
   }
