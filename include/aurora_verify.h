@@ -351,7 +351,7 @@ void aurora_debug_set_tree_spin_limit(int polls);
  * structure of the many-row LM-head kernel with its parts switched on one at a time, on operands the caller provides,
  * so that a benchmark can say what a bf16 contraction reaches on the device at hand - and how much that depends on
  * the values multiplied.  mode 0: matrix cores only (operands in registers); 1: + operand reads from LDS; 2: + the
- * LDS-direct global loads that refill a stage (L2 resident, no HBM traffic); 3: those loads alone; 4: the vocabulary
+ * LDS-direct loads that refill a stage, issued as that kernel issues them (L2 resident, no HBM traffic); 3: those loads alone; 4: the vocabulary
  * sweep alone - all of `operands` (whole multiples of 2 MiB; e.g. the LM head itself) streamed once from HBM through a
  * three-stage LDS ring in the LM head's tile shape, one workgroup per 256 rows of 8 KB, `workgroups` and `stages`
  * ignored.  `operands`:
