@@ -33,13 +33,22 @@ __device__ __forceinline__ void lm_tile_out(f32x16_t& a0, f32x16_t& a1, int vrow
                                             float& mx_out, float& sum_out, int& arg_out, float& half_max_out) {
   const int li = lane & 31, lh = lane >> 5;
   float m01[2] = {-INFINITY, -INFINITY};  // this lane's largest entry among vocab rows vrow0 .. +31 and vrow0 + 32 .. +63
+  const bool v_whole = vrow0 + 64 <= V;  // wave-uniform: only the vocabulary's last tile has rows to mask
+  if (!v_whole) {
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        f32x16_t& acc = a ? a1 : a0;
+        const int v = vrow0 + 32 * a + 8 * (r >> 2) + 4 * lh + (r & 3);
+        if (v >= V) acc[r] = -INFINITY;
+      }
+  }
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      f32x16_t& acc = a ? a1 : a0;
-      const int v = vrow0 + 32 * a + 8 * (r >> 2) + 4 * lh + (r & 3);
-      if (v >= V) acc[r] = -INFINITY;
+      const f32x16_t& acc = a ? a1 : a0;
       m01[a] = fmaxf(m01[a], acc[r]);
     }
   float mx = fmaxf(m01[0], m01[1]);
@@ -86,6 +95,18 @@ __device__ __forceinline__ void lm_tile_out(f32x16_t& a0, f32x16_t& a1, int vrow
       *(f32x4_t*)(tb + li * 256 + ((slot ^ (li & 15)) * 16)) = o;
     }
   const int srow = lane >> 4, sslot = lane & 15;
+  if (vec_ok && v_whole && mrow0 + 32 <= M) {
+    // the common case, decided once per wavefront: every row and column of the tile exists - eight plain vector stores
+    float* dst = logits + (size_t)(mrow0 + srow) * V + (vrow0 + 4 * sslot);
+    const size_t step = (size_t)4 * V;  // four token rows further
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int n = 4 * j + srow;
+      const f32x4_t o = *(const f32x4_t*)(tb + n * 256 + ((sslot ^ (n & 15)) * 16));
+      __builtin_nontemporal_store(o, (f32x4_t*)(dst + j * step));  // written once, read much later: keep it out of the way of W
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int n = 4 * j + srow;  // token row of the tile
