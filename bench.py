@@ -24,9 +24,9 @@ MFMA_PEAK_TFLOPS = {4: 157.3, 2: 2500.0, 1: 5000.0}  # dense, by bytes per opera
 # names the file under profiles/ that holds the counters it was computed from (attention = sweep kernel + combine).
 # Constants of an earlier profiling run, not measured live: None for workloads and seeds that were not profiled.
 MEASURED_TRAFFIC = {
-    ("llama", 1, "lmhead"): {"read_bytes": 1061787792, "write_bytes": 92673465,
+    ("llama", 1, "lmhead"): {"read_bytes": 1061782509, "write_bytes": 92701395,
         "source": "profiles/lmhead_counters_llama3_8b_chain_k4.txt"},
-    ("llama", 1, "attn"): {"read_bytes": 314706446 + 8241264, "write_bytes": 7953420 + 1310720,
+    ("llama", 1, "attn"): {"read_bytes": 314706187 + 8241253, "write_bytes": 7954598 + 1310720,
         "source": "profiles/attn_counters_llama3_8b_chain_k4.txt"},
     ("qwen_greedy", 1, "lmhead"): {"read_bytes": 1582910131, "write_bytes": 306656812,
         "source": "profiles/lmhead_counters_qwen3_8b_greedy_k6.txt"},
