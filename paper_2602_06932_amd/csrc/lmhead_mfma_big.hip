@@ -10,7 +10,7 @@
 // wavefront multiplies; wavefronts 0-3 also load W and 4-7 the token rows, each operand into its own
 // LDS ring (W: 3 stages of 32 KB, it comes from HBM; token rows: 2 stages, they come from L2), by direct
 // global->LDS loads of 128-byte row segments through a buffer descriptor that covers exactly the tile's rows; a
-// stage's loads leave in four parts between the matrix-core steps rather than in one burst (a burst stalls the
+// stage's loads leave in two halves, a matrix-core step apart, rather than in one burst (a burst stalls the
 // matrix cores of the issuing wavefronts' SIMDs).  A stage is 64 hidden elements = 4 MFMA steps; operand
 // fragments are double-buffered in registers one step ahead, and the barrier that opens the next
 // stage sits before the last step of the current one, so the matrix pipe never waits on it.
@@ -117,8 +117,8 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
     voff[j] = (unsigned)(r * row_bytes + chunk * 16);
   }
   const unsigned ring0 = lds0 + (w_loader ? 0 : kBgWRing) + row0 * kBgRowBytes;
-  // A stage's loads go out in four parts (a W loader: two instructions each; a token-row loader: NT each in the first two
-  // parts), so that they can be spread over the matrix-core work instead of leaving in one burst.
+  // A stage's loads are cut into four parts (a W loader: two instructions each; a token-row loader: NT each in the first two
+  // parts), so that they can be placed between the matrix-core work instead of leaving in one burst.
   auto issue_part = [&](int ks, int slot, int part) {
     const unsigned base = ring0 + slot * kBgWBytes;
     const unsigned koff = (unsigned)(ks * kBgRowBytes);
@@ -304,28 +304,30 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
   } else {
   bf16x8_t wa0[2], hb0[NT], wa1[2], hb1[NT];
   load_frag(0, 0, 0, wa0, hb0);
-  // The loads of stage ks + depth leave in four parts: one right after the barrier that frees their slot (below), the
-  // others between the first three steps of the next stage.  All of a stage's loads are out before the next vmcnt
-  // wait, so the counts waited for are the same as with one burst.
-  int pend = -1, pslot = 0;  // stage whose parts 1..3 are still to be issued, and its slot
-#define BG_PART(p)                                       \
+  // The loads of stage ks + depth leave in two halves: one right after the barrier that frees their slot (below), the
+  // other after the first step of the next stage (later than that and the W rows that come from HBM arrive too late for
+  // the stage that needs them; all at once and the burst holds up the matrix cores).  All of a stage's loads are out before
+  // the next vmcnt wait, so the counts waited for are the same as with one burst.
+  int pend = -1, pslot = 0;  // stage whose second half is still to be issued, and its slot
+#define BG_HALF(h)                                       \
   do {                                                   \
-    if (pend >= 0) issue_part(pend, pslot, p);           \
+    if (pend >= 0) {                                     \
+      issue_part(pend, pslot, 2 * (h));                  \
+      issue_part(pend, pslot, 2 * (h) + 1);              \
+    }                                                    \
     __builtin_amdgcn_sched_barrier(0);                   \
   } while (0)
   for (int ks = 0; ks + 1 < nk; ++ks) {
     load_frag(wslot, hslot, 1, wa1, hb1);
     multiply(wa0, hb0);
     BG_STEP_ORDER();
-    BG_PART(1);
+    BG_HALF(1);
     load_frag(wslot, hslot, 2, wa0, hb0);
     multiply(wa1, hb1);
     BG_STEP_ORDER();
-    BG_PART(2);
     load_frag(wslot, hslot, 3, wa1, hb1);
     multiply(wa0, hb0);
     BG_STEP_ORDER();
-    BG_PART(3);
     // every read of stage ks by this wavefront has returned before it says so to the others
     __builtin_amdgcn_s_waitcnt((7 << 4) | (3 << 14) | 15);  // lgkmcnt(0) only
     wait_younger(nk - 2 - ks < depth - 2 ? nk - 2 - ks : depth - 2);
@@ -333,7 +335,7 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
     asm volatile("" ::: "memory");
     pend = ks + depth < nk ? ks + depth : -1;
     pslot = myslot;
-    BG_PART(0);
+    BG_HALF(0);
     myslot = myslot + 1 == depth ? 0 : myslot + 1;
     wslot = wslot + 1 == kBgWStages ? 0 : wslot + 1;
     hslot = hslot + 1 == kBgHStages ? 0 : hslot + 1;
@@ -341,7 +343,7 @@ __device__ __forceinline__ void bg_tile(const BgArgs& A, char* lds, int vt, int 
     multiply(wa1, hb1);
     BG_STEP_ORDER();
   }
-#undef BG_PART
+#undef BG_HALF
   load_frag(wslot, hslot, 1, wa1, hb1);
   multiply(wa0, hb0);
   load_frag(wslot, hslot, 2, wa0, hb0);
